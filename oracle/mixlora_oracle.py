@@ -1,0 +1,185 @@
+"""CPU oracle for the MixLoRA feed-forward block.  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the bench's cpu_baseline leg may import this
+file; the product path never does.  It shares no code with the HIP library.
+
+It is the plain definition of the block written out in float64 NumPy:
+
+* Router (Top-K router paragraph, Eq. 7, and the Norm step of Algorithm 1):
+  logits z = W_r x, probabilities p = softmax(z), keep the k largest, divide the
+  kept probabilities by their sum.
+* Expert (Eq. 1 and Eq. 6, with the SwiGLU shape given in Section 3.3): expert e
+  is the frozen FFN  W_down(SiLU(W_gate x) * W_up x)  in which each of the three
+  projections has its own low-rank update  W + s B_e A_e  (s = alpha / r, the
+  appendix hyper-parameter table).
+* Block output (Eq. 2 / Eq. 6): y_t = sum over the kept experts of
+  weight * expert output.  The residual add of Eq. 5 is outside this block.
+* Auxiliary loss (Eq. 8 and Eq. 9): L = a N sum_i F_i P_i.
+* Backward: the reverse-mode derivative of the above with the three base
+  matrices frozen and A, B, W_r and x receiving gradients (the paper does not
+  print it; it is derived here and pinned by finite differences in the tests).
+
+Every expert is evaluated from the definition on the tokens routed to it
+(base projection and low-rank update computed per expert); nothing of
+Algorithm 1's shared-projection schedule or of the HIP path's grouping is used.
+
+Readings of the paper where it is silent or inconsistent (listed in full in the
+design notes): top-k selection is on the logits with ties going to the lowest
+expert index; slots are ordered by descending logit; F_i of Eq. 9 counts the
+first-choice expert ("top1", as printed) or all k choices divided by k
+("topk"); P_i uses the full softmax; no gradient flows through F_i.
+
+Pinned by tests/test_oracle_pins.py (dense-FFN special case, k = N mixture,
+merged-weight identity, brute-force loops, closed-form auxiliary losses,
+finite differences, autograd of an independent formulation).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F64 = np.float64
+
+
+def _f64(a):
+    return np.asarray(a, dtype=F64)
+
+
+def sigmoid(v):
+    return 1.0 / (1.0 + np.exp(-v))
+
+
+def router(x, W_router, k):
+    """Eq. 7 + Norm of Algorithm 1.  Returns z, p [T,N]; idx [T,k]; w [T,k]."""
+    x = _f64(x)
+    W_router = _f64(W_router)
+    z = x @ W_router.T
+    zmax = z.max(axis=1, keepdims=True)
+    ez = np.exp(z - zmax)
+    p = ez / ez.sum(axis=1, keepdims=True)
+    # stable sort of -z: largest logit first, equal logits keep ascending expert index
+    order = np.argsort(-z, axis=1, kind="stable")
+    idx = order[:, :k].astype(np.int64)
+    kept = np.take_along_axis(p, idx, axis=1)
+    w = kept / kept.sum(axis=1, keepdims=True)
+    return z, p, idx, w
+
+
+def aux_loss(probs, topk_idx, N, coeff, mode="top1"):
+    """Eq. 8-9.  Returns (loss, F [N], P [N])."""
+    probs = _f64(probs)
+    topk_idx = np.asarray(topk_idx)
+    T = probs.shape[0]
+    if mode == "top1":
+        F = np.bincount(topk_idx[:, 0], minlength=N).astype(F64) / T
+    elif mode == "topk":
+        F = np.bincount(topk_idx.reshape(-1), minlength=N).astype(F64) / (T * topk_idx.shape[1])
+    else:
+        raise ValueError(mode)
+    P = probs.sum(axis=0) / T
+    return coeff * N * float((F * P).sum()), F, P
+
+
+def aux_loss_dprobs(probs, topk_idx, N, coeff, mode="top1"):
+    """d L_aux / d probs [T,N]; F_i is piecewise constant so only P_i carries gradient."""
+    T = np.asarray(probs).shape[0]
+    _, F, _ = aux_loss(probs, topk_idx, N, coeff, mode)
+    return np.broadcast_to(coeff * N * F / T, (T, N)).copy()
+
+
+def expert_forward(xe, W, e, s):
+    """One expert (Eq. 1 on each projection, SwiGLU of Section 3.3) on rows xe [n,d]."""
+    pg = xe @ W["A_gate"][e].T                       # [n,r]
+    pu = xe @ W["A_up"][e].T
+    g = xe @ W["W_gate"].T + s * (pg @ W["B_gate"][e].T)   # [n,f]
+    u = xe @ W["W_up"].T + s * (pu @ W["B_up"][e].T)
+    a = g * sigmoid(g) * u
+    q = a @ W["A_down"][e].T                         # [n,r]
+    o = a @ W["W_down"].T + s * (q @ W["B_down"][e].T)     # [n,d]
+    return dict(pg=pg, pu=pu, g=g, u=u, a=a, q=q, o=o)
+
+
+def forward(x, W, k, lora_scale, aux_coeff=0.01, aux_mode="top1", keep=False):
+    """Whole block.  W: dict of arrays (any float dtype).  Returns a dict with
+    y [T,d], probs, logits, topk_idx, topk_w, counts [N], aux_loss, F, P
+    (and the per-expert intermediates when keep=True)."""
+    x = _f64(x)
+    W = {n: _f64(v) for n, v in W.items()}
+    T, d = x.shape
+    N = W["W_router"].shape[0]
+    z, p, idx, w = router(x, W["W_router"], k)
+    y = np.zeros((T, d), dtype=F64)
+    counts = np.zeros(N, dtype=np.int64)
+    saved = {}
+    for e in range(N):
+        tok, slot = np.nonzero(idx == e)
+        counts[e] = tok.size
+        if tok.size == 0:
+            continue
+        res = expert_forward(x[tok], W, e, lora_scale)
+        np.add.at(y, tok, w[tok, slot][:, None] * res["o"])
+        if keep:
+            res["tok"], res["slot"] = tok, slot
+            saved[e] = res
+    loss, F, P = aux_loss(p, idx, N, aux_coeff, aux_mode)
+    out = dict(y=y, logits=z, probs=p, topk_idx=idx, topk_w=w, counts=counts,
+               aux_loss=loss, F=F, P=P)
+    if keep:
+        out["saved"] = saved
+    return out
+
+
+def backward(x, W, k, lora_scale, dy, d_aux=1.0, aux_coeff=0.01, aux_mode="top1"):
+    """Gradients of  <y, dy> + d_aux * L_aux  with W_gate, W_up, W_down frozen.
+
+    Returns dict: dx [T,d], dA_gate/dA_up [N,r,d], dB_gate/dB_up [N,f,r],
+    dA_down [N,r,f], dB_down [N,d,r], dW_router [N,d], plus dw [T,k] and dz [T,N]."""
+    x = _f64(x)
+    dy = _f64(dy)
+    W = {n: _f64(v) for n, v in W.items()}
+    s = lora_scale
+    fw = forward(x, W, k, s, aux_coeff, aux_mode, keep=True)
+    T, d = x.shape
+    N = W["W_router"].shape[0]
+    p, idx, w = fw["probs"], fw["topk_idx"], fw["topk_w"]
+    G = {n: np.zeros_like(W[n]) for n in
+         ("A_gate", "B_gate", "A_up", "B_up", "A_down", "B_down", "W_router")}
+    dx = np.zeros_like(x)
+    dw = np.zeros((T, k), dtype=F64)
+    for e, sv in fw["saved"].items():
+        tok, slot = sv["tok"], sv["slot"]
+        xe, dye = x[tok], dy[tok]
+        dw[tok, slot] = (dye * sv["o"]).sum(axis=1)
+        do = w[tok, slot][:, None] * dye                     # [n,d]
+        # down projection  o = a W_d^T + s (a A_d^T) B_d^T
+        G["B_down"][e] = s * (do.T @ sv["q"])                # [d,r]
+        v = do @ W["B_down"][e]                              # [n,r]
+        G["A_down"][e] = s * (v.T @ sv["a"])                 # [r,f]
+        da = do @ W["W_down"] + s * (v @ W["A_down"][e])     # [n,f]
+        # a = g sigmoid(g) u
+        g, u = sv["g"], sv["u"]
+        sg = sigmoid(g)
+        dg = da * u * sg * (1.0 + g * (1.0 - sg))
+        du = da * g * sg
+        # gate / up projections
+        G["B_gate"][e] = s * (dg.T @ sv["pg"])               # [f,r]
+        tg = dg @ W["B_gate"][e]                             # [n,r]
+        G["A_gate"][e] = s * (tg.T @ xe)                     # [r,d]
+        G["B_up"][e] = s * (du.T @ sv["pu"])
+        tu = du @ W["B_up"][e]
+        G["A_up"][e] = s * (tu.T @ xe)
+        dxe = dg @ W["W_gate"] + du @ W["W_up"] + s * (tg @ W["A_gate"][e]) \
+            + s * (tu @ W["A_up"][e])
+        np.add.at(dx, tok, dxe)
+    # router: w = p_S / sum(p_S) on the kept set, zero elsewhere
+    kept = np.take_along_axis(p, idx, axis=1)
+    ssum = kept.sum(axis=1, keepdims=True)
+    dkept = (dw - (w * dw).sum(axis=1, keepdims=True)) / ssum
+    dp = np.zeros((T, N), dtype=F64)
+    np.put_along_axis(dp, idx, dkept, axis=1)
+    dp += d_aux * aux_loss_dprobs(p, idx, N, aux_coeff, aux_mode)
+    dz = p * (dp - (p * dp).sum(axis=1, keepdims=True))
+    G["W_router"] = dz.T @ x
+    dx += dz @ W["W_router"]
+    out = {"d" + n: v for n, v in G.items()}
+    out.update(dx=dx, dw=dw, dz=dz, forward=fw)
+    return out

@@ -1,0 +1,202 @@
+"""Seeded synthetic inputs for the MixLoRA FFN block.
+
+This module holds no arithmetic of the method itself: it only draws random
+tensors of the shapes, value distributions and routing structure of the
+LLaMA-shaped fine-tuning workloads (hyper-parameter table of the appendix:
+rank 16, alpha 32, 8 experts, top-2), and rounds them to the storage dtype.
+Both the CPU oracle's tests and the HIP path's tests/bench consume the arrays
+produced here; neither side's code is imported.
+
+Random numbers come from a counter-based generator (splitmix64 of
+``(seed, tensor, element)`` followed by Box-Muller) so the values do not
+depend on the NumPy version or on the order in which tensors are requested.
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+from typing import Dict, Optional
+
+import numpy as np
+
+SEED_BASE = 240415159
+
+TENSOR_ORDER = (
+    "x", "W_gate", "W_up", "W_down", "A_gate", "B_gate", "A_up", "B_up",
+    "A_down", "B_down", "W_router", "dy", "aux",
+)
+
+_M64 = np.uint64(0xFFFFFFFFFFFFFFFF)
+_GOLDEN = np.uint64(0x9E3779B97F4A7C15)
+_C1 = np.uint64(0xBF58476D1CE4E5B9)
+_C2 = np.uint64(0x94D049BB133111EB)
+
+
+def _mix(z: np.ndarray) -> np.ndarray:
+    """splitmix64 finaliser on a uint64 array (wrap-around arithmetic)."""
+    z = (z ^ (z >> np.uint64(30))) * _C1
+    z = (z ^ (z >> np.uint64(27))) * _C2
+    return z ^ (z >> np.uint64(31))
+
+
+def _stream_key(seed: int, stream: int) -> np.uint64:
+    with np.errstate(over="ignore"):
+        k = _mix(np.array([np.uint64(seed) * _GOLDEN + np.uint64(stream + 1) * _C2],
+                          dtype=np.uint64))
+    return k[0]
+
+
+def uniform01(seed: int, stream: int, n: int, offset: int = 0) -> np.ndarray:
+    """n doubles in the open interval (0, 1); element i depends only on (seed, stream, i)."""
+    key = _stream_key(seed, stream)
+    out = np.empty(n, dtype=np.float64)
+    chunk = 1 << 22
+    with np.errstate(over="ignore"):
+        for lo in range(0, n, chunk):
+            hi = min(n, lo + chunk)
+            ctr = np.arange(lo + offset, hi + offset, dtype=np.uint64)
+            bits = _mix(key + ctr * _GOLDEN)
+            out[lo:hi] = ((bits >> np.uint64(11)).astype(np.float64) + 0.5) * (1.0 / (1 << 53))
+    return out
+
+
+def normal(seed: int, stream: int, n: int) -> np.ndarray:
+    """n standard normal doubles via Box-Muller on counters (2i, 2i+1)."""
+    out = np.empty(n, dtype=np.float64)
+    chunk = 1 << 22
+    for lo in range(0, n, chunk):
+        hi = min(n, lo + chunk)
+        u = uniform01(seed, stream, 2 * (hi - lo), offset=2 * lo)
+        r = np.sqrt(-2.0 * np.log(u[0::2]))
+        out[lo:hi] = r * np.cos(2.0 * math.pi * u[1::2])
+    return out
+
+
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """fp32 array -> fp32 array holding the nearest-even bfloat16 value of each element."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    bits = a.view(np.uint32)
+    lsb = (bits >> np.uint32(16)) & np.uint32(1)
+    rounded = (bits + np.uint32(0x7FFF) + lsb) & np.uint32(0xFFFF0000)
+    return rounded.view(np.float32)
+
+
+def bf16_bits(a: np.ndarray) -> np.ndarray:
+    """fp32 array of bf16-representable values -> uint16 bit patterns."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return (a.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+
+
+@dataclasses.dataclass(frozen=True)
+class Config:
+    name: str
+    index: int            # position in the workload list; seed = SEED_BASE + index
+    T: int
+    d: int
+    d_ff: int
+    N: int
+    k: int
+    r: int
+    alpha: float
+    dtype: str            # "f32" or "bf16"
+    b_std: float          # std of the LoRA B banks
+    aux_coeff: float = 0.01
+    backward: bool = True
+    structure: str = "uniform"   # "uniform" | "skew0" | "clusters4"
+    seq_len: int = 1024
+
+    @property
+    def lora_scale(self) -> float:
+        return self.alpha / self.r
+
+    @property
+    def seed(self) -> int:
+        return SEED_BASE + self.index
+
+
+CONFIGS = {
+    "tiny_f32": Config("tiny_f32", 1, T=256, d=128, d_ff=344, N=8, k=2, r=8, alpha=16.0,
+                       dtype="f32", b_std=0.02, seq_len=256),
+    "llama2_7b_fwd": Config("llama2_7b_fwd", 2, T=4096, d=4096, d_ff=11008, N=8, k=2, r=16,
+                            alpha=32.0, dtype="bf16", b_std=0.01, backward=False),
+    "llama2_7b": Config("llama2_7b", 3, T=4096, d=4096, d_ff=11008, N=8, k=2, r=16,
+                        alpha=32.0, dtype="bf16", b_std=0.01),
+    "llama2_13b_skew": Config("llama2_13b_skew", 4, T=8192, d=5120, d_ff=13824, N=8, k=2, r=16,
+                              alpha=32.0, dtype="bf16", b_std=0.01, structure="skew0"),
+    "llama3_8b_clusters": Config("llama3_8b_clusters", 5, T=16384, d=4096, d_ff=14336, N=16, k=2,
+                                 r=8, alpha=16.0, dtype="bf16", b_std=0.01,
+                                 structure="clusters4"),
+}
+
+
+def scaled(cfg: Config, **kw) -> Config:
+    """A copy of cfg with some dimensions replaced (used for small parity cases)."""
+    return dataclasses.replace(cfg, **kw)
+
+
+def _store(a: np.ndarray, dtype: str) -> np.ndarray:
+    a = a.astype(np.float32)
+    return round_to_bf16(a) if dtype == "bf16" else a
+
+
+def make_inputs(cfg: Config, only: Optional[tuple] = None) -> Dict[str, np.ndarray]:
+    """Draw every tensor of one workload.
+
+    Returns fp32 arrays whose values are exactly representable in cfg.dtype:
+      x [T,d], W_gate/W_up [d_ff,d], W_down [d,d_ff], A_gate/A_up [N,r,d],
+      B_gate/B_up [N,d_ff,r], A_down [N,r,d_ff], B_down [N,d,r], W_router [N,d],
+      dy [T,d].
+    Distributions: x, dy ~ N(0,1); frozen W ~ N(0,0.02^2); A ~ U(+-1/sqrt(fan_in));
+    B ~ N(0,b_std^2) (non-zero so that every LoRA path is exercised);
+    W_router ~ N(0,0.02^2).
+    Structure:
+      skew0     - last channel of x is the constant 1 and W_router[0,d-1] is raised by
+                  1.5, i.e. expert 0's logit gets exactly +1.5 (skewed expert load);
+      clusters4 - sequence s (seq_len tokens) belongs to cluster s mod 4 and its tokens
+                  are shifted by 0.5 * (random sign vector of the cluster).
+    """
+    T, d, f, N, r = cfg.T, cfg.d, cfg.d_ff, cfg.N, cfg.r
+    seed = cfg.seed
+    sid = {n: i for i, n in enumerate(TENSOR_ORDER)}
+    want = set(only) if only is not None else set(TENSOR_ORDER)
+    out: Dict[str, np.ndarray] = {}
+
+    def nrm(name, shape, std):
+        n = int(np.prod(shape))
+        return (normal(seed, sid[name], n) * std).reshape(shape)
+
+    def uni(name, shape, bound):
+        n = int(np.prod(shape))
+        return ((uniform01(seed, sid[name], n) * 2.0 - 1.0) * bound).reshape(shape)
+
+    if "x" in want:
+        x = nrm("x", (T, d), 1.0)
+        if cfg.structure == "skew0":
+            x[:, d - 1] = 1.0
+        elif cfg.structure == "clusters4":
+            signs = np.where(uniform01(seed, sid["aux"], 4 * d) < 0.5, -1.0, 1.0).reshape(4, d)
+            cluster = (np.arange(T) // cfg.seq_len) % 4
+            x += 0.5 * signs[cluster]
+        out["x"] = _store(x, cfg.dtype)
+    for name, shape in (("W_gate", (f, d)), ("W_up", (f, d)), ("W_down", (d, f))):
+        if name in want:
+            out[name] = _store(nrm(name, shape, 0.02), cfg.dtype)
+    for name, shape, fan_in in (("A_gate", (N, r, d), d), ("A_up", (N, r, d), d),
+                                ("A_down", (N, r, f), f)):
+        if name in want:
+            out[name] = _store(uni(name, shape, 1.0 / math.sqrt(fan_in)), cfg.dtype)
+    for name, shape in (("B_gate", (N, f, r)), ("B_up", (N, f, r)), ("B_down", (N, d, r))):
+        if name in want:
+            out[name] = _store(nrm(name, shape, cfg.b_std), cfg.dtype)
+    if "W_router" in want:
+        wr = nrm("W_router", (N, d), 0.02)
+        if cfg.structure == "skew0":
+            wr[0, d - 1] += 1.5
+        out["W_router"] = _store(wr, cfg.dtype)
+    if "dy" in want:
+        out["dy"] = _store(nrm("dy", (T, d), 1.0), cfg.dtype)
+    return out
+
+
+WEIGHT_NAMES = ("W_gate", "W_up", "W_down", "A_gate", "B_gate", "A_up", "B_up",
+                "A_down", "B_down", "W_router")

@@ -1,0 +1,331 @@
+"""Pins of the CPU oracle to things other than itself (all CPU-only).
+
+Each test names the passage of the paper or the mathematical fact it rests on.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import bruteforce
+from oracle import mixlora_oracle as orc
+from paper_2404_15159_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+WNAMES = synth.WEIGHT_NAMES
+
+
+def small_cfg(**kw):
+    base = dict(T=24, d=16, d_ff=20, N=5, k=2, r=4, alpha=8.0, dtype="f32", b_std=0.3,
+                seq_len=8)
+    base.update(kw)
+    return synth.scaled(synth.CONFIGS["tiny_f32"], **base)
+
+
+def inputs(cfg, wr_std=None):
+    t = synth.make_inputs(cfg)
+    t = {n: v.astype(np.float64) for n, v in t.items()}
+    # small-shape pins want lively routers and non-negligible LoRA paths
+    t["W_router"] *= (wr_std or 10.0)
+    for n in ("W_gate", "W_up", "W_down"):
+        t[n] *= 10.0
+    return t
+
+
+def weights(t):
+    return {n: t[n] for n in WNAMES}
+
+
+def read_golden(name):
+    out = {}
+    with open(os.path.join(GOLDEN, name)) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            parts = line.split()
+            out[tuple(parts[:-1])] = float(parts[-1])
+    return out
+
+
+# ----------------------------------------------------------------------------------------
+# P1: all B = 0  =>  the block is the dense SwiGLU FFN of Section 3.3 (weights sum to one by
+# the Norm step of Algorithm 1), evaluated here with torch's library routines.
+def test_zero_B_reduces_to_dense_swiglu():
+    cfg = small_cfg()
+    t = inputs(cfg)
+    for n in ("B_gate", "B_up", "B_down"):
+        t[n][:] = 0.0
+    out = orc.forward(t["x"], weights(t), cfg.k, cfg.lora_scale)
+    x = torch.from_numpy(t["x"])
+    lin = torch.nn.functional.linear
+    dense = lin(torch.nn.functional.silu(lin(x, torch.from_numpy(t["W_gate"])))
+                * lin(x, torch.from_numpy(t["W_up"])), torch.from_numpy(t["W_down"]))
+    np.testing.assert_allclose(out["y"], dense.numpy(), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(out["topk_w"].sum(axis=1), 1.0, rtol=0, atol=1e-14)
+
+
+def torch_expert(x, t, e, s):
+    """Dense FFN with the merged weights of Eq. 1 (library matmul / silu)."""
+    lin = torch.nn.functional.linear
+    tt = {n: torch.from_numpy(np.ascontiguousarray(t[n])) for n in WNAMES}
+    Wg = tt["W_gate"] + s * tt["B_gate"][e] @ tt["A_gate"][e]
+    Wu = tt["W_up"] + s * tt["B_up"][e] @ tt["A_up"][e]
+    Wd = tt["W_down"] + s * tt["B_down"][e] @ tt["A_down"][e]
+    return lin(torch.nn.functional.silu(lin(x, Wg)) * lin(x, Wu), Wd)
+
+
+# P2: k = N  =>  KeepTop-N keeps everything, the block is the dense softmax mixture (Eq. 2, 7).
+def test_k_equals_N_is_dense_softmax_mixture():
+    cfg = small_cfg(k=5)
+    t = inputs(cfg)
+    out = orc.forward(t["x"], weights(t), cfg.k, cfg.lora_scale)
+    x = torch.from_numpy(t["x"])
+    p = torch.softmax(torch.nn.functional.linear(x, torch.from_numpy(t["W_router"])), dim=1)
+    ref = sum(p[:, e:e + 1] * torch_expert(x, t, e, cfg.lora_scale) for e in range(cfg.N))
+    np.testing.assert_allclose(out["y"], ref.numpy(), rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(out["probs"], p.numpy(), rtol=1e-12, atol=1e-15)
+    assert (out["counts"] == cfg.T).all()
+
+
+# P3: N = 1, k = 1  =>  a plain LoRA FFN with merged weights W + s B A (Eq. 1).
+def test_single_expert_is_merged_lora_ffn():
+    cfg = small_cfg(N=1, k=1)
+    t = inputs(cfg)
+    out = orc.forward(t["x"], weights(t), 1, cfg.lora_scale)
+    ref = torch_expert(torch.from_numpy(t["x"]), t, 0, cfg.lora_scale)
+    np.testing.assert_allclose(out["y"], ref.numpy(), rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(out["topk_w"], 1.0)
+
+
+# P3b: top-k sparse case against the same library formulation with torch.topk on the logits.
+def test_topk_against_torch_formulation():
+    cfg = small_cfg(T=40, N=6, k=3)
+    t = inputs(cfg)
+    out = orc.forward(t["x"], weights(t), cfg.k, cfg.lora_scale)
+    x = torch.from_numpy(t["x"])
+    z = torch.nn.functional.linear(x, torch.from_numpy(t["W_router"]))
+    p = torch.softmax(z, dim=1)
+    val, idx = torch.topk(z, cfg.k, dim=1)
+    kept = torch.gather(p, 1, idx)
+    w = kept / kept.sum(dim=1, keepdim=True)
+    ref = torch.zeros_like(x)
+    for e in range(cfg.N):
+        oe = torch_expert(x, t, e, cfg.lora_scale)
+        for j in range(cfg.k):
+            m = (idx[:, j] == e).to(x.dtype)[:, None]
+            ref += m * w[:, j:j + 1] * oe
+    assert (out["topk_idx"] == idx.numpy()).all()
+    np.testing.assert_allclose(out["topk_w"], w.numpy(), rtol=1e-12)
+    np.testing.assert_allclose(out["y"], ref.numpy(), rtol=1e-10, atol=1e-12)
+    # identity: renormalised kept probabilities == softmax over the kept logits
+    np.testing.assert_allclose(out["topk_w"], torch.softmax(val, dim=1).numpy(), rtol=1e-12)
+
+
+# P4: scalar-loop brute force on tiny inputs (independent code, merged weights).
+@pytest.mark.parametrize("aux_mode", ["top1", "topk"])
+def test_brute_force_tiny(aux_mode):
+    cfg = small_cfg(T=7, d=6, d_ff=9, N=4, k=2, r=2)
+    t = inputs(cfg)
+    out = orc.forward(t["x"], weights(t), cfg.k, cfg.lora_scale, 0.01, aux_mode)
+    bf = bruteforce.forward(t["x"].tolist(), {n: t[n].tolist() for n in WNAMES}, cfg.k,
+                            cfg.lora_scale, 0.01, aux_mode)
+    np.testing.assert_allclose(out["y"], np.array(bf["y"]), rtol=1e-11, atol=1e-13)
+    assert out["topk_idx"].tolist() == bf["topk_idx"]
+    np.testing.assert_allclose(out["topk_w"], np.array(bf["topk_w"]), rtol=1e-12)
+    np.testing.assert_allclose(out["probs"], np.array(bf["probs"]), rtol=1e-12)
+    assert out["counts"].tolist() == bf["counts"]
+    assert math.isclose(out["aux_loss"], bf["aux_loss"], rel_tol=1e-12)
+
+
+def test_tie_break_lowest_index():
+    # two identical router rows => identical logits; the lower expert index must come first
+    cfg = small_cfg(N=4, k=2)
+    t = inputs(cfg)
+    t["W_router"][2] = t["W_router"][0]
+    t["W_router"][1] = t["W_router"][0] - 1e3 * np.abs(t["W_router"][0])  # pushed far away
+    z, p, idx, w = orc.router(t["x"], t["W_router"], 2)
+    both = np.isin(idx, [0, 2]).all(axis=1)
+    assert both.any()
+    assert (idx[both][:, 0] == 0).all() and (idx[both][:, 1] == 2).all()
+
+
+# P5: closed forms and a hand-built example of Eq. 8-9.
+def test_aux_hand_built_golden():
+    g = read_golden("aux_loss_handbuilt.txt")
+    probs = np.array([[.50, .30, .10, .10], [.45, .35, .10, .10],
+                      [.10, .60, .20, .10], [.20, .10, .30, .40]])
+    idx = np.array([[0, 1], [0, 1], [1, 2], [3, 2]])
+    for mode in ("top1", "topk"):
+        loss, F, P = orc.aux_loss(probs, idx, 4, 0.01, mode)
+        assert math.isclose(loss, g[(mode,)], rel_tol=1e-12)
+        assert math.isclose(F.sum(), 1.0, rel_tol=1e-14)
+        assert math.isclose(P.sum(), 1.0, rel_tol=1e-14)
+
+
+@pytest.mark.parametrize("N", [2, 4, 8, 16])
+def test_aux_closed_forms(N):
+    a, T = 0.01, 4 * N
+    # (i) uniform probabilities, balanced first choices: L = a for every N ("multiplied by N
+    # to keep the loss constant as the number of experts varies").
+    probs = np.full((T, N), 1.0 / N)
+    idx = np.stack([np.arange(T) % N, (np.arange(T) + 1) % N], axis=1)
+    assert math.isclose(orc.aux_loss(probs, idx, N, a, "top1")[0], a, rel_tol=1e-12)
+    assert math.isclose(orc.aux_loss(probs, idx, N, a, "topk")[0], a, rel_tol=1e-12)
+    # (ii) every token's first choice is expert 0 with probability q: L = a N q.
+    q = 0.7
+    probs = np.full((T, N), (1 - q) / (N - 1))
+    probs[:, 0] = q
+    idx0 = np.stack([np.zeros(T, int), np.ones(T, int)], axis=1)
+    assert math.isclose(orc.aux_loss(probs, idx0, N, a, "top1")[0], a * N * q, rel_tol=1e-12)
+    # (iii) balanced first choices, arbitrary probabilities: L = a N (1/N) sum P = a.
+    rng = np.random.default_rng(N)
+    probs = rng.random((T, N))
+    probs /= probs.sum(axis=1, keepdims=True)
+    assert math.isclose(orc.aux_loss(probs, idx, N, a, "top1")[0], a, rel_tol=1e-12)
+
+
+# P6: central finite differences of  <y, dy> + d_aux L_aux  in float64.
+def fd_loss(t, cfg, d_aux, mode):
+    out = orc.forward(t["x"], weights(t), cfg.k, cfg.lora_scale, 0.05, mode)
+    return float((out["y"] * t["dy"]).sum() + d_aux * out["aux_loss"]), out
+
+
+@pytest.mark.parametrize("mode,k", [("top1", 2), ("topk", 3), ("top1", 1)])
+def test_backward_finite_differences(mode, k):
+    cfg = small_cfg(T=10, d=8, d_ff=12, N=5, k=k, r=3, alpha=6.0)
+    t = inputs(cfg, wr_std=20.0)
+    d_aux = 1.7
+    base, out0 = fd_loss(t, cfg, d_aux, mode)
+    zs = np.sort(out0["logits"], axis=1)[:, ::-1]
+    gaps = np.abs(np.diff(zs, axis=1)).min()
+    assert gaps > 1e-3, "test inputs must sit away from routing ties"
+    grads = orc.backward(t["x"], weights(t), cfg.k, cfg.lora_scale, t["dy"], d_aux, 0.05, mode)
+    h = 1e-6
+    checked = 0
+    for name, gname in [("x", "dx"), ("A_gate", "dA_gate"), ("B_gate", "dB_gate"),
+                        ("A_up", "dA_up"), ("B_up", "dB_up"), ("A_down", "dA_down"),
+                        ("B_down", "dB_down"), ("W_router", "dW_router")]:
+        arr = t[name]
+        g = grads[gname]
+        assert g.shape == arr.shape
+        flat = arr.reshape(-1)
+        num = np.empty_like(flat)
+        for i in range(flat.size):
+            keep = flat[i]
+            flat[i] = keep + h
+            lp, _ = fd_loss(t, cfg, d_aux, mode)
+            flat[i] = keep - h
+            lm, _ = fd_loss(t, cfg, d_aux, mode)
+            flat[i] = keep
+            num[i] = (lp - lm) / (2 * h)
+        scale = max(np.abs(num).max(), 1e-8)
+        err = np.abs(num - g.reshape(-1)).max() / scale
+        assert err < 2e-6, (name, err)
+        checked += flat.size
+    assert checked > 500
+
+
+# P6b: autograd of the independent torch formulation (merged weights, torch.topk).
+def test_backward_against_autograd():
+    cfg = small_cfg(T=32, d=12, d_ff=18, N=6, k=2, r=4)
+    t = inputs(cfg, wr_std=15.0)
+    s, a, d_aux = cfg.lora_scale, 0.03, 0.9
+    tt = {n: torch.tensor(t[n], dtype=torch.float64, requires_grad=(n not in
+          ("W_gate", "W_up", "W_down", "dy"))) for n in list(WNAMES) + ["x", "dy"]}
+    lin = torch.nn.functional.linear
+    x = tt["x"]
+    z = lin(x, tt["W_router"])
+    p = torch.softmax(z, dim=1)
+    _, idx = torch.topk(z, cfg.k, dim=1)
+    kept = torch.gather(p, 1, idx)
+    w = kept / kept.sum(dim=1, keepdim=True)
+    y = torch.zeros_like(x)
+    for e in range(cfg.N):
+        Wg = tt["W_gate"] + s * tt["B_gate"][e] @ tt["A_gate"][e]
+        Wu = tt["W_up"] + s * tt["B_up"][e] @ tt["A_up"][e]
+        Wd = tt["W_down"] + s * tt["B_down"][e] @ tt["A_down"][e]
+        oe = lin(torch.nn.functional.silu(lin(x, Wg)) * lin(x, Wu), Wd)
+        for j in range(cfg.k):
+            y = y + (idx[:, j] == e).to(x.dtype)[:, None] * w[:, j:j + 1] * oe
+    F = torch.bincount(idx[:, 0], minlength=cfg.N).to(torch.float64) / cfg.T
+    aux = a * cfg.N * (F * p.mean(dim=0)).sum()
+    loss = (y * tt["dy"]).sum() + d_aux * aux
+    loss.backward()
+    g = orc.backward(t["x"], weights(t), cfg.k, s, t["dy"], d_aux, a, "top1")
+    for name in ("x", "A_gate", "B_gate", "A_up", "B_up", "A_down", "B_down", "W_router"):
+        ref = tt[name].grad.numpy()
+        got = g["d" + name]
+        np.testing.assert_allclose(got, ref, rtol=1e-9, atol=1e-12 * max(1.0, np.abs(ref).max()))
+
+
+# P7: identities that hold for any inputs.
+def test_identities():
+    cfg = small_cfg(T=48, N=6, k=2)
+    t = inputs(cfg)
+    W = weights(t)
+    s = cfg.lora_scale
+    g = orc.backward(t["x"], W, cfg.k, s, t["dy"], 1.0, 0.01, "top1")
+    fw = g["forward"]
+    assert fw["counts"].sum() == cfg.k * cfg.T
+    np.testing.assert_allclose(g["dz"].sum(axis=1), 0.0, atol=1e-12)
+    # token-permutation equivariance of y, dx; invariance of the summed grads
+    perm = np.random.default_rng(0).permutation(cfg.T)
+    gp = orc.backward(t["x"][perm], W, cfg.k, s, t["dy"][perm], 1.0, 0.01, "top1")
+    np.testing.assert_allclose(gp["forward"]["y"], fw["y"][perm], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(gp["dx"], g["dx"][perm], rtol=1e-11, atol=1e-12)
+    for n in ("dA_gate", "dB_down", "dW_router"):
+        np.testing.assert_allclose(gp[n], g[n], rtol=1e-9, atol=1e-11)
+    # gradients are linear in (dy, d_aux)
+    g2 = orc.backward(t["x"], W, cfg.k, s, 2.0 * t["dy"], 2.0, 0.01, "top1")
+    for n in ("dx", "dA_up", "dB_gate", "dA_down", "dW_router"):
+        np.testing.assert_allclose(g2[n], 2.0 * g[n], rtol=1e-11, atol=1e-12)
+    # expert relabelling: swapping experts 1 and 3 everywhere leaves y unchanged
+    sw = np.arange(cfg.N)
+    sw[[1, 3]] = sw[[3, 1]]
+    W2 = {n: (v[sw] if n.startswith(("A_", "B_")) or n == "W_router" else v) for n, v in W.items()}
+    y2 = orc.forward(t["x"], W2, cfg.k, s)["y"]
+    np.testing.assert_allclose(y2, fw["y"], rtol=1e-12, atol=1e-13)
+
+
+def test_unused_expert_gets_zero_grads():
+    cfg = small_cfg(T=20, N=5, k=2)
+    t = inputs(cfg)
+    t["x"] = np.abs(t["x"]) + 0.01     # positive inputs, so that ...
+    t["W_router"][4] = -100.0          # ... expert 4's logit is hugely negative for every token
+    g = orc.backward(t["x"], weights(t), cfg.k, cfg.lora_scale, t["dy"], 0.0)
+    assert g["forward"]["counts"][4] == 0
+    for n in ("dA_gate", "dB_gate", "dA_up", "dB_up", "dA_down", "dB_down"):
+        assert (g[n][4] == 0.0).all()
+
+
+# P8/P9: structure figures printed in the paper.
+def test_paper_structure_figures():
+    g = read_golden("paper_structure.txt")
+    k = 2
+    assert math.isclose((2 + k) / (3 * k), g[("shared_over_vanilla_k2",)], rel_tol=1e-9)
+    # LLaMA-2 7B: 32 layers, d = 4096, d_ff = 11008, vocabulary 32000; LoRA on gate/up/down of
+    # each of 8 experts, one N x d router per layer, plain LoRA on q, k, v, o.
+    L, d, f, V, N = 32, 4096, 11008, 32000, 8
+    base = L * (4 * d * d + 3 * d * f + 2 * d) + 2 * V * d + d
+    for r in (2, 4, 8, 16, 32):
+        per_layer = N * 3 * r * (d + f) + N * d + 4 * r * 2 * d
+        pct = 100.0 * L * per_layer / (base + L * per_layer)
+        # loose (4 %) because the paper does not say what its denominator counts; dropping the
+        # LoRA of any one of the three FFN matrices would move the share by about 30 %.
+        printed = g[("params_pct_rank", str(r))]
+        assert abs(pct - printed) < 0.04 * printed, (r, pct)
+
+
+def test_synth_is_deterministic_and_in_dtype():
+    cfg = synth.scaled(synth.CONFIGS["llama2_7b"], T=32, d=64, d_ff=96)
+    a = synth.make_inputs(cfg)
+    b = synth.make_inputs(cfg, only=("W_down", "x"))
+    assert np.array_equal(a["W_down"], b["W_down"]) and np.array_equal(a["x"], b["x"])
+    for n, v in a.items():
+        assert np.array_equal(synth.round_to_bf16(v), v), n
+    assert abs(a["x"].std() - 1.0) < 0.05
+    assert abs(a["W_gate"].std() - 0.02) < 0.002
+    assert np.abs(a["A_gate"]).max() <= 1 / math.sqrt(cfg.d) + 1e-3
