@@ -1,0 +1,142 @@
+/*
+ * mixlora.h - C ABI of the MI355X (gfx950) MixLoRA feed-forward block.
+ *
+ * The block replaces the dense FFN of a LLaMA-style layer (Eq. 5) by N LoRA experts that
+ * all sit on one frozen SwiGLU FFN (Eq. 6, Section 3.3) behind a top-k softmax router
+ * (Eq. 7, renormalised as in Algorithm 1) with the auxiliary load-balance loss of Eq. 8-9.
+ * The frozen gate/up projections are computed once per token and shared by the experts
+ * (Section 3.3, "Reducing the Computational Complexity (I)"; Algorithm 1).
+ *
+ * Notation: T tokens, d model width, f = d_ff, N experts, k kept experts per token,
+ * r LoRA rank, s = lora_scale = alpha / r.  A "pair" is (token t, slot j < k).
+ *
+ * General rules for every entry point
+ *   - Every data pointer is a DEVICE pointer (HIP, one GPU), row-major, 16-byte aligned,
+ *     owned by the caller and not retained after the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued on it; no entry point allocates, frees or synchronises.
+ *   - The return value is a mixlora_status.  Argument errors are detected on the host before
+ *     any HIP call is made and leave all buffers untouched.  No C++ exception crosses the ABI.
+ *   - Storage dtype (dims.dtype) applies to x, y, dy, dx and all weight matrices; routing
+ *     weights, probabilities, losses and all returned LoRA/router gradients are float32.
+ *     All accumulation is float32.
+ *   - Limits: 1 <= k <= N <= 64; N*r <= 512; r % 8 == 0; d % 8 == 0; d_ff % 8 == 0; T >= 1;
+ *     T*k < 2^24.  Anything else returns MIXLORA_E_SHAPE.
+ */
+#ifndef MIXLORA_H
+#define MIXLORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define MIXLORA_API __attribute__((visibility("default")))
+#else
+#define MIXLORA_API
+#endif
+
+typedef enum {
+  MIXLORA_OK = 0,
+  MIXLORA_E_NULL = -1,      /* a required pointer is NULL                              */
+  MIXLORA_E_SHAPE = -2,     /* a dimension is outside the limits above                 */
+  MIXLORA_E_DTYPE = -3,     /* unknown dtype or aux_mode value                         */
+  MIXLORA_E_ALIGN = -4,     /* a pointer is not 16-byte aligned                        */
+  MIXLORA_E_WORKSPACE = -5, /* workspace_bytes < mixlora_workspace_bytes(...)          */
+  MIXLORA_E_HIP = -6        /* a kernel launch failed (hipGetLastError after enqueue)  */
+} mixlora_status;
+
+typedef enum { MIXLORA_F32 = 0, MIXLORA_BF16 = 1 } mixlora_dtype;
+
+/* How F_i of Eq. 9 counts "tokens dispatched to expert i" when k > 1:
+ * TOP1 = as printed (the arg-max expert only); TOPK = all k kept experts, divided by k. */
+typedef enum { MIXLORA_AUX_TOP1 = 0, MIXLORA_AUX_TOPK = 1 } mixlora_aux_mode;
+
+typedef struct {
+  int32_t T, d, d_ff, N, k, r;
+  float lora_scale; /* s = alpha / r (hyper-parameter table: alpha 32, r 16)           */
+  float aux_coeff;  /* a of Eq. 8 (paper: 1e-2)                                        */
+  int32_t aux_mode; /* mixlora_aux_mode                                                */
+  int32_t dtype;    /* mixlora_dtype                                                   */
+} mixlora_dims;
+
+/* Weights, all in the storage dtype.  Frozen: W_gate, W_up, W_down (W1, W3, W2 of
+ * Section 3.3).  Trainable: the LoRA banks (Eq. 1: W' = W + s B A) and the router (Eq. 7). */
+typedef struct {
+  const void *W_gate;   /* [f, d]                                                      */
+  const void *W_up;     /* [f, d]                                                      */
+  const void *W_down;   /* [d, f]                                                      */
+  const void *A_gate;   /* [N, r, d]                                                   */
+  const void *B_gate;   /* [N, f, r]                                                   */
+  const void *A_up;     /* [N, r, d]                                                   */
+  const void *B_up;     /* [N, f, r]                                                   */
+  const void *A_down;   /* [N, r, f]                                                   */
+  const void *B_down;   /* [N, d, r]                                                   */
+  const void *W_router; /* [N, d], no bias                                             */
+  /* Optional transposed copies of the frozen matrices, used by the backward pass only
+   * (W_gate_T, W_up_T: [d, f]; W_down_T: [f, d]); make them once with
+   * mixlora_transpose.  Where one is NULL, backward transposes that matrix into its
+   * workspace on every call.                                                          */
+  const void *W_gate_T;
+  const void *W_up_T;
+  const void *W_down_T;
+} mixlora_weights;
+
+/* Gradients of the trainable tensors: float32, same shapes as the tensors, OVERWRITTEN
+ * (not accumulated).  Experts that received no token get exact zeros.                  */
+typedef struct {
+  float *dA_gate, *dB_gate, *dA_up, *dB_up, *dA_down, *dB_down, *dW_router;
+} mixlora_grads;
+
+/* Bytes of workspace the forward (for_backward = 0) or forward+backward (1) needs for
+ * these dims; 0 if the dims are invalid.  Host-only, no HIP call. */
+MIXLORA_API size_t mixlora_workspace_bytes(const mixlora_dims *dims, int for_backward);
+
+/* Forward of the block (Eq. 6 with SwiGLU experts, Eq. 7, Algorithm 1 lines 4-15, Eq. 8-9):
+ *   y[t] = sum_j topk_w[t,j] * E_{topk_idx[t,j]}(x[t]),  without the residual add of Eq. 5.
+ * in : x [T,d] (storage dtype)
+ * out: y [T,d] (storage dtype); topk_idx [T,k] int32, slots by descending logit, equal
+ *      logits to the lower expert index; topk_w [T,k] float32 (sums to 1 per token);
+ *      expert_counts [N] int32 = number of pairs routed to each expert;
+ *      aux_loss [1] float32 (device) = Eq. 8 with dims.aux_coeff / dims.aux_mode.
+ * workspace: scratch, and the activations the backward needs; pass the same buffer,
+ *      untouched, to mixlora_ffn_backward.  Calls sharing a workspace must not overlap. */
+MIXLORA_API int mixlora_ffn_forward(const mixlora_dims *dims, const mixlora_weights *w, const void *x,
+                        void *y, int32_t *topk_idx, float *topk_w, int32_t *expert_counts,
+                        float *aux_loss, void *workspace, size_t workspace_bytes,
+                        void *stream);
+
+/* Backward of the same block for the loss  <y, dy> + d_aux * aux_loss, base matrices frozen
+ * (derived from Algorithm 1 lines 4-15; the paper leaves it to autograd).
+ * in : x, dy [T,d]; workspace as left by mixlora_ffn_forward for the same dims/weights/x
+ *      (its size must be the for_backward = 1 size).
+ * out: dx [T,d] (storage dtype, includes the paths through the router and the auxiliary
+ *      loss); grads (all seven required).                                               */
+MIXLORA_API int mixlora_ffn_backward(const mixlora_dims *dims, const mixlora_weights *w, const void *x,
+                         const void *dy, float d_aux, void *workspace,
+                         size_t workspace_bytes, void *dx, const mixlora_grads *grads,
+                         void *stream);
+
+/* Auxiliary load-balance loss alone (Eq. 8-9) from router probabilities and kept experts.
+ * in : probs [T,N] float32 (full softmax), topk_idx [T,k] int32.
+ * out: loss [1]; F [N], P [N] (each may be NULL); dprobs [T,N] = d loss / d probs (may be
+ *      NULL; F is piecewise constant, so only P carries gradient).  All float32, device. */
+MIXLORA_API int mixlora_aux_loss(const float *probs, const int32_t *topk_idx, int32_t T, int32_t N,
+                     int32_t k, float coeff, int32_t mode, float *loss, float *F, float *P,
+                     float *dprobs, void *stream);
+
+/* out[cols, rows] = in[rows, cols]^T in the given dtype; for preparing the optional
+ * transposed frozen copies.  rows, cols >= 1. */
+MIXLORA_API int mixlora_transpose(const void *in, void *out, int32_t rows, int32_t cols, int32_t dtype,
+                      void *stream);
+
+/* Library version as major*10000 + minor*100 + patch.  Host-only. */
+MIXLORA_API int mixlora_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MIXLORA_H */

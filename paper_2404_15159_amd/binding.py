@@ -1,0 +1,155 @@
+"""Thin ctypes binding over libmixlora.so: argument marshalling only.
+
+Every step of the block runs inside the library's HIP kernels; PyTorch is used here for
+device memory (tensors' data_ptr) and the current stream's handle.  The functions carry the
+same names as the C entry points (see include/mixlora.h for the full contract).
+There is no CPU fallback: load() raises if the library has not been built.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libmixlora.so")
+
+F32, BF16 = 0, 1
+AUX_TOP1, AUX_TOPK = 0, 1
+STATUS = {0: "OK", -1: "E_NULL", -2: "E_SHAPE", -3: "E_DTYPE", -4: "E_ALIGN", -5: "E_WORKSPACE",
+          -6: "E_HIP"}
+
+EXPORTS = ("mixlora_workspace_bytes", "mixlora_ffn_forward", "mixlora_ffn_backward",
+           "mixlora_aux_loss", "mixlora_transpose", "mixlora_version")
+
+
+class Dims(C.Structure):
+    _fields_ = [("T", C.c_int32), ("d", C.c_int32), ("d_ff", C.c_int32), ("N", C.c_int32),
+                ("k", C.c_int32), ("r", C.c_int32), ("lora_scale", C.c_float),
+                ("aux_coeff", C.c_float), ("aux_mode", C.c_int32), ("dtype", C.c_int32)]
+
+
+WEIGHT_FIELDS = ("W_gate", "W_up", "W_down", "A_gate", "B_gate", "A_up", "B_up", "A_down",
+                 "B_down", "W_router", "W_gate_T", "W_up_T", "W_down_T")
+GRAD_FIELDS = ("dA_gate", "dB_gate", "dA_up", "dB_up", "dA_down", "dB_down", "dW_router")
+
+
+class Weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in WEIGHT_FIELDS]
+
+
+class Grads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in GRAD_FIELDS]
+
+
+class MixLoraError(RuntimeError):
+    def __init__(self, fn: str, code: int):
+        super().__init__(f"{fn} returned {code} ({STATUS.get(code, '?')})")
+        self.code = code
+
+
+_lib = None
+
+
+def load():
+    """Load the HIP library (once).  Raises if it is missing: there is no fallback path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} not built; run `python -m paper_2404_15159_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, f32, sz = C.c_void_p, C.c_int32, C.c_float, C.c_size_t
+    lib.mixlora_workspace_bytes.restype = sz
+    lib.mixlora_workspace_bytes.argtypes = [C.POINTER(Dims), C.c_int]
+    lib.mixlora_ffn_forward.restype = C.c_int
+    lib.mixlora_ffn_forward.argtypes = [C.POINTER(Dims), C.POINTER(Weights), vp, vp, vp, vp, vp,
+                                        vp, vp, sz, vp]
+    lib.mixlora_ffn_backward.restype = C.c_int
+    lib.mixlora_ffn_backward.argtypes = [C.POINTER(Dims), C.POINTER(Weights), vp, vp, f32, vp, sz,
+                                         vp, C.POINTER(Grads), vp]
+    lib.mixlora_aux_loss.restype = C.c_int
+    lib.mixlora_aux_loss.argtypes = [vp, vp, i32, i32, i32, f32, i32, vp, vp, vp, vp, vp]
+    lib.mixlora_transpose.restype = C.c_int
+    lib.mixlora_transpose.argtypes = [vp, vp, i32, i32, i32, vp]
+    lib.mixlora_version.restype = C.c_int
+    lib.mixlora_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def make_dims(T, d, d_ff, N, k, r, lora_scale, aux_coeff=0.01, aux_mode=AUX_TOP1, dtype=BF16):
+    return Dims(T, d, d_ff, N, k, r, lora_scale, aux_coeff, aux_mode, dtype)
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def make_weights(tensors: Dict[str, object]) -> Weights:
+    """tensors: name -> device tensor (or raw pointer); the three *_T entries are optional."""
+    w = Weights()
+    for n in WEIGHT_FIELDS:
+        setattr(w, n, _ptr(tensors.get(n)))
+    return w
+
+
+def make_grads(tensors: Dict[str, object]) -> Grads:
+    g = Grads()
+    for n in GRAD_FIELDS:
+        setattr(g, n, _ptr(tensors.get(n)))
+    return g
+
+
+def mixlora_workspace_bytes(dims: Dims, for_backward: bool) -> int:
+    return int(load().mixlora_workspace_bytes(C.byref(dims), int(bool(for_backward))))
+
+
+def mixlora_ffn_forward(dims: Dims, weights: Weights, x, y, topk_idx, topk_w, expert_counts,
+                        aux_loss, workspace, workspace_bytes: int, stream=None) -> None:
+    rc = load().mixlora_ffn_forward(C.byref(dims), C.byref(weights), _ptr(x), _ptr(y),
+                                    _ptr(topk_idx), _ptr(topk_w), _ptr(expert_counts),
+                                    _ptr(aux_loss), _ptr(workspace), workspace_bytes,
+                                    _stream(stream))
+    if rc != 0:
+        raise MixLoraError("mixlora_ffn_forward", rc)
+
+
+def mixlora_ffn_backward(dims: Dims, weights: Weights, x, dy, d_aux: float, workspace,
+                         workspace_bytes: int, dx, grads: Grads, stream=None) -> None:
+    rc = load().mixlora_ffn_backward(C.byref(dims), C.byref(weights), _ptr(x), _ptr(dy),
+                                     float(d_aux), _ptr(workspace), workspace_bytes, _ptr(dx),
+                                     C.byref(grads), _stream(stream))
+    if rc != 0:
+        raise MixLoraError("mixlora_ffn_backward", rc)
+
+
+def mixlora_aux_loss(probs, topk_idx, T: int, N: int, k: int, coeff: float, mode: int, loss,
+                     F=None, P=None, dprobs=None, stream=None) -> None:
+    rc = load().mixlora_aux_loss(_ptr(probs), _ptr(topk_idx), T, N, k, float(coeff), mode,
+                                 _ptr(loss), _ptr(F), _ptr(P), _ptr(dprobs), _stream(stream))
+    if rc != 0:
+        raise MixLoraError("mixlora_aux_loss", rc)
+
+
+def mixlora_transpose(src, dst, rows: int, cols: int, dtype: int, stream=None) -> None:
+    rc = load().mixlora_transpose(_ptr(src), _ptr(dst), rows, cols, dtype, _stream(stream))
+    if rc != 0:
+        raise MixLoraError("mixlora_transpose", rc)
+
+
+def mixlora_version() -> int:
+    return int(load().mixlora_version())

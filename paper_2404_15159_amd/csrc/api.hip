@@ -1,0 +1,379 @@
+// C ABI of libmixlora: argument validation (host only, before any HIP call), workspace
+// carving and the stream-ordered kernel sequences of the forward and backward passes.
+//
+// Schedule (Section 3.3 "Reducing the Computational Complexity (I)", Algorithm 1): the frozen
+// gate/up projections run once over all T tokens and are shared by the experts; LoRA deltas,
+// SiLU * up and everything per (token, expert) pair run on expert-grouped rows.  Because the
+// frozen down projection is linear and shared, it is applied once per token to the
+// routing-weighted sum of the pair activations, with the per-expert low-rank part entering as a
+// K-extension of the same GEMM; its transpose is used the same way in the backward.
+#include "common.h"
+
+using namespace mixlora;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+inline int up8(int v) { return (v + 7) / 8 * 8; }
+
+struct Layout {
+  // saved by forward
+  size_t probs, idx, w, counts, first_counts, offs, row_of_pair, pair_of_row, F, P, tok_offs;
+  size_t G, U, Pg_all, Pu_all, a_grp, Q_all;
+  // forward scratch
+  size_t a_comb, Qw, Bd_cat;
+  size_t fwd_end;
+  // backward scratch
+  size_t WdT, WgT, WuT, H, Bd_T, VB_all, dg_grp, du_grp, dgsum, dusum, dw_part, dw, Bg_T, Bu_T,
+      TG_all, TU_all, small[6], S, Bx, dz, partials;
+  size_t partial_floats;
+  size_t bwd_end;
+  int Kx, nct;
+};
+
+Layout make_layout(const mixlora_dims &D) {
+  Layout L{};
+  const size_t T = D.T, d = D.d, f = D.d_ff, N = D.N, k = D.k, r = D.r;
+  const size_t R = N * r, kT = k * T;
+  const size_t E = D.dtype == MIXLORA_BF16 ? 2 : 4;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = up(o + bytes); return at; };
+  L.probs = take(T * N * 4);
+  L.idx = take(kT * 4);
+  L.w = take(kT * 4);
+  L.counts = take(N * 4);
+  L.first_counts = take(N * 4);
+  L.offs = take((N + 1) * 4);
+  L.row_of_pair = take(kT * 4);
+  L.pair_of_row = take(kT * 4);
+  L.F = take(N * 4);
+  L.P = take(N * 4);
+  L.tok_offs = take(2 * 4);
+  L.G = take(T * f * E);
+  L.U = take(T * f * E);
+  L.Pg_all = take(T * R * 4);
+  L.Pu_all = take(T * R * 4);
+  L.a_grp = take(kT * f * E);
+  L.Q_all = take(kT * R * 4);
+  L.a_comb = take(T * f * E);
+  L.Qw = take(T * R * E);
+  L.Bd_cat = take(d * R * E);
+  L.fwd_end = o;
+  L.Kx = (int)(2 * R) + up8((int)N);
+  L.nct = swiglu_col_tiles((int)f);
+  L.WdT = take(f * d * E);
+  L.WgT = take(f * d * E);
+  L.WuT = take(f * d * E);
+  L.H = take(T * f * E);
+  L.Bd_T = take(R * d * E);
+  L.VB_all = take(T * R * 4);
+  L.dg_grp = take(kT * f * E);
+  L.du_grp = take(kT * f * E);
+  L.dgsum = take(T * f * E);
+  L.dusum = take(T * f * E);
+  L.dw_part = take(kT * (size_t)L.nct * 4);
+  L.dw = take(kT * 4);
+  L.Bg_T = take(R * f * E);
+  L.Bu_T = take(R * f * E);
+  L.TG_all = take(kT * R * 4);
+  L.TU_all = take(kT * R * 4);
+  for (int i = 0; i < 6; i++) L.small[i] = take(kT * r * 4);
+  L.S = take(T * (size_t)L.Kx * E);
+  L.Bx = take(d * (size_t)L.Kx * E);
+  L.dz = take(T * N * 4);
+  size_t pf = group_outer_partial_floats((int)N, (int)r, (int)f);
+  size_t pd = group_outer_partial_floats((int)N, (int)r, (int)d);
+  size_t pr = group_outer_partial_floats(1, (int)N, (int)d);
+  L.partial_floats = pf > pd ? pf : pd;
+  if (pr > L.partial_floats) L.partial_floats = pr;
+  L.partials = take(L.partial_floats * 4);
+  L.bwd_end = o;
+  return L;
+}
+
+int check_dims(const mixlora_dims *D) {
+  if (!D) return MIXLORA_E_NULL;
+  if (D->dtype != MIXLORA_F32 && D->dtype != MIXLORA_BF16) return MIXLORA_E_DTYPE;
+  if (D->aux_mode != MIXLORA_AUX_TOP1 && D->aux_mode != MIXLORA_AUX_TOPK) return MIXLORA_E_DTYPE;
+  if (D->T < 1 || D->d < 8 || D->d_ff < 8 || D->N < 1 || D->N > 64 || D->k < 1 || D->k > D->N ||
+      D->r < 8)
+    return MIXLORA_E_SHAPE;
+  if (D->r % 8 || D->d % 8 || D->d_ff % 8 || D->r > 64) return MIXLORA_E_SHAPE;
+  if ((int64_t)D->N * D->r > 512) return MIXLORA_E_SHAPE;
+  if ((int64_t)D->T * D->k >= (1 << 24)) return MIXLORA_E_SHAPE;
+  if ((int64_t)D->T * D->k * D->d_ff >= ((int64_t)1 << 40)) return MIXLORA_E_SHAPE;
+  return MIXLORA_OK;
+}
+
+inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
+
+int check_weights(const mixlora_weights *w) {
+  if (!w) return MIXLORA_E_NULL;
+  const void *req[] = {w->W_gate, w->W_up,   w->W_down, w->A_gate, w->B_gate,
+                       w->A_up,   w->B_up,   w->A_down, w->B_down, w->W_router};
+  for (const void *p : req) {
+    if (!p) return MIXLORA_E_NULL;
+    if (misaligned(p)) return MIXLORA_E_ALIGN;
+  }
+  const void *opt[] = {w->W_gate_T, w->W_up_T, w->W_down_T};
+  for (const void *p : opt)
+    if (p && misaligned(p)) return MIXLORA_E_ALIGN;
+  return MIXLORA_OK;
+}
+
+__global__ void set_pair_kernel(int32_t *p, int a, int b) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) { p[0] = a; p[1] = b; }
+}
+
+#define HIP_TRY(expr)                                   \
+  do {                                                  \
+    hipError_t e_ = (expr);                             \
+    if (e_ != hipSuccess) return MIXLORA_E_HIP;         \
+  } while (0)
+
+GemmProblem problem(int M, int N, void *C, int64_t ldc, int c_f32) {
+  GemmProblem p{};
+  p.M = M;
+  p.N = N;
+  p.C = C;
+  p.ldc = ldc;
+  p.c_f32 = c_f32;
+  p.nseg = 0;
+  return p;
+}
+void add_seg(GemmProblem &p, const void *A, int64_t lda, const void *B, int64_t ldb, int K) {
+  GemmSeg &s = p.seg[p.nseg++];
+  s.A = A;
+  s.lda = lda;
+  s.B = B;
+  s.ldb = ldb;
+  s.K = K;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mixlora_version(void) { return 100; }
+
+size_t mixlora_workspace_bytes(const mixlora_dims *dims, int for_backward) {
+  if (check_dims(dims) != MIXLORA_OK) return 0;
+  const Layout L = make_layout(*dims);
+  return for_backward ? L.bwd_end : L.fwd_end;
+}
+
+int mixlora_ffn_forward(const mixlora_dims *dims, const mixlora_weights *w, const void *x,
+                        void *y, int32_t *topk_idx, float *topk_w, int32_t *expert_counts,
+                        float *aux_loss, void *workspace, size_t workspace_bytes,
+                        void *stream) {
+  int rc = check_dims(dims);
+  if (rc) return rc;
+  rc = check_weights(w);
+  if (rc) return rc;
+  if (!x || !y || !topk_idx || !topk_w || !expert_counts || !aux_loss || !workspace)
+    return MIXLORA_E_NULL;
+  if (misaligned(x) || misaligned(y) || misaligned(workspace)) return MIXLORA_E_ALIGN;
+  const mixlora_dims &D = *dims;
+  const Layout L = make_layout(D);
+  if (workspace_bytes < L.fwd_end) return MIXLORA_E_WORKSPACE;
+
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  char *ws = reinterpret_cast<char *>(workspace);
+  const int T = D.T, d = D.d, f = D.d_ff, N = D.N, k = D.k, r = D.r, R = N * r, kT = k * T;
+  const int dt = D.dtype;
+  float *probs = (float *)(ws + L.probs);
+  int32_t *idx = (int32_t *)(ws + L.idx);
+  float *wts = (float *)(ws + L.w);
+  int32_t *offs = (int32_t *)(ws + L.offs);
+  int32_t *row_of_pair = (int32_t *)(ws + L.row_of_pair);
+  int32_t *pair_of_row = (int32_t *)(ws + L.pair_of_row);
+
+  // Eq. 7 + Norm (Algorithm 1 lines 4-5)
+  HIP_TRY(launch_router(dt, x, w->W_router, T, d, N, k, probs, topk_idx, topk_w, idx, wts, st));
+  HIP_TRY(launch_group_pairs(idx, T, N, k, (int32_t *)(ws + L.counts), expert_counts,
+                             (int32_t *)(ws + L.first_counts), offs, row_of_pair, pair_of_row, st));
+  // Eq. 8-9
+  HIP_TRY(launch_aux_loss(probs, idx, T, N, k, D.aux_coeff, D.aux_mode, aux_loss,
+                          (float *)(ws + L.F), (float *)(ws + L.P), nullptr, st));
+  hipLaunchKernelGGL(set_pair_kernel, dim3(1), dim3(64), 0, st, (int32_t *)(ws + L.tok_offs), 0, T);
+  HIP_TRY(hipGetLastError());
+
+  // shared frozen projections, once for all tokens (Algorithm 1 lines 7-8)
+  {
+    GemmProblem p[2] = {problem(T, f, ws + L.G, f, 0), problem(T, f, ws + L.U, f, 0)};
+    add_seg(p[0], x, d, w->W_gate, d, d);
+    add_seg(p[1], x, d, w->W_up, d, d);
+    HIP_TRY(launch_gemm(dt, p, 2, st));
+  }
+  // LoRA A projections of every expert (rank-r, N*r output columns per bank)
+  {
+    GemmProblem p[2] = {problem(T, R, ws + L.Pg_all, R, 1), problem(T, R, ws + L.Pu_all, R, 1)};
+    add_seg(p[0], x, d, w->A_gate, d, d);
+    add_seg(p[1], x, d, w->A_up, d, d);
+    HIP_TRY(launch_gemm(dt, p, 2, st));
+  }
+  PairCtx pc{offs, pair_of_row, row_of_pair, wts, idx, T, N, k, r};
+  // Algorithm 1 lines 11-13 on the routed pairs, expert-grouped rows
+  HIP_TRY(launch_swiglu_fwd(dt, pc, f, D.lora_scale, ws + L.G, ws + L.U, (float *)(ws + L.Pg_all),
+                            (float *)(ws + L.Pu_all), w->B_gate, w->B_up, ws + L.a_grp, st));
+  // A_down of every expert on the grouped activations
+  {
+    GemmProblem p = problem(kT, R, ws + L.Q_all, R, 1);
+    add_seg(p, ws + L.a_grp, f, w->A_down, f, f);
+    HIP_TRY(launch_gemm(dt, &p, 1, st));
+  }
+  // weighted combine of the pair activations (Algorithm 1 line 15, moved in front of the linear
+  // frozen down projection) and the block-sparse low-rank operand
+  HIP_TRY(launch_pair_combine(dt, pc, f, ws + L.a_grp, ws + L.a_comb, 1, st));
+  HIP_TRY(launch_scatter_blocks(dt, pc, (float *)(ws + L.Q_all), R, 1, 1, ws + L.Qw, R, 0, st));
+  HIP_TRY(launch_pack_bank_cat(dt, w->B_down, N, d, r, D.lora_scale, ws + L.Bd_cat, R, 0, st));
+  // down projection (Algorithm 1 line 14): y = a_comb W_down^T + Qw (s B_down)^T
+  {
+    GemmProblem p = problem(T, d, y, d, 0);
+    add_seg(p, ws + L.a_comb, f, w->W_down, f, f);
+    add_seg(p, ws + L.Qw, R, ws + L.Bd_cat, R, R);
+    HIP_TRY(launch_gemm(dt, &p, 1, st));
+  }
+  return MIXLORA_OK;
+}
+
+int mixlora_ffn_backward(const mixlora_dims *dims, const mixlora_weights *w, const void *x,
+                         const void *dy, float d_aux, void *workspace,
+                         size_t workspace_bytes, void *dx, const mixlora_grads *grads,
+                         void *stream) {
+  int rc = check_dims(dims);
+  if (rc) return rc;
+  rc = check_weights(w);
+  if (rc) return rc;
+  if (!x || !dy || !dx || !workspace || !grads) return MIXLORA_E_NULL;
+  float *gp[] = {grads->dA_gate, grads->dB_gate, grads->dA_up,    grads->dB_up,
+                 grads->dA_down, grads->dB_down, grads->dW_router};
+  for (float *p : gp) {
+    if (!p) return MIXLORA_E_NULL;
+    if (misaligned(p)) return MIXLORA_E_ALIGN;
+  }
+  if (misaligned(x) || misaligned(dy) || misaligned(dx) || misaligned(workspace))
+    return MIXLORA_E_ALIGN;
+  const mixlora_dims &D = *dims;
+  const Layout L = make_layout(D);
+  if (workspace_bytes < L.bwd_end) return MIXLORA_E_WORKSPACE;
+
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  char *ws = reinterpret_cast<char *>(workspace);
+  const int T = D.T, d = D.d, f = D.d_ff, N = D.N, k = D.k, r = D.r, R = N * r, kT = k * T;
+  const int dt = D.dtype, Kx = L.Kx;
+  const float s = D.lora_scale;
+  float *probs = (float *)(ws + L.probs);
+  int32_t *idx = (int32_t *)(ws + L.idx);
+  float *wts = (float *)(ws + L.w);
+  int32_t *offs = (int32_t *)(ws + L.offs);
+  int32_t *row_of_pair = (int32_t *)(ws + L.row_of_pair);
+  int32_t *pair_of_row = (int32_t *)(ws + L.pair_of_row);
+  PairCtx pc{offs, pair_of_row, row_of_pair, wts, idx, T, N, k, r};
+
+  const void *WdT = w->W_down_T, *WgT = w->W_gate_T, *WuT = w->W_up_T;
+  if (!WdT) { HIP_TRY(launch_transpose(dt, w->W_down, ws + L.WdT, d, f, st)); WdT = ws + L.WdT; }
+  if (!WgT) { HIP_TRY(launch_transpose(dt, w->W_gate, ws + L.WgT, f, d, st)); WgT = ws + L.WgT; }
+  if (!WuT) { HIP_TRY(launch_transpose(dt, w->W_up, ws + L.WuT, f, d, st)); WuT = ws + L.WuT; }
+
+  // H = dy W_down  (once per token: the frozen down projection is shared and linear)
+  {
+    GemmProblem p = problem(T, f, ws + L.H, f, 0);
+    add_seg(p, dy, d, WdT, d, d);
+    HIP_TRY(launch_gemm(dt, &p, 1, st));
+  }
+  // VB[t, e, :] = B_down[e]^T dy[t]
+  HIP_TRY(launch_pack_bank_T(dt, w->B_down, N, d, r, ws + L.Bd_T, st));
+  {
+    GemmProblem p = problem(T, R, ws + L.VB_all, R, 1);
+    add_seg(p, dy, d, ws + L.Bd_T, d, d);
+    HIP_TRY(launch_gemm(dt, &p, 1, st));
+  }
+  // through SiLU * up and the LoRA deltas, per pair
+  HIP_TRY(launch_swiglu_bwd(dt, pc, f, s, ws + L.G, ws + L.U, (float *)(ws + L.Pg_all),
+                            (float *)(ws + L.Pu_all), w->B_gate, w->B_up, ws + L.H,
+                            (float *)(ws + L.VB_all), w->A_down, ws + L.dg_grp, ws + L.du_grp,
+                            (float *)(ws + L.dw_part), L.nct, st));
+  HIP_TRY(launch_pair_combine(dt, pc, f, ws + L.dg_grp, ws + L.dgsum, 0, st));
+  HIP_TRY(launch_pair_combine(dt, pc, f, ws + L.du_grp, ws + L.dusum, 0, st));
+  // TG[row, e, :] = B_gate[e]^T dg[row]  (and up)
+  HIP_TRY(launch_pack_bank_T(dt, w->B_gate, N, f, r, ws + L.Bg_T, st));
+  HIP_TRY(launch_pack_bank_T(dt, w->B_up, N, f, r, ws + L.Bu_T, st));
+  {
+    GemmProblem p[2] = {problem(kT, R, ws + L.TG_all, R, 1), problem(kT, R, ws + L.TU_all, R, 1)};
+    add_seg(p[0], ws + L.dg_grp, f, ws + L.Bg_T, f, f);
+    add_seg(p[1], ws + L.du_grp, f, ws + L.Bu_T, f, f);
+    HIP_TRY(launch_gemm(dt, p, 2, st));
+  }
+  // compact per-row rank-r factors of the LoRA gradients
+  float *Pg_grp = (float *)(ws + L.small[0]), *Pu_grp = (float *)(ws + L.small[1]);
+  float *TG_grp = (float *)(ws + L.small[2]), *TU_grp = (float *)(ws + L.small[3]);
+  float *Vw_grp = (float *)(ws + L.small[4]), *wQ_grp = (float *)(ws + L.small[5]);
+  HIP_TRY(launch_gather_small(pc, (float *)(ws + L.Pg_all), 1, 0, Pg_grp, st));
+  HIP_TRY(launch_gather_small(pc, (float *)(ws + L.Pu_all), 1, 0, Pu_grp, st));
+  HIP_TRY(launch_gather_small(pc, (float *)(ws + L.TG_all), 0, 0, TG_grp, st));
+  HIP_TRY(launch_gather_small(pc, (float *)(ws + L.TU_all), 0, 0, TU_grp, st));
+  HIP_TRY(launch_gather_small(pc, (float *)(ws + L.VB_all), 1, 1, Vw_grp, st));
+  HIP_TRY(launch_gather_small(pc, (float *)(ws + L.Q_all), 0, 1, wQ_grp, st));
+  float *part = (float *)(ws + L.partials);
+  const size_t pfl = L.partial_floats;
+  // dB_gate[e] = s sum dg (x) Pg ; dA_gate[e] = s sum TG (x) x ; same for up
+  HIP_TRY(launch_group_outer(dt, offs, N, kT, nullptr, k, Pg_grp, r, ws + L.dg_grp, f, s, 0,
+                             grads->dB_gate, part, pfl, st));
+  HIP_TRY(launch_group_outer(dt, offs, N, kT, nullptr, k, Pu_grp, r, ws + L.du_grp, f, s, 0,
+                             grads->dB_up, part, pfl, st));
+  HIP_TRY(launch_group_outer(dt, offs, N, kT, pair_of_row, k, TG_grp, r, x, d, s, 1,
+                             grads->dA_gate, part, pfl, st));
+  HIP_TRY(launch_group_outer(dt, offs, N, kT, pair_of_row, k, TU_grp, r, x, d, s, 1,
+                             grads->dA_up, part, pfl, st));
+  // dA_down[e] = s sum (w B_down^T dy) (x) a ; dB_down[e] = s sum dy (x) (w A_down a)
+  HIP_TRY(launch_group_outer(dt, offs, N, kT, nullptr, k, Vw_grp, r, ws + L.a_grp, f, s, 1,
+                             grads->dA_down, part, pfl, st));
+  HIP_TRY(launch_group_outer(dt, offs, N, kT, pair_of_row, k, wQ_grp, r, dy, d, s, 0,
+                             grads->dB_down, part, pfl, st));
+  // router: dw -> dz (also written into the K-extension operand S), dW_router = dz^T x
+  HIP_TRY(launch_router_bwd(dt, pc, probs, (float *)(ws + L.dw_part), L.nct,
+                            (float *)(ws + L.VB_all), (float *)(ws + L.Q_all), (float *)(ws + L.F),
+                            s, d_aux, D.aux_coeff, (float *)(ws + L.dw), (float *)(ws + L.dz),
+                            ws + L.S, Kx, 2 * R, Kx - 2 * R, st));
+  HIP_TRY(launch_group_outer(dt, (int32_t *)(ws + L.tok_offs), 1, T, nullptr, 1,
+                             (float *)(ws + L.dz), N, x, d, 1.f, 1, grads->dW_router, part, pfl, st));
+  // dx = dgsum W_gate + dusum W_up + [TG | TU | dz] [s A_gate ; s A_up ; W_router]
+  HIP_TRY(launch_scatter_blocks(dt, pc, (float *)(ws + L.TG_all), R, 1, 0, ws + L.S, Kx, 0, st));
+  HIP_TRY(launch_scatter_blocks(dt, pc, (float *)(ws + L.TU_all), R, 1, 0, ws + L.S, Kx, R, st));
+  HIP_TRY(launch_pack_A_cat(dt, w->A_gate, N, r, d, s, ws + L.Bx, Kx, 0, st));
+  HIP_TRY(launch_pack_A_cat(dt, w->A_up, N, r, d, s, ws + L.Bx, Kx, R, st));
+  HIP_TRY(launch_pack_router_T(dt, w->W_router, N, d, ws + L.Bx, Kx, 2 * R, Kx - 2 * R, st));
+  {
+    GemmProblem p = problem(T, d, dx, d, 0);
+    add_seg(p, ws + L.dgsum, f, WgT, f, f);
+    add_seg(p, ws + L.dusum, f, WuT, f, f);
+    add_seg(p, ws + L.S, Kx, ws + L.Bx, Kx, Kx);
+    HIP_TRY(launch_gemm(dt, &p, 1, st));
+  }
+  return MIXLORA_OK;
+}
+
+int mixlora_aux_loss(const float *probs, const int32_t *topk_idx, int32_t T, int32_t N,
+                     int32_t k, float coeff, int32_t mode, float *loss, float *F, float *P,
+                     float *dprobs, void *stream) {
+  if (!probs || !topk_idx || !loss) return MIXLORA_E_NULL;
+  if (mode != MIXLORA_AUX_TOP1 && mode != MIXLORA_AUX_TOPK) return MIXLORA_E_DTYPE;
+  if (T < 1 || N < 1 || N > 64 || k < 1 || k > N || (int64_t)T * k >= (1 << 24))
+    return MIXLORA_E_SHAPE;
+  HIP_TRY(launch_aux_loss(probs, topk_idx, T, N, k, coeff, mode, loss, F, P, dprobs,
+                          reinterpret_cast<hipStream_t>(stream)));
+  return MIXLORA_OK;
+}
+
+int mixlora_transpose(const void *in, void *out, int32_t rows, int32_t cols, int32_t dtype,
+                      void *stream) {
+  if (!in || !out) return MIXLORA_E_NULL;
+  if (dtype != MIXLORA_F32 && dtype != MIXLORA_BF16) return MIXLORA_E_DTYPE;
+  if (rows < 1 || cols < 1) return MIXLORA_E_SHAPE;
+  HIP_TRY(launch_transpose(dtype, in, out, rows, cols, reinterpret_cast<hipStream_t>(stream)));
+  return MIXLORA_OK;
+}
+
+}  // extern "C"

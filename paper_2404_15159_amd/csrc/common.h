@@ -1,0 +1,145 @@
+// Internal declarations shared by the HIP translation units of libmixlora (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/mixlora.h"
+
+namespace mixlora {
+
+typedef __bf16 bf16_t;
+typedef bf16_t bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+// ---- element access in the storage dtype, arithmetic always in fp32 -------------------
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
+template <typename E> __device__ __forceinline__ E from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }
+
+template <typename E> struct Vec8;  // 8 consecutive elements
+template <> struct Vec8<bf16_t> {
+  bf16x8_t v;
+  __device__ __forceinline__ void load(const bf16_t *p) { v = *reinterpret_cast<const bf16x8_t *>(p); }
+  __device__ __forceinline__ void store(bf16_t *p) const { *reinterpret_cast<bf16x8_t *>(p) = v; }
+  __device__ __forceinline__ float get(int i) const { return (float)v[i]; }
+  __device__ __forceinline__ void set(int i, float f) { v[i] = (bf16_t)f; }
+};
+template <> struct Vec8<float> {
+  float4 a, b;
+  __device__ __forceinline__ void load(const float *p) {
+    a = *reinterpret_cast<const float4 *>(p);
+    b = *reinterpret_cast<const float4 *>(p + 4);
+  }
+  __device__ __forceinline__ void store(float *p) const {
+    *reinterpret_cast<float4 *>(p) = a;
+    *reinterpret_cast<float4 *>(p + 4) = b;
+  }
+  __device__ __forceinline__ float get(int i) const {
+    const float *q = i < 4 ? &a.x : &b.x;
+    return q[i & 3];
+  }
+  __device__ __forceinline__ void set(int i, float f) {
+    float *q = i < 4 ? &a.x : &b.x;
+    q[i & 3] = f;
+  }
+};
+
+// ---- GEMM engine:  C[M,N] = sum over segments  A_s[M,K_s] * B_s[N,K_s]^T -----------------
+// Both operands are K-contiguous ("NT").  K_s % 8 == 0, lda/ldb % 8 == 0, 16-byte aligned
+// bases.  C is written in the storage dtype or as float32.
+struct GemmSeg {
+  const void *A;
+  const void *B;
+  int64_t lda, ldb;
+  int K;
+};
+struct GemmProblem {
+  GemmSeg seg[3];
+  int nseg;
+  int M, N;
+  void *C;
+  int64_t ldc;
+  int c_f32;  // 1: C is float32 regardless of the storage dtype
+};
+// Enqueue up to two independent problems of identical M, N in one launch.
+hipError_t launch_gemm(int dtype, const GemmProblem *probs, int nprob, hipStream_t st);
+
+// ---- routing -----------------------------------------------------------------------------
+hipError_t launch_router(int dtype, const void *x, const void *W_router, int T, int d, int N,
+                         int k, float *probs, int32_t *idx_out, float *w_out, int32_t *idx_ws,
+                         float *w_ws, hipStream_t st);
+// Stable grouping of the k*T pairs by expert: counts[N], first_counts[N] (slot-0 histogram),
+// offs[N+1], row_of_pair[kT], pair_of_row[kT].  counts_out may be NULL.
+hipError_t launch_group_pairs(const int32_t *idx, int T, int N, int k, int32_t *counts,
+                              int32_t *counts_out, int32_t *first_counts, int32_t *offs,
+                              int32_t *row_of_pair, int32_t *pair_of_row, hipStream_t st);
+hipError_t launch_aux_loss(const float *probs, const int32_t *idx, int T, int N, int k,
+                           float coeff, int mode, float *loss, float *F, float *P,
+                           float *dprobs, hipStream_t st);
+
+// ---- element-wise / rank-r pieces -------------------------------------------------------
+struct PairCtx {  // device pointers describing the grouped pairs
+  const int32_t *offs;         // [N+1]
+  const int32_t *pair_of_row;  // [kT]
+  const int32_t *row_of_pair;  // [kT]
+  const float *w;              // [T,k] routing weights
+  const int32_t *idx;          // [T,k]
+  int T, N, k, r;
+};
+
+// a_grp[row,:] = SiLU(G[t] + s B_gate[e] Pg[t,e]) * (U[t] + s B_up[e] Pu[t,e]),  rows grouped
+hipError_t launch_swiglu_fwd(int dtype, const PairCtx &pc, int f, float s, const void *G,
+                             const void *U, const float *Pg_all, const float *Pu_all,
+                             const void *B_gate, const void *B_up, void *a_grp,
+                             hipStream_t st);
+// backward of the above; also the per-(row, column tile) partial sums of <H[t], a_row>
+hipError_t launch_swiglu_bwd(int dtype, const PairCtx &pc, int f, float s, const void *G,
+                             const void *U, const float *Pg_all, const float *Pu_all,
+                             const void *B_gate, const void *B_up, const void *H,
+                             const float *VB_all, const void *A_down, void *dg_grp,
+                             void *du_grp, float *dw_part, int n_col_tiles, hipStream_t st);
+int swiglu_col_tiles(int f);
+
+// out[t,:] = sum_j (weighted ? w[t,j] : 1) * in_grp[row_of_pair[t,j], :]
+hipError_t launch_pair_combine(int dtype, const PairCtx &pc, int width, const void *in_grp,
+                               void *out, int weighted, hipStream_t st);
+// dst[t, e_j*r + q] = scale_j * src[row_j, src_col0 + q] for the kept experts, 0 elsewhere;
+// dst is in the storage dtype with leading dimension ldd, columns [col0, col0 + N*r).
+hipError_t launch_scatter_blocks(int dtype, const PairCtx &pc, const float *src, int lds_,
+                                 int src_dense, int weighted, void *dst, int ldd, int col0,
+                                 hipStream_t st);
+// small_grp[row, q] = scale * src[(by_token ? t(row) : row), e(row)*r + q]   (float32)
+hipError_t launch_gather_small(const PairCtx &pc, const float *src, int by_token, int weighted,
+                               float *small_grp, hipStream_t st);
+
+// Weight re-layouts (tiny): see the definitions for the index maps.
+hipError_t launch_pack_bank_cat(int dtype, const void *bank, int N, int rows, int r, float scale,
+                                void *out, int ldo, int col0, hipStream_t st);
+hipError_t launch_pack_bank_T(int dtype, const void *bank, int N, int rows, int r, void *out,
+                              hipStream_t st);
+hipError_t launch_pack_A_cat(int dtype, const void *A, int N, int r, int cols, float scale,
+                             void *out, int ldo, int col0, hipStream_t st);
+hipError_t launch_pack_router_T(int dtype, const void *W_router, int N, int d, void *out,
+                                int ldo, int col0, int ncols, hipStream_t st);
+hipError_t launch_transpose(int dtype, const void *in, void *out, int rows, int cols,
+                            hipStream_t st);
+
+// ---- gradients --------------------------------------------------------------------------
+// out[g][q][c] (layout_qc = 1) or out[g][c][q] (0) = scale * sum over rows of group g of
+//   small[row, q] * wide[(tok_of_row ? tok(row) : row), c];   groups from offs[0..G].
+hipError_t launch_group_outer(int dtype, const int32_t *offs, int G, int max_rows,
+                              const int32_t *pair_of_row, int k, const float *small, int r,
+                              const void *wide, int C, float scale, int layout_qc, float *out,
+                              float *partials, size_t partial_floats, hipStream_t st);
+size_t group_outer_partial_floats(int G, int r, int C);
+
+hipError_t launch_router_bwd(int dtype, const PairCtx &pc, const float *probs, const float *dw_part,
+                             int n_col_tiles, const float *VB_all, const float *Q_all,
+                             const float *F, float s, float d_aux, float aux_coeff, float *dw_ws,
+                             float *dz, void *S, int lds_, int col0, int ncols, hipStream_t st);
+
+}  // namespace mixlora

@@ -1,0 +1,467 @@
+// Element-wise and rank-r kernels of the MixLoRA block.
+//
+// Pairs (token, slot) are processed in expert-grouped row order: every row tile belongs to one
+// expert, so the tile's threads keep that expert's LoRA B columns in registers while they walk
+// the tile's rows (Algorithm 1 lines 11-13: add the LoRA deltas to the shared gate/up
+// projections, then SiLU * up).
+#include "common.h"
+
+namespace mixlora {
+
+// ---- two adjacent elements ------------------------------------------------------------------
+__device__ __forceinline__ float2 load2(const float *p) { return *reinterpret_cast<const float2 *>(p); }
+__device__ __forceinline__ float2 load2(const bf16_t *p) {
+  typedef bf16_t bf16x2_t __attribute__((ext_vector_type(2)));
+  const bf16x2_t v = *reinterpret_cast<const bf16x2_t *>(p);
+  return make_float2((float)v[0], (float)v[1]);
+}
+__device__ __forceinline__ void store2(float *p, float a, float b) {
+  *reinterpret_cast<float2 *>(p) = make_float2(a, b);
+}
+__device__ __forceinline__ void store2(bf16_t *p, float a, float b) {
+  typedef bf16_t bf16x2_t __attribute__((ext_vector_type(2)));
+  bf16x2_t v;
+  v[0] = (bf16_t)a;
+  v[1] = (bf16_t)b;
+  *reinterpret_cast<bf16x2_t *>(p) = v;
+}
+
+// Row tile `b` (of RM rows) in the grouped order: which expert, first row, number of rows.
+__device__ __forceinline__ bool tile_rows(const int32_t *offs, int N, int RM, int b, int &e,
+                                          int &row0, int &rows) {
+  for (e = 0; e < N; e++) {
+    const int lo = offs[e], hi = offs[e + 1];
+    const int nt = (hi - lo + RM - 1) / RM;
+    if (b < nt) {
+      row0 = lo + b * RM;
+      rows = hi - row0 < RM ? hi - row0 : RM;
+      return true;
+    }
+    b -= nt;
+  }
+  return false;
+}
+
+constexpr int SW_COLS = 512;   // columns per block: 256 threads x 2 adjacent columns
+constexpr int SW_RMAX = 64;    // largest LoRA rank
+
+int swiglu_col_tiles(int f) { return (f + SW_COLS - 1) / SW_COLS; }
+
+__device__ __forceinline__ float sigmoidf_(float v) { return 1.f / (1.f + expf(-v)); }
+
+// a_grp[row, c] = SiLU(g) * u with  g = G[t,c] + s * <B_gate[e,c,:], Pg[t,e,:]>  (same for u)
+template <typename E, int RM>
+__global__ __launch_bounds__(256) void swiglu_fwd_kernel(
+    PairCtx pc, int f, float s, const E *__restrict__ G, const E *__restrict__ U,
+    const float *__restrict__ Pg_all, const float *__restrict__ Pu_all,
+    const E *__restrict__ B_gate, const E *__restrict__ B_up, E *__restrict__ a_grp) {
+  __shared__ float Pg_s[RM][SW_RMAX];
+  __shared__ float Pu_s[RM][SW_RMAX];
+  __shared__ int tok_s[RM];
+  int e, row0, rows;
+  if (!tile_rows(pc.offs, pc.N, RM, blockIdx.x, e, row0, rows)) return;
+  const int r = pc.r, R = pc.N * pc.r;
+  for (int i = threadIdx.x; i < RM * r; i += 256) {
+    const int rr = i / r, q = i % r;
+    float vg = 0.f, vu = 0.f;
+    if (rr < rows) {
+      const int t = pc.pair_of_row[row0 + rr] / pc.k;
+      vg = Pg_all[(int64_t)t * R + e * r + q];
+      vu = Pu_all[(int64_t)t * R + e * r + q];
+      if (q == 0) tok_s[rr] = t;
+    }
+    Pg_s[rr][q] = vg;
+    Pu_s[rr][q] = vu;
+  }
+  __syncthreads();
+  const int c = blockIdx.y * SW_COLS + threadIdx.x * 2;
+  if (c >= f) return;
+  float ag[RM][2], au[RM][2];
+#pragma unroll
+  for (int i = 0; i < RM; i++) ag[i][0] = ag[i][1] = au[i][0] = au[i][1] = 0.f;
+  const E *bg = B_gate + ((int64_t)e * f + c) * r;
+  const E *bu = B_up + ((int64_t)e * f + c) * r;
+  for (int q0 = 0; q0 < r; q0 += 8) {
+    Vec8<E> g0, g1, u0, u1;
+    g0.load(bg + q0);
+    g1.load(bg + r + q0);
+    u0.load(bu + q0);
+    u1.load(bu + r + q0);
+#pragma unroll
+    for (int q = 0; q < 8; q++) {
+      const float b0 = g0.get(q), b1 = g1.get(q), c0 = u0.get(q), c1 = u1.get(q);
+#pragma unroll
+      for (int i = 0; i < RM; i++) {
+        const float pg = Pg_s[i][q0 + q], pu = Pu_s[i][q0 + q];
+        ag[i][0] = fmaf(b0, pg, ag[i][0]);
+        ag[i][1] = fmaf(b1, pg, ag[i][1]);
+        au[i][0] = fmaf(c0, pu, au[i][0]);
+        au[i][1] = fmaf(c1, pu, au[i][1]);
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < RM; i++) {
+    if (i < rows) {
+      const int64_t t = tok_s[i];
+      const float2 gv = load2(G + t * f + c), uv = load2(U + t * f + c);
+      const float g0 = gv.x + s * ag[i][0], g1 = gv.y + s * ag[i][1];
+      const float u0 = uv.x + s * au[i][0], u1 = uv.y + s * au[i][1];
+      store2(a_grp + (int64_t)(row0 + i) * f + c, g0 * sigmoidf_(g0) * u0, g1 * sigmoidf_(g1) * u1);
+    }
+  }
+}
+
+// Backward of the tile above.  With H[t] = W_down^T dy[t] (shared by the token's pairs, since
+// the frozen down projection is linear) and Vw[row] = w_row * B_down[e]^T dy[t]:
+//   da = w_row * H[t] + s * A_down[e]^T Vw[row];   dg = da * u * sig(g) * (1 + g (1 - sig(g)));
+//   du = da * g * sig(g);   dw_part[row, column tile] = sum over the tile's columns of H * a.
+template <typename E, int RM>
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(
+    PairCtx pc, int f, float s, const E *__restrict__ G, const E *__restrict__ U,
+    const float *__restrict__ Pg_all, const float *__restrict__ Pu_all,
+    const E *__restrict__ B_gate, const E *__restrict__ B_up, const E *__restrict__ H,
+    const float *__restrict__ VB_all, const E *__restrict__ A_down, E *__restrict__ dg_grp,
+    E *__restrict__ du_grp, float *__restrict__ dw_part, int n_col_tiles) {
+  __shared__ float Pg_s[RM][SW_RMAX];
+  __shared__ float Pu_s[RM][SW_RMAX];
+  __shared__ float Vw_s[RM][SW_RMAX];
+  __shared__ int tok_s[RM];
+  __shared__ float wrow_s[RM];
+  __shared__ float red[4][RM];
+  int e, row0, rows;
+  if (!tile_rows(pc.offs, pc.N, RM, blockIdx.x, e, row0, rows)) return;
+  const int r = pc.r, R = pc.N * pc.r;
+  for (int i = threadIdx.x; i < RM * r; i += 256) {
+    const int rr = i / r, q = i % r;
+    float vg = 0.f, vu = 0.f, vv = 0.f;
+    if (rr < rows) {
+      const int p = pc.pair_of_row[row0 + rr];
+      const int t = p / pc.k;
+      const float w = pc.w[p];
+      vg = Pg_all[(int64_t)t * R + e * r + q];
+      vu = Pu_all[(int64_t)t * R + e * r + q];
+      vv = w * VB_all[(int64_t)t * R + e * r + q];
+      if (q == 0) { tok_s[rr] = t; wrow_s[rr] = w; }
+    }
+    Pg_s[rr][q] = vg;
+    Pu_s[rr][q] = vu;
+    Vw_s[rr][q] = vv;
+  }
+  __syncthreads();
+  const int c = blockIdx.y * SW_COLS + threadIdx.x * 2;
+  const bool active = c < f;
+  float ag[RM][2], au[RM][2], ad[RM][2];
+#pragma unroll
+  for (int i = 0; i < RM; i++)
+    ag[i][0] = ag[i][1] = au[i][0] = au[i][1] = ad[i][0] = ad[i][1] = 0.f;
+  if (active) {
+    const E *bg = B_gate + ((int64_t)e * f + c) * r;
+    const E *bu = B_up + ((int64_t)e * f + c) * r;
+    const E *adn = A_down + (int64_t)e * r * f + c;
+    for (int q0 = 0; q0 < r; q0 += 8) {
+      Vec8<E> g0, g1, u0, u1;
+      g0.load(bg + q0);
+      g1.load(bg + r + q0);
+      u0.load(bu + q0);
+      u1.load(bu + r + q0);
+#pragma unroll
+      for (int q = 0; q < 8; q++) {
+        const float b0 = g0.get(q), b1 = g1.get(q), c0 = u0.get(q), c1 = u1.get(q);
+        const float2 av = load2(adn + (int64_t)(q0 + q) * f);
+#pragma unroll
+        for (int i = 0; i < RM; i++) {
+          const float pg = Pg_s[i][q0 + q], pu = Pu_s[i][q0 + q], vw = Vw_s[i][q0 + q];
+          ag[i][0] = fmaf(b0, pg, ag[i][0]);
+          ag[i][1] = fmaf(b1, pg, ag[i][1]);
+          au[i][0] = fmaf(c0, pu, au[i][0]);
+          au[i][1] = fmaf(c1, pu, au[i][1]);
+          ad[i][0] = fmaf(av.x, vw, ad[i][0]);
+          ad[i][1] = fmaf(av.y, vw, ad[i][1]);
+        }
+      }
+    }
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int i = 0; i < RM; i++) {
+    float part = 0.f;
+    if (active && i < rows) {
+      const int64_t t = tok_s[i];
+      const float w = wrow_s[i];
+      const float2 gv = load2(G + t * f + c), uv = load2(U + t * f + c), hv = load2(H + t * f + c);
+      const float g0 = gv.x + s * ag[i][0], g1 = gv.y + s * ag[i][1];
+      const float u0 = uv.x + s * au[i][0], u1 = uv.y + s * au[i][1];
+      const float s0 = sigmoidf_(g0), s1 = sigmoidf_(g1);
+      const float da0 = w * hv.x + s * ad[i][0], da1 = w * hv.y + s * ad[i][1];
+      part = hv.x * (g0 * s0 * u0) + hv.y * (g1 * s1 * u1);
+      store2(dg_grp + (int64_t)(row0 + i) * f + c, da0 * u0 * s0 * (1.f + g0 * (1.f - s0)),
+             da1 * u1 * s1 * (1.f + g1 * (1.f - s1)));
+      store2(du_grp + (int64_t)(row0 + i) * f + c, da0 * g0 * s0, da1 * g1 * s1);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
+    if (lane == 0) red[wave][i] = part;
+  }
+  __syncthreads();
+  if (threadIdx.x < rows)
+    dw_part[(int64_t)(row0 + threadIdx.x) * n_col_tiles + blockIdx.y] =
+        (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+}
+
+constexpr int FWD_RM = 16, BWD_RM = 8;
+
+hipError_t launch_swiglu_fwd(int dtype, const PairCtx &pc, int f, float s, const void *G,
+                             const void *U, const float *Pg_all, const float *Pu_all,
+                             const void *B_gate, const void *B_up, void *a_grp,
+                             hipStream_t st) {
+  const int nP = pc.T * pc.k;
+  const dim3 grid((nP + FWD_RM - 1) / FWD_RM + pc.N, swiglu_col_tiles(f)), block(256);
+  if (dtype == MIXLORA_BF16)
+    hipLaunchKernelGGL((swiglu_fwd_kernel<bf16_t, FWD_RM>), grid, block, 0, st, pc, f, s,
+                       (const bf16_t *)G, (const bf16_t *)U, Pg_all, Pu_all,
+                       (const bf16_t *)B_gate, (const bf16_t *)B_up, (bf16_t *)a_grp);
+  else
+    hipLaunchKernelGGL((swiglu_fwd_kernel<float, FWD_RM>), grid, block, 0, st, pc, f, s,
+                       (const float *)G, (const float *)U, Pg_all, Pu_all, (const float *)B_gate,
+                       (const float *)B_up, (float *)a_grp);
+  return hipGetLastError();
+}
+
+hipError_t launch_swiglu_bwd(int dtype, const PairCtx &pc, int f, float s, const void *G,
+                             const void *U, const float *Pg_all, const float *Pu_all,
+                             const void *B_gate, const void *B_up, const void *H,
+                             const float *VB_all, const void *A_down, void *dg_grp,
+                             void *du_grp, float *dw_part, int n_col_tiles, hipStream_t st) {
+  const int nP = pc.T * pc.k;
+  const dim3 grid((nP + BWD_RM - 1) / BWD_RM + pc.N, swiglu_col_tiles(f)), block(256);
+  if (dtype == MIXLORA_BF16)
+    hipLaunchKernelGGL((swiglu_bwd_kernel<bf16_t, BWD_RM>), grid, block, 0, st, pc, f, s,
+                       (const bf16_t *)G, (const bf16_t *)U, Pg_all, Pu_all,
+                       (const bf16_t *)B_gate, (const bf16_t *)B_up, (const bf16_t *)H, VB_all,
+                       (const bf16_t *)A_down, (bf16_t *)dg_grp, (bf16_t *)du_grp, dw_part,
+                       n_col_tiles);
+  else
+    hipLaunchKernelGGL((swiglu_bwd_kernel<float, BWD_RM>), grid, block, 0, st, pc, f, s,
+                       (const float *)G, (const float *)U, Pg_all, Pu_all, (const float *)B_gate,
+                       (const float *)B_up, (const float *)H, VB_all, (const float *)A_down,
+                       (float *)dg_grp, (float *)du_grp, dw_part, n_col_tiles);
+  return hipGetLastError();
+}
+
+// ---- out[t, :] = sum_j (w[t,j] or 1) * in_grp[row_of_pair[t,j], :] ------------------------------
+// Gather form of the weighted combine (Eq. 6; Algorithm 1 line 15): each output row is written
+// once, by one thread per 8 columns, slots added in ascending order (deterministic).
+template <typename E>
+__global__ __launch_bounds__(256) void pair_combine_kernel(PairCtx pc, int width,
+                                                           const E *__restrict__ in_grp,
+                                                           E *__restrict__ out, int weighted) {
+  const int t = blockIdx.x;
+  const int c = (blockIdx.y * 256 + threadIdx.x) * 8;
+  if (c >= width) return;
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int j = 0; j < pc.k; j++) {
+    const int p = t * pc.k + j;
+    const float w = weighted ? pc.w[p] : 1.f;
+    Vec8<E> v;
+    v.load(in_grp + (int64_t)pc.row_of_pair[p] * width + c);
+#pragma unroll
+    for (int i = 0; i < 8; i++) acc[i] = fmaf(w, v.get(i), acc[i]);
+  }
+  Vec8<E> o;
+#pragma unroll
+  for (int i = 0; i < 8; i++) o.set(i, acc[i]);
+  o.store(out + (int64_t)t * width + c);
+}
+
+hipError_t launch_pair_combine(int dtype, const PairCtx &pc, int width, const void *in_grp,
+                               void *out, int weighted, hipStream_t st) {
+  const dim3 grid(pc.T, (width / 8 + 255) / 256), block(256);
+  if (dtype == MIXLORA_BF16)
+    hipLaunchKernelGGL(pair_combine_kernel<bf16_t>, grid, block, 0, st, pc, width,
+                       (const bf16_t *)in_grp, (bf16_t *)out, weighted);
+  else
+    hipLaunchKernelGGL(pair_combine_kernel<float>, grid, block, 0, st, pc, width,
+                       (const float *)in_grp, (float *)out, weighted);
+  return hipGetLastError();
+}
+
+// dst[t, col0 + e*r + q] = (w[t,j] or 1) * src[row_j, (src_dense ? e*r : 0) + q] when expert e is
+// slot j of token t, else 0.  Builds the block-sparse low-rank operand of a K-extension.
+template <typename E>
+__global__ void scatter_blocks_kernel(PairCtx pc, const float *__restrict__ src, int lds_,
+                                      int src_dense, int weighted, E *__restrict__ dst, int ldd,
+                                      int col0) {
+  const int R = pc.N * pc.r;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)pc.T * R) return;
+  const int t = (int)(i / R), er = (int)(i % R);
+  const int e = er / pc.r, q = er % pc.r;
+  float v = 0.f;
+  for (int j = 0; j < pc.k; j++) {
+    const int p = t * pc.k + j;
+    if (pc.idx[p] == e) {
+      const float w = weighted ? pc.w[p] : 1.f;
+      v = w * src[(int64_t)pc.row_of_pair[p] * lds_ + (src_dense ? e * pc.r : 0) + q];
+    }
+  }
+  dst[(int64_t)t * ldd + col0 + er] = from_f32<E>(v);
+}
+
+hipError_t launch_scatter_blocks(int dtype, const PairCtx &pc, const float *src, int lds_,
+                                 int src_dense, int weighted, void *dst, int ldd, int col0,
+                                 hipStream_t st) {
+  const int64_t n = (int64_t)pc.T * pc.N * pc.r;
+  const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+  if (dtype == MIXLORA_BF16)
+    hipLaunchKernelGGL(scatter_blocks_kernel<bf16_t>, grid, block, 0, st, pc, src, lds_, src_dense,
+                       weighted, (bf16_t *)dst, ldd, col0);
+  else
+    hipLaunchKernelGGL(scatter_blocks_kernel<float>, grid, block, 0, st, pc, src, lds_, src_dense,
+                       weighted, (float *)dst, ldd, col0);
+  return hipGetLastError();
+}
+
+// small_grp[row, q] = (w_row or 1) * src[(by_token ? t(row) : row), e(row)*r + q]
+__global__ void gather_small_kernel(PairCtx pc, const float *__restrict__ src, int by_token,
+                                    int weighted, float *__restrict__ small_grp) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int nP = pc.T * pc.k;
+  if (i >= (int64_t)nP * pc.r) return;
+  const int row = (int)(i / pc.r), q = (int)(i % pc.r);
+  const int p = pc.pair_of_row[row];
+  const int e = pc.idx[p];
+  const int64_t srow = by_token ? p / pc.k : row;
+  const float w = weighted ? pc.w[p] : 1.f;
+  small_grp[i] = w * src[srow * (pc.N * pc.r) + e * pc.r + q];
+}
+
+hipError_t launch_gather_small(const PairCtx &pc, const float *src, int by_token, int weighted,
+                               float *small_grp, hipStream_t st) {
+  const int64_t n = (int64_t)pc.T * pc.k * pc.r;
+  hipLaunchKernelGGL(gather_small_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, pc,
+                     src, by_token, weighted, small_grp);
+  return hipGetLastError();
+}
+
+// ---- weight re-layouts (all tiny next to the frozen matrices) -------------------------------
+// bank [N, rows, r]  ->  out[i, col0 + e*r + q] = scale * bank[e, i, q]
+template <typename E>
+__global__ void pack_bank_cat_kernel(const E *__restrict__ bank, int N, int rows, int r,
+                                     float scale, E *__restrict__ out, int ldo, int col0) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)N * rows * r) return;
+  const int q = (int)(i % r);
+  const int row = (int)((i / r) % rows);
+  const int e = (int)(i / ((int64_t)r * rows));
+  out[(int64_t)row * ldo + col0 + e * r + q] = from_f32<E>(scale * to_f32(bank[i]));
+}
+// bank [N, rows, r]  ->  out[e*r + q, i] = bank[e, i, q]      (out is [N*r, rows])
+template <typename E>
+__global__ void pack_bank_T_kernel(const E *__restrict__ bank, int N, int rows, int r,
+                                   E *__restrict__ out) {
+  const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (o >= (int64_t)N * rows * r) return;
+  const int i = (int)(o % rows);
+  const int er = (int)(o / rows);
+  const int e = er / r, q = er % r;
+  out[o] = bank[((int64_t)e * rows + i) * r + q];
+}
+// A [N, r, cols]  ->  out[c, col0 + e*r + q] = scale * A[e, q, c]
+template <typename E>
+__global__ void pack_A_cat_kernel(const E *__restrict__ A, int N, int r, int cols, float scale,
+                                  E *__restrict__ out, int ldo, int col0) {
+  const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int R = N * r;
+  if (o >= (int64_t)cols * R) return;
+  const int er = (int)(o % R);
+  const int c = (int)(o / R);
+  out[(int64_t)c * ldo + col0 + er] = from_f32<E>(scale * to_f32(A[(int64_t)er * cols + c]));
+}
+// W_router [N, d]  ->  out[c, col0 + n] = W_router[n, c] for n < N, 0 for N <= n < ncols
+template <typename E>
+__global__ void pack_router_T_kernel(const E *__restrict__ Wr, int N, int d, E *__restrict__ out,
+                                     int ldo, int col0, int ncols) {
+  const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (o >= (int64_t)d * ncols) return;
+  const int n = (int)(o % ncols);
+  const int c = (int)(o / ncols);
+  out[(int64_t)c * ldo + col0 + n] = n < N ? Wr[(int64_t)n * d + c] : from_f32<E>(0.f);
+}
+
+hipError_t launch_pack_bank_cat(int dtype, const void *bank, int N, int rows, int r, float scale,
+                                void *out, int ldo, int col0, hipStream_t st) {
+  const int64_t n = (int64_t)N * rows * r;
+  if (dtype == MIXLORA_BF16)
+    hipLaunchKernelGGL(pack_bank_cat_kernel<bf16_t>, dim3((unsigned)((n + 255) / 256)), dim3(256),
+                       0, st, (const bf16_t *)bank, N, rows, r, scale, (bf16_t *)out, ldo, col0);
+  else
+    hipLaunchKernelGGL(pack_bank_cat_kernel<float>, dim3((unsigned)((n + 255) / 256)), dim3(256),
+                       0, st, (const float *)bank, N, rows, r, scale, (float *)out, ldo, col0);
+  return hipGetLastError();
+}
+hipError_t launch_pack_bank_T(int dtype, const void *bank, int N, int rows, int r, void *out,
+                              hipStream_t st) {
+  const int64_t n = (int64_t)N * rows * r;
+  if (dtype == MIXLORA_BF16)
+    hipLaunchKernelGGL(pack_bank_T_kernel<bf16_t>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                       st, (const bf16_t *)bank, N, rows, r, (bf16_t *)out);
+  else
+    hipLaunchKernelGGL(pack_bank_T_kernel<float>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                       st, (const float *)bank, N, rows, r, (float *)out);
+  return hipGetLastError();
+}
+hipError_t launch_pack_A_cat(int dtype, const void *A, int N, int r, int cols, float scale,
+                             void *out, int ldo, int col0, hipStream_t st) {
+  const int64_t n = (int64_t)N * r * cols;
+  if (dtype == MIXLORA_BF16)
+    hipLaunchKernelGGL(pack_A_cat_kernel<bf16_t>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                       st, (const bf16_t *)A, N, r, cols, scale, (bf16_t *)out, ldo, col0);
+  else
+    hipLaunchKernelGGL(pack_A_cat_kernel<float>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                       st, (const float *)A, N, r, cols, scale, (float *)out, ldo, col0);
+  return hipGetLastError();
+}
+hipError_t launch_pack_router_T(int dtype, const void *W_router, int N, int d, void *out,
+                                int ldo, int col0, int ncols, hipStream_t st) {
+  const int64_t n = (int64_t)d * ncols;
+  if (dtype == MIXLORA_BF16)
+    hipLaunchKernelGGL(pack_router_T_kernel<bf16_t>, dim3((unsigned)((n + 255) / 256)), dim3(256),
+                       0, st, (const bf16_t *)W_router, N, d, (bf16_t *)out, ldo, col0, ncols);
+  else
+    hipLaunchKernelGGL(pack_router_T_kernel<float>, dim3((unsigned)((n + 255) / 256)), dim3(256),
+                       0, st, (const float *)W_router, N, d, (float *)out, ldo, col0, ncols);
+  return hipGetLastError();
+}
+
+// out[cols, rows] = in[rows, cols]^T through a padded 64x64 LDS tile
+template <typename E>
+__global__ __launch_bounds__(256) void transpose_kernel(const E *__restrict__ in,
+                                                        E *__restrict__ out, int rows, int cols) {
+  __shared__ E tile[64][64 + 2];
+  const int c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int i = ty; i < 64; i += 4) {
+    const int r = r0 + i, c = c0 + tx;
+    if (r < rows && c < cols) tile[i][tx] = in[(int64_t)r * cols + c];
+  }
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4) {
+    const int c = c0 + i, r = r0 + tx;
+    if (r < rows && c < cols) out[(int64_t)c * rows + r] = tile[tx][i];
+  }
+}
+
+hipError_t launch_transpose(int dtype, const void *in, void *out, int rows, int cols,
+                            hipStream_t st) {
+  const dim3 grid((cols + 63) / 64, (rows + 63) / 64), block(256);
+  if (dtype == MIXLORA_BF16)
+    hipLaunchKernelGGL(transpose_kernel<bf16_t>, grid, block, 0, st, (const bf16_t *)in,
+                       (bf16_t *)out, rows, cols);
+  else
+    hipLaunchKernelGGL(transpose_kernel<float>, grid, block, 0, st, (const float *)in,
+                       (float *)out, rows, cols);
+  return hipGetLastError();
+}
+
+}  // namespace mixlora

@@ -1,0 +1,253 @@
+// GEMM engine of libmixlora:  C[M,N] = sum_s A_s[M,K_s] * B_s[N,K_s]^T  ("NT", K contiguous).
+//
+// bf16 storage: MFMA 32x32x16 bf16 -> fp32 tiles, 64-wide wavefronts, operands staged through
+// padded LDS tiles with register prefetch of the next K tile (double-buffered LDS, one barrier
+// per K tile), XCD-aware + grouped tile order so that the tiles resident on one XCD share
+// operand rows in that XCD's L2.
+// fp32 storage: plain FMA tiles (the fp32 configuration is a small parity case).
+//
+// Every frozen projection of the block (shared gate/up: Algorithm 1 lines 7-8; down: line 14)
+// and their transposes in the backward go through here; LoRA terms enter either as extra
+// K segments (low-rank K-extension) or through the element-wise kernels.
+#include "common.h"
+
+namespace mixlora {
+
+struct GemmBatch {
+  GemmProblem p[2];
+};
+
+// Map the hardware block id to a tile so that (a) blocks that land on the same XCD (id % 8)
+// get consecutive logical ids and (b) consecutive logical ids walk GROUP tile-rows at a time.
+__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int &tm, int &tn) {
+  const int nb = tiles_m * tiles_n;
+  const int q = nb >> 3, rem = nb & 7;
+  const int xcd = bid & 7, local = bid >> 3;
+  const int lid = xcd * q + (xcd < rem ? xcd : rem) + local;
+  constexpr int GROUP = 8;
+  const int width = GROUP * tiles_n;
+  const int group_id = lid / width;
+  const int first_m = group_id * GROUP;
+  const int gsz = (tiles_m - first_m) < GROUP ? (tiles_m - first_m) : GROUP;
+  const int in_group = lid - group_id * width;
+  tm = first_m + in_group % gsz;
+  tn = in_group / gsz;
+}
+
+template <typename OutT> __device__ __forceinline__ void store_c(OutT *p, float v);
+template <> __device__ __forceinline__ void store_c<float>(float *p, float v) { *p = v; }
+template <> __device__ __forceinline__ void store_c<bf16_t>(bf16_t *p, float v) { *p = (bf16_t)v; }
+
+template <int BM, int BN, int BK, int WGM, int WGN, typename OutT>
+__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_kernel(GemmBatch args) {
+  constexpr int NT = WGM * WGN * 64;
+  constexpr int LD = BK + 8;        // LDS row pitch in elements: 16 bytes of padding per row
+  constexpr int CPR = BK / 8;       // 16-byte chunks per tile row
+  constexpr int RPP = NT / CPR;     // tile rows covered by one pass of all threads
+  constexpr int A_IT = BM / RPP, B_IT = BN / RPP;
+  constexpr int TM = BM / WGM, TN = BN / WGN, MI = TM / 32, NI = TN / 32;
+  static_assert(BM % RPP == 0 && BN % RPP == 0, "tile/threads mismatch");
+  static_assert(TM % 32 == 0 && TN % 32 == 0 && BK % 16 == 0, "wave tile");
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  bf16_t *As = reinterpret_cast<bf16_t *>(smem);   // [2][BM][LD]
+  bf16_t *Bs = As + 2 * BM * LD;                   // [2][BN][LD]
+
+  const GemmProblem &P = args.p[blockIdx.z];
+  const int M = P.M, N = P.N;
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  int tm, tn;
+  tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn);
+  const int row0 = tm * BM, col0 = tn * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int kc = tid % CPR;         // this thread's 16-byte chunk within a tile row
+  const int r_in = tid / CPR;       // first tile row this thread loads
+
+  f32x16_t acc[MI][NI];
+#pragma unroll
+  for (int i = 0; i < MI; i++)
+#pragma unroll
+    for (int j = 0; j < NI; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+  uint4 ra[A_IT], rb[B_IT];
+
+  auto gload = [&](int s, int k0) {
+    const GemmSeg &S = P.seg[s];
+    const bf16_t *Ab = reinterpret_cast<const bf16_t *>(S.A);
+    const bf16_t *Bb = reinterpret_cast<const bf16_t *>(S.B);
+    const int k = k0 + kc * 8;
+    const bool kok = k < S.K;
+#pragma unroll
+    for (int i = 0; i < A_IT; i++) {
+      const int r = row0 + r_in + i * RPP;
+      ra[i] = (kok && r < M) ? *reinterpret_cast<const uint4 *>(Ab + (int64_t)r * S.lda + k)
+                             : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < B_IT; i++) {
+      const int c = col0 + r_in + i * RPP;
+      rb[i] = (kok && c < N) ? *reinterpret_cast<const uint4 *>(Bb + (int64_t)c * S.ldb + k)
+                             : make_uint4(0, 0, 0, 0);
+    }
+  };
+  auto lstore = [&](int buf) {
+    bf16_t *a = As + buf * BM * LD, *b = Bs + buf * BN * LD;
+#pragma unroll
+    for (int i = 0; i < A_IT; i++)
+      *reinterpret_cast<uint4 *>(a + (r_in + i * RPP) * LD + kc * 8) = ra[i];
+#pragma unroll
+    for (int i = 0; i < B_IT; i++)
+      *reinterpret_cast<uint4 *>(b + (r_in + i * RPP) * LD + kc * 8) = rb[i];
+  };
+
+  int seg = 0, k0 = 0;
+  gload(0, 0);
+  lstore(0);
+  __syncthreads();
+  int buf = 0;
+  while (true) {
+    // advance to the next K tile (possibly in the next segment)
+    int nseg = seg, nk0 = k0 + BK;
+    if (nk0 >= P.seg[seg].K) { nseg = seg + 1; nk0 = 0; }
+    const bool more = nseg < P.nseg;
+    if (more) gload(nseg, nk0);
+
+    const bf16_t *a = As + buf * BM * LD + (wm * TM + (lane & 31)) * LD + (lane >> 5) * 8;
+    const bf16_t *b = Bs + buf * BN * LD + (wn * TN + (lane & 31)) * LD + (lane >> 5) * 8;
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 16) {
+      bf16x8_t af[MI], bfr[NI];
+#pragma unroll
+      for (int i = 0; i < MI; i++) af[i] = *reinterpret_cast<const bf16x8_t *>(a + i * 32 * LD + kk);
+#pragma unroll
+      for (int j = 0; j < NI; j++) bfr[j] = *reinterpret_cast<const bf16x8_t *>(b + j * 32 * LD + kk);
+#pragma unroll
+      for (int i = 0; i < MI; i++)
+#pragma unroll
+        for (int j = 0; j < NI; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    if (!more) break;
+    lstore(buf ^ 1);
+    __syncthreads();
+    buf ^= 1;
+    seg = nseg;
+    k0 = nk0;
+  }
+
+  // C fragment of a 32x32 block: column = lane % 32, row = 8*(e/4) + 4*(lane/32) + e%4
+  OutT *C = reinterpret_cast<OutT *>(P.C);
+  const int cbase = col0 + wn * TN + (lane & 31);
+  const int rbase = row0 + wm * TM + (lane >> 5) * 4;
+#pragma unroll
+  for (int i = 0; i < MI; i++)
+#pragma unroll
+    for (int j = 0; j < NI; j++) {
+      const int c = cbase + j * 32;
+      if (c < N) {
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          const int r = rbase + i * 32 + (e >> 2) * 8 + (e & 3);
+          if (r < M) store_c<OutT>(C + (int64_t)r * P.ldc + c, acc[i][j][e]);
+        }
+      }
+    }
+}
+
+// ---- fp32 storage: 64x64 tile, 256 threads, 4x4 outputs per thread ----------------------
+__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmBatch args) {
+  constexpr int BM = 64, BN = 64, BK = 16;
+  __shared__ float As[BK][BM + 4];
+  __shared__ float Bs[BK][BN + 4];
+  const GemmProblem &P = args.p[blockIdx.z];
+  const int M = P.M, N = P.N;
+  const int tiles_n = (N + BN - 1) / BN;
+  const int tm = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
+  const int row0 = tm * BM, col0 = tn * BN;
+  const int tid = threadIdx.x;
+  const int tx = tid & 15, ty = tid >> 4;
+  float acc[4][4] = {};
+  const int lr = tid >> 2, lk = (tid & 3) * 4;   // 64 rows x 4 float4 chunks
+  for (int s = 0; s < P.nseg; s++) {
+    const GemmSeg &S = P.seg[s];
+    const float *A = reinterpret_cast<const float *>(S.A);
+    const float *B = reinterpret_cast<const float *>(S.B);
+    for (int k0 = 0; k0 < S.K; k0 += BK) {
+      float4 va = make_float4(0, 0, 0, 0), vb = va;
+      if (k0 + lk < S.K) {   // K % 8 == 0, so a float4 chunk is entirely in or out
+        if (row0 + lr < M) va = *reinterpret_cast<const float4 *>(A + (int64_t)(row0 + lr) * S.lda + k0 + lk);
+        if (col0 + lr < N) vb = *reinterpret_cast<const float4 *>(B + (int64_t)(col0 + lr) * S.ldb + k0 + lk);
+      }
+      __syncthreads();
+      As[lk + 0][lr] = va.x; As[lk + 1][lr] = va.y; As[lk + 2][lr] = va.z; As[lk + 3][lr] = va.w;
+      Bs[lk + 0][lr] = vb.x; Bs[lk + 1][lr] = vb.y; Bs[lk + 2][lr] = vb.z; Bs[lk + 3][lr] = vb.w;
+      __syncthreads();
+#pragma unroll
+      for (int kk = 0; kk < BK; kk++) {
+        float a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++) a[i] = As[kk][ty * 4 + i];
+#pragma unroll
+        for (int j = 0; j < 4; j++) b[j] = Bs[kk][tx * 4 + j];
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+          for (int j = 0; j < 4; j++) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+      }
+    }
+  }
+  float *C = reinterpret_cast<float *>(P.C);
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const int r = row0 + ty * 4 + i;
+    if (r >= M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      const int c = col0 + tx * 4 + j;
+      if (c < N) C[(int64_t)r * P.ldc + c] = acc[i][j];
+    }
+  }
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, typename OutT>
+static hipError_t launch_bf16(const GemmBatch &b, int nprob, hipStream_t st) {
+  constexpr size_t smem = (size_t)2 * (BM + BN) * (BK + 8) * sizeof(bf16_t);
+  auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, OutT>;
+  static bool attr_set = false;   // per template instance; the attribute is per function
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int tiles = ((b.p[0].M + BM - 1) / BM) * ((b.p[0].N + BN - 1) / BN);
+  hipLaunchKernelGGL(kern, dim3(tiles, 1, nprob), dim3(WGM * WGN * 64), smem, st, b);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm(int dtype, const GemmProblem *probs, int nprob, hipStream_t st) {
+  if (nprob < 1 || nprob > 2) return hipErrorInvalidValue;
+  GemmBatch b;
+  for (int i = 0; i < nprob; i++) b.p[i] = probs[i];
+  if (nprob == 1) b.p[1] = probs[0];
+  const int M = probs[0].M, N = probs[0].N;
+  if (M <= 0 || N <= 0) return hipSuccess;
+  if (dtype == MIXLORA_F32) {
+    const int tiles = ((M + 63) / 64) * ((N + 63) / 64);
+    hipLaunchKernelGGL(gemm_f32_kernel, dim3(tiles, 1, nprob), dim3(256), 0, st, b);
+    return hipGetLastError();
+  }
+  const bool f32out = probs[0].c_f32 != 0;
+  if (N <= 128 || M <= 128) {
+    return f32out ? launch_bf16<128, 128, 64, 2, 2, float>(b, nprob, st)
+                  : launch_bf16<128, 128, 64, 2, 2, bf16_t>(b, nprob, st);
+  }
+  return f32out ? launch_bf16<256, 256, 64, 2, 4, float>(b, nprob, st)
+                : launch_bf16<256, 256, 64, 2, 4, bf16_t>(b, nprob, st);
+}
+
+}  // namespace mixlora

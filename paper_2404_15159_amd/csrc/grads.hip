@@ -1,0 +1,203 @@
+// Gradient kernels: sums of outer products over the rows of each expert group (the LoRA A/B
+// gradients and the router weight gradient), and the router's backward (top-k renormalised
+// softmax of Eq. 7 / Algorithm 1 plus the auxiliary term of Eq. 8-9).
+//
+// Each LoRA gradient has the form  out[g] = scale * sum_{rows of group g} small[row] (x) wide[row']
+// with `small` an r-vector per grouped row and `wide` a d- or d_ff-wide row (grouped, or the
+// token's row).  The sum over rows is split into fixed slices whose partial results are added
+// in a fixed order by a second kernel: no floating-point atomics, bit-reproducible.
+#include "common.h"
+
+namespace mixlora {
+
+constexpr int GO_COLS = 512;   // 256 threads x 2 adjacent columns
+constexpr int GO_STAGE = 64;   // rows staged per pass
+
+__device__ __forceinline__ float2 ld2(const float *p) { return *reinterpret_cast<const float2 *>(p); }
+__device__ __forceinline__ float2 ld2(const bf16_t *p) {
+  typedef bf16_t bf16x2_t __attribute__((ext_vector_type(2)));
+  const bf16x2_t v = *reinterpret_cast<const bf16x2_t *>(p);
+  return make_float2((float)v[0], (float)v[1]);
+}
+
+// partial[split][g][q][c], q < r.  RQ = rank chunk held in registers.
+template <typename E, int RQ>
+__global__ __launch_bounds__(256) void group_outer_kernel(
+    const int32_t *__restrict__ offs, const int32_t *__restrict__ pair_of_row, int k,
+    const float *__restrict__ small, int r, const E *__restrict__ wide, int C, int nsplit,
+    float *__restrict__ partial) {
+  __shared__ float sm[GO_STAGE][RQ];
+  __shared__ int src_s[GO_STAGE];
+  const int g = blockIdx.y, sp = blockIdx.z, G = gridDim.y;
+  const int lo = offs[g], hi = offs[g + 1];
+  const int len = (hi - lo + nsplit - 1) / nsplit;
+  const int r_lo = lo + sp * len;
+  const int r_hi = r_lo + len < hi ? r_lo + len : hi;
+  const int c = blockIdx.x * GO_COLS + threadIdx.x * 2;
+  const bool active = c < C;
+  for (int q0 = 0; q0 < r; q0 += RQ) {
+    float acc[RQ][2];
+#pragma unroll
+    for (int q = 0; q < RQ; q++) acc[q][0] = acc[q][1] = 0.f;
+    for (int rb = r_lo; rb < r_hi; rb += GO_STAGE) {
+      const int n = r_hi - rb < GO_STAGE ? r_hi - rb : GO_STAGE;
+      __syncthreads();
+      for (int i = threadIdx.x; i < GO_STAGE * RQ; i += 256) {
+        const int rr = i / RQ, q = i % RQ;
+        sm[rr][q] = (rr < n && q0 + q < r) ? small[(int64_t)(rb + rr) * r + q0 + q] : 0.f;
+      }
+      if (threadIdx.x < GO_STAGE && threadIdx.x < n)
+        src_s[threadIdx.x] = pair_of_row ? pair_of_row[rb + threadIdx.x] / k : rb + threadIdx.x;
+      __syncthreads();
+      if (active) {
+        for (int rr = 0; rr < n; rr++) {
+          const float2 v = ld2(wide + (int64_t)src_s[rr] * C + c);
+#pragma unroll
+          for (int q = 0; q < RQ; q++) {
+            const float sv = sm[rr][q];
+            acc[q][0] = fmaf(sv, v.x, acc[q][0]);
+            acc[q][1] = fmaf(sv, v.y, acc[q][1]);
+          }
+        }
+      }
+    }
+    if (active) {
+#pragma unroll
+      for (int q = 0; q < RQ; q++) {
+        if (q0 + q < r) {
+          float *o = partial + (((int64_t)sp * G + g) * r + q0 + q) * C + c;
+          *reinterpret_cast<float2 *>(o) = make_float2(acc[q][0], acc[q][1]);
+        }
+      }
+    }
+  }
+}
+
+// out = scale * sum_split partial, written as [g][q][c] (layout_qc) or [g][c][q].
+__global__ void group_outer_reduce_kernel(const float *__restrict__ partial, int G, int r, int C,
+                                          int nsplit, float scale, int layout_qc,
+                                          float *__restrict__ out) {
+  const int64_t n = (int64_t)G * r * C;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float acc = 0.f;
+  for (int sp = 0; sp < nsplit; sp++) acc += partial[(int64_t)sp * n + i];
+  acc *= scale;
+  if (layout_qc) {
+    out[i] = acc;
+  } else {
+    const int c = (int)(i % C);
+    const int q = (int)((i / C) % r);
+    const int g = (int)(i / ((int64_t)C * r));
+    out[((int64_t)g * C + c) * r + q] = acc;
+  }
+}
+
+static int go_splits(int G, int C) {
+  const int col_tiles = (C + GO_COLS - 1) / GO_COLS;
+  int s = 1024 / (col_tiles * G);
+  if (s < 1) s = 1;
+  if (s > 32) s = 32;
+  return s;
+}
+
+size_t group_outer_partial_floats(int G, int r, int C) {
+  return (size_t)go_splits(G, C) * G * r * C;
+}
+
+hipError_t launch_group_outer(int dtype, const int32_t *offs, int G, int max_rows,
+                              const int32_t *pair_of_row, int k, const float *small, int r,
+                              const void *wide, int C, float scale, int layout_qc, float *out,
+                              float *partials, size_t partial_floats, hipStream_t st) {
+  (void)max_rows;
+  const int nsplit = go_splits(G, C);
+  if ((size_t)nsplit * G * r * C > partial_floats) return hipErrorInvalidValue;
+  const dim3 grid((C + GO_COLS - 1) / GO_COLS, G, nsplit), block(256);
+  const bool r16 = r > 8;
+#define MIXLORA_GO(E_, RQ_)                                                                   \
+  hipLaunchKernelGGL((group_outer_kernel<E_, RQ_>), grid, block, 0, st, offs, pair_of_row, k,   \
+                     small, r, (const E_ *)wide, C, nsplit, partials)
+  if (dtype == MIXLORA_BF16) {
+    if (r16) MIXLORA_GO(bf16_t, 16); else MIXLORA_GO(bf16_t, 8);
+  } else {
+    if (r16) MIXLORA_GO(float, 16); else MIXLORA_GO(float, 8);
+  }
+#undef MIXLORA_GO
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int64_t n = (int64_t)G * r * C;
+  hipLaunchKernelGGL(group_outer_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                     st, partials, G, r, C, nsplit, scale, layout_qc, out);
+  return hipGetLastError();
+}
+
+// ---- router backward -------------------------------------------------------------------------
+// One thread per token.  dw_j = <dy_t, o_pair> is assembled from the column-tile partials of
+// <H[t], a_row> plus the low-rank part  s <B_down[e]^T dy_t, A_down[e] a_row>.  Then, with
+// w_j = p_j / sum_kept p (Norm of Algorithm 1):  dp_j = (dw_j - sum_i w_i dw_i) / sum_kept p on
+// the kept experts, plus the auxiliary term  d_aux * a * N * F_e / T  on every expert (Eq. 8-9;
+// F is piecewise constant), and dz = p * (dp - <p, dp>) through the softmax of Eq. 7.
+template <typename E>
+__global__ void router_bwd_kernel(PairCtx pc, const float *__restrict__ probs,
+                                  const float *__restrict__ dw_part, int n_col_tiles,
+                                  const float *__restrict__ VB_all, const float *__restrict__ Q_all,
+                                  const float *__restrict__ F, float s, float d_aux,
+                                  float aux_coeff, float *__restrict__ dw_ws,
+                                  float *__restrict__ dz, E *__restrict__ S, int lds_, int col0,
+                                  int ncols) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= pc.T) return;
+  const int N = pc.N, k = pc.k, r = pc.r, R = N * r;
+  float wdw = 0.f, ssum = 0.f;
+  for (int j = 0; j < k; j++) {
+    const int p = t * k + j;
+    const int row = pc.row_of_pair[p];
+    const int e = pc.idx[p];
+    float acc = 0.f;
+    for (int ct = 0; ct < n_col_tiles; ct++) acc += dw_part[(int64_t)row * n_col_tiles + ct];
+    float lr = 0.f;
+    for (int q = 0; q < r; q++)
+      lr = fmaf(VB_all[(int64_t)t * R + e * r + q], Q_all[(int64_t)row * R + e * r + q], lr);
+    const float dwj = acc + s * lr;
+    dw_ws[p] = dwj;
+    wdw = fmaf(pc.w[p], dwj, wdw);
+    ssum += probs[(int64_t)t * N + e];
+  }
+  const float auxg = d_aux * aux_coeff * (float)N / (float)pc.T;
+  float dot = 0.f;
+  for (int e = 0; e < N; e++) {
+    float dp = auxg * F[e];
+    for (int j = 0; j < k; j++)
+      if (pc.idx[t * k + j] == e) dp += (dw_ws[t * k + j] - wdw) / ssum;
+    dot = fmaf(probs[(int64_t)t * N + e], dp, dot);
+  }
+  for (int e = 0; e < ncols; e++) {
+    float v = 0.f;
+    if (e < N) {
+      float dp = auxg * F[e];
+      for (int j = 0; j < k; j++)
+        if (pc.idx[t * k + j] == e) dp += (dw_ws[t * k + j] - wdw) / ssum;
+      v = probs[(int64_t)t * N + e] * (dp - dot);
+      dz[(int64_t)t * N + e] = v;
+    }
+    S[(int64_t)t * lds_ + col0 + e] = from_f32<E>(v);
+  }
+}
+
+hipError_t launch_router_bwd(int dtype, const PairCtx &pc, const float *probs, const float *dw_part,
+                             int n_col_tiles, const float *VB_all, const float *Q_all,
+                             const float *F, float s, float d_aux, float aux_coeff, float *dw_ws,
+                             float *dz, void *S, int lds_, int col0, int ncols, hipStream_t st) {
+  const dim3 grid((pc.T + 127) / 128), block(128);
+  if (dtype == MIXLORA_BF16)
+    hipLaunchKernelGGL(router_bwd_kernel<bf16_t>, grid, block, 0, st, pc, probs, dw_part,
+                       n_col_tiles, VB_all, Q_all, F, s, d_aux, aux_coeff, dw_ws, dz, (bf16_t *)S,
+                       lds_, col0, ncols);
+  else
+    hipLaunchKernelGGL(router_bwd_kernel<float>, grid, block, 0, st, pc, probs, dw_part,
+                       n_col_tiles, VB_all, Q_all, F, s, d_aux, aux_coeff, dw_ws, dz, (float *)S,
+                       lds_, col0, ncols);
+  return hipGetLastError();
+}
+
+}  // namespace mixlora

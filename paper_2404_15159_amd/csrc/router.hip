@@ -1,0 +1,282 @@
+// Routing kernels: router logits + softmax + top-k + renormalisation (Eq. 7, Norm step of
+// Algorithm 1), stable grouping of the (token, expert) pairs by expert with wavefront ballots
+// and prefix counts, and the auxiliary load-balance loss (Eq. 8-9).
+#include "common.h"
+
+namespace mixlora {
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// One wavefront per token.  Lane l accumulates, for every expert, the products of the 8-wide
+// chunks l, l+64, ... of the row; a butterfly then gives every lane the full logit.
+// Selection is on the logits (monotone with the probabilities); equal logits go to the lower
+// expert index; slots are in descending order.
+template <typename E, int NMAX>
+__global__ __launch_bounds__(256) void router_kernel(const E *__restrict__ x,
+                                                     const E *__restrict__ Wr, int T, int d,
+                                                     int N, int k, float *__restrict__ probs,
+                                                     int32_t *__restrict__ idx_out,
+                                                     float *__restrict__ w_out,
+                                                     int32_t *__restrict__ idx_ws,
+                                                     float *__restrict__ w_ws) {
+  __shared__ float zbuf[4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int t = blockIdx.x * 4 + wave;
+  if (t >= T) return;   // whole wave leaves together; no block-wide barrier below
+  float acc[NMAX];
+#pragma unroll
+  for (int e = 0; e < NMAX; e++) acc[e] = 0.f;
+  const E *xr = x + (int64_t)t * d;
+  for (int c = lane * 8; c < d; c += 64 * 8) {
+    Vec8<E> xv;
+    xv.load(xr + c);
+#pragma unroll
+    for (int e = 0; e < NMAX; e++) {
+      if (e < N) {
+        Vec8<E> wv;
+        wv.load(Wr + (int64_t)e * d + c);
+#pragma unroll
+        for (int i = 0; i < 8; i++) acc[e] = fmaf(xv.get(i), wv.get(i), acc[e]);
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < NMAX; e++) {
+    const float s = wave_sum(acc[e]);
+    if (lane == e) zbuf[wave][e] = s;
+  }
+  __builtin_amdgcn_wave_barrier();
+  const float z = lane < N ? zbuf[wave][lane] : -INFINITY;
+  const float zmax = wave_max(z);
+  const float ez = lane < N ? expf(z - zmax) : 0.f;
+  const float p = ez / wave_sum(ez);
+  if (lane < N) probs[(int64_t)t * N + lane] = p;
+  // k rounds of arg-max with ties to the lowest lane
+  float zc = z;
+  float psel = 0.f;     // lane j keeps the probability of slot j
+  int esel = 0;
+  float ksum = 0.f;
+  for (int j = 0; j < k; j++) {
+    const float m = wave_max(zc);
+    const unsigned long long b = __ballot(zc == m && lane < N);
+    const int e = __ffsll((long long)b) - 1;
+    const float pe = __shfl(p, e, 64);
+    ksum += pe;
+    if (lane == j) { psel = pe; esel = e; }
+    if (lane == e) zc = -INFINITY;
+  }
+  if (lane < k) {
+    const float w = psel / ksum;
+    const int64_t o = (int64_t)t * k + lane;
+    idx_out[o] = esel;
+    w_out[o] = w;
+    idx_ws[o] = esel;
+    w_ws[o] = w;
+  }
+}
+
+template <typename E>
+static hipError_t launch_router_t(const void *x, const void *Wr, int T, int d, int N, int k,
+                                  float *probs, int32_t *idx_out, float *w_out, int32_t *idx_ws,
+                                  float *w_ws, hipStream_t st) {
+  const dim3 grid((T + 3) / 4), block(256);
+  const E *xe = reinterpret_cast<const E *>(x), *we = reinterpret_cast<const E *>(Wr);
+#define MIXLORA_ROUTER(NM)                                                                    \
+  hipLaunchKernelGGL((router_kernel<E, NM>), grid, block, 0, st, xe, we, T, d, N, k, probs,   \
+                     idx_out, w_out, idx_ws, w_ws)
+  if (N <= 8) MIXLORA_ROUTER(8);
+  else if (N <= 16) MIXLORA_ROUTER(16);
+  else if (N <= 32) MIXLORA_ROUTER(32);
+  else MIXLORA_ROUTER(64);
+#undef MIXLORA_ROUTER
+  return hipGetLastError();
+}
+
+hipError_t launch_router(int dtype, const void *x, const void *W_router, int T, int d, int N,
+                         int k, float *probs, int32_t *idx_out, float *w_out, int32_t *idx_ws,
+                         float *w_ws, hipStream_t st) {
+  return dtype == MIXLORA_BF16
+             ? launch_router_t<bf16_t>(x, W_router, T, d, N, k, probs, idx_out, w_out, idx_ws, w_ws, st)
+             : launch_router_t<float>(x, W_router, T, d, N, k, probs, idx_out, w_out, idx_ws, w_ws, st);
+}
+
+// ---- grouping of pairs by expert ---------------------------------------------------------
+// One workgroup of 16 wavefronts.  Wave w owns a contiguous range of pairs.  Pass 1 counts the
+// range's pairs per expert (lane n keeps the count of expert n: one ballot + popcount per
+// expert per 64 pairs).  After an exclusive scan over (expert, wave), pass 2 walks the range
+// again and gives each pair the row  base[expert] + (number of earlier pairs of that expert),
+// i.e. a stable counting sort: rows of one expert are in ascending pair order.
+constexpr int GP_WAVES = 16;
+
+__global__ __launch_bounds__(GP_WAVES * 64) void group_pairs_kernel(
+    const int32_t *__restrict__ idx, int nP, int N, int k, int32_t *__restrict__ counts,
+    int32_t *__restrict__ counts_out, int32_t *__restrict__ first_counts,
+    int32_t *__restrict__ offs, int32_t *__restrict__ row_of_pair,
+    int32_t *__restrict__ pair_of_row) {
+  __shared__ int tot[GP_WAVES][64];
+  __shared__ int first[GP_WAVES][64];
+  __shared__ int base[GP_WAVES][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int per = (((nP + GP_WAVES - 1) / GP_WAVES) + 63) & ~63;
+  const int lo = wave * per;
+  const int hi = lo + per < nP ? lo + per : nP;
+  int cnt = 0, fcnt = 0;
+  for (int p0 = lo; p0 < hi; p0 += 64) {
+    const int p = p0 + lane;
+    const int e = p < hi ? idx[p] : -1;
+    const bool is_first = (p % k) == 0;
+    for (int n = 0; n < N; n++) {
+      const unsigned long long b = __ballot(e == n);
+      const unsigned long long bf = __ballot(e == n && is_first);
+      if (lane == n) { cnt += __popcll(b); fcnt += __popcll(bf); }
+    }
+  }
+  tot[wave][lane] = cnt;
+  first[wave][lane] = fcnt;
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    // lane n: totals of expert n over the waves, then an exclusive scan over experts
+    int c = 0, fc = 0;
+    for (int w = 0; w < GP_WAVES; w++) { c += tot[w][lane]; fc += first[w][lane]; }
+    if (lane >= N) c = 0;
+    int incl = c;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int v = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += v;
+    }
+    const int excl = incl - c;
+    if (lane < N) {
+      counts[lane] = c;
+      if (counts_out) counts_out[lane] = c;
+      first_counts[lane] = fc;
+      offs[lane] = excl;
+      if (lane == N - 1) offs[N] = incl;
+    }
+    int run = excl;
+    for (int w = 0; w < GP_WAVES; w++) { base[w][lane] = run; run += tot[w][lane]; }
+  }
+  __syncthreads();
+  int running = base[wave][lane];   // lane n: next free row of expert n for this wave
+  const unsigned long long lt = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+  for (int p0 = lo; p0 < hi; p0 += 64) {
+    const int p = p0 + lane;
+    const int e = p < hi ? idx[p] : -1;
+    unsigned long long mine = 0;
+    int add = 0;
+    for (int n = 0; n < N; n++) {
+      const unsigned long long b = __ballot(e == n);
+      if (e == n) mine = b;
+      if (lane == n) add = __popcll(b);
+    }
+    const int start = __shfl(running, e < 0 ? 0 : e, 64);
+    if (e >= 0) {
+      const int row = start + __popcll(mine & lt);
+      row_of_pair[p] = row;
+      pair_of_row[row] = p;
+    }
+    running += add;
+  }
+}
+
+hipError_t launch_group_pairs(const int32_t *idx, int T, int N, int k, int32_t *counts,
+                              int32_t *counts_out, int32_t *first_counts, int32_t *offs,
+                              int32_t *row_of_pair, int32_t *pair_of_row, hipStream_t st) {
+  hipLaunchKernelGGL(group_pairs_kernel, dim3(1), dim3(GP_WAVES * 64), 0, st, idx, T * k, N, k,
+                     counts, counts_out, first_counts, offs, row_of_pair, pair_of_row);
+  return hipGetLastError();
+}
+
+// ---- auxiliary loss (Eq. 8-9) -------------------------------------------------------------
+// One workgroup.  F from an integer histogram of the kept experts (first slot only, or all k
+// slots divided by k); P from column sums taken in a fixed order (thread (g, e) sums rows
+// g, g + G, ...; thread e then adds the G partials in ascending g), so the result is
+// bit-reproducible.
+__global__ __launch_bounds__(1024) void aux_loss_kernel(const float *__restrict__ probs,
+                                                        const int32_t *__restrict__ idx, int T,
+                                                        int N, int k, float coeff, int mode,
+                                                        float *__restrict__ loss,
+                                                        float *__restrict__ F_out,
+                                                        float *__restrict__ P_out) {
+  __shared__ int hist[64];
+  __shared__ float part[1024];
+  __shared__ float fp[64];
+  const int tid = threadIdx.x;
+  if (tid < 64) hist[tid] = 0;
+  __syncthreads();
+  if (mode == MIXLORA_AUX_TOP1) {
+    for (int t = tid; t < T; t += 1024) atomicAdd(&hist[idx[(int64_t)t * k]], 1);
+  } else {
+    for (int64_t p = tid; p < (int64_t)T * k; p += 1024) atomicAdd(&hist[idx[p]], 1);
+  }
+  const int G = 1024 / N;
+  const int e = tid % N, g = tid / N;
+  float s = 0.f;
+  if (g < G)
+    for (int t = g; t < T; t += G) s += probs[(int64_t)t * N + e];
+  part[tid] = s;
+  __syncthreads();
+  if (tid < N) {
+    float ps = 0.f;
+    for (int gg = 0; gg < G; gg++) ps += part[gg * N + tid];
+    const float P = ps / (float)T;
+    const float F = (float)hist[tid] / (mode == MIXLORA_AUX_TOP1 ? (float)T : (float)T * (float)k);
+    if (P_out) P_out[tid] = P;
+    if (F_out) F_out[tid] = F;
+    fp[tid] = F * P;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    float acc = 0.f;
+    for (int n = 0; n < N; n++) acc += fp[n];
+    *loss = coeff * (float)N * acc;
+  }
+}
+
+// d loss / d probs[t, e] = coeff * N * F_e / T   (F is piecewise constant)
+__global__ void aux_dprobs_kernel(const int32_t *__restrict__ idx, int T, int N, int k,
+                                  float coeff, int mode, float *__restrict__ dprobs) {
+  __shared__ int hist[64];
+  if (threadIdx.x < 64) hist[threadIdx.x] = 0;
+  __syncthreads();
+  // every block rebuilds the (tiny) histogram: integer counts, identical in every block
+  if (mode == MIXLORA_AUX_TOP1) {
+    for (int t = threadIdx.x; t < T; t += blockDim.x) atomicAdd(&hist[idx[(int64_t)t * k]], 1);
+  } else {
+    for (int64_t p = threadIdx.x; p < (int64_t)T * k; p += blockDim.x) atomicAdd(&hist[idx[p]], 1);
+  }
+  __syncthreads();
+  const float denom = mode == MIXLORA_AUX_TOP1 ? (float)T : (float)T * (float)k;
+  const int64_t total = (int64_t)T * N;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    const int e = (int)(i % N);
+    dprobs[i] = coeff * (float)N * ((float)hist[e] / denom) / (float)T;
+  }
+}
+
+hipError_t launch_aux_loss(const float *probs, const int32_t *idx, int T, int N, int k,
+                           float coeff, int mode, float *loss, float *F, float *P,
+                           float *dprobs, hipStream_t st) {
+  hipLaunchKernelGGL(aux_loss_kernel, dim3(1), dim3(1024), 0, st, probs, idx, T, N, k, coeff,
+                     mode, loss, F, P);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (dprobs) {
+    hipLaunchKernelGGL(aux_dprobs_kernel, dim3(8), dim3(1024), 0, st, idx, T, N, k, coeff, mode,
+                       dprobs);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+}  // namespace mixlora

@@ -1,0 +1,80 @@
+"""Device-side plumbing around the binding: owns the tensors of one MixLoRA FFN problem.
+
+No arithmetic of the method happens here: tensors are allocated with PyTorch, pointers are
+handed to the C ABI, and results are read back.  Used by the GPU tests, the smoke check and
+bench.py.
+"""
+from __future__ import annotations
+
+from typing import Dict, Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+from . import synth
+
+
+def _tdtype(dtype: str):
+    return torch.bfloat16 if dtype == "bf16" else torch.float32
+
+
+class MixLoraFFN:
+    """One problem instance on cuda:0: weights, workspace and output buffers."""
+
+    def __init__(self, cfg: synth.Config, host: Dict[str, np.ndarray], aux_mode: int = B.AUX_TOP1,
+                 pretransposed: bool = True, with_backward: bool = True, device: str = "cuda:0"):
+        B.load()
+        self.cfg = cfg
+        self.dev = torch.device(device)
+        self.with_backward = with_backward
+        td = _tdtype(cfg.dtype)
+        self.dims = B.make_dims(cfg.T, cfg.d, cfg.d_ff, cfg.N, cfg.k, cfg.r, cfg.lora_scale,
+                                cfg.aux_coeff, aux_mode, B.BF16 if cfg.dtype == "bf16" else B.F32)
+        self.t: Dict[str, torch.Tensor] = {}
+        for n in synth.WEIGHT_NAMES + ("x",) + (("dy",) if with_backward and "dy" in host else ()):
+            self.t[n] = torch.from_numpy(np.ascontiguousarray(host[n])).to(self.dev).to(td).contiguous()
+        T, d, f, N, k, r = cfg.T, cfg.d, cfg.d_ff, cfg.N, cfg.k, cfg.r
+        if with_backward and pretransposed:
+            for n, (rows, cols) in (("W_gate", (f, d)), ("W_up", (f, d)), ("W_down", (d, f))):
+                out = torch.empty((cols, rows), dtype=td, device=self.dev)
+                B.mixlora_transpose(self.t[n], out, rows, cols, self.dims.dtype)
+                self.t[n + "_T"] = out
+        self.weights = B.make_weights(self.t)
+        self.ws_bytes = B.mixlora_workspace_bytes(self.dims, with_backward)
+        if self.ws_bytes == 0:
+            raise ValueError("dims rejected by mixlora_workspace_bytes")
+        self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.dev)
+        self.y = torch.empty((T, d), dtype=td, device=self.dev)
+        self.topk_idx = torch.empty((T, k), dtype=torch.int32, device=self.dev)
+        self.topk_w = torch.empty((T, k), dtype=torch.float32, device=self.dev)
+        self.counts = torch.empty((N,), dtype=torch.int32, device=self.dev)
+        self.aux = torch.empty((1,), dtype=torch.float32, device=self.dev)
+        if with_backward:
+            self.dx = torch.empty((T, d), dtype=td, device=self.dev)
+            shapes = dict(dA_gate=(N, r, d), dB_gate=(N, f, r), dA_up=(N, r, d), dB_up=(N, f, r),
+                          dA_down=(N, r, f), dB_down=(N, d, r), dW_router=(N, d))
+            self.g = {n: torch.empty(s, dtype=torch.float32, device=self.dev)
+                      for n, s in shapes.items()}
+            self.grads = B.make_grads(self.g)
+
+    def forward(self, x: Optional[torch.Tensor] = None, stream=None) -> None:
+        B.mixlora_ffn_forward(self.dims, self.weights, self.t["x"] if x is None else x, self.y,
+                              self.topk_idx, self.topk_w, self.counts, self.aux, self.workspace,
+                              self.ws_bytes, stream)
+
+    def backward(self, dy: Optional[torch.Tensor] = None, d_aux: float = 1.0, stream=None) -> None:
+        B.mixlora_ffn_backward(self.dims, self.weights, self.t["x"],
+                               self.t["dy"] if dy is None else dy, d_aux, self.workspace,
+                               self.ws_bytes, self.dx, self.grads, stream)
+
+    def results(self) -> Dict[str, np.ndarray]:
+        torch.cuda.synchronize()
+        out = dict(y=self.y.float().cpu().numpy(), topk_idx=self.topk_idx.cpu().numpy(),
+                   topk_w=self.topk_w.cpu().numpy(), counts=self.counts.cpu().numpy(),
+                   aux_loss=float(self.aux.cpu().item()))
+        if self.with_backward:
+            out["dx"] = self.dx.float().cpu().numpy()
+            for n, v in self.g.items():
+                out[n] = v.cpu().numpy()
+        return out

@@ -1,0 +1,124 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol, sizes its
+workspace sensibly and rejects bad arguments on the host before any HIP call."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2404_15159_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2404_15159_amd import build
+        build.build(verbose=False)
+    return B.load()
+
+
+def test_exports_match_header(lib):
+    text = open(os.path.join(ROOT, "include", "mixlora.h")).read()
+    declared = set(re.findall(r"MIXLORA_API\s+[\w\s\*]+?\b(mixlora_\w+)\s*\(", text))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert B.mixlora_version() >= 100
+
+
+def dims(**kw):
+    base = dict(T=4096, d=4096, d_ff=11008, N=8, k=2, r=16, lora_scale=2.0)
+    base.update(kw)
+    return B.make_dims(**base)
+
+
+def test_workspace_bytes(lib):
+    d = dims()
+    fwd, bwd = B.mixlora_workspace_bytes(d, False), B.mixlora_workspace_bytes(d, True)
+    # forward keeps G, U [T,f], the grouped activations [kT,f] and their combination [T,f]
+    assert fwd >= 5 * 4096 * 11008 * 2
+    assert bwd > fwd
+    assert bwd < 8 << 30
+    assert B.mixlora_workspace_bytes(dims(T=8192), True) > bwd
+    for bad in (dict(k=0), dict(k=9), dict(N=65), dict(r=4), dict(r=12), dict(d=4100),
+                dict(d_ff=11004), dict(T=0), dict(dtype=7), dict(aux_mode=3), dict(N=64, r=16),
+                dict(T=1 << 23, k=2)):
+        assert B.mixlora_workspace_bytes(dims(**bad), True) == 0, bad
+
+
+FAKE = 0x10000   # a non-null, 16-byte aligned value that is never dereferenced on these paths
+
+
+def fake_weights(**kw):
+    t = {n: FAKE for n in B.WEIGHT_FIELDS[:10]}
+    t.update(kw)
+    return B.make_weights(t)
+
+
+def fwd_args(**kw):
+    a = dict(x=FAKE, y=FAKE, topk_idx=FAKE, topk_w=FAKE, expert_counts=FAKE, aux_loss=FAKE,
+             workspace=FAKE, workspace_bytes=1 << 40)
+    a.update(kw)
+    return a
+
+
+def fwd_code(d, w, **kw):
+    with pytest.raises(B.MixLoraError) as ei:
+        B.mixlora_ffn_forward(d, w, stream=0, **fwd_args(**kw))
+    return ei.value.code
+
+
+def test_forward_argument_errors(lib):
+    assert fwd_code(dims(k=3, N=2), fake_weights()) == -2
+    assert fwd_code(dims(dtype=5), fake_weights()) == -3
+    assert fwd_code(dims(), fake_weights(W_up=None)) == -1
+    assert fwd_code(dims(), fake_weights(B_down=FAKE + 4)) == -4
+    assert fwd_code(dims(), fake_weights(), y=None) == -1
+    assert fwd_code(dims(), fake_weights(), x=FAKE + 8) == -4
+    assert fwd_code(dims(), fake_weights(), workspace_bytes=1024) == -5
+
+
+def test_backward_argument_errors(lib):
+    g = B.make_grads({n: FAKE for n in B.GRAD_FIELDS})
+
+    def code(d=None, w=None, grads=g, **kw):
+        a = dict(x=FAKE, dy=FAKE, d_aux=1.0, workspace=FAKE, workspace_bytes=1 << 40, dx=FAKE)
+        a.update(kw)
+        with pytest.raises(B.MixLoraError) as ei:
+            B.mixlora_ffn_backward(d or dims(), w or fake_weights(), grads=grads, stream=0, **a)
+        return ei.value.code
+
+    assert code(d=dims(r=7)) == -2
+    assert code(dy=None) == -1
+    assert code(grads=B.make_grads({n: FAKE for n in B.GRAD_FIELDS[:-1]})) == -1
+    assert code(dx=FAKE + 2) == -4
+    assert code(w=fake_weights(W_gate_T=FAKE + 1)) == -4
+    fwd_only = B.mixlora_workspace_bytes(dims(), False)
+    assert code(workspace_bytes=fwd_only) == -5
+
+
+def test_aux_and_transpose_argument_errors(lib):
+    with pytest.raises(B.MixLoraError) as ei:
+        B.mixlora_aux_loss(FAKE, FAKE, 16, 4, 5, 0.01, 0, FAKE, stream=0)
+    assert ei.value.code == -2
+    with pytest.raises(B.MixLoraError) as ei:
+        B.mixlora_aux_loss(FAKE, None, 16, 4, 2, 0.01, 0, FAKE, stream=0)
+    assert ei.value.code == -1
+    with pytest.raises(B.MixLoraError) as ei:
+        B.mixlora_aux_loss(FAKE, FAKE, 16, 4, 2, 0.01, 9, FAKE, stream=0)
+    assert ei.value.code == -3
+    with pytest.raises(B.MixLoraError) as ei:
+        B.mixlora_transpose(FAKE, FAKE, 0, 4, 1, stream=0)
+    assert ei.value.code == -2
+    with pytest.raises(B.MixLoraError) as ei:
+        B.mixlora_transpose(FAKE, FAKE, 4, 4, 3, stream=0)
+    assert ei.value.code == -3
+
+
+def test_binding_refuses_missing_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError):
+        B.load()

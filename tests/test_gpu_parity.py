@@ -1,0 +1,205 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Small and medium cases span several tiles and ragged tails of every kernel (GEMM tiles of
+256/128/64, 512-column element-wise tiles, 8/16-row grouped tiles); full-size cases run in
+the launch configuration bench.py times.
+"""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import mixlora_oracle as orc
+from paper_2404_15159_amd import binding as B
+from paper_2404_15159_amd import synth
+from paper_2404_15159_amd.runner import MixLoraFFN
+
+import parity_utils as pu
+
+pytestmark = pytest.mark.gpu
+
+BASE_BF16 = synth.CONFIGS["llama2_7b"]
+BASE_F32 = synth.CONFIGS["tiny_f32"]
+
+
+def run_case(cfg, host, aux_mode="top1", d_aux=1.0, pretransposed=True, backward=True):
+    print(f"\ncase {cfg.name}: T={cfg.T} d={cfg.d} f={cfg.d_ff} N={cfg.N} k={cfg.k} r={cfg.r} "
+          f"{cfg.dtype} aux={aux_mode}", flush=True)
+    mode = B.AUX_TOP1 if aux_mode == "top1" else B.AUX_TOPK
+    m = MixLoraFFN(cfg, host, aux_mode=mode, pretransposed=pretransposed, with_backward=backward)
+    m.forward()
+    if backward:
+        m.backward(d_aux=d_aux)
+    res = m.results()
+    W = {n: host[n] for n in synth.WEIGHT_NAMES}
+    if backward:
+        bw = orc.backward(host["x"], W, cfg.k, cfg.lora_scale, host["dy"], d_aux, cfg.aux_coeff,
+                          aux_mode)
+        fw = bw["forward"]
+    else:
+        bw = None
+        fw = orc.forward(host["x"], W, cfg.k, cfg.lora_scale, cfg.aux_coeff, aux_mode)
+    return res, fw, bw, m
+
+
+def test_tiny_f32_config():
+    cfg = BASE_F32
+    host = synth.make_inputs(cfg)
+    for aux_mode in ("top1", "topk"):
+        res, fw, bw, _ = run_case(cfg, host, aux_mode)
+        rep = pu.compare_all(res, fw, bw, cfg)
+        assert rep["routing_mismatch_tokens"] == 0
+
+
+SMALL_CASES = [
+    # name, base, overrides
+    ("bf16_ragged", BASE_BF16, dict(T=300, d=256, d_ff=520, N=8, k=2, r=16)),
+    ("bf16_multi_tile", BASE_BF16, dict(T=1000, d=512, d_ff=1288, N=16, k=2, r=8, alpha=16.0)),
+    ("bf16_top3_r32", BASE_BF16, dict(T=257, d=136, d_ff=264, N=5, k=3, r=32, alpha=64.0)),
+    ("bf16_k_eq_N", BASE_BF16, dict(T=130, d=128, d_ff=256, N=4, k=4, r=8, alpha=16.0)),
+    ("bf16_top1", BASE_BF16, dict(T=200, d=128, d_ff=384, N=8, k=1, r=16)),
+    ("bf16_one_expert", BASE_BF16, dict(T=70, d=64, d_ff=136, N=1, k=1, r=8, alpha=16.0)),
+    ("bf16_one_token", BASE_BF16, dict(T=1, d=64, d_ff=128, N=8, k=2, r=16)),
+    ("bf16_skew", synth.CONFIGS["llama2_13b_skew"], dict(T=600, d=256, d_ff=768)),
+    ("bf16_clusters", synth.CONFIGS["llama3_8b_clusters"], dict(T=1024, d=256, d_ff=512, seq_len=64)),
+    ("f32_ragged", BASE_F32, dict(T=333, d=72, d_ff=200, N=6, k=2, r=8)),
+    ("f32_top3", BASE_F32, dict(T=129, d=64, d_ff=136, N=8, k=3, r=16, alpha=32.0)),
+]
+
+
+@pytest.mark.parametrize("name,base,over", SMALL_CASES, ids=[c[0] for c in SMALL_CASES])
+def test_small_cases(name, base, over):
+    cfg = synth.scaled(base, name=name, **over)
+    host = synth.make_inputs(cfg)
+    # livelier LoRA paths than the large-shape recipe so that a wrong rank-r term shows
+    for n in ("B_gate", "B_up", "B_down"):
+        host[n] = synth.round_to_bf16(host[n] * 4.0) if cfg.dtype == "bf16" else host[n] * 4.0
+    res, fw, bw, _ = run_case(cfg, host, "topk" if cfg.k == 3 else "top1", d_aux=1.5)
+    pu.compare_all(res, fw, bw, cfg)
+
+
+def test_unused_expert_and_untransposed_weights():
+    cfg = synth.scaled(synth.CONFIGS["llama2_13b_skew"], name="bf16_unused", T=260, d=128,
+                       d_ff=264, N=8, k=2, r=16)
+    host = synth.make_inputs(cfg)
+    host["W_router"][5, cfg.d - 1] = -60.0      # x[:, d-1] == 1: expert 5 is never kept
+    host["W_router"] = synth.round_to_bf16(host["W_router"])
+    res, fw, bw, _ = run_case(cfg, host, pretransposed=False)
+    assert fw["counts"][5] == 0 and res["counts"][5] == 0
+    pu.compare_all(res, fw, bw, cfg)
+    for n in ("dA_gate", "dB_gate", "dA_up", "dB_up", "dA_down", "dB_down"):
+        assert (res[n][5] == 0.0).all(), n
+
+
+def test_deterministic_reruns():
+    cfg = synth.scaled(BASE_BF16, name="bf16_rerun", T=700, d=256, d_ff=1032, N=8, k=2, r=16)
+    host = synth.make_inputs(cfg)
+    m = MixLoraFFN(cfg, host)
+    m.forward(); m.backward()
+    a = m.results()
+    m.forward(); m.backward()
+    b = m.results()
+    for n in a:
+        assert np.array_equal(np.asarray(a[n]), np.asarray(b[n])), n
+
+
+@pytest.mark.parametrize("mode", ["top1", "topk"])
+def test_aux_loss_entry(mode):
+    T, N, k = 5000, 16, 2
+    rng = np.random.default_rng(7)
+    z = rng.normal(size=(T, N)) * 1.3
+    p = np.exp(z - z.max(axis=1, keepdims=True))
+    p = (p / p.sum(axis=1, keepdims=True)).astype(np.float32)
+    idx = np.argsort(-p, axis=1, kind="stable")[:, :k].astype(np.int32)
+    dev = torch.device("cuda:0")
+    tp, ti = torch.from_numpy(p).to(dev), torch.from_numpy(idx).to(dev)
+    loss = torch.empty(1, device=dev)
+    F = torch.empty(N, device=dev)
+    P = torch.empty(N, device=dev)
+    dp = torch.empty((T, N), device=dev)
+    B.mixlora_aux_loss(tp, ti, T, N, k, 0.01, B.AUX_TOP1 if mode == "top1" else B.AUX_TOPK,
+                       loss, F, P, dp)
+    torch.cuda.synchronize()
+    rl, rF, rP = orc.aux_loss(p, idx, N, 0.01, mode)
+    rdp = orc.aux_loss_dprobs(p, idx, N, 0.01, mode)
+    assert abs(loss.item() - rl) <= 1e-5 * abs(rl)
+    assert np.array_equal(F.cpu().numpy(), rF.astype(np.float32))   # counts / T: exact in fp32
+    np.testing.assert_allclose(P.cpu().numpy(), rP, rtol=1e-5)
+    np.testing.assert_allclose(dp.cpu().numpy(), rdp, rtol=1e-5)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_transpose_entry(dtype):
+    rows, cols = 130, 257
+    a = synth.round_to_bf16(np.random.default_rng(3).normal(size=(rows, cols)).astype(np.float32))
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    src = torch.from_numpy(a).to("cuda:0").to(td)
+    dst = torch.empty((cols, rows), dtype=td, device="cuda:0")
+    B.mixlora_transpose(src, dst, rows, cols, B.BF16 if dtype == "bf16" else B.F32)
+    torch.cuda.synchronize()
+    assert np.array_equal(dst.float().cpu().numpy(), a.T)
+
+
+# ---- full-size workloads, in the launch configuration the bench times -----------------------
+def test_llama2_7b_full_forward_backward():
+    """Whole LLaMA-2-7B-shaped workload against the full oracle (every token, every gradient)."""
+    cfg = synth.CONFIGS["llama2_7b"]
+    t0 = time.time()
+    host = synth.make_inputs(cfg)
+    print(f"inputs {time.time() - t0:.1f}s", flush=True)
+    t0 = time.time()
+    res, fw, bw, _ = run_case(cfg, host)
+    print(f"gpu + oracle {time.time() - t0:.1f}s", flush=True)
+    pu.compare_all(res, fw, bw, cfg)
+
+
+def subset_property_case(cfg, n_sub, seed):
+    """Full-size GPU run with dy zero outside a token subset and d_aux = 0: by linearity in dy
+    and token independence the gradients equal the oracle's on the sub-batch alone, dx is zero
+    outside the subset, and y / routing of the subset equal the oracle's for those tokens."""
+    host = synth.make_inputs(cfg)
+    rng = np.random.default_rng(seed)
+    sub = np.sort(rng.choice(cfg.T, size=n_sub, replace=False))
+    dy_full = np.zeros_like(host["dy"])
+    dy_full[sub] = host["dy"][sub]
+    host_gpu = dict(host, dy=dy_full)
+    m = MixLoraFFN(cfg, host_gpu)
+    m.forward()
+    m.backward(d_aux=0.0)
+    res = m.results()
+    W = {n: host[n] for n in synth.WEIGHT_NAMES}
+    bw = orc.backward(host["x"][sub], W, cfg.k, cfg.lora_scale, host["dy"][sub], 0.0,
+                      cfg.aux_coeff, "top1")
+    fw = bw["forward"]
+    sub_cfg = synth.scaled(cfg, T=n_sub)
+    sub_res = dict(res)
+    for n in ("y", "dx", "topk_idx", "topk_w"):
+        sub_res[n] = res[n][sub]
+    sub_res["counts"] = np.bincount(sub_res["topk_idx"].reshape(-1), minlength=cfg.N)
+    sub_res["aux_loss"] = fw["aux_loss"]          # batch statistic: not comparable on a subset
+    pu.compare_all(sub_res, fw, bw, sub_cfg)
+    rest = np.ones(cfg.T, bool)
+    rest[sub] = False
+    assert (res["dx"][rest] == 0.0).all()
+    # whole-batch properties that hold at any size
+    gi = res["topk_idx"]
+    assert (res["counts"] == np.bincount(gi.reshape(-1), minlength=cfg.N)).all()
+    assert np.isfinite(res["y"]).all()
+    # the auxiliary loss over all tokens from the oracle's cheap router pass
+    z, p, idx, w = orc.router(host["x"], host["W_router"], cfg.k)
+    ref_aux = orc.aux_loss(p, idx, cfg.N, cfg.aux_coeff, "top1")[0]
+    assert abs(res["aux_loss"] - ref_aux) <= 2e-4 * abs(ref_aux)
+    share = res["counts"] / res["counts"].sum()
+    print("expert load share:", np.round(share, 3), flush=True)
+    return res
+
+
+def test_llama2_13b_skew_subset():
+    res = subset_property_case(synth.CONFIGS["llama2_13b_skew"], 384, 11)
+    share0 = res["counts"][0] / res["counts"].sum()
+    assert share0 > 0.22      # the skewed expert carries well above the uniform 12.5 %
+
+
+def test_llama3_8b_clusters_subset():
+    subset_property_case(synth.CONFIGS["llama3_8b_clusters"], 384, 12)
