@@ -1,0 +1,170 @@
+"""Benchmark of the MixLoRA FFN block (forward + backward) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+One step = one pass of the whole hot path: mixlora_ffn_forward followed by
+mixlora_ffn_backward on the LLaMA-2-7B-shaped workload (T=4096 tokens, d=4096, d_ff=11008,
+8 experts, top-2, rank 16, bf16), inputs resident in HBM before the timed region.
+Prints ONE JSON line: tokens/s, the roofline record of the dominant kernel (the large-tile
+bf16 MFMA GEMM, timed live with HIP events on its stream) and the CPU oracle's rate on a
+bounded token sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK = 2.5e15     # dense bf16 MFMA, FLOP/s (MI355X published)
+
+
+def flop_model(cfg, units_fwd, units_bwd):
+    """Algorithmic FLOPs of one step: frozen GEMM units (one unit = 2*T*d*d_ff) plus the rank-r
+    LoRA and router work of the method itself (no padding, no dense-over-all-experts work)."""
+    T, d, f, N, k, r = cfg.T, cfg.d, cfg.d_ff, cfg.N, cfg.k, cfg.r
+    unit = 2.0 * T * d * f
+    fwd = unit * units_fwd + T * (6.0 * k * r * (d + f) + 2.0 * d * N)
+    bwd = unit * units_bwd + T * (12.0 * k * r * (d + f) + 4.0 * d * N)
+    return unit, fwd, bwd
+
+
+def read_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
+    (profiles/), or None when no such summary exists."""
+    path = os.path.join(ROOT, "profiles", f"gemm_bf16_traffic_{workload}.txt")
+    try:
+        with open(path) as fh:
+            for line in fh:
+                if line.startswith("traffic_bytes_per_launch"):
+                    return float(line.split()[1])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(cfg, host, n_tokens):
+    """The oracle as it stands on the first n_tokens tokens (forward + backward)."""
+    import numpy as np
+    from oracle import mixlora_oracle as orc
+    from paper_2404_15159_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    W = {n: np.asarray(host[n], dtype=np.float64) for n in synth.WEIGHT_NAMES}
+    x = np.asarray(host["x"][:n_tokens], dtype=np.float64)
+    dy = np.asarray(host["dy"][:n_tokens], dtype=np.float64)
+    t0 = time.perf_counter()
+    orc.backward(x, W, cfg.k, cfg.lora_scale, dy, 1.0, cfg.aux_coeff, "top1")
+    dt = time.perf_counter() - t0
+    return {"value": n_tokens / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {n_tokens} of {cfg.T} tokens, forward+backward, float64 NumPy, "
+                      f"{dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llama2_7b")
+    ap.add_argument("--cpu-tokens", type=int, default=2048)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--forward-only", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(the block shards by tokens; see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2404_15159_amd import binding as B
+    from paper_2404_15159_amd import synth
+    from paper_2404_15159_amd.runner import MixLoraFFN
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.load()   # raises if the HIP library is missing: there is no fallback path
+    cfg = synth.CONFIGS[args.workload]
+    if cfg.dtype != "bf16":
+        print("bench.py: the timed workloads are the bf16 ones", file=sys.stderr)
+        sys.exit(2)
+    do_bwd = not args.forward_only
+    t0 = time.perf_counter()
+    host = synth.make_inputs(cfg)
+    t_inputs = time.perf_counter() - t0
+    m = MixLoraFFN(cfg, host, with_backward=do_bwd)
+
+    def step():
+        m.forward()
+        if do_bwd:
+            m.backward(d_aux=1.0)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+
+    # dominant kernel, timed live with HIP events on its launch stream
+    B.mixlora_profile_begin(args.steps * 8)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    k_ms, k_launches, k_flops_exec = B.mixlora_profile_end()
+
+    unit, fwd_fl, bwd_fl = flop_model(cfg, 3, 3)
+    _, fwd_paper, bwd_paper = flop_model(cfg, 2 + cfg.k, 2 + cfg.k)
+    step_flops = fwd_fl + (bwd_fl if do_bwd else 0.0)
+    units_per_step = 3 + (3 if do_bwd else 0)
+    launches_per_step = k_launches / args.steps
+    avg_launch_s = k_ms / 1e3 / max(k_launches, 1)
+    alg_flops_per_launch = units_per_step * unit / launches_per_step
+    achieved = alg_flops_per_launch / avg_launch_s
+    traffic = read_traffic(args.workload)
+
+    out = {
+        "metric": "MixLoRA FFN fwd+bwd tokens/sec on 1 MI355X + % bf16 MFMA peak",
+        "value": cfg.T / (ms_per_step / 1e3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} d_ff={cfg.d_ff} N={cfg.N} "
+                               f"top-{cfg.k} r={cfg.r} bf16 "
+                               f"{'forward+backward' if do_bwd else 'forward'}",
+                   "schedule": "shared gate/up (2 units) + linear frozen down (1 unit) per "
+                               "direction; LoRA as rank-r terms on routed pairs",
+                   "frozen_gemm_units_per_step": units_per_step,
+                   "algorithmic_tflop_per_step": step_flops / 1e12,
+                   "paper_schedule_tflop_per_step": (fwd_paper + (bwd_paper if do_bwd else 0)) / 1e12,
+                   "mfma_frac_whole_step": step_flops / (ms_per_step / 1e3) / MFMA_BF16_PEAK,
+                   "input_generation_s": round(t_inputs, 1)},
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel<256,256,64>",
+                     "achieved": achieved / 1e12, "peak": MFMA_BF16_PEAK / 1e12,
+                     "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK,
+                     "launches_per_step": launches_per_step,
+                     "avg_launch_ms": avg_launch_s * 1e3,
+                     "executed_tflop_per_launch": k_flops_exec / max(k_launches, 1) / 1e12,
+                     "traffic": traffic},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, host, min(args.cpu_tokens, cfg.T))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

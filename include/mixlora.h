@@ -133,6 +133,15 @@ MIXLORA_API int mixlora_aux_loss(const float *probs, const int32_t *topk_idx, in
 MIXLORA_API int mixlora_transpose(const void *in, void *out, int32_t rows, int32_t cols, int32_t dtype,
                       void *stream);
 
+/* Measurement hook for benchmarks (the only entry points that synchronise or create HIP
+ * objects): between begin and end, every launch of the library's large-tile bf16 MFMA GEMM
+ * kernel - the kernel that carries the frozen projections - is bracketed by HIP events on
+ * its stream.  end waits for those events and returns, in HOST memory, the summed kernel
+ * time in milliseconds, the number of launches and the floating-point operations those
+ * launches executed (2*M*N*K over their K segments).  Not thread-safe.                  */
+MIXLORA_API int mixlora_profile_begin(int32_t max_launches);
+MIXLORA_API int mixlora_profile_end(double *ms_total, int32_t *launches, double *flops_total);
+
 /* Library version as major*10000 + minor*100 + patch.  Host-only. */
 MIXLORA_API int mixlora_version(void);
 

@@ -20,7 +20,8 @@ STATUS = {0: "OK", -1: "E_NULL", -2: "E_SHAPE", -3: "E_DTYPE", -4: "E_ALIGN", -5
           -6: "E_HIP"}
 
 EXPORTS = ("mixlora_workspace_bytes", "mixlora_ffn_forward", "mixlora_ffn_backward",
-           "mixlora_aux_loss", "mixlora_transpose", "mixlora_version")
+           "mixlora_aux_loss", "mixlora_transpose", "mixlora_version",
+           "mixlora_profile_begin", "mixlora_profile_end")
 
 
 class Dims(C.Structure):
@@ -74,6 +75,11 @@ def load():
     lib.mixlora_transpose.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.mixlora_version.restype = C.c_int
     lib.mixlora_version.argtypes = []
+    lib.mixlora_profile_begin.restype = C.c_int
+    lib.mixlora_profile_begin.argtypes = [i32]
+    lib.mixlora_profile_end.restype = C.c_int
+    lib.mixlora_profile_end.argtypes = [C.POINTER(C.c_double), C.POINTER(i32),
+                                        C.POINTER(C.c_double)]
     _lib = lib
     return lib
 
@@ -153,3 +159,18 @@ def mixlora_transpose(src, dst, rows: int, cols: int, dtype: int, stream=None) -
 
 def mixlora_version() -> int:
     return int(load().mixlora_version())
+
+
+def mixlora_profile_begin(max_launches: int) -> None:
+    rc = load().mixlora_profile_begin(max_launches)
+    if rc != 0:
+        raise MixLoraError("mixlora_profile_begin", rc)
+
+
+def mixlora_profile_end():
+    """Returns (summed kernel ms, launches, executed flops) of the large-tile GEMM kernel."""
+    ms, n, fl = C.c_double(), C.c_int32(), C.c_double()
+    rc = load().mixlora_profile_end(C.byref(ms), C.byref(n), C.byref(fl))
+    if rc != 0:
+        raise MixLoraError("mixlora_profile_end", rc)
+    return ms.value, n.value, fl.value

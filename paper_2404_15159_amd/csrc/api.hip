@@ -367,6 +367,18 @@ int mixlora_aux_loss(const float *probs, const int32_t *topk_idx, int32_t T, int
   return MIXLORA_OK;
 }
 
+int mixlora_profile_begin(int32_t max_launches) {
+  return gemm_timer_begin(max_launches) == 0 ? MIXLORA_OK : MIXLORA_E_HIP;
+}
+
+int mixlora_profile_end(double *ms_total, int32_t *launches, double *flops_total) {
+  if (!ms_total || !launches || !flops_total) return MIXLORA_E_NULL;
+  int n = 0;
+  if (gemm_timer_end(ms_total, &n, flops_total) != 0) return MIXLORA_E_HIP;
+  *launches = n;
+  return MIXLORA_OK;
+}
+
 int mixlora_transpose(const void *in, void *out, int32_t rows, int32_t cols, int32_t dtype,
                       void *stream) {
   if (!in || !out) return MIXLORA_E_NULL;

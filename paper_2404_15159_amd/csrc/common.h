@@ -68,6 +68,11 @@ struct GemmProblem {
 // Enqueue up to two independent problems of identical M, N in one launch.
 hipError_t launch_gemm(int dtype, const GemmProblem *probs, int nprob, hipStream_t st);
 
+// Measurement hook: HIP-event timing of every launch of the large-tile bf16 kernel between
+// begin and end (events are recorded on the launch stream).  Not thread-safe; off by default.
+int gemm_timer_begin(int max_launches);
+int gemm_timer_end(double *ms_total, int *launches, double *flops_total);
+
 // ---- routing -----------------------------------------------------------------------------
 hipError_t launch_router(int dtype, const void *x, const void *W_router, int T, int d, int N,
                          int k, float *probs, int32_t *idx_out, float *w_out, int32_t *idx_ws,

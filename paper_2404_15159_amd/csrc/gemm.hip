@@ -213,6 +213,49 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmBatch args) {
   }
 }
 
+// ---- optional timing of the large-tile kernel (measurement hook, off by default) -----------
+namespace {
+struct GemmTimer {
+  bool on = false;
+  int cap = 0, used = 0;
+  hipEvent_t *beg = nullptr, *end = nullptr;
+  double flops = 0.0;
+} g_timer;
+}  // namespace
+
+int gemm_timer_begin(int max_launches) {
+  if (g_timer.on || max_launches < 1) return -1;
+  if (g_timer.cap < max_launches) {
+    hipEvent_t *b = new hipEvent_t[max_launches], *e = new hipEvent_t[max_launches];
+    for (int i = 0; i < max_launches; i++) {
+      if (hipEventCreate(&b[i]) != hipSuccess || hipEventCreate(&e[i]) != hipSuccess) return -1;
+    }
+    g_timer.beg = b;   // an earlier, smaller pool is kept alive until process exit
+    g_timer.end = e;
+    g_timer.cap = max_launches;
+  }
+  g_timer.used = 0;
+  g_timer.flops = 0.0;
+  g_timer.on = true;
+  return 0;
+}
+
+int gemm_timer_end(double *ms_total, int *launches, double *flops_total) {
+  if (!g_timer.on) return -1;
+  g_timer.on = false;
+  double ms = 0.0;
+  for (int i = 0; i < g_timer.used; i++) {
+    if (hipEventSynchronize(g_timer.end[i]) != hipSuccess) return -1;
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, g_timer.beg[i], g_timer.end[i]) != hipSuccess) return -1;
+    ms += t;
+  }
+  *ms_total = ms;
+  *launches = g_timer.used;
+  *flops_total = g_timer.flops;
+  return 0;
+}
+
 template <int BM, int BN, int BK, int WGM, int WGN, typename OutT>
 static hipError_t launch_bf16(const GemmBatch &b, int nprob, hipStream_t st) {
   constexpr size_t smem = (size_t)2 * (BM + BN) * (BK + 8) * sizeof(bf16_t);
@@ -225,7 +268,15 @@ static hipError_t launch_bf16(const GemmBatch &b, int nprob, hipStream_t st) {
     attr_set = true;
   }
   const int tiles = ((b.p[0].M + BM - 1) / BM) * ((b.p[0].N + BN - 1) / BN);
+  const bool timed = BM == 256 && g_timer.on && g_timer.used < g_timer.cap;
+  if (timed) (void)hipEventRecord(g_timer.beg[g_timer.used], st);
   hipLaunchKernelGGL(kern, dim3(tiles, 1, nprob), dim3(WGM * WGN * 64), smem, st, b);
+  if (timed) {
+    (void)hipEventRecord(g_timer.end[g_timer.used++], st);
+    for (int i = 0; i < nprob; i++)
+      for (int sgi = 0; sgi < b.p[i].nseg; sgi++)
+        g_timer.flops += 2.0 * b.p[i].M * (double)b.p[i].N * b.p[i].seg[sgi].K;
+  }
   return hipGetLastError();
 }
 
