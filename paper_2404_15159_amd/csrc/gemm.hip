@@ -73,25 +73,42 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_kernel(GemmBatch args
 #pragma unroll
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
 
+  // Global -> register prefetch.  Rows/columns past the matrix edge are clamped to the last
+  // valid one: their products land in C rows/columns that are never stored.  K chunks past
+  // the segment's end are loaded from a valid address and replaced by zeros.
   uint4 ra[A_IT], rb[B_IT];
-
-  auto gload = [&](int s, int k0) {
+  const bf16_t *pa[A_IT], *pb[B_IT];
+  int Kcur = 0;
+  auto setup = [&](int s) {
     const GemmSeg &S = P.seg[s];
-    const bf16_t *Ab = reinterpret_cast<const bf16_t *>(S.A);
-    const bf16_t *Bb = reinterpret_cast<const bf16_t *>(S.B);
-    const int k = k0 + kc * 8;
-    const bool kok = k < S.K;
+    const bf16_t *Ab = reinterpret_cast<const bf16_t *>(S.A) + kc * 8;
+    const bf16_t *Bb = reinterpret_cast<const bf16_t *>(S.B) + kc * 8;
 #pragma unroll
     for (int i = 0; i < A_IT; i++) {
-      const int r = row0 + r_in + i * RPP;
-      ra[i] = (kok && r < M) ? *reinterpret_cast<const uint4 *>(Ab + (int64_t)r * S.lda + k)
-                             : make_uint4(0, 0, 0, 0);
+      int r = row0 + r_in + i * RPP;
+      r = r < M ? r : M - 1;
+      pa[i] = Ab + (int64_t)r * S.lda;
     }
 #pragma unroll
     for (int i = 0; i < B_IT; i++) {
-      const int c = col0 + r_in + i * RPP;
-      rb[i] = (kok && c < N) ? *reinterpret_cast<const uint4 *>(Bb + (int64_t)c * S.ldb + k)
-                             : make_uint4(0, 0, 0, 0);
+      int c = col0 + r_in + i * RPP;
+      c = c < N ? c : N - 1;
+      pb[i] = Bb + (int64_t)c * S.ldb;
+    }
+    Kcur = S.K;
+  };
+  auto gload = [&](int k0) {
+    const bool kok = k0 + kc * 8 < Kcur;
+    const int ko = kok ? k0 : 0;
+#pragma unroll
+    for (int i = 0; i < A_IT; i++) {
+      const uint4 v = *reinterpret_cast<const uint4 *>(pa[i] + ko);
+      ra[i] = kok ? v : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < B_IT; i++) {
+      const uint4 v = *reinterpret_cast<const uint4 *>(pb[i] + ko);
+      rb[i] = kok ? v : make_uint4(0, 0, 0, 0);
     }
   };
   auto lstore = [&](int buf) {
@@ -104,20 +121,31 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_kernel(GemmBatch args
       *reinterpret_cast<uint4 *>(b + (r_in + i * RPP) * LD + kc * 8) = rb[i];
   };
 
-  int seg = 0, k0 = 0;
-  gload(0, 0);
+  const int nseg_total = P.nseg;
+  int total_tiles = 0;
+  for (int s = 0; s < nseg_total; s++) total_tiles += (P.seg[s].K + BK - 1) / BK;
+
+  int seg = 0, k0 = 0;   // position of the tile being prefetched
+  setup(0);
+  gload(0);
   lstore(0);
   __syncthreads();
   int buf = 0;
-  while (true) {
-    // advance to the next K tile (possibly in the next segment)
-    int nseg = seg, nk0 = k0 + BK;
-    if (nk0 >= P.seg[seg].K) { nseg = seg + 1; nk0 = 0; }
-    const bool more = nseg < P.nseg;
-    if (more) gload(nseg, nk0);
-
-    const bf16_t *a = As + buf * BM * LD + (wm * TM + (lane & 31)) * LD + (lane >> 5) * 8;
-    const bf16_t *b = Bs + buf * BN * LD + (wn * TN + (lane & 31)) * LD + (lane >> 5) * 8;
+  const bf16_t *a_rd = As + (wm * TM + (lane & 31)) * LD + (lane >> 5) * 8;
+  const bf16_t *b_rd = Bs + (wn * TN + (lane & 31)) * LD + (lane >> 5) * 8;
+  for (int it = 0; it < total_tiles; it++) {
+    const bool more = it + 1 < total_tiles;
+    if (more) {
+      k0 += BK;
+      if (k0 >= Kcur) {   // next segment (rare)
+        seg++;
+        setup(seg);
+        k0 = 0;
+      }
+      gload(k0);
+    }
+    const bf16_t *a = a_rd + buf * BM * LD;
+    const bf16_t *b = b_rd + buf * BN * LD;
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 16) {
       bf16x8_t af[MI], bfr[NI];
@@ -131,12 +159,11 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_kernel(GemmBatch args
         for (int j = 0; j < NI; j++)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
-    if (!more) break;
-    lstore(buf ^ 1);
-    __syncthreads();
-    buf ^= 1;
-    seg = nseg;
-    k0 = nk0;
+    if (more) {
+      lstore(buf ^ 1);
+      __syncthreads();
+      buf ^= 1;
+    }
   }
 
   // C fragment of a 32x32 block: column = lane % 32, row = 8*(e/4) + 4*(lane/32) + e%4
