@@ -15,7 +15,7 @@ namespace {
 
 constexpr size_t ALIGN = 256;
 inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
-inline int up8(int v) { return (v + 7) / 8 * 8; }
+inline int up32(int v) { return (v + 31) / 32 * 32; }
 
 struct Layout {
   // saved by forward
@@ -60,7 +60,7 @@ Layout make_layout(const mixlora_dims &D) {
   L.Qw = take(T * R * E);
   L.Bd_cat = take(d * R * E);
   L.fwd_end = o;
-  L.Kx = (int)(2 * R) + up8((int)N);
+  L.Kx = up32((int)(2 * R) + (int)N);   // whole K tiles of the GEMM's DMA path
   L.nct = swiglu_col_tiles((int)f);
   L.WdT = take(f * d * E);
   L.WgT = take(f * d * E);

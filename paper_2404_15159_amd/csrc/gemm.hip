@@ -11,6 +11,8 @@
 // K segments (low-rank K-extension) or through the element-wise kernels.
 #include "common.h"
 
+#include <cstdlib>
+
 namespace mixlora {
 
 struct GemmBatch {
@@ -185,6 +187,183 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_kernel(GemmBatch args
     }
 }
 
+// ---- bf16, direct-to-LDS variant ---------------------------------------------------------------
+// Same tiling and MFMA fragments as above, but the operand tiles go from global memory straight
+// into LDS (global_load_lds_dwordx4: lane i's 16 bytes land at M0 + 16*i, no VGPR round trip)
+// through a ring of STAGES tiles, so that STAGES-1 K tiles are in flight while one is consumed:
+// HBM latency under load is longer than one K tile's worth of MFMA work.  LDS rows are unpadded
+// (the DMA writes 1 KiB contiguous per wave instruction); bank conflicts of the 128-bit
+// fragment reads are avoided by an XOR swizzle of the 16-byte chunk index with the row's
+// 256-byte bank-row number, applied on the global-address side of the copy.
+// The loads and their s_waitcnt are inline asm: the compiler's own bookkeeping would wait for
+// all outstanding LDS DMA before every LDS read and collapse the ring to depth one.
+// Requires every K_s % BK == 0 and operands below 4 GiB (32-bit lane offsets).
+__device__ __forceinline__ void dma16(uint32_t voff, const void *sbase, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(voff), "s"(sbase), "s"(lds_addr)
+               : "memory", "m0");
+}
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt range");
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+__device__ __forceinline__ const void *uniform_ptr(const void *p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return reinterpret_cast<const void *>(((uint64_t)hi << 32) | lo);
+}
+
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, typename OutT>
+__global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_dl_kernel(GemmBatch args) {
+  constexpr int NW = WGM * WGN;
+  constexpr int ROWB = BK * 2;            // bytes per tile row in LDS
+  constexpr int CPR = BK / 8;             // 16-byte chunks per row
+  constexpr int RPI = 64 / CPR;           // rows covered by one wave-wide DMA instruction
+  constexpr int RPB = 256 / ROWB;         // rows per 256-byte bank row
+  constexpr int IA = BM / RPI / NW, IB = BN / RPI / NW;   // DMA instructions per wave per tile
+  constexpr int IPW = IA + IB;
+  constexpr int STAGE_BYTES = (BM + BN) * ROWB;
+  constexpr int TM = BM / WGM, TN = BN / WGN, MI = TM / 32, NI = TN / 32, KS = BK / 16;
+  static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile/waves mismatch");
+  static_assert((STAGES - 2) * IPW < 64 && STAGES >= 3, "ring depth");
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char *)smem;
+
+  const GemmProblem &P = args.p[blockIdx.z];
+  const int M = P.M, N = P.N;
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  int tm, tn;
+  tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn);
+  const int row0 = tm * BM, col0 = tn * BN;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WGN, wn = wave % WGN;
+
+  f32x16_t acc[MI][NI];
+#pragma unroll
+  for (int i = 0; i < MI; i++)
+#pragma unroll
+    for (int j = 0; j < NI; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+  // --- producer side: per-lane byte offsets of this wave's DMA instructions -----------------
+  const int lrow = lane / CPR, lpos = lane % CPR;
+  uint32_t offA[IA], offB[IB];
+  const unsigned char *baseA = nullptr, *baseB = nullptr;
+  int Kcur = 0;
+  auto setup = [&](int sgi) {
+    const GemmSeg &S = P.seg[sgi];
+#pragma unroll
+    for (int j = 0; j < IA; j++) {
+      const int rt = (wave * IA + j) * RPI + lrow;        // row within the tile
+      const int kc = lpos ^ ((rt / RPB) % CPR);
+      int r = row0 + rt;
+      r = r < M ? r : M - 1;
+      offA[j] = (uint32_t)r * (uint32_t)S.lda * 2u + kc * 16;
+    }
+#pragma unroll
+    for (int j = 0; j < IB; j++) {
+      const int rt = (wave * IB + j) * RPI + lrow;
+      const int kc = lpos ^ ((rt / RPB) % CPR);
+      int c = col0 + rt;
+      c = c < N ? c : N - 1;
+      offB[j] = (uint32_t)c * (uint32_t)S.ldb * 2u + kc * 16;
+    }
+    baseA = reinterpret_cast<const unsigned char *>(S.A);
+    baseB = reinterpret_cast<const unsigned char *>(S.B);
+    Kcur = S.K;
+  };
+  auto issue = [&](int k0, int stage) {
+    const void *ga = uniform_ptr(baseA + (size_t)k0 * 2);
+    const void *gb = uniform_ptr(baseB + (size_t)k0 * 2);
+    const uint32_t la = lds0 + stage * STAGE_BYTES + wave * IA * 1024;
+    const uint32_t lb = lds0 + stage * STAGE_BYTES + BM * ROWB + wave * IB * 1024;
+#pragma unroll
+    for (int j = 0; j < IA; j++) dma16(offA[j], ga, la + j * 1024);
+#pragma unroll
+    for (int j = 0; j < IB; j++) dma16(offB[j], gb, lb + j * 1024);
+  };
+
+  int total_tiles = 0;
+  for (int sgi = 0; sgi < P.nseg; sgi++) total_tiles += P.seg[sgi].K / BK;
+
+  int seg = 0, k0 = 0, issued = 0;
+  setup(0);
+  auto issue_next = [&]() {   // issue tile number `issued` (if any) into its ring slot
+    if (issued < total_tiles) {
+      if (k0 >= Kcur) {
+        seg++;
+        setup(seg);
+        k0 = 0;
+      }
+      issue(k0, issued % STAGES);
+      k0 += BK;
+    }
+    issued++;
+  };
+#pragma unroll
+  for (int s0 = 0; s0 < STAGES - 1; s0++) issue_next();
+
+  // --- consumer side: swizzled fragment addresses -------------------------------------------
+  const int l31 = lane & 31, hi = lane >> 5;
+  const int swz = (l31 / RPB) % CPR;
+  int koff[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ks++) koff[ks] = ((ks * 2 + hi) ^ swz) * 16;
+  const unsigned char *a_rd = smem + (wm * TM + l31) * ROWB;
+  const unsigned char *b_rd = smem + BM * ROWB + (wn * TN + l31) * ROWB;
+
+  for (int it = 0; it < total_tiles; it++) {
+    // tiles it+1 .. min(it+STAGES-2, last) may stay in flight; tile `it` must have landed
+    const int newer = total_tiles - 1 - it;
+    if (newer >= STAGES - 2) wait_vmcnt<(STAGES - 2) * IPW>();
+    else if (STAGES > 3 && newer == 1) wait_vmcnt<IPW>();
+    else if (STAGES > 4 && newer == 2) wait_vmcnt<2 * IPW>();
+    else wait_vmcnt<0>();
+    __syncthreads();
+    issue_next();   // refills the slot that tile it-1 occupied: every wave is past reading it
+    const int st = it % STAGES;
+    const unsigned char *a = a_rd + st * STAGE_BYTES;
+    const unsigned char *b = b_rd + st * STAGE_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+      bf16x8_t af[MI], bfr[NI];
+#pragma unroll
+      for (int i = 0; i < MI; i++)
+        af[i] = *reinterpret_cast<const bf16x8_t *>(a + i * 32 * ROWB + koff[ks]);
+#pragma unroll
+      for (int j = 0; j < NI; j++)
+        bfr[j] = *reinterpret_cast<const bf16x8_t *>(b + j * 32 * ROWB + koff[ks]);
+#pragma unroll
+      for (int i = 0; i < MI; i++)
+#pragma unroll
+        for (int j = 0; j < NI; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+  }
+
+  OutT *C = reinterpret_cast<OutT *>(P.C);
+  const int cbase = col0 + wn * TN + l31;
+  const int rbase = row0 + wm * TM + hi * 4;
+#pragma unroll
+  for (int i = 0; i < MI; i++)
+#pragma unroll
+    for (int j = 0; j < NI; j++) {
+      const int c = cbase + j * 32;
+      if (c < N) {
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          const int r = rbase + i * 32 + (e >> 2) * 8 + (e & 3);
+          if (r < M) store_c<OutT>(C + (int64_t)r * P.ldc + c, acc[i][j][e]);
+        }
+      }
+    }
+}
+
 // ---- fp32 storage: 64x64 tile, 256 threads, 4x4 outputs per thread ----------------------
 __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmBatch args) {
   constexpr int BM = 64, BN = 64, BK = 16;
@@ -307,6 +486,53 @@ static hipError_t launch_bf16(const GemmBatch &b, int nprob, hipStream_t st) {
   return hipGetLastError();
 }
 
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, typename OutT>
+static hipError_t launch_bf16_dl(const GemmBatch &b, int nprob, hipStream_t st) {
+  constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * sizeof(bf16_t);
+  auto kern = gemm_bf16_dl_kernel<BM, BN, BK, STAGES, WGM, WGN, OutT>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int tiles = ((b.p[0].M + BM - 1) / BM) * ((b.p[0].N + BN - 1) / BN);
+  const bool timed = BM == 256 && g_timer.on && g_timer.used < g_timer.cap;
+  if (timed) (void)hipEventRecord(g_timer.beg[g_timer.used], st);
+  hipLaunchKernelGGL(kern, dim3(tiles, 1, nprob), dim3(WGM * WGN * 64), smem, st, b);
+  if (timed) {
+    (void)hipEventRecord(g_timer.end[g_timer.used++], st);
+    for (int i = 0; i < nprob; i++)
+      for (int sgi = 0; sgi < b.p[i].nseg; sgi++)
+        g_timer.flops += 2.0 * b.p[i].M * (double)b.p[i].N * b.p[i].seg[sgi].K;
+  }
+  return hipGetLastError();
+}
+
+// The direct-to-LDS kernel needs whole K tiles and 32-bit operand offsets.
+static bool dl_eligible(const GemmBatch &b, int nprob, int BK) {
+  for (int i = 0; i < nprob; i++) {
+    const GemmProblem &p = b.p[i];
+    for (int sgi = 0; sgi < p.nseg; sgi++) {
+      const GemmSeg &sg = p.seg[sgi];
+      if (sg.K <= 0 || sg.K % BK) return false;
+      if ((uint64_t)p.M * (uint64_t)sg.lda * 2 >= (1ull << 32)) return false;
+      if ((uint64_t)p.N * (uint64_t)sg.ldb * 2 >= (1ull << 32)) return false;
+    }
+  }
+  return true;
+}
+
+static int gemm_variant() {
+  static int v = -1;
+  if (v < 0) {
+    const char *e = getenv("MIXLORA_GEMM_VARIANT");
+    v = e ? atoi(e) : 1;
+  }
+  return v;
+}
+
 hipError_t launch_gemm(int dtype, const GemmProblem *probs, int nprob, hipStream_t st) {
   if (nprob < 1 || nprob > 2) return hipErrorInvalidValue;
   GemmBatch b;
@@ -324,6 +550,13 @@ hipError_t launch_gemm(int dtype, const GemmProblem *probs, int nprob, hipStream
     return f32out ? launch_bf16<128, 128, 64, 2, 2, float>(b, nprob, st)
                   : launch_bf16<128, 128, 64, 2, 2, bf16_t>(b, nprob, st);
   }
+  const int var = gemm_variant();
+  if (!f32out && var == 1 && dl_eligible(b, nprob, 32))
+    return launch_bf16_dl<256, 256, 32, 4, 2, 4, bf16_t>(b, nprob, st);
+  if (!f32out && var == 2 && dl_eligible(b, nprob, 64))
+    return launch_bf16_dl<256, 256, 64, 2 + 1, 2, 2, bf16_t>(b, nprob, st);
+  if (!f32out && var == 3 && dl_eligible(b, nprob, 32))
+    return launch_bf16_dl<256, 256, 32, 4, 2, 2, bf16_t>(b, nprob, st);
   return f32out ? launch_bf16<256, 256, 64, 2, 4, float>(b, nprob, st)
                 : launch_bf16<256, 256, 64, 2, 4, bf16_t>(b, nprob, st);
 }
