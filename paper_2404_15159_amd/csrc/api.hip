@@ -22,7 +22,7 @@ struct Layout {
   size_t probs, idx, w, counts, first_counts, offs, row_of_pair, pair_of_row, F, P, tok_offs;
   size_t G, U, Pg_all, Pu_all, a_grp, Q_all;
   // forward scratch
-  size_t a_comb, Qw, Bd_cat;
+  size_t a_comb, Qw, Bd_cat, rank_part;
   size_t fwd_end;
   // backward scratch
   size_t WdT, WgT, WuT, H, Bd_T, VB_all, dg_grp, du_grp, dgsum, dusum, dw_part, dw, Bg_T, Bu_T,
@@ -59,6 +59,7 @@ Layout make_layout(const mixlora_dims &D) {
   L.a_comb = take(T * f * E);
   L.Qw = take(T * R * E);
   L.Bd_cat = take(d * R * E);
+  L.rank_part = take(2 * 8 * kT * r * 4);   // per-split rank-r partial sums (two banks)
   L.fwd_end = o;
   L.Kx = up32((int)(2 * R) + (int)N);   // whole K tiles of the GEMM's DMA path
   L.nct = swiglu_col_tiles((int)f);
@@ -215,10 +216,17 @@ int mixlora_ffn_forward(const mixlora_dims *dims, const mixlora_weights *w, cons
   }
   PairCtx pc{offs, pair_of_row, row_of_pair, wts, idx, T, N, k, r};
   // Algorithm 1 lines 11-13 on the routed pairs, expert-grouped rows
-  HIP_TRY(launch_swiglu_fwd(dt, pc, f, D.lora_scale, ws + L.G, ws + L.U, (float *)(ws + L.Pg_all),
-                            (float *)(ws + L.Pu_all), w->B_gate, w->B_up, ws + L.a_grp, st));
-  // A_down of every expert on the grouped activations
-  {
+  if (dt == MIXLORA_BF16 && f % 32 == 0) {
+    // fused: LoRA deltas + SiLU * up + A_down of the row's expert, all on MFMA
+    HIP_TRY(launch_swiglu_fwd_mfma(pc, f, D.lora_scale, ws + L.G, ws + L.U,
+                                   (float *)(ws + L.Pg_all), (float *)(ws + L.Pu_all), w->B_gate,
+                                   w->B_up, w->A_down, ws + L.a_grp, (float *)(ws + L.rank_part),
+                                   (float *)(ws + L.Q_all), st));
+  } else {
+    HIP_TRY(launch_swiglu_fwd(dt, pc, f, D.lora_scale, ws + L.G, ws + L.U,
+                              (float *)(ws + L.Pg_all), (float *)(ws + L.Pu_all), w->B_gate,
+                              w->B_up, ws + L.a_grp, st));
+    // A_down of every expert on the grouped activations
     GemmProblem p = problem(kT, R, ws + L.Q_all, R, 1);
     add_seg(p, ws + L.a_grp, f, w->A_down, f, f);
     HIP_TRY(launch_gemm(dt, &p, 1, st));

@@ -109,6 +109,14 @@ hipError_t launch_swiglu_bwd(int dtype, const PairCtx &pc, int f, float s, const
                              void *du_grp, float *dw_part, int n_col_tiles, hipStream_t st);
 int swiglu_col_tiles(int f);
 
+// bf16 MFMA fusion of the above with the A_down projection of the row's expert (needs
+// f % 32 == 0): writes a_grp and Q_all[row, e(row)*r + q]; Q_part is scratch of
+// 8 * kT * r floats.
+hipError_t launch_swiglu_fwd_mfma(const PairCtx &pc, int f, float s, const void *G, const void *U,
+                                  const float *Pg_all, const float *Pu_all, const void *B_gate,
+                                  const void *B_up, const void *A_down, void *a_grp,
+                                  float *Q_part, float *Q_all, hipStream_t st);
+
 // out[t,:] = sum_j (weighted ? w[t,j] : 1) * in_grp[row_of_pair[t,j], :]
 hipError_t launch_pair_combine(int dtype, const PairCtx &pc, int width, const void *in_grp,
                                void *out, int weighted, hipStream_t st);

@@ -55,6 +55,10 @@ def test_tiny_f32_config():
 SMALL_CASES = [
     # name, base, overrides
     ("bf16_ragged", BASE_BF16, dict(T=300, d=256, d_ff=520, N=8, k=2, r=16)),
+    ("bf16_ragged_f32x", BASE_BF16, dict(T=300, d=256, d_ff=544, N=8, k=2, r=16)),
+    ("bf16_r8_f32x", BASE_BF16, dict(T=777, d=192, d_ff=1056, N=16, k=2, r=8, alpha=16.0)),
+    ("bf16_top3_r24_f32x", BASE_BF16, dict(T=257, d=136, d_ff=288, N=5, k=3, r=24, alpha=48.0)),
+    ("bf16_r64_f32x", BASE_BF16, dict(T=130, d=128, d_ff=256, N=4, k=2, r=64, alpha=128.0)),
     ("bf16_multi_tile", BASE_BF16, dict(T=1000, d=512, d_ff=1288, N=16, k=2, r=8, alpha=16.0)),
     ("bf16_top3_r32", BASE_BF16, dict(T=257, d=136, d_ff=264, N=5, k=3, r=32, alpha=64.0)),
     ("bf16_k_eq_N", BASE_BF16, dict(T=130, d=128, d_ff=256, N=4, k=4, r=8, alpha=16.0)),
