@@ -25,7 +25,7 @@ struct Layout {
   size_t a_comb, Qw, Bd_cat, rank_part;
   size_t fwd_end;
   // backward scratch
-  size_t WdT, WgT, WuT, H, Bd_T, VB_all, dg_grp, du_grp, dgsum, dusum, dw_part, dw, Bg_T, Bu_T,
+  size_t WdT, WgT, WuT, H, Bd_T, VB_all, dg_grp, du_grp, dgsum, dusum, dw_part, dw, Bg_T, Bu_T, AdT,
       TG_all, TU_all, small[6], S, Bx, dz, partials;
   size_t partial_floats;
   size_t bwd_end;
@@ -73,10 +73,11 @@ Layout make_layout(const mixlora_dims &D) {
   L.du_grp = take(kT * f * E);
   L.dgsum = take(T * f * E);
   L.dusum = take(T * f * E);
-  L.dw_part = take(kT * (size_t)L.nct * 4);
+  L.dw_part = take(kT * (size_t)(L.nct > 8 ? L.nct : 8) * 4);
   L.dw = take(kT * 4);
   L.Bg_T = take(R * f * E);
   L.Bu_T = take(R * f * E);
+  L.AdT = take(R * f * E);
   L.TG_all = take(kT * R * 4);
   L.TU_all = take(kT * R * 4);
   for (int i = 0; i < 6; i++) L.small[i] = take(kT * r * 4);
@@ -298,22 +299,31 @@ int mixlora_ffn_backward(const mixlora_dims *dims, const mixlora_weights *w, con
     add_seg(p, dy, d, ws + L.Bd_T, d, d);
     HIP_TRY(launch_gemm(dt, &p, 1, st));
   }
-  // through SiLU * up and the LoRA deltas, per pair
-  HIP_TRY(launch_swiglu_bwd(dt, pc, f, s, ws + L.G, ws + L.U, (float *)(ws + L.Pg_all),
-                            (float *)(ws + L.Pu_all), w->B_gate, w->B_up, ws + L.H,
-                            (float *)(ws + L.VB_all), w->A_down, ws + L.dg_grp, ws + L.du_grp,
-                            (float *)(ws + L.dw_part), L.nct, st));
-  HIP_TRY(launch_pair_combine(dt, pc, f, ws + L.dg_grp, ws + L.dgsum, 0, st));
-  HIP_TRY(launch_pair_combine(dt, pc, f, ws + L.du_grp, ws + L.dusum, 0, st));
-  // TG[row, e, :] = B_gate[e]^T dg[row]  (and up)
+  // through SiLU * up and the LoRA deltas, per pair; TG[row, e, :] = B_gate[e]^T dg[row] (and up)
   HIP_TRY(launch_pack_bank_T(dt, w->B_gate, N, f, r, ws + L.Bg_T, st));
   HIP_TRY(launch_pack_bank_T(dt, w->B_up, N, f, r, ws + L.Bu_T, st));
-  {
+  int nct = L.nct;
+  if (dt == MIXLORA_BF16 && f % 32 == 0) {
+    nct = fused_splits(f);
+    HIP_TRY(launch_pack_bank_T(dt, w->A_down, N, r, f, ws + L.AdT, st));   // [N,r,f] -> [N,f,r]
+    HIP_TRY(launch_swiglu_bwd_mfma(pc, f, s, ws + L.G, ws + L.U, ws + L.H, (float *)(ws + L.Pg_all),
+                                   (float *)(ws + L.Pu_all), (float *)(ws + L.VB_all), w->B_gate,
+                                   w->B_up, ws + L.AdT, ws + L.Bg_T, ws + L.Bu_T, ws + L.dg_grp,
+                                   ws + L.du_grp, (float *)(ws + L.dw_part),
+                                   (float *)(ws + L.rank_part), (float *)(ws + L.TG_all),
+                                   (float *)(ws + L.TU_all), st));
+  } else {
+    HIP_TRY(launch_swiglu_bwd(dt, pc, f, s, ws + L.G, ws + L.U, (float *)(ws + L.Pg_all),
+                              (float *)(ws + L.Pu_all), w->B_gate, w->B_up, ws + L.H,
+                              (float *)(ws + L.VB_all), w->A_down, ws + L.dg_grp, ws + L.du_grp,
+                              (float *)(ws + L.dw_part), L.nct, st));
     GemmProblem p[2] = {problem(kT, R, ws + L.TG_all, R, 1), problem(kT, R, ws + L.TU_all, R, 1)};
     add_seg(p[0], ws + L.dg_grp, f, ws + L.Bg_T, f, f);
     add_seg(p[1], ws + L.du_grp, f, ws + L.Bu_T, f, f);
     HIP_TRY(launch_gemm(dt, p, 2, st));
   }
+  HIP_TRY(launch_pair_combine(dt, pc, f, ws + L.dg_grp, ws + L.dgsum, 0, st));
+  HIP_TRY(launch_pair_combine(dt, pc, f, ws + L.du_grp, ws + L.dusum, 0, st));
   // compact per-row rank-r factors of the LoRA gradients
   float *Pg_grp = (float *)(ws + L.small[0]), *Pu_grp = (float *)(ws + L.small[1]);
   float *TG_grp = (float *)(ws + L.small[2]), *TU_grp = (float *)(ws + L.small[3]);
@@ -341,7 +351,7 @@ int mixlora_ffn_backward(const mixlora_dims *dims, const mixlora_weights *w, con
   HIP_TRY(launch_group_outer(dt, offs, N, kT, pair_of_row, k, wQ_grp, r, dy, d, s, 0,
                              grads->dB_down, part, pfl, st));
   // router: dw -> dz (also written into the K-extension operand S), dW_router = dz^T x
-  HIP_TRY(launch_router_bwd(dt, pc, probs, (float *)(ws + L.dw_part), L.nct,
+  HIP_TRY(launch_router_bwd(dt, pc, probs, (float *)(ws + L.dw_part), nct,
                             (float *)(ws + L.VB_all), (float *)(ws + L.Q_all), (float *)(ws + L.F),
                             s, d_aux, D.aux_coeff, (float *)(ws + L.dw), (float *)(ws + L.dz),
                             ws + L.S, Kx, 2 * R, Kx - 2 * R, st));

@@ -117,6 +117,17 @@ hipError_t launch_swiglu_fwd_mfma(const PairCtx &pc, int f, float s, const void 
                                   const void *B_up, const void *A_down, void *a_grp,
                                   float *Q_part, float *Q_all, hipStream_t st);
 
+// bf16 MFMA backward of the same stage (f % 32 == 0): dg_grp, du_grp, dw_part[row][split]
+// (split count = fused_splits(f)), TG_all / TU_all at [row, e(row)*r + q].  AdT = A_down re-laid
+// [N, f, r]; BgT / BuT = B banks re-laid [N, r, f]; rank_part is scratch of 16 * kT * r floats.
+hipError_t launch_swiglu_bwd_mfma(const PairCtx &pc, int f, float s, const void *G, const void *U,
+                                  const void *H, const float *Pg_all, const float *Pu_all,
+                                  const float *VB_all, const void *B_gate, const void *B_up,
+                                  const void *AdT, const void *BgT, const void *BuT, void *dg_grp,
+                                  void *du_grp, float *dw_part, float *rank_part, float *TG_all,
+                                  float *TU_all, hipStream_t st);
+int fused_splits(int f);
+
 // out[t,:] = sum_j (weighted ? w[t,j] : 1) * in_grp[row_of_pair[t,j], :]
 hipError_t launch_pair_combine(int dtype, const PairCtx &pc, int width, const void *in_grp,
                                void *out, int weighted, hipStream_t st);

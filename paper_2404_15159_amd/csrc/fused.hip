@@ -189,6 +189,158 @@ __global__ __launch_bounds__(FT_WAVES * 64) void swiglu_fwd_mfma_kernel(
   }
 }
 
+// Backward of the tile above, same ownership (32 grouped rows x a range of 32-column blocks).
+// With H[t] = W_down^T dy[t] and Vw[row] = w_row * B_down[e]^T dy[t]:
+//   da = w_row * H[t] + s * A_down[e]^T Vw[row]      (rank-r MFMA on the transposed bank AdT)
+//   dg = da * u * sig(g) * (1 + g (1 - sig(g))),  du = da * g * sig(g)   -> dg_grp, du_grp
+//   dw_part[row][split]   = sum over the split's columns of H * a
+//   TG_part[split][row][q] = sum_c dg[row, c] * B_gate[e, c, q]   (and TU with du, B_up)
+// BgT / BuT are the banks re-laid as [N, r, f] so that the column index is contiguous.
+__global__ __launch_bounds__(FT_WAVES * 64) void swiglu_bwd_mfma_kernel(
+    PairCtx pc, int f, float s, const bf16_t *__restrict__ G, const bf16_t *__restrict__ U,
+    const bf16_t *__restrict__ H, const float *__restrict__ Pg_all,
+    const float *__restrict__ Pu_all, const float *__restrict__ VB_all,
+    const bf16_t *__restrict__ B_gate, const bf16_t *__restrict__ B_up,
+    const bf16_t *__restrict__ AdT, const bf16_t *__restrict__ BgT, const bf16_t *__restrict__ BuT,
+    bf16_t *__restrict__ dg_grp, bf16_t *__restrict__ du_grp, float *__restrict__ dw_part,
+    float *__restrict__ TG_part, float *__restrict__ TU_part, int nsplit) {
+  __shared__ float red[FT_WAVES][NQ_MAX][16][64];
+  __shared__ float dwred[FT_WAVES][32];
+  int e, row0, rows;
+  if (!fused_tile_rows(pc.offs, pc.N, blockIdx.x, e, row0, rows)) return;
+  const int r = pc.r, R = pc.N * r, nP = pc.T * pc.k;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l31 = lane & 31, hi = lane >> 5;
+  const bool rvalid = l31 < rows;
+  const int row = row0 + (rvalid ? l31 : 0);
+  const int pair = pc.pair_of_row[row];
+  const int64_t t = pair / pc.k;
+  const float wrow = pc.w[pair];
+  const int ksr = (r + 15) >> 4, nq = (r + 31) >> 5;
+
+  bf16x8_t pg[KSR_MAX], pu[KSR_MAX], vw[KSR_MAX];
+#pragma unroll
+  for (int ks = 0; ks < KSR_MAX; ks++) {
+    const int q0 = ks * 16 + hi * 8;
+    const bool v = ks < ksr && q0 < r;
+    const int64_t o = t * R + e * r + (v ? q0 : 0);
+    pg[ks] = cvt8(Pg_all + o, v, 1.f);
+    pu[ks] = cvt8(Pu_all + o, v, 1.f);
+    vw[ks] = cvt8(VB_all + o, v, wrow);
+  }
+  f32x16_t acctg[NQ_MAX], acctu[NQ_MAX];
+#pragma unroll
+  for (int j = 0; j < NQ_MAX; j++)
+#pragma unroll
+    for (int i = 0; i < 16; i++) acctg[j][i] = acctu[j][i] = 0.f;
+  float dwacc = 0.f;
+
+  const int nblk = f / 32;
+  const int per = (nblk + nsplit - 1) / nsplit;
+  const int b_lo = blockIdx.y * per;
+  const int b_hi = b_lo + per < nblk ? b_lo + per : nblk;
+  const bf16_t *bg_e = B_gate + (int64_t)e * f * r;
+  const bf16_t *bu_e = B_up + (int64_t)e * f * r;
+  const bf16_t *ad_e = AdT + (int64_t)e * f * r;
+  const bf16_t *bgt_e = BgT + (int64_t)e * r * f;
+  const bf16_t *but_e = BuT + (int64_t)e * r * f;
+
+  for (int cb = b_lo + wave; cb < b_hi; cb += FT_WAVES) {
+    const int c0 = cb * 32;
+    f32x16_t dgm, dum, ddm;
+#pragma unroll
+    for (int i = 0; i < 16; i++) dgm[i] = dum[i] = ddm[i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KSR_MAX; ks++) {
+      if (ks < ksr) {
+        const int q0 = ks * 16 + hi * 8;
+        bf16x8_t wg = zero8(), wu = zero8(), wd = zero8();
+        if (q0 < r) {
+          const int64_t o = (int64_t)(c0 + l31) * r + q0;
+          wg = *reinterpret_cast<const bf16x8_t *>(bg_e + o);
+          wu = *reinterpret_cast<const bf16x8_t *>(bu_e + o);
+          wd = *reinterpret_cast<const bf16x8_t *>(ad_e + o);
+        }
+        dgm = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wg, pg[ks], dgm, 0, 0, 0);
+        dum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wu, pu[ks], dum, 0, 0, 0);
+        ddm = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wd, vw[ks], ddm, 0, 0, 0);
+      }
+    }
+    const int64_t tin = t * f + c0 + hi * 4;
+    const int64_t rout = (int64_t)row * f + c0 + hi * 4;
+    bf16x4_t dgv[4], duv[4];
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+      const bf16x4_t gv = *reinterpret_cast<const bf16x4_t *>(G + tin + g * 8);
+      const bf16x4_t uv = *reinterpret_cast<const bf16x4_t *>(U + tin + g * 8);
+      const bf16x4_t hv = *reinterpret_cast<const bf16x4_t *>(H + tin + g * 8);
+#pragma unroll
+      for (int m = 0; m < 4; m++) {
+        const float gg = (float)gv[m] + s * dgm[g * 4 + m];
+        const float uu = (float)uv[m] + s * dum[g * 4 + m];
+        const float hh = (float)hv[m];
+        const float sg = fsigmoid(gg);
+        const float da = wrow * hh + s * ddm[g * 4 + m];
+        dwacc = fmaf(hh, gg * sg * uu, dwacc);
+        dgv[g][m] = (bf16_t)(da * uu * sg * (1.f + gg * (1.f - sg)));
+        duv[g][m] = (bf16_t)(da * gg * sg);
+      }
+      if (rvalid) {
+        *reinterpret_cast<bf16x4_t *>(dg_grp + rout + g * 8) = dgv[g];
+        *reinterpret_cast<bf16x4_t *>(du_grp + rout + g * 8) = duv[g];
+      }
+    }
+#pragma unroll
+    for (int s2 = 0; s2 < 2; s2++) {
+      bf16x8_t fg, fu;
+#pragma unroll
+      for (int m = 0; m < 4; m++) {
+        fg[m] = dgv[2 * s2][m]; fg[4 + m] = dgv[2 * s2 + 1][m];
+        fu[m] = duv[2 * s2][m]; fu[4 + m] = duv[2 * s2 + 1][m];
+      }
+#pragma unroll
+      for (int j = 0; j < NQ_MAX; j++) {
+        if (j < nq) {
+          const int q = j * 32 + l31;
+          bf16x8_t wg = zero8(), wu = zero8();
+          if (q < r) {
+            const int64_t o = (int64_t)q * f + c0 + 16 * s2 + hi * 4;
+            wg = join44(bgt_e + o, bgt_e + o + 8);
+            wu = join44(but_e + o, but_e + o + 8);
+          }
+          acctg[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fg, wg, acctg[j], 0, 0, 0);
+          acctu[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fu, wu, acctu[j], 0, 0, 0);
+        }
+      }
+    }
+  }
+  // <H, a> per row: the two half-waves hold complementary columns of the same row
+  dwacc += __shfl_xor(dwacc, 32, 64);
+  if (hi == 0) dwred[wave][l31] = dwacc;
+  // rank-r sums: add the 4 waves in a fixed order, gate bank first, then up
+  for (int bank = 0; bank < 2; bank++) {
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < NQ_MAX; j++)
+#pragma unroll
+      for (int i = 0; i < 16; i++) red[wave][j][i][lane] = bank == 0 ? acctg[j][i] : acctu[j][i];
+    __syncthreads();
+    float *out = bank == 0 ? TG_part : TU_part;
+    for (int idx = threadIdx.x; idx < NQ_MAX * 16 * 64; idx += FT_WAVES * 64) {
+      const int j = idx / (16 * 64), i = (idx / 64) % 16, ln = idx % 64;
+      const int q = j * 32 + (ln & 31);
+      const int rr = 8 * (i >> 2) + 4 * (ln >> 5) + (i & 3);
+      if (j < nq && q < r && rr < rows) {
+        const float v = (red[0][j][i][ln] + red[1][j][i][ln]) + (red[2][j][i][ln] + red[3][j][i][ln]);
+        out[((int64_t)blockIdx.y * nP + row0 + rr) * r + q] = v;
+      }
+    }
+  }
+  if (threadIdx.x < rows)
+    dw_part[(int64_t)(row0 + threadIdx.x) * nsplit + blockIdx.y] =
+        (dwred[0][threadIdx.x] + dwred[1][threadIdx.x]) + (dwred[2][threadIdx.x] + dwred[3][threadIdx.x]);
+}
+
 // dense[row, e(row)*r + q] = sum over splits of part[split][row][q]   (fixed order)
 __global__ void reduce_rank_parts_kernel(PairCtx pc, const float *__restrict__ part, int nsplit,
                                          float *__restrict__ dense) {
@@ -223,6 +375,29 @@ hipError_t launch_swiglu_fwd_mfma(const PairCtx &pc, int f, float s, const void 
   const int64_t n = (int64_t)nP * pc.r;
   hipLaunchKernelGGL(reduce_rank_parts_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
                      pc, Q_part, nsplit, Q_all);
+  return hipGetLastError();
+}
+
+hipError_t launch_swiglu_bwd_mfma(const PairCtx &pc, int f, float s, const void *G, const void *U,
+                                  const void *H, const float *Pg_all, const float *Pu_all,
+                                  const float *VB_all, const void *B_gate, const void *B_up,
+                                  const void *AdT, const void *BgT, const void *BuT, void *dg_grp,
+                                  void *du_grp, float *dw_part, float *rank_part, float *TG_all,
+                                  float *TU_all, hipStream_t st) {
+  const int nP = pc.T * pc.k, nsplit = fused_splits(f);
+  float *TG_part = rank_part, *TU_part = rank_part + (size_t)8 * nP * pc.r;
+  const dim3 grid((nP + FT_ROWS - 1) / FT_ROWS + pc.N, nsplit), block(FT_WAVES * 64);
+  hipLaunchKernelGGL(swiglu_bwd_mfma_kernel, grid, block, 0, st, pc, f, s, (const bf16_t *)G,
+                     (const bf16_t *)U, (const bf16_t *)H, Pg_all, Pu_all, VB_all,
+                     (const bf16_t *)B_gate, (const bf16_t *)B_up, (const bf16_t *)AdT,
+                     (const bf16_t *)BgT, (const bf16_t *)BuT, (bf16_t *)dg_grp, (bf16_t *)du_grp,
+                     dw_part, TG_part, TU_part, nsplit);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int64_t n = (int64_t)nP * pc.r;
+  const dim3 rgrid((unsigned)((n + 255) / 256));
+  hipLaunchKernelGGL(reduce_rank_parts_kernel, rgrid, dim3(256), 0, st, pc, TG_part, nsplit, TG_all);
+  hipLaunchKernelGGL(reduce_rank_parts_kernel, rgrid, dim3(256), 0, st, pc, TU_part, nsplit, TU_all);
   return hipGetLastError();
 }
 
