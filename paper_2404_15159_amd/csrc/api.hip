@@ -26,7 +26,8 @@ struct Layout {
   size_t fwd_end;
   // backward scratch
   size_t WdT, WgT, WuT, H, Bd_T, VB_all, dg_grp, du_grp, dgsum, dusum, dw_part, dw, Bg_T, Bu_T, AdT,
-      TG_all, TU_all, small[6], S, Bx, dz, partials;
+      TG_all, TU_all, small[6], S, Bx, dz, partials, dzT;
+  int ldT, ldTz;
   size_t partial_floats;
   size_t bwd_end;
   int Kx, nct;
@@ -80,7 +81,10 @@ Layout make_layout(const mixlora_dims &D) {
   L.AdT = take(R * f * E);
   L.TG_all = take(kT * R * 4);
   L.TU_all = take(kT * R * 4);
-  for (int i = 0; i < 6; i++) L.small[i] = take(kT * r * 4);
+  L.ldT = (int)((kT + 15) / 16 * 16 + 16);   // transposed bf16 factors, padded for whole MFMA steps
+  L.ldTz = (int)((T + 15) / 16 * 16 + 16);
+  for (int i = 0; i < 6; i++) L.small[i] = take(kT * r * 4 > (size_t)L.ldT * r * 2 ? kT * r * 4 : (size_t)L.ldT * r * 2);
+  L.dzT = take((size_t)L.ldTz * N * 2);
   L.S = take(T * (size_t)L.Kx * E);
   L.Bx = take(d * (size_t)L.Kx * E);
   L.dz = take(T * N * 4);
@@ -89,6 +93,10 @@ Layout make_layout(const mixlora_dims &D) {
   size_t pr = group_outer_partial_floats(1, (int)N, (int)d);
   L.partial_floats = pf > pd ? pf : pd;
   if (pr > L.partial_floats) L.partial_floats = pr;
+  for (size_t v : {group_outer_mfma_partial_floats((int)N, (int)r, (int)f),
+                   group_outer_mfma_partial_floats((int)N, (int)r, (int)d),
+                   group_outer_mfma_partial_floats(1, (int)N, (int)d)})
+    if (v > L.partial_floats) L.partial_floats = v;
   L.partials = take(L.partial_floats * 4);
   L.bwd_end = o;
   return L;
@@ -324,39 +332,44 @@ int mixlora_ffn_backward(const mixlora_dims *dims, const mixlora_weights *w, con
   }
   HIP_TRY(launch_pair_combine(dt, pc, f, ws + L.dg_grp, ws + L.dgsum, 0, st));
   HIP_TRY(launch_pair_combine(dt, pc, f, ws + L.du_grp, ws + L.dusum, 0, st));
-  // compact per-row rank-r factors of the LoRA gradients
-  float *Pg_grp = (float *)(ws + L.small[0]), *Pu_grp = (float *)(ws + L.small[1]);
-  float *TG_grp = (float *)(ws + L.small[2]), *TU_grp = (float *)(ws + L.small[3]);
-  float *Vw_grp = (float *)(ws + L.small[4]), *wQ_grp = (float *)(ws + L.small[5]);
-  HIP_TRY(launch_gather_small(pc, (float *)(ws + L.Pg_all), 1, 0, Pg_grp, st));
-  HIP_TRY(launch_gather_small(pc, (float *)(ws + L.Pu_all), 1, 0, Pu_grp, st));
-  HIP_TRY(launch_gather_small(pc, (float *)(ws + L.TG_all), 0, 0, TG_grp, st));
-  HIP_TRY(launch_gather_small(pc, (float *)(ws + L.TU_all), 0, 0, TU_grp, st));
-  HIP_TRY(launch_gather_small(pc, (float *)(ws + L.VB_all), 1, 1, Vw_grp, st));
-  HIP_TRY(launch_gather_small(pc, (float *)(ws + L.Q_all), 0, 1, wQ_grp, st));
+  // per-row rank-r factors of the LoRA gradients, then the grouped outer-product sums:
+  //   dB_gate[e] = s sum dg (x) Pg ; dA_gate[e] = s sum TG (x) x ; same for up ;
+  //   dA_down[e] = s sum (w B_down^T dy) (x) a ; dB_down[e] = s sum dy (x) (w A_down a)
   float *part = (float *)(ws + L.partials);
   const size_t pfl = L.partial_floats;
-  // dB_gate[e] = s sum dg (x) Pg ; dA_gate[e] = s sum TG (x) x ; same for up
-  HIP_TRY(launch_group_outer(dt, offs, N, kT, nullptr, k, Pg_grp, r, ws + L.dg_grp, f, s, 0,
-                             grads->dB_gate, part, pfl, st));
-  HIP_TRY(launch_group_outer(dt, offs, N, kT, nullptr, k, Pu_grp, r, ws + L.du_grp, f, s, 0,
-                             grads->dB_up, part, pfl, st));
-  HIP_TRY(launch_group_outer(dt, offs, N, kT, pair_of_row, k, TG_grp, r, x, d, s, 1,
-                             grads->dA_gate, part, pfl, st));
-  HIP_TRY(launch_group_outer(dt, offs, N, kT, pair_of_row, k, TU_grp, r, x, d, s, 1,
-                             grads->dA_up, part, pfl, st));
-  // dA_down[e] = s sum (w B_down^T dy) (x) a ; dB_down[e] = s sum dy (x) (w A_down a)
-  HIP_TRY(launch_group_outer(dt, offs, N, kT, nullptr, k, Vw_grp, r, ws + L.a_grp, f, s, 1,
-                             grads->dA_down, part, pfl, st));
-  HIP_TRY(launch_group_outer(dt, offs, N, kT, pair_of_row, k, wQ_grp, r, dy, d, s, 0,
-                             grads->dB_down, part, pfl, st));
-  // router: dw -> dz (also written into the K-extension operand S), dW_router = dz^T x
+  const float *fsrc[6] = {(float *)(ws + L.Pg_all), (float *)(ws + L.Pu_all),
+                          (float *)(ws + L.TG_all), (float *)(ws + L.TU_all),
+                          (float *)(ws + L.VB_all), (float *)(ws + L.Q_all)};
+  const int by_token[6] = {1, 1, 0, 0, 1, 0}, weighted[6] = {0, 0, 0, 0, 1, 1};
+  const void *wide[6] = {ws + L.dg_grp, ws + L.du_grp, x, x, ws + L.a_grp, dy};
+  const int32_t *gat[6] = {nullptr, nullptr, pair_of_row, pair_of_row, nullptr, pair_of_row};
+  const int width[6] = {f, f, d, d, f, d}, layout_qc[6] = {0, 0, 1, 1, 1, 0};
+  float *gout[6] = {grads->dB_gate, grads->dB_up, grads->dA_gate, grads->dA_up,
+                    grads->dA_down, grads->dB_down};
+  // router: dw -> dz (also written into the K-extension operand S)
   HIP_TRY(launch_router_bwd(dt, pc, probs, (float *)(ws + L.dw_part), nct,
                             (float *)(ws + L.VB_all), (float *)(ws + L.Q_all), (float *)(ws + L.F),
                             s, d_aux, D.aux_coeff, (float *)(ws + L.dw), (float *)(ws + L.dz),
                             ws + L.S, Kx, 2 * R, Kx - 2 * R, st));
-  HIP_TRY(launch_group_outer(dt, (int32_t *)(ws + L.tok_offs), 1, T, nullptr, 1,
-                             (float *)(ws + L.dz), N, x, d, 1.f, 1, grads->dW_router, part, pfl, st));
+  if (dt == MIXLORA_BF16) {
+    for (int i = 0; i < 6; i++) {
+      HIP_TRY(launch_gather_small_T(pc, fsrc[i], by_token[i], weighted[i], ws + L.small[i], L.ldT, st));
+      HIP_TRY(launch_group_outer_mfma(offs, N, kT, gat[i], k, ws + L.small[i], L.ldT, r, wide[i],
+                                      width[i], s, layout_qc[i], gout[i], part, pfl, st));
+    }
+    // dW_router = dz^T x
+    HIP_TRY(launch_f32_to_bf16T((float *)(ws + L.dz), T, N, ws + L.dzT, L.ldTz, st));
+    HIP_TRY(launch_group_outer_mfma((int32_t *)(ws + L.tok_offs), 1, T, nullptr, 1, ws + L.dzT,
+                                    L.ldTz, N, x, d, 1.f, 1, grads->dW_router, part, pfl, st));
+  } else {
+    for (int i = 0; i < 6; i++) {
+      HIP_TRY(launch_gather_small(pc, fsrc[i], by_token[i], weighted[i], (float *)(ws + L.small[i]), st));
+      HIP_TRY(launch_group_outer(dt, offs, N, kT, gat[i], k, (float *)(ws + L.small[i]), r, wide[i],
+                                 width[i], s, layout_qc[i], gout[i], part, pfl, st));
+    }
+    HIP_TRY(launch_group_outer(dt, (int32_t *)(ws + L.tok_offs), 1, T, nullptr, 1,
+                               (float *)(ws + L.dz), N, x, d, 1.f, 1, grads->dW_router, part, pfl, st));
+  }
   // dx = dgsum W_gate + dusum W_up + [TG | TU | dz] [s A_gate ; s A_up ; W_router]
   HIP_TRY(launch_scatter_blocks(dt, pc, (float *)(ws + L.TG_all), R, 1, 0, ws + L.S, Kx, 0, st));
   HIP_TRY(launch_scatter_blocks(dt, pc, (float *)(ws + L.TU_all), R, 1, 0, ws + L.S, Kx, R, st));

@@ -161,6 +161,19 @@ hipError_t launch_group_outer(int dtype, const int32_t *offs, int G, int max_row
                               float *partials, size_t partial_floats, hipStream_t st);
 size_t group_outer_partial_floats(int G, int r, int C);
 
+// bf16 MFMA version: smallT is the transposed bf16 factor [r][ldT] (ldT % 8 == 0, readable up to
+// the next multiple of 16 rows past the last group), wide is bf16 with C % 8 == 0.
+hipError_t launch_group_outer_mfma(const int32_t *offs, int G, int nrows,
+                                   const int32_t *pair_of_row, int k, const void *smallT, int ldT,
+                                   int r, const void *wide, int C, float scale, int layout_qc,
+                                   float *out, float *partials, size_t partial_floats,
+                                   hipStream_t st);
+size_t group_outer_mfma_partial_floats(int G, int r, int C);
+hipError_t launch_gather_small_T(const PairCtx &pc, const float *src, int by_token, int weighted,
+                                 void *outT, int ldT, hipStream_t st);
+hipError_t launch_f32_to_bf16T(const float *src, int rows, int r, void *outT, int ldT,
+                               hipStream_t st);
+
 hipError_t launch_router_bwd(int dtype, const PairCtx &pc, const float *probs, const float *dw_part,
                              int n_col_tiles, const float *VB_all, const float *Q_all,
                              const float *F, float s, float d_aux, float aux_coeff, float *dw_ws,

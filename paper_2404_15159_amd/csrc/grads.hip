@@ -131,6 +131,173 @@ hipError_t launch_group_outer(int dtype, const int32_t *offs, int G, int max_row
   return hipGetLastError();
 }
 
+// ---- bf16 MFMA version of the grouped outer-product sums ----------------------------------------
+// out[g][q][c] partial = sum over a slice of group g's rows of smallT[q][row] * wide[src(row)][c].
+// The contraction index is the row: first MFMA operand = wide (index = column, 8 rows per
+// lane, read as 2-byte-pair loads whose even/odd halves feed two column-interleaved MFMA
+// blocks), second operand = smallT (index = q, 8 consecutive rows = one 16-byte load from the
+// transposed bf16 copy).  Rows outside the group are masked in the small operand.
+typedef bf16_t bf16x2v_t __attribute__((ext_vector_type(2)));
+constexpr int GOM_NQ = 2;   // q <= 64
+
+template <bool GATHER>
+__global__ __launch_bounds__(256) void group_outer_mfma_kernel(
+    const int32_t *__restrict__ offs, const int32_t *__restrict__ pair_of_row, int k, int nrows,
+    const bf16_t *__restrict__ smallT, int ldT, int r, const bf16_t *__restrict__ wide, int C,
+    int nsplit, float *__restrict__ partial) {
+  const int g = blockIdx.y, sp = blockIdx.z, G = gridDim.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l31 = lane & 31, hi = lane >> 5;
+  const int lo = offs[g], hi_ = offs[g + 1];
+  const int base = lo & ~15;
+  const int nsteps = hi_ > lo ? (hi_ - base + 15) >> 4 : 0;
+  const int per = (nsteps + nsplit - 1) / nsplit;
+  const int st_lo = sp * per;
+  const int st_hi = st_lo + per < nsteps ? st_lo + per : nsteps;
+  const int c0 = (blockIdx.x * 4 + wave) * 64;
+  int ccol = c0 + 2 * l31;
+  if (ccol >= C) ccol = C - 2;
+  const int nq = (r + 31) >> 5;
+  f32x16_t acc[2][GOM_NQ];
+#pragma unroll
+  for (int a = 0; a < 2; a++)
+#pragma unroll
+    for (int j = 0; j < GOM_NQ; j++)
+#pragma unroll
+      for (int i = 0; i < 16; i++) acc[a][j][i] = 0.f;
+
+  for (int st = st_lo; st < st_hi; st++) {
+    const int rbase = base + st * 16 + hi * 8;
+    bf16x8_t bq[GOM_NQ];
+#pragma unroll
+    for (int j = 0; j < GOM_NQ; j++) {
+      const int q = j * 32 + l31;
+      bf16x8_t v;
+#pragma unroll
+      for (int p = 0; p < 8; p++) v[p] = (bf16_t)0.f;
+      if (j < nq && q < r) {
+        const bf16x8_t ld = *reinterpret_cast<const bf16x8_t *>(smallT + (int64_t)q * ldT + rbase);
+#pragma unroll
+        for (int p = 0; p < 8; p++) {
+          const int row = rbase + p;
+          v[p] = (row >= lo && row < hi_) ? ld[p] : (bf16_t)0.f;
+        }
+      }
+      bq[j] = v;
+    }
+    bf16x8_t fe, fo;
+#pragma unroll
+    for (int p = 0; p < 8; p++) {
+      int row = rbase + p;
+      row = row < nrows ? row : nrows - 1;
+      const int64_t src = GATHER ? pair_of_row[row] / k : row;
+      const bf16x2v_t v2 = *reinterpret_cast<const bf16x2v_t *>(wide + src * C + ccol);
+      fe[p] = v2[0];
+      fo[p] = v2[1];
+    }
+#pragma unroll
+    for (int j = 0; j < GOM_NQ; j++) {
+      if (j < nq) {
+        acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fe, bq[j], acc[0][j], 0, 0, 0);
+        acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo, bq[j], acc[1][j], 0, 0, 0);
+      }
+    }
+  }
+  // lane (q, hi) holds columns c0 + 2*(8*gg + 4*hi + m) + {0 (even block), 1 (odd block)}
+#pragma unroll
+  for (int j = 0; j < GOM_NQ; j++) {
+    const int q = j * 32 + l31;
+    if (j < nq && q < r) {
+      float *o = partial + (((int64_t)sp * G + g) * r + q) * C;
+#pragma unroll
+      for (int gg = 0; gg < 4; gg++) {
+        const int c = c0 + 16 * gg + 8 * hi;
+        if (c + 3 < C)
+          *reinterpret_cast<float4 *>(o + c) = make_float4(acc[0][j][gg * 4], acc[1][j][gg * 4],
+                                                           acc[0][j][gg * 4 + 1], acc[1][j][gg * 4 + 1]);
+        if (c + 7 < C)
+          *reinterpret_cast<float4 *>(o + c + 4) = make_float4(acc[0][j][gg * 4 + 2], acc[1][j][gg * 4 + 2],
+                                                               acc[0][j][gg * 4 + 3], acc[1][j][gg * 4 + 3]);
+      }
+    }
+  }
+}
+
+static int gom_splits(int G, int C) {
+  const int col_groups = (C + 255) / 256;
+  int s = 2048 / (col_groups * G);
+  if (s < 1) s = 1;
+  if (s > 32) s = 32;
+  return s;
+}
+
+size_t group_outer_mfma_partial_floats(int G, int r, int C) {
+  return (size_t)gom_splits(G, C) * G * r * C;
+}
+
+hipError_t launch_group_outer_mfma(const int32_t *offs, int G, int nrows,
+                                   const int32_t *pair_of_row, int k, const void *smallT, int ldT,
+                                   int r, const void *wide, int C, float scale, int layout_qc,
+                                   float *out, float *partials, size_t partial_floats,
+                                   hipStream_t st) {
+  const int nsplit = gom_splits(G, C);
+  if ((size_t)nsplit * G * r * C > partial_floats) return hipErrorInvalidValue;
+  const dim3 grid((C + 255) / 256, G, nsplit), block(256);
+  if (pair_of_row)
+    hipLaunchKernelGGL(group_outer_mfma_kernel<true>, grid, block, 0, st, offs, pair_of_row, k,
+                       nrows, (const bf16_t *)smallT, ldT, r, (const bf16_t *)wide, C, nsplit,
+                       partials);
+  else
+    hipLaunchKernelGGL(group_outer_mfma_kernel<false>, grid, block, 0, st, offs, pair_of_row, k,
+                       nrows, (const bf16_t *)smallT, ldT, r, (const bf16_t *)wide, C, nsplit,
+                       partials);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int64_t n = (int64_t)G * r * C;
+  hipLaunchKernelGGL(group_outer_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                     st, partials, G, r, C, nsplit, scale, layout_qc, out);
+  return hipGetLastError();
+}
+
+// smallT[q][row] (bf16, leading dimension ldT) = (w_row or 1) * src[(by_token ? t : row), e*r + q]
+__global__ void gather_small_T_kernel(PairCtx pc, const float *__restrict__ src, int by_token,
+                                      int weighted, bf16_t *__restrict__ outT, int ldT) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int nP = pc.T * pc.k;
+  if (i >= (int64_t)nP * pc.r) return;
+  const int q = (int)(i / nP), row = (int)(i % nP);
+  const int p = pc.pair_of_row[row];
+  const int e = pc.idx[p];
+  const int64_t srow = by_token ? p / pc.k : row;
+  const float w = weighted ? pc.w[p] : 1.f;
+  outT[(int64_t)q * ldT + row] = (bf16_t)(w * src[srow * (pc.N * pc.r) + e * pc.r + q]);
+}
+
+hipError_t launch_gather_small_T(const PairCtx &pc, const float *src, int by_token, int weighted,
+                                 void *outT, int ldT, hipStream_t st) {
+  const int64_t n = (int64_t)pc.T * pc.k * pc.r;
+  hipLaunchKernelGGL(gather_small_T_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, pc,
+                     src, by_token, weighted, (bf16_t *)outT, ldT);
+  return hipGetLastError();
+}
+
+// outT[q][row] (bf16) = src[row][q] (fp32, [rows, r])
+__global__ void f32_to_bf16T_kernel(const float *__restrict__ src, int rows, int r,
+                                    bf16_t *__restrict__ outT, int ldT) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)rows * r) return;
+  const int q = (int)(i / rows), row = (int)(i % rows);
+  outT[(int64_t)q * ldT + row] = (bf16_t)src[(int64_t)row * r + q];
+}
+
+hipError_t launch_f32_to_bf16T(const float *src, int rows, int r, void *outT, int ldT,
+                               hipStream_t st) {
+  const int64_t n = (int64_t)rows * r;
+  hipLaunchKernelGGL(f32_to_bf16T_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, src,
+                     rows, r, (bf16_t *)outT, ldT);
+  return hipGetLastError();
+}
+
 // ---- router backward -------------------------------------------------------------------------
 // One thread per token.  dw_j = <dy_t, o_pair> is assembled from the column-tile partials of
 // <H[t], a_row> plus the low-rank part  s <B_down[e]^T dy_t, A_down[e] a_row>.  Then, with
