@@ -21,8 +21,6 @@ typedef bf16_t bf16x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int FT_ROWS = 32;    // grouped rows per tile
 constexpr int FT_WAVES = 4;
-constexpr int KSR_MAX = 4;     // rank <= 64 -> at most 4 K steps of 16
-constexpr int NQ_MAX = 2;      // rank <= 64 -> at most 2 result blocks of 32
 
 __device__ __forceinline__ bool fused_tile_rows(const int32_t *offs, int N, int b, int &e,
                                                 int &row0, int &rows) {
@@ -77,13 +75,14 @@ __device__ __forceinline__ bf16x8_t join44(const bf16_t *p0, const bf16_t *p1) {
 
 // Forward: a_grp[row, :] and the per-split partial sums  Q_part[split][row][q] = sum over the
 // split's columns of a[row, c] * A_down[e, q, c].
+template <int KSR, int NQ>
 __global__ __launch_bounds__(FT_WAVES * 64) void swiglu_fwd_mfma_kernel(
     PairCtx pc, int f, float s, const bf16_t *__restrict__ G, const bf16_t *__restrict__ U,
     const float *__restrict__ Pg_all, const float *__restrict__ Pu_all,
     const bf16_t *__restrict__ B_gate, const bf16_t *__restrict__ B_up,
     const bf16_t *__restrict__ A_down, bf16_t *__restrict__ a_grp, float *__restrict__ Q_part,
     int nsplit) {
-  __shared__ float red[FT_WAVES][NQ_MAX][16][64];
+  __shared__ float red[FT_WAVES][NQ][16][64];
   int e, row0, rows;
   if (!fused_tile_rows(pc.offs, pc.N, blockIdx.x, e, row0, rows)) return;
   const int r = pc.r, R = pc.N * r, nP = pc.T * pc.k;
@@ -92,20 +91,19 @@ __global__ __launch_bounds__(FT_WAVES * 64) void swiglu_fwd_mfma_kernel(
   const bool rvalid = l31 < rows;
   const int row = row0 + (rvalid ? l31 : 0);
   const int64_t t = pc.pair_of_row[row] / pc.k;
-  const int ksr = (r + 15) >> 4, nq = (r + 31) >> 5;
 
   // per-row LoRA-A projections of this expert as second-operand fragments
-  bf16x8_t pg[KSR_MAX], pu[KSR_MAX];
+  bf16x8_t pg[KSR], pu[KSR];
 #pragma unroll
-  for (int ks = 0; ks < KSR_MAX; ks++) {
+  for (int ks = 0; ks < KSR; ks++) {
     const int q0 = ks * 16 + hi * 8;
-    const bool v = ks < ksr && q0 < r;
+    const bool v = q0 < r;
     pg[ks] = cvt8(Pg_all + t * R + e * r + (v ? q0 : 0), v, 1.f);
     pu[ks] = cvt8(Pu_all + t * R + e * r + (v ? q0 : 0), v, 1.f);
   }
-  f32x16_t accq[NQ_MAX];
+  f32x16_t accq[NQ];
 #pragma unroll
-  for (int j = 0; j < NQ_MAX; j++)
+  for (int j = 0; j < NQ; j++)
 #pragma unroll
     for (int i = 0; i < 16; i++) accq[j][i] = 0.f;
 
@@ -117,33 +115,62 @@ __global__ __launch_bounds__(FT_WAVES * 64) void swiglu_fwd_mfma_kernel(
   const bf16_t *bu_e = B_up + (int64_t)e * f * r;
   const bf16_t *ad_e = A_down + (int64_t)e * r * f;
 
+  bf16x4_t gnx[4], unx[4];
+  {
+    const int cbf = b_lo + wave < b_hi ? b_lo + wave : 0;   // any valid block if this wave has none
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+      gnx[g] = *reinterpret_cast<const bf16x4_t *>(G + t * f + cbf * 32 + hi * 4 + g * 8);
+      unx[g] = *reinterpret_cast<const bf16x4_t *>(U + t * f + cbf * 32 + hi * 4 + g * 8);
+    }
+  }
   for (int cb = b_lo + wave; cb < b_hi; cb += FT_WAVES) {
     const int c0 = cb * 32;
+    // (1) this block's weight fragments (L2-resident banks), (2) the NEXT block's gathered G/U
+    // runs.  Loads return in order, so waiting for (1) leaves (2) in flight during the math.
+    bf16x8_t wg[KSR], wu[KSR], wf[2][NQ];
+#pragma unroll
+    for (int ks = 0; ks < KSR; ks++) {
+      const int q0 = ks * 16 + hi * 8;
+      const int64_t o = (int64_t)(c0 + l31) * r + (q0 < r ? q0 : 0);
+      wg[ks] = *reinterpret_cast<const bf16x8_t *>(bg_e + o);
+      wu[ks] = *reinterpret_cast<const bf16x8_t *>(bu_e + o);
+    }
+#pragma unroll
+    for (int s2 = 0; s2 < 2; s2++)
+#pragma unroll
+      for (int j = 0; j < NQ; j++) {
+        const int q = j * 32 + l31;
+        const bf16_t *wp = ad_e + (int64_t)(q < r ? q : 0) * f + c0 + 16 * s2 + hi * 4;
+        wf[s2][j] = join44(wp, wp + 8);
+      }
+    bf16x4_t gcur[4], ucur[4];
+#pragma unroll
+    for (int g = 0; g < 4; g++) { gcur[g] = gnx[g]; ucur[g] = unx[g]; }
+    {   // unconditional (the last iteration re-reads its own block) so that the wait counts
+        // the compiler derives are the same on every path
+      const int cn = cb + FT_WAVES < b_hi ? c0 + FT_WAVES * 32 : c0;
+#pragma unroll
+      for (int g = 0; g < 4; g++) {
+        gnx[g] = *reinterpret_cast<const bf16x4_t *>(G + t * f + cn + hi * 4 + g * 8);
+        unx[g] = *reinterpret_cast<const bf16x4_t *>(U + t * f + cn + hi * 4 + g * 8);
+      }
+    }
     f32x16_t dg, du;
 #pragma unroll
     for (int i = 0; i < 16; i++) dg[i] = du[i] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < KSR_MAX; ks++) {
-      if (ks < ksr) {
-        const int q0 = ks * 16 + hi * 8;
-        const bool v = q0 < r;
-        bf16x8_t wg = zero8(), wu = zero8();
-        if (v) {
-          wg = *reinterpret_cast<const bf16x8_t *>(bg_e + (int64_t)(c0 + l31) * r + q0);
-          wu = *reinterpret_cast<const bf16x8_t *>(bu_e + (int64_t)(c0 + l31) * r + q0);
-        }
-        dg = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wg, pg[ks], dg, 0, 0, 0);
-        du = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wu, pu[ks], du, 0, 0, 0);
-      }
+    for (int ks = 0; ks < KSR; ks++) {
+      const bool v = ks * 16 + hi * 8 < r;
+      dg = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v ? wg[ks] : zero8(), pg[ks], dg, 0, 0, 0);
+      du = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v ? wu[ks] : zero8(), pu[ks], du, 0, 0, 0);
     }
-    const bf16_t *gp = G + t * f + c0 + hi * 4;
-    const bf16_t *up = U + t * f + c0 + hi * 4;
     bf16_t *ap = a_grp + (int64_t)row * f + c0 + hi * 4;
     bf16x4_t av[4];
 #pragma unroll
     for (int g = 0; g < 4; g++) {
-      const bf16x4_t gv = *reinterpret_cast<const bf16x4_t *>(gp + g * 8);
-      const bf16x4_t uv = *reinterpret_cast<const bf16x4_t *>(up + g * 8);
+      const bf16x4_t gv = gcur[g];
+      const bf16x4_t uv = ucur[g];
 #pragma unroll
       for (int m = 0; m < 4; m++) {
         const float gg = (float)gv[m] + s * dg[g * 4 + m];
@@ -159,30 +186,23 @@ __global__ __launch_bounds__(FT_WAVES * 64) void swiglu_fwd_mfma_kernel(
 #pragma unroll
       for (int m = 0; m < 4; m++) { af[m] = av[2 * s2][m]; af[4 + m] = av[2 * s2 + 1][m]; }
 #pragma unroll
-      for (int j = 0; j < NQ_MAX; j++) {
-        if (j < nq) {
-          const int q = j * 32 + l31;
-          bf16x8_t wf = zero8();
-          if (q < r) {
-            const bf16_t *wp = ad_e + (int64_t)q * f + c0 + 16 * s2 + hi * 4;
-            wf = join44(wp, wp + 8);
-          }
-          accq[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, wf, accq[j], 0, 0, 0);
-        }
+      for (int j = 0; j < NQ; j++) {
+        const bool v = j * 32 + l31 < r;
+        accq[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, v ? wf[s2][j] : zero8(), accq[j], 0, 0, 0);
       }
     }
   }
   // accq[j][i]: row 8*(i/4) + 4*hi + i%4 of the tile, q = j*32 + l31.  Sum the 4 waves.
 #pragma unroll
-  for (int j = 0; j < NQ_MAX; j++)
+  for (int j = 0; j < NQ; j++)
 #pragma unroll
     for (int i = 0; i < 16; i++) red[wave][j][i][lane] = accq[j][i];
   __syncthreads();
-  for (int idx = threadIdx.x; idx < NQ_MAX * 16 * 64; idx += FT_WAVES * 64) {
+  for (int idx = threadIdx.x; idx < NQ * 16 * 64; idx += FT_WAVES * 64) {
     const int j = idx / (16 * 64), i = (idx / 64) % 16, ln = idx % 64;
     const int q = j * 32 + (ln & 31);
     const int rr = 8 * (i >> 2) + 4 * (ln >> 5) + (i & 3);
-    if (j < nq && q < r && rr < rows) {
+    if (q < r && rr < rows) {
       const float v = (red[0][j][i][ln] + red[1][j][i][ln]) + (red[2][j][i][ln] + red[3][j][i][ln]);
       Q_part[((int64_t)blockIdx.y * nP + row0 + rr) * r + q] = v;
     }
@@ -196,6 +216,7 @@ __global__ __launch_bounds__(FT_WAVES * 64) void swiglu_fwd_mfma_kernel(
 //   dw_part[row][split]   = sum over the split's columns of H * a
 //   TG_part[split][row][q] = sum_c dg[row, c] * B_gate[e, c, q]   (and TU with du, B_up)
 // BgT / BuT are the banks re-laid as [N, r, f] so that the column index is contiguous.
+template <int KSR, int NQ>
 __global__ __launch_bounds__(FT_WAVES * 64) void swiglu_bwd_mfma_kernel(
     PairCtx pc, int f, float s, const bf16_t *__restrict__ G, const bf16_t *__restrict__ U,
     const bf16_t *__restrict__ H, const float *__restrict__ Pg_all,
@@ -204,7 +225,7 @@ __global__ __launch_bounds__(FT_WAVES * 64) void swiglu_bwd_mfma_kernel(
     const bf16_t *__restrict__ AdT, const bf16_t *__restrict__ BgT, const bf16_t *__restrict__ BuT,
     bf16_t *__restrict__ dg_grp, bf16_t *__restrict__ du_grp, float *__restrict__ dw_part,
     float *__restrict__ TG_part, float *__restrict__ TU_part, int nsplit) {
-  __shared__ float red[FT_WAVES][NQ_MAX][16][64];
+  __shared__ float red[FT_WAVES][NQ][16][64];
   __shared__ float dwred[FT_WAVES][32];
   int e, row0, rows;
   if (!fused_tile_rows(pc.offs, pc.N, blockIdx.x, e, row0, rows)) return;
@@ -216,21 +237,20 @@ __global__ __launch_bounds__(FT_WAVES * 64) void swiglu_bwd_mfma_kernel(
   const int pair = pc.pair_of_row[row];
   const int64_t t = pair / pc.k;
   const float wrow = pc.w[pair];
-  const int ksr = (r + 15) >> 4, nq = (r + 31) >> 5;
 
-  bf16x8_t pg[KSR_MAX], pu[KSR_MAX], vw[KSR_MAX];
+  bf16x8_t pg[KSR], pu[KSR], vw[KSR];
 #pragma unroll
-  for (int ks = 0; ks < KSR_MAX; ks++) {
+  for (int ks = 0; ks < KSR; ks++) {
     const int q0 = ks * 16 + hi * 8;
-    const bool v = ks < ksr && q0 < r;
+    const bool v = q0 < r;
     const int64_t o = t * R + e * r + (v ? q0 : 0);
     pg[ks] = cvt8(Pg_all + o, v, 1.f);
     pu[ks] = cvt8(Pu_all + o, v, 1.f);
     vw[ks] = cvt8(VB_all + o, v, wrow);
   }
-  f32x16_t acctg[NQ_MAX], acctu[NQ_MAX];
+  f32x16_t acctg[NQ], acctu[NQ];
 #pragma unroll
-  for (int j = 0; j < NQ_MAX; j++)
+  for (int j = 0; j < NQ; j++)
 #pragma unroll
     for (int i = 0; i < 16; i++) acctg[j][i] = acctu[j][i] = 0.f;
   float dwacc = 0.f;
@@ -245,35 +265,64 @@ __global__ __launch_bounds__(FT_WAVES * 64) void swiglu_bwd_mfma_kernel(
   const bf16_t *bgt_e = BgT + (int64_t)e * r * f;
   const bf16_t *but_e = BuT + (int64_t)e * r * f;
 
+  bf16x4_t gnx[4], unx[4], hnx[4];
+  {
+    const int cbf = b_lo + wave < b_hi ? b_lo + wave : 0;
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+      gnx[g] = *reinterpret_cast<const bf16x4_t *>(G + t * f + cbf * 32 + hi * 4 + g * 8);
+      unx[g] = *reinterpret_cast<const bf16x4_t *>(U + t * f + cbf * 32 + hi * 4 + g * 8);
+      hnx[g] = *reinterpret_cast<const bf16x4_t *>(H + t * f + cbf * 32 + hi * 4 + g * 8);
+    }
+  }
   for (int cb = b_lo + wave; cb < b_hi; cb += FT_WAVES) {
     const int c0 = cb * 32;
+    // weight fragments of this block first, then the next block's gathered runs (see forward)
+    bf16x8_t wg[KSR], wu[KSR], wd[KSR], tg[2][NQ], tu[2][NQ];
+#pragma unroll
+    for (int ks = 0; ks < KSR; ks++) {
+      const int q0 = ks * 16 + hi * 8;
+      const int64_t o = (int64_t)(c0 + l31) * r + (q0 < r ? q0 : 0);
+      wg[ks] = *reinterpret_cast<const bf16x8_t *>(bg_e + o);
+      wu[ks] = *reinterpret_cast<const bf16x8_t *>(bu_e + o);
+      wd[ks] = *reinterpret_cast<const bf16x8_t *>(ad_e + o);
+    }
+#pragma unroll
+    for (int s2 = 0; s2 < 2; s2++)
+#pragma unroll
+      for (int j = 0; j < NQ; j++) {
+        const int q = j * 32 + l31;
+        const int64_t o = (int64_t)(q < r ? q : 0) * f + c0 + 16 * s2 + hi * 4;
+        tg[s2][j] = join44(bgt_e + o, bgt_e + o + 8);
+        tu[s2][j] = join44(but_e + o, but_e + o + 8);
+      }
+    bf16x4_t gcur[4], ucur[4], hcur[4];
+#pragma unroll
+    for (int g = 0; g < 4; g++) { gcur[g] = gnx[g]; ucur[g] = unx[g]; hcur[g] = hnx[g]; }
+    {
+      const int64_t nx = t * f + (cb + FT_WAVES < b_hi ? c0 + FT_WAVES * 32 : c0) + hi * 4;
+#pragma unroll
+      for (int g = 0; g < 4; g++) {
+        gnx[g] = *reinterpret_cast<const bf16x4_t *>(G + nx + g * 8);
+        unx[g] = *reinterpret_cast<const bf16x4_t *>(U + nx + g * 8);
+        hnx[g] = *reinterpret_cast<const bf16x4_t *>(H + nx + g * 8);
+      }
+    }
     f32x16_t dgm, dum, ddm;
 #pragma unroll
     for (int i = 0; i < 16; i++) dgm[i] = dum[i] = ddm[i] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < KSR_MAX; ks++) {
-      if (ks < ksr) {
-        const int q0 = ks * 16 + hi * 8;
-        bf16x8_t wg = zero8(), wu = zero8(), wd = zero8();
-        if (q0 < r) {
-          const int64_t o = (int64_t)(c0 + l31) * r + q0;
-          wg = *reinterpret_cast<const bf16x8_t *>(bg_e + o);
-          wu = *reinterpret_cast<const bf16x8_t *>(bu_e + o);
-          wd = *reinterpret_cast<const bf16x8_t *>(ad_e + o);
-        }
-        dgm = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wg, pg[ks], dgm, 0, 0, 0);
-        dum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wu, pu[ks], dum, 0, 0, 0);
-        ddm = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wd, vw[ks], ddm, 0, 0, 0);
-      }
+    for (int ks = 0; ks < KSR; ks++) {
+      const bool v = ks * 16 + hi * 8 < r;
+      dgm = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v ? wg[ks] : zero8(), pg[ks], dgm, 0, 0, 0);
+      dum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v ? wu[ks] : zero8(), pu[ks], dum, 0, 0, 0);
+      ddm = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v ? wd[ks] : zero8(), vw[ks], ddm, 0, 0, 0);
     }
-    const int64_t tin = t * f + c0 + hi * 4;
     const int64_t rout = (int64_t)row * f + c0 + hi * 4;
     bf16x4_t dgv[4], duv[4];
 #pragma unroll
     for (int g = 0; g < 4; g++) {
-      const bf16x4_t gv = *reinterpret_cast<const bf16x4_t *>(G + tin + g * 8);
-      const bf16x4_t uv = *reinterpret_cast<const bf16x4_t *>(U + tin + g * 8);
-      const bf16x4_t hv = *reinterpret_cast<const bf16x4_t *>(H + tin + g * 8);
+      const bf16x4_t gv = gcur[g], uv = ucur[g], hv = hcur[g];
 #pragma unroll
       for (int m = 0; m < 4; m++) {
         const float gg = (float)gv[m] + s * dgm[g * 4 + m];
@@ -299,18 +348,10 @@ __global__ __launch_bounds__(FT_WAVES * 64) void swiglu_bwd_mfma_kernel(
         fu[m] = duv[2 * s2][m]; fu[4 + m] = duv[2 * s2 + 1][m];
       }
 #pragma unroll
-      for (int j = 0; j < NQ_MAX; j++) {
-        if (j < nq) {
-          const int q = j * 32 + l31;
-          bf16x8_t wg = zero8(), wu = zero8();
-          if (q < r) {
-            const int64_t o = (int64_t)q * f + c0 + 16 * s2 + hi * 4;
-            wg = join44(bgt_e + o, bgt_e + o + 8);
-            wu = join44(but_e + o, but_e + o + 8);
-          }
-          acctg[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fg, wg, acctg[j], 0, 0, 0);
-          acctu[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fu, wu, acctu[j], 0, 0, 0);
-        }
+      for (int j = 0; j < NQ; j++) {
+        const bool v = j * 32 + l31 < r;
+        acctg[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fg, v ? tg[s2][j] : zero8(), acctg[j], 0, 0, 0);
+        acctu[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fu, v ? tu[s2][j] : zero8(), acctu[j], 0, 0, 0);
       }
     }
   }
@@ -321,16 +362,16 @@ __global__ __launch_bounds__(FT_WAVES * 64) void swiglu_bwd_mfma_kernel(
   for (int bank = 0; bank < 2; bank++) {
     __syncthreads();
 #pragma unroll
-    for (int j = 0; j < NQ_MAX; j++)
+    for (int j = 0; j < NQ; j++)
 #pragma unroll
       for (int i = 0; i < 16; i++) red[wave][j][i][lane] = bank == 0 ? acctg[j][i] : acctu[j][i];
     __syncthreads();
     float *out = bank == 0 ? TG_part : TU_part;
-    for (int idx = threadIdx.x; idx < NQ_MAX * 16 * 64; idx += FT_WAVES * 64) {
+    for (int idx = threadIdx.x; idx < NQ * 16 * 64; idx += FT_WAVES * 64) {
       const int j = idx / (16 * 64), i = (idx / 64) % 16, ln = idx % 64;
       const int q = j * 32 + (ln & 31);
       const int rr = 8 * (i >> 2) + 4 * (ln >> 5) + (i & 3);
-      if (j < nq && q < r && rr < rows) {
+      if (q < r && rr < rows) {
         const float v = (red[0][j][i][ln] + red[1][j][i][ln]) + (red[2][j][i][ln] + red[3][j][i][ln]);
         out[((int64_t)blockIdx.y * nP + row0 + rr) * r + q] = v;
       }
@@ -367,9 +408,14 @@ hipError_t launch_swiglu_fwd_mfma(const PairCtx &pc, int f, float s, const void 
                                   float *Q_part, float *Q_all, hipStream_t st) {
   const int nP = pc.T * pc.k, nsplit = fused_splits(f);
   const dim3 grid((nP + FT_ROWS - 1) / FT_ROWS + pc.N, nsplit), block(FT_WAVES * 64);
-  hipLaunchKernelGGL(swiglu_fwd_mfma_kernel, grid, block, 0, st, pc, f, s, (const bf16_t *)G,
-                     (const bf16_t *)U, Pg_all, Pu_all, (const bf16_t *)B_gate,
-                     (const bf16_t *)B_up, (const bf16_t *)A_down, (bf16_t *)a_grp, Q_part, nsplit);
+#define MIXLORA_FWD(KSR_, NQ_)                                                                   \
+  hipLaunchKernelGGL((swiglu_fwd_mfma_kernel<KSR_, NQ_>), grid, block, 0, st, pc, f, s,           \
+                     (const bf16_t *)G, (const bf16_t *)U, Pg_all, Pu_all, (const bf16_t *)B_gate, \
+                     (const bf16_t *)B_up, (const bf16_t *)A_down, (bf16_t *)a_grp, Q_part, nsplit)
+  if (pc.r <= 16) MIXLORA_FWD(1, 1);
+  else if (pc.r <= 32) MIXLORA_FWD(2, 1);
+  else MIXLORA_FWD(4, 2);
+#undef MIXLORA_FWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int64_t n = (int64_t)nP * pc.r;
@@ -387,11 +433,16 @@ hipError_t launch_swiglu_bwd_mfma(const PairCtx &pc, int f, float s, const void 
   const int nP = pc.T * pc.k, nsplit = fused_splits(f);
   float *TG_part = rank_part, *TU_part = rank_part + (size_t)8 * nP * pc.r;
   const dim3 grid((nP + FT_ROWS - 1) / FT_ROWS + pc.N, nsplit), block(FT_WAVES * 64);
-  hipLaunchKernelGGL(swiglu_bwd_mfma_kernel, grid, block, 0, st, pc, f, s, (const bf16_t *)G,
-                     (const bf16_t *)U, (const bf16_t *)H, Pg_all, Pu_all, VB_all,
-                     (const bf16_t *)B_gate, (const bf16_t *)B_up, (const bf16_t *)AdT,
-                     (const bf16_t *)BgT, (const bf16_t *)BuT, (bf16_t *)dg_grp, (bf16_t *)du_grp,
-                     dw_part, TG_part, TU_part, nsplit);
+#define MIXLORA_BWD(KSR_, NQ_)                                                                   \
+  hipLaunchKernelGGL((swiglu_bwd_mfma_kernel<KSR_, NQ_>), grid, block, 0, st, pc, f, s,           \
+                     (const bf16_t *)G, (const bf16_t *)U, (const bf16_t *)H, Pg_all, Pu_all,      \
+                     VB_all, (const bf16_t *)B_gate, (const bf16_t *)B_up, (const bf16_t *)AdT,    \
+                     (const bf16_t *)BgT, (const bf16_t *)BuT, (bf16_t *)dg_grp, (bf16_t *)du_grp, \
+                     dw_part, TG_part, TU_part, nsplit)
+  if (pc.r <= 16) MIXLORA_BWD(1, 1);
+  else if (pc.r <= 32) MIXLORA_BWD(2, 1);
+  else MIXLORA_BWD(4, 2);
+#undef MIXLORA_BWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int64_t n = (int64_t)nP * pc.r;
