@@ -153,7 +153,7 @@ def main():
                    "paper_schedule_tflop_per_step": (fwd_paper + (bwd_paper if do_bwd else 0)) / 1e12,
                    "mfma_frac_whole_step": step_flops / (ms_per_step / 1e3) / MFMA_BF16_PEAK,
                    "input_generation_s": round(t_inputs, 1)},
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_dl_kernel<256,256,32,4 stages>",
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_dl_kernel<256,256,64,2 stages,8 waves>",
                      "achieved": achieved / 1e12, "peak": MFMA_BF16_PEAK / 1e12,
                      "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK,
                      "launches_per_step": launches_per_step,

@@ -15,7 +15,7 @@ namespace {
 
 constexpr size_t ALIGN = 256;
 inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
-inline int up32(int v) { return (v + 31) / 32 * 32; }
+inline int up64(int v) { return (v + 63) / 64 * 64; }
 
 struct Layout {
   // saved by forward
@@ -62,7 +62,7 @@ Layout make_layout(const mixlora_dims &D) {
   L.Bd_cat = take(d * R * E);
   L.rank_part = take(2 * 8 * kT * r * 4);   // per-split rank-r partial sums (two banks)
   L.fwd_end = o;
-  L.Kx = up32((int)(2 * R) + (int)N);   // whole K tiles of the GEMM's DMA path
+  L.Kx = up64((int)(2 * R) + (int)N);   // whole K tiles of the GEMM's DMA path
   L.nct = swiglu_col_tiles((int)f);
   L.WdT = take(f * d * E);
   L.WgT = take(f * d * E);

@@ -11,8 +11,6 @@
 // K segments (low-rank K-extension) or through the element-wise kernels.
 #include "common.h"
 
-#include <cstdlib>
-
 namespace mixlora {
 
 struct GemmBatch {
@@ -215,7 +213,7 @@ __device__ __forceinline__ const void *uniform_ptr(const void *p) {
   return reinterpret_cast<const void *>(((uint64_t)hi << 32) | lo);
 }
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, typename OutT>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, typename OutT, bool PIPE = false>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_dl_kernel(GemmBatch args) {
   constexpr int NW = WGM * WGN;
   constexpr int ROWB = BK * 2;            // bytes per tile row in LDS
@@ -227,7 +225,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_dl_kernel(GemmBatch a
   constexpr int STAGE_BYTES = (BM + BN) * ROWB;
   constexpr int TM = BM / WGM, TN = BN / WGN, MI = TM / 32, NI = TN / 32, KS = BK / 16;
   static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile/waves mismatch");
-  static_assert((STAGES - 2) * IPW < 64 && STAGES >= 3, "ring depth");
+  static_assert((STAGES - 2) * IPW < 64 && STAGES >= 2, "ring depth");
 
   extern __shared__ __align__(16) unsigned char smem[];
   const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char *)smem;
@@ -317,32 +315,75 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_dl_kernel(GemmBatch a
   const unsigned char *a_rd = smem + (wm * TM + l31) * ROWB;
   const unsigned char *b_rd = smem + BM * ROWB + (wn * TN + l31) * ROWB;
 
-  for (int it = 0; it < total_tiles; it++) {
+  auto wait_tile = [&](int it) {
     // tiles it+1 .. min(it+STAGES-2, last) may stay in flight; tile `it` must have landed
     const int newer = total_tiles - 1 - it;
     if (newer >= STAGES - 2) wait_vmcnt<(STAGES - 2) * IPW>();
     else if (STAGES > 3 && newer == 1) wait_vmcnt<IPW>();
     else if (STAGES > 4 && newer == 2) wait_vmcnt<2 * IPW>();
     else wait_vmcnt<0>();
-    __syncthreads();
-    issue_next();   // refills the slot that tile it-1 occupied: every wave is past reading it
-    const int st = it % STAGES;
-    const unsigned char *a = a_rd + st * STAGE_BYTES;
-    const unsigned char *b = b_rd + st * STAGE_BYTES;
+  };
+  if constexpr (!PIPE) {
+    for (int it = 0; it < total_tiles; it++) {
+      wait_tile(it);
+      __syncthreads();
+      issue_next();   // refills the slot that tile it-1 occupied: every wave is past reading it
+      const int st = it % STAGES;
+      const unsigned char *a = a_rd + st * STAGE_BYTES;
+      const unsigned char *b = b_rd + st * STAGE_BYTES;
 #pragma unroll
-    for (int ks = 0; ks < KS; ks++) {
-      bf16x8_t af[MI], bfr[NI];
+      for (int ks = 0; ks < KS; ks++) {
+        bf16x8_t af[MI], bfr[NI];
 #pragma unroll
-      for (int i = 0; i < MI; i++)
-        af[i] = *reinterpret_cast<const bf16x8_t *>(a + i * 32 * ROWB + koff[ks]);
-#pragma unroll
-      for (int j = 0; j < NI; j++)
-        bfr[j] = *reinterpret_cast<const bf16x8_t *>(b + j * 32 * ROWB + koff[ks]);
-#pragma unroll
-      for (int i = 0; i < MI; i++)
+        for (int i = 0; i < MI; i++)
+          af[i] = *reinterpret_cast<const bf16x8_t *>(a + i * 32 * ROWB + koff[ks]);
 #pragma unroll
         for (int j = 0; j < NI; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          bfr[j] = *reinterpret_cast<const bf16x8_t *>(b + j * 32 * ROWB + koff[ks]);
+#pragma unroll
+        for (int i = 0; i < MI; i++)
+#pragma unroll
+          for (int j = 0; j < NI; j++)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+      }
+    }
+  } else {
+    // Register double-buffered fragments: the LDS reads of K step s+1 (or of the next tile's
+    // first step, right after its barrier) are issued before the MFMAs of step s.
+    bf16x8_t af[2][MI], bfr[2][NI];
+    auto load_frags = [&](int buf, int st, int ks) {
+      const unsigned char *a = a_rd + st * STAGE_BYTES + koff[ks];
+      const unsigned char *b = b_rd + st * STAGE_BYTES + koff[ks];
+#pragma unroll
+      for (int i = 0; i < MI; i++) af[buf][i] = *reinterpret_cast<const bf16x8_t *>(a + i * 32 * ROWB);
+#pragma unroll
+      for (int j = 0; j < NI; j++) bfr[buf][j] = *reinterpret_cast<const bf16x8_t *>(b + j * 32 * ROWB);
+    };
+    wait_tile(0);
+    __syncthreads();
+    issue_next();
+    load_frags(0, 0, 0);
+    for (int it = 0; it < total_tiles; it++) {
+      const int st = it % STAGES;
+#pragma unroll
+      for (int ks = 0; ks < KS; ks++) {
+        const int cur = ks & 1, nxt = cur ^ 1;   // KS is even, so step 0 always uses buffer 0
+        if (ks + 1 < KS) {
+          load_frags(nxt, st, ks + 1);
+        } else if (it + 1 < total_tiles) {
+          wait_tile(it + 1);
+          __syncthreads();
+          issue_next();
+          load_frags(nxt, (it + 1) % STAGES, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < MI; i++)
+#pragma unroll
+          for (int j = 0; j < NI; j++)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
   }
 
@@ -486,10 +527,10 @@ static hipError_t launch_bf16(const GemmBatch &b, int nprob, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, typename OutT>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, typename OutT, bool PIPE = false>
 static hipError_t launch_bf16_dl(const GemmBatch &b, int nprob, hipStream_t st) {
   constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * sizeof(bf16_t);
-  auto kern = gemm_bf16_dl_kernel<BM, BN, BK, STAGES, WGM, WGN, OutT>;
+  auto kern = gemm_bf16_dl_kernel<BM, BN, BK, STAGES, WGM, WGN, OutT, PIPE>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -524,15 +565,6 @@ static bool dl_eligible(const GemmBatch &b, int nprob, int BK) {
   return true;
 }
 
-static int gemm_variant() {
-  static int v = -1;
-  if (v < 0) {
-    const char *e = getenv("MIXLORA_GEMM_VARIANT");
-    v = e ? atoi(e) : 1;
-  }
-  return v;
-}
-
 hipError_t launch_gemm(int dtype, const GemmProblem *probs, int nprob, hipStream_t st) {
   if (nprob < 1 || nprob > 2) return hipErrorInvalidValue;
   GemmBatch b;
@@ -550,13 +582,11 @@ hipError_t launch_gemm(int dtype, const GemmProblem *probs, int nprob, hipStream
     return f32out ? launch_bf16<128, 128, 64, 2, 2, float>(b, nprob, st)
                   : launch_bf16<128, 128, 64, 2, 2, bf16_t>(b, nprob, st);
   }
-  const int var = gemm_variant();
-  if (!f32out && var == 1 && dl_eligible(b, nprob, 32))
-    return launch_bf16_dl<256, 256, 32, 4, 2, 4, bf16_t>(b, nprob, st);
-  if (!f32out && var == 2 && dl_eligible(b, nprob, 64))
-    return launch_bf16_dl<256, 256, 64, 2 + 1, 2, 2, bf16_t>(b, nprob, st);
-  if (!f32out && var == 3 && dl_eligible(b, nprob, 32))
-    return launch_bf16_dl<256, 256, 32, 4, 2, 2, bf16_t>(b, nprob, st);
+  if (!f32out) {
+    // large tiles: direct-to-LDS ring; BK = 64 needs whole 64-wide K tiles, else BK = 32
+    if (dl_eligible(b, nprob, 64)) return launch_bf16_dl<256, 256, 64, 2, 2, 4, bf16_t, true>(b, nprob, st);
+    if (dl_eligible(b, nprob, 32)) return launch_bf16_dl<256, 256, 32, 4, 2, 4, bf16_t, false>(b, nprob, st);
+  }
   return f32out ? launch_bf16<256, 256, 64, 2, 4, float>(b, nprob, st)
                 : launch_bf16<256, 256, 64, 2, 4, bf16_t>(b, nprob, st);
 }
