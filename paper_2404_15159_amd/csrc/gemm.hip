@@ -38,6 +38,18 @@ template <typename OutT> __device__ __forceinline__ void store_c(OutT *p, float 
 template <> __device__ __forceinline__ void store_c<float>(float *p, float v) { *p = v; }
 template <> __device__ __forceinline__ void store_c<bf16_t>(bf16_t *p, float v) { *p = (bf16_t)v; }
 
+template <typename OutT>
+__device__ __forceinline__ void store_c4(OutT *p, float a, float b, float c, float d);
+template <> __device__ __forceinline__ void store_c4<float>(float *p, float a, float b, float c, float d) {
+  *reinterpret_cast<float4 *>(p) = make_float4(a, b, c, d);
+}
+template <> __device__ __forceinline__ void store_c4<bf16_t>(bf16_t *p, float a, float b, float c, float d) {
+  typedef bf16_t bf16x4v_t __attribute__((ext_vector_type(4)));
+  bf16x4v_t v;
+  v[0] = (bf16_t)a; v[1] = (bf16_t)b; v[2] = (bf16_t)c; v[3] = (bf16_t)d;
+  *reinterpret_cast<bf16x4v_t *>(p) = v;
+}
+
 template <int BM, int BN, int BK, int WGM, int WGN, typename OutT>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_kernel(GemmBatch args) {
   constexpr int NT = WGM * WGN * 64;
@@ -344,7 +356,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_dl_kernel(GemmBatch a
         for (int i = 0; i < MI; i++)
 #pragma unroll
           for (int j = 0; j < NI; j++)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
       }
     }
   } else {
@@ -381,28 +393,38 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_dl_kernel(GemmBatch a
         for (int i = 0; i < MI; i++)
 #pragma unroll
           for (int j = 0; j < NI; j++)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][j], af[cur][i], acc[i][j], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
 
+  // The weight fragment is the FIRST MFMA operand, so a lane holds, for its row (lane % 32),
+  // the columns 8g + 4*(lane/32) + m: four runs of 4 consecutive outputs -> 8/16-byte stores.
   OutT *C = reinterpret_cast<OutT *>(P.C);
-  const int cbase = col0 + wn * TN + l31;
-  const int rbase = row0 + wm * TM + hi * 4;
+  const int cbase = col0 + wn * TN + hi * 4;
+  const int rbase = row0 + wm * TM + l31;
 #pragma unroll
-  for (int i = 0; i < MI; i++)
+  for (int i = 0; i < MI; i++) {
+    const int r = rbase + i * 32;
+    if (r < M) {
 #pragma unroll
-    for (int j = 0; j < NI; j++) {
-      const int c = cbase + j * 32;
-      if (c < N) {
+      for (int j = 0; j < NI; j++)
 #pragma unroll
-        for (int e = 0; e < 16; e++) {
-          const int r = rbase + i * 32 + (e >> 2) * 8 + (e & 3);
-          if (r < M) store_c<OutT>(C + (int64_t)r * P.ldc + c, acc[i][j][e]);
+        for (int g = 0; g < 4; g++) {
+          const int c = cbase + j * 32 + g * 8;
+          OutT *o = C + (int64_t)r * P.ldc + c;
+          if (c + 3 < N && (P.ldc & 3) == 0) {
+            store_c4<OutT>(o, acc[i][j][g * 4], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2],
+                           acc[i][j][g * 4 + 3]);
+          } else {
+#pragma unroll
+            for (int m = 0; m < 4; m++)
+              if (c + m < N) store_c<OutT>(o + m, acc[i][j][g * 4 + m]);
+          }
         }
-      }
     }
+  }
 }
 
 // ---- fp32 storage: 64x64 tile, 256 threads, 4x4 outputs per thread ----------------------

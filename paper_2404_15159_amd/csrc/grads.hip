@@ -137,10 +137,15 @@ hipError_t launch_group_outer(int dtype, const int32_t *offs, int G, int max_row
 // lane, read as 2-byte-pair loads whose even/odd halves feed two column-interleaved MFMA
 // blocks), second operand = smallT (index = q, 8 consecutive rows = one 16-byte load from the
 // transposed bf16 copy).  Rows outside the group are masked in the small operand.
-typedef bf16_t bf16x2v_t __attribute__((ext_vector_type(2)));
-constexpr int GOM_NQ = 2;   // q <= 64
+constexpr int GOM_NQ = 2;     // q <= 64
+constexpr int GOM_CB = 8;     // column blocks per wave: a lane reads 8 adjacent columns (16 bytes)
 
-template <bool GATHER>
+// A wave covers 256 columns: lane (l31, hi) reads, for each of its 8 rows, the 16-byte run of
+// columns c0 + 8*l31 .. +7; element b of the run feeds MFMA block b, whose operand index i = l31
+// therefore stands for column c0 + 8*i + b.  In the result, lane (q, hi) register 4*gg + m of
+// block b is column c0 + 8*(8*gg + 4*hi + m) + b: for fixed (gg, m) the 8 blocks give 8
+// consecutive columns, stored as two float4.
+template <bool GATHER, int NQ>
 __global__ __launch_bounds__(256) void group_outer_mfma_kernel(
     const int32_t *__restrict__ offs, const int32_t *__restrict__ pair_of_row, int k, int nrows,
     const bf16_t *__restrict__ smallT, int ldT, int r, const bf16_t *__restrict__ wide, int C,
@@ -154,79 +159,77 @@ __global__ __launch_bounds__(256) void group_outer_mfma_kernel(
   const int per = (nsteps + nsplit - 1) / nsplit;
   const int st_lo = sp * per;
   const int st_hi = st_lo + per < nsteps ? st_lo + per : nsteps;
-  const int c0 = (blockIdx.x * 4 + wave) * 64;
-  int ccol = c0 + 2 * l31;
-  if (ccol >= C) ccol = C - 2;
-  const int nq = (r + 31) >> 5;
-  f32x16_t acc[2][GOM_NQ];
+  const int c0 = (blockIdx.x * 4 + wave) * (32 * GOM_CB);
+  if (c0 >= C) return;   // whole wave out of range (no barriers in this kernel)
+  int ccol = c0 + 8 * l31;
+  if (ccol >= C) ccol = C - 8;
+  f32x16_t acc[GOM_CB][NQ];
 #pragma unroll
-  for (int a = 0; a < 2; a++)
+  for (int b = 0; b < GOM_CB; b++)
 #pragma unroll
-    for (int j = 0; j < GOM_NQ; j++)
+    for (int j = 0; j < NQ; j++)
 #pragma unroll
-      for (int i = 0; i < 16; i++) acc[a][j][i] = 0.f;
+      for (int i = 0; i < 16; i++) acc[b][j][i] = 0.f;
 
   for (int st = st_lo; st < st_hi; st++) {
     const int rbase = base + st * 16 + hi * 8;
-    bf16x8_t bq[GOM_NQ];
+    bf16x8_t bq[NQ];
 #pragma unroll
-    for (int j = 0; j < GOM_NQ; j++) {
+    for (int j = 0; j < NQ; j++) {
       const int q = j * 32 + l31;
+      const bf16x8_t ld = *reinterpret_cast<const bf16x8_t *>(smallT + (int64_t)(q < r ? q : 0) * ldT + rbase);
       bf16x8_t v;
 #pragma unroll
-      for (int p = 0; p < 8; p++) v[p] = (bf16_t)0.f;
-      if (j < nq && q < r) {
-        const bf16x8_t ld = *reinterpret_cast<const bf16x8_t *>(smallT + (int64_t)q * ldT + rbase);
-#pragma unroll
-        for (int p = 0; p < 8; p++) {
-          const int row = rbase + p;
-          v[p] = (row >= lo && row < hi_) ? ld[p] : (bf16_t)0.f;
-        }
+      for (int p = 0; p < 8; p++) {
+        const int row = rbase + p;
+        v[p] = (q < r && row >= lo && row < hi_) ? ld[p] : (bf16_t)0.f;
       }
       bq[j] = v;
     }
-    bf16x8_t fe, fo;
+    bf16x8_t wrow[8];
 #pragma unroll
     for (int p = 0; p < 8; p++) {
       int row = rbase + p;
       row = row < nrows ? row : nrows - 1;
       const int64_t src = GATHER ? pair_of_row[row] / k : row;
-      const bf16x2v_t v2 = *reinterpret_cast<const bf16x2v_t *>(wide + src * C + ccol);
-      fe[p] = v2[0];
-      fo[p] = v2[1];
+      wrow[p] = *reinterpret_cast<const bf16x8_t *>(wide + src * C + ccol);
     }
 #pragma unroll
-    for (int j = 0; j < GOM_NQ; j++) {
-      if (j < nq) {
-        acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fe, bq[j], acc[0][j], 0, 0, 0);
-        acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo, bq[j], acc[1][j], 0, 0, 0);
-      }
+    for (int b = 0; b < GOM_CB; b++) {
+      bf16x8_t fa;
+#pragma unroll
+      for (int p = 0; p < 8; p++) fa[p] = wrow[p][b];
+#pragma unroll
+      for (int j = 0; j < NQ; j++)
+        acc[b][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, bq[j], acc[b][j], 0, 0, 0);
     }
   }
-  // lane (q, hi) holds columns c0 + 2*(8*gg + 4*hi + m) + {0 (even block), 1 (odd block)}
 #pragma unroll
-  for (int j = 0; j < GOM_NQ; j++) {
+  for (int j = 0; j < NQ; j++) {
     const int q = j * 32 + l31;
-    if (j < nq && q < r) {
+    if (q < r) {
       float *o = partial + (((int64_t)sp * G + g) * r + q) * C;
 #pragma unroll
-      for (int gg = 0; gg < 4; gg++) {
-        const int c = c0 + 16 * gg + 8 * hi;
-        if (c + 3 < C)
-          *reinterpret_cast<float4 *>(o + c) = make_float4(acc[0][j][gg * 4], acc[1][j][gg * 4],
-                                                           acc[0][j][gg * 4 + 1], acc[1][j][gg * 4 + 1]);
-        if (c + 7 < C)
-          *reinterpret_cast<float4 *>(o + c + 4) = make_float4(acc[0][j][gg * 4 + 2], acc[1][j][gg * 4 + 2],
-                                                               acc[0][j][gg * 4 + 3], acc[1][j][gg * 4 + 3]);
-      }
+      for (int gg = 0; gg < 4; gg++)
+#pragma unroll
+        for (int m = 0; m < 4; m++) {
+          const int c = c0 + 8 * (8 * gg + 4 * hi + m);
+          if (c + 7 < C) {
+            *reinterpret_cast<float4 *>(o + c) = make_float4(acc[0][j][gg * 4 + m], acc[1][j][gg * 4 + m],
+                                                             acc[2][j][gg * 4 + m], acc[3][j][gg * 4 + m]);
+            *reinterpret_cast<float4 *>(o + c + 4) = make_float4(acc[4][j][gg * 4 + m], acc[5][j][gg * 4 + m],
+                                                                 acc[6][j][gg * 4 + m], acc[7][j][gg * 4 + m]);
+          }
+        }
     }
   }
 }
 
 static int gom_splits(int G, int C) {
-  const int col_groups = (C + 255) / 256;
-  int s = 2048 / (col_groups * G);
+  const int col_groups = (C + 1023) / 1024;
+  int s = 1024 / (col_groups * G);
   if (s < 1) s = 1;
+  if (s > 8 && G > 1) s = 8;     // partial sums cost HBM traffic: nsplit * G * r * C floats
   if (s > 32) s = 32;
   return s;
 }
@@ -242,15 +245,14 @@ hipError_t launch_group_outer_mfma(const int32_t *offs, int G, int nrows,
                                    hipStream_t st) {
   const int nsplit = gom_splits(G, C);
   if ((size_t)nsplit * G * r * C > partial_floats) return hipErrorInvalidValue;
-  const dim3 grid((C + 255) / 256, G, nsplit), block(256);
-  if (pair_of_row)
-    hipLaunchKernelGGL(group_outer_mfma_kernel<true>, grid, block, 0, st, offs, pair_of_row, k,
-                       nrows, (const bf16_t *)smallT, ldT, r, (const bf16_t *)wide, C, nsplit,
-                       partials);
-  else
-    hipLaunchKernelGGL(group_outer_mfma_kernel<false>, grid, block, 0, st, offs, pair_of_row, k,
-                       nrows, (const bf16_t *)smallT, ldT, r, (const bf16_t *)wide, C, nsplit,
-                       partials);
+  const dim3 grid((C + 1023) / 1024, G, nsplit), block(256);
+#define MIXLORA_GOM(GA_, NQ_)                                                                   \
+  hipLaunchKernelGGL((group_outer_mfma_kernel<GA_, NQ_>), grid, block, 0, st, offs, pair_of_row, \
+                     k, nrows, (const bf16_t *)smallT, ldT, r, (const bf16_t *)wide, C, nsplit,   \
+                     partials)
+  if (pair_of_row) { if (r <= 32) MIXLORA_GOM(true, 1); else MIXLORA_GOM(true, 2); }
+  else { if (r <= 32) MIXLORA_GOM(false, 1); else MIXLORA_GOM(false, 2); }
+#undef MIXLORA_GOM
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int64_t n = (int64_t)G * r * C;
