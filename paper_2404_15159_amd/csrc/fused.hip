@@ -37,7 +37,9 @@ __device__ __forceinline__ bool fused_tile_rows(const int32_t *offs, int N, int 
   return false;
 }
 
-__device__ __forceinline__ float fsigmoid(float v) { return 1.f / (1.f + __expf(-v)); }
+// v_exp_f32 + v_rcp_f32 (about 1 ulp each): far inside the bf16 tolerance, a tenth of the
+// instructions of an IEEE division
+__device__ __forceinline__ float fsigmoid(float v) { return __builtin_amdgcn_rcpf(1.f + __expf(-v)); }
 
 // 8 consecutive fp32 -> bf16x8 (or zeros)
 __device__ __forceinline__ bf16x8_t cvt8(const float *p, bool valid, float scale) {
