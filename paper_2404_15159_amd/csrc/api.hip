@@ -225,7 +225,7 @@ int mixlora_ffn_forward(const mixlora_dims *dims, const mixlora_weights *w, cons
   }
   PairCtx pc{offs, pair_of_row, row_of_pair, wts, idx, T, N, k, r};
   // Algorithm 1 lines 11-13 on the routed pairs, expert-grouped rows
-  if (dt == MIXLORA_BF16 && f % 32 == 0) {
+  if (dt == MIXLORA_BF16) {
     // fused: LoRA deltas + SiLU * up + A_down of the row's expert, all on MFMA
     HIP_TRY(launch_swiglu_fwd_mfma(pc, f, D.lora_scale, ws + L.G, ws + L.U,
                                    (float *)(ws + L.Pg_all), (float *)(ws + L.Pu_all), w->B_gate,
@@ -311,7 +311,7 @@ int mixlora_ffn_backward(const mixlora_dims *dims, const mixlora_weights *w, con
   HIP_TRY(launch_pack_bank_T(dt, w->B_gate, N, f, r, ws + L.Bg_T, st));
   HIP_TRY(launch_pack_bank_T(dt, w->B_up, N, f, r, ws + L.Bu_T, st));
   int nct = L.nct;
-  if (dt == MIXLORA_BF16 && f % 32 == 0) {
+  if (dt == MIXLORA_BF16) {
     nct = fused_splits(f);
     HIP_TRY(launch_pack_bank_T(dt, w->A_down, N, r, f, ws + L.AdT, st));   // [N,r,f] -> [N,f,r]
     HIP_TRY(launch_swiglu_bwd_mfma(pc, f, s, ws + L.G, ws + L.U, ws + L.H, (float *)(ws + L.Pg_all),

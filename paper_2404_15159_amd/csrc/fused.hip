@@ -75,6 +75,37 @@ __device__ __forceinline__ bf16x8_t join44(const bf16_t *p0, const bf16_t *p1) {
   return o;
 }
 
+// ---- version 2 of the fused stages: coalesced global traffic ---------------------------------
+// The MFMA result layout gives a lane 4-column runs of 32 different rows, which makes every
+// gathered load and every store an 8-byte piece.  Here the rank-r MFMA results go through a
+// small per-wave LDS tile ([32 rows][64 columns] bf16, padded pitch) instead, and all global
+// traffic uses the "row-major" lane role: lane = (row 8p + lane/8, 8-column chunk lane%8), i.e.
+// 16 bytes per lane and 128 contiguous bytes per row per instruction.  The activation (or
+// gradient) tile is written back into the same LDS tile and read once more as MFMA first
+// operand (index = row, contraction = columns) for the rank-r products with A_down / B^T.
+// LDS operations of one wave execute in order, so the tiles need no workgroup barrier.
+constexpr int FT_SB = 64;                 // columns per super-block
+constexpr int FT_PITCH = FT_SB + 8;       // bf16 elements per LDS tile row (144 bytes)
+constexpr int FT_TILE = FT_ROWS * FT_PITCH;
+
+struct FusedRoles {
+  int lane, wave, l31, hi, rr, cc;
+};
+
+__device__ __forceinline__ bf16x8_t ld8(const bf16_t *p) { return *reinterpret_cast<const bf16x8_t *>(p); }
+
+// write one 32x32 MFMA result block (scaled) into an LDS tile at column offset cb32
+__device__ __forceinline__ void tile_put(bf16_t *tile, int l31, int hi, int cb32, const f32x16_t &d,
+                                         float scale) {
+#pragma unroll
+  for (int g = 0; g < 4; g++) {
+    bf16x4_t v;
+#pragma unroll
+    for (int m = 0; m < 4; m++) v[m] = (bf16_t)(scale * d[g * 4 + m]);
+    *reinterpret_cast<bf16x4_t *>(tile + l31 * FT_PITCH + cb32 + 8 * g + 4 * hi) = v;
+  }
+}
+
 // Forward: a_grp[row, :] and the per-split partial sums  Q_part[split][row][q] = sum over the
 // split's columns of a[row, c] * A_down[e, q, c].
 template <int KSR, int NQ>
@@ -84,24 +115,40 @@ __global__ __launch_bounds__(FT_WAVES * 64) void swiglu_fwd_mfma_kernel(
     const bf16_t *__restrict__ B_gate, const bf16_t *__restrict__ B_up,
     const bf16_t *__restrict__ A_down, bf16_t *__restrict__ a_grp, float *__restrict__ Q_part,
     int nsplit) {
-  __shared__ float red[FT_WAVES][NQ][16][64];
+  constexpr int TILES = 2;
+  constexpr int LDS_BYTES = FT_WAVES * TILES * FT_TILE * 2 > FT_WAVES * NQ * 16 * 64 * 4
+                                ? FT_WAVES * TILES * FT_TILE * 2 : FT_WAVES * NQ * 16 * 64 * 4;
+  __shared__ __align__(16) unsigned char lds[LDS_BYTES];
   int e, row0, rows;
   if (!fused_tile_rows(pc.offs, pc.N, blockIdx.x, e, row0, rows)) return;
   const int r = pc.r, R = pc.N * r, nP = pc.T * pc.k;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int l31 = lane & 31, hi = lane >> 5;
-  const bool rvalid = l31 < rows;
-  const int row = row0 + (rvalid ? l31 : 0);
-  const int64_t t = pc.pair_of_row[row] / pc.k;
+  const int l31 = lane & 31, hi = lane >> 5, rr = lane >> 3, cc = lane & 7;
+  bf16_t *tg = reinterpret_cast<bf16_t *>(lds) + wave * TILES * FT_TILE;
+  bf16_t *tu = tg + FT_TILE;
 
-  // per-row LoRA-A projections of this expert as second-operand fragments
+  // MFMA role: second-operand fragments of this lane's row
   bf16x8_t pg[KSR], pu[KSR];
+  {
+    const int64_t tm = pc.pair_of_row[row0 + (l31 < rows ? l31 : 0)] / pc.k;
 #pragma unroll
-  for (int ks = 0; ks < KSR; ks++) {
-    const int q0 = ks * 16 + hi * 8;
-    const bool v = q0 < r;
-    pg[ks] = cvt8(Pg_all + t * R + e * r + (v ? q0 : 0), v, 1.f);
-    pu[ks] = cvt8(Pu_all + t * R + e * r + (v ? q0 : 0), v, 1.f);
+    for (int ks = 0; ks < KSR; ks++) {
+      const int q0 = ks * 16 + hi * 8;
+      const bool v = q0 < r;
+      pg[ks] = cvt8(Pg_all + tm * R + e * r + (v ? q0 : 0), v, 1.f);
+      pu[ks] = cvt8(Pu_all + tm * R + e * r + (v ? q0 : 0), v, 1.f);
+    }
+  }
+  // row-major role: the four rows (8p + rr) this lane serves
+  int64_t gsrc[4], adst[4];
+  bool rvalid[4];
+#pragma unroll
+  for (int p = 0; p < 4; p++) {
+    const int rl = 8 * p + rr;
+    rvalid[p] = rl < rows;
+    const int row = row0 + (rvalid[p] ? rl : 0);
+    gsrc[p] = (int64_t)(pc.pair_of_row[row] / pc.k) * f;
+    adst[p] = (int64_t)row * f;
   }
   f32x16_t accq[NQ];
 #pragma unroll
@@ -109,92 +156,110 @@ __global__ __launch_bounds__(FT_WAVES * 64) void swiglu_fwd_mfma_kernel(
 #pragma unroll
     for (int i = 0; i < 16; i++) accq[j][i] = 0.f;
 
-  const int nblk = f / 32;                       // f % 32 == 0 is required by the launcher
-  const int per = (nblk + nsplit - 1) / nsplit;
-  const int b_lo = blockIdx.y * per;
-  const int b_hi = b_lo + per < nblk ? b_lo + per : nblk;
+  const int nsb = (f + FT_SB - 1) / FT_SB;
+  const int per = (nsb + nsplit - 1) / nsplit;
+  const int sb_lo = blockIdx.y * per;
+  const int sb_hi = sb_lo + per < nsb ? sb_lo + per : nsb;
   const bf16_t *bg_e = B_gate + (int64_t)e * f * r;
   const bf16_t *bu_e = B_up + (int64_t)e * f * r;
   const bf16_t *ad_e = A_down + (int64_t)e * r * f;
 
-  bf16x4_t gnx[4], unx[4];
-  {
-    const int cbf = b_lo + wave < b_hi ? b_lo + wave : 0;   // any valid block if this wave has none
+  // software pipeline: everything a super-block needs from memory is requested one iteration
+  // ahead, weights first (they are consumed first; loads complete in order)
+  bf16x8_t wg[2][KSR], wu[2][KSR], wf[4][NQ], gnx[4], unx[4];
+  auto load_w = [&](int c0) {
 #pragma unroll
-    for (int g = 0; g < 4; g++) {
-      gnx[g] = *reinterpret_cast<const bf16x4_t *>(G + t * f + cbf * 32 + hi * 4 + g * 8);
-      unx[g] = *reinterpret_cast<const bf16x4_t *>(U + t * f + cbf * 32 + hi * 4 + g * 8);
+    for (int b = 0; b < 2; b++) {
+      int col = c0 + 32 * b + l31;
+      col = col < f ? col : f - 1;
+#pragma unroll
+      for (int ks = 0; ks < KSR; ks++) {
+        const int q0 = ks * 16 + hi * 8;
+        const int64_t o = (int64_t)col * r + (q0 < r ? q0 : 0);
+        wg[b][ks] = ld8(bg_e + o);
+        wu[b][ks] = ld8(bu_e + o);
+      }
     }
-  }
-  for (int cb = b_lo + wave; cb < b_hi; cb += FT_WAVES) {
-    const int c0 = cb * 32;
-    // (1) this block's weight fragments (L2-resident banks), (2) the NEXT block's gathered G/U
-    // runs.  Loads return in order, so waiting for (1) leaves (2) in flight during the math.
-    bf16x8_t wg[KSR], wu[KSR], wf[2][NQ];
+  };
+  auto load_wf = [&](int c0) {
 #pragma unroll
-    for (int ks = 0; ks < KSR; ks++) {
-      const int q0 = ks * 16 + hi * 8;
-      const int64_t o = (int64_t)(c0 + l31) * r + (q0 < r ? q0 : 0);
-      wg[ks] = *reinterpret_cast<const bf16x8_t *>(bg_e + o);
-      wu[ks] = *reinterpret_cast<const bf16x8_t *>(bu_e + o);
-    }
-#pragma unroll
-    for (int s2 = 0; s2 < 2; s2++)
+    for (int s4 = 0; s4 < 4; s4++)
 #pragma unroll
       for (int j = 0; j < NQ; j++) {
         const int q = j * 32 + l31;
-        const bf16_t *wp = ad_e + (int64_t)(q < r ? q : 0) * f + c0 + 16 * s2 + hi * 4;
-        wf[s2][j] = join44(wp, wp + 8);
+        int col = c0 + 16 * s4 + 8 * hi;
+        col = col < f ? col : f - 8;
+        wf[s4][j] = ld8(ad_e + (int64_t)(q < r ? q : 0) * f + col);
       }
-    bf16x4_t gcur[4], ucur[4];
+  };
+  auto col_of = [&](int c0) { const int c = c0 + 8 * cc; return c < f ? c : f - 8; };
+  const int sb_first = sb_lo + wave < sb_hi ? sb_lo + wave : (nsb - 1);
+  load_w(sb_first * FT_SB);
 #pragma unroll
-    for (int g = 0; g < 4; g++) { gcur[g] = gnx[g]; ucur[g] = unx[g]; }
-    {   // unconditional (the last iteration re-reads its own block) so that the wait counts
-        // the compiler derives are the same on every path
-      const int cn = cb + FT_WAVES < b_hi ? c0 + FT_WAVES * 32 : c0;
+  for (int p = 0; p < 4; p++) {
+    gnx[p] = ld8(G + gsrc[p] + col_of(sb_first * FT_SB));
+    unx[p] = ld8(U + gsrc[p] + col_of(sb_first * FT_SB));
+  }
+  load_wf(sb_first * FT_SB);
+
+  for (int sb = sb_lo + wave; sb < sb_hi; sb += FT_WAVES) {
+    const int c0 = sb * FT_SB;
+    const int cn = sb + FT_WAVES < sb_hi ? c0 + FT_WAVES * FT_SB : c0;   // next (or again this)
+    // rank-r deltas of both 32-column blocks -> LDS tiles
 #pragma unroll
-      for (int g = 0; g < 4; g++) {
-        gnx[g] = *reinterpret_cast<const bf16x4_t *>(G + t * f + cn + hi * 4 + g * 8);
-        unx[g] = *reinterpret_cast<const bf16x4_t *>(U + t * f + cn + hi * 4 + g * 8);
+    for (int b = 0; b < 2; b++) {
+      f32x16_t dg, du;
+#pragma unroll
+      for (int i = 0; i < 16; i++) dg[i] = du[i] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KSR; ks++) {
+        const bool v = ks * 16 + hi * 8 < r;
+        dg = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v ? wg[b][ks] : zero8(), pg[ks], dg, 0, 0, 0);
+        du = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v ? wu[b][ks] : zero8(), pu[ks], du, 0, 0, 0);
       }
+      tile_put(tg, l31, hi, 32 * b, dg, s);
+      tile_put(tu, l31, hi, 32 * b, du, s);
     }
-    f32x16_t dg, du;
+    load_w(cn);   // next iteration's delta weights: oldest outstanding loads from here on
+    __builtin_amdgcn_wave_barrier();
+    // row-major phase
+    const int col = c0 + 8 * cc;
+    const bool cvalid = col < f;
 #pragma unroll
-    for (int i = 0; i < 16; i++) dg[i] = du[i] = 0.f;
+    for (int p = 0; p < 4; p++) {
+      bf16_t *tp = tg + (8 * p + rr) * FT_PITCH + 8 * cc;
+      const bf16x8_t dgl = ld8(tp), dul = ld8(tu + (8 * p + rr) * FT_PITCH + 8 * cc);
+      const bf16x8_t gv = gnx[p], uv = unx[p];
+      bf16x8_t av;
 #pragma unroll
-    for (int ks = 0; ks < KSR; ks++) {
-      const bool v = ks * 16 + hi * 8 < r;
-      dg = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v ? wg[ks] : zero8(), pg[ks], dg, 0, 0, 0);
-      du = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v ? wu[ks] : zero8(), pu[ks], du, 0, 0, 0);
-    }
-    bf16_t *ap = a_grp + (int64_t)row * f + c0 + hi * 4;
-    bf16x4_t av[4];
-#pragma unroll
-    for (int g = 0; g < 4; g++) {
-      const bf16x4_t gv = gcur[g];
-      const bf16x4_t uv = ucur[g];
-#pragma unroll
-      for (int m = 0; m < 4; m++) {
-        const float gg = (float)gv[m] + s * dg[g * 4 + m];
-        const float uu = (float)uv[m] + s * du[g * 4 + m];
-        av[g][m] = (bf16_t)(gg * fsigmoid(gg) * uu);
+      for (int m = 0; m < 8; m++) {
+        const float gg = (float)gv[m] + (float)dgl[m];
+        const float uu = (float)uv[m] + (float)dul[m];
+        av[m] = cvalid ? (bf16_t)(gg * fsigmoid(gg) * uu) : (bf16_t)0.f;
       }
-      if (rvalid) *reinterpret_cast<bf16x4_t *>(ap + g * 8) = av[g];
+      gnx[p] = ld8(G + gsrc[p] + col_of(cn));
+      unx[p] = ld8(U + gsrc[p] + col_of(cn));
+      if (rvalid[p] && cvalid) *reinterpret_cast<bf16x8_t *>(a_grp + adst[p] + col) = av;
+      *reinterpret_cast<bf16x8_t *>(tp) = av;
     }
-    // Q += a[rows, 32 cols] * A_down[e, q, same cols]^T : two K steps of 16 columns
+    __builtin_amdgcn_wave_barrier();
+    // Q += a[rows, 64 cols] * A_down[e, q, same cols]^T : four K steps of 16 columns
 #pragma unroll
-    for (int s2 = 0; s2 < 2; s2++) {
-      bf16x8_t af;
-#pragma unroll
-      for (int m = 0; m < 4; m++) { af[m] = av[2 * s2][m]; af[4 + m] = av[2 * s2 + 1][m]; }
+    for (int s4 = 0; s4 < 4; s4++) {
+      const bf16x8_t af = ld8(tg + l31 * FT_PITCH + 16 * s4 + 8 * hi);
+      const bool kv = c0 + 16 * s4 + 8 * hi < f;
 #pragma unroll
       for (int j = 0; j < NQ; j++) {
-        const bool v = j * 32 + l31 < r;
-        accq[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, v ? wf[s2][j] : zero8(), accq[j], 0, 0, 0);
+        const bool v = kv && j * 32 + l31 < r;
+        accq[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, v ? wf[s4][j] : zero8(), accq[j], 0, 0, 0);
       }
     }
+    load_wf(cn);
+    __builtin_amdgcn_wave_barrier();
   }
   // accq[j][i]: row 8*(i/4) + 4*hi + i%4 of the tile, q = j*32 + l31.  Sum the 4 waves.
+  __syncthreads();   // the tiles are dead; their space becomes the reduction buffer
+  float(*red)[NQ][16][64] = reinterpret_cast<float(*)[NQ][16][64]>(lds);
 #pragma unroll
   for (int j = 0; j < NQ; j++)
 #pragma unroll
@@ -203,21 +268,21 @@ __global__ __launch_bounds__(FT_WAVES * 64) void swiglu_fwd_mfma_kernel(
   for (int idx = threadIdx.x; idx < NQ * 16 * 64; idx += FT_WAVES * 64) {
     const int j = idx / (16 * 64), i = (idx / 64) % 16, ln = idx % 64;
     const int q = j * 32 + (ln & 31);
-    const int rr = 8 * (i >> 2) + 4 * (ln >> 5) + (i & 3);
-    if (q < r && rr < rows) {
+    const int rl = 8 * (i >> 2) + 4 * (ln >> 5) + (i & 3);
+    if (q < r && rl < rows) {
       const float v = (red[0][j][i][ln] + red[1][j][i][ln]) + (red[2][j][i][ln] + red[3][j][i][ln]);
-      Q_part[((int64_t)blockIdx.y * nP + row0 + rr) * r + q] = v;
+      Q_part[((int64_t)blockIdx.y * nP + row0 + rl) * r + q] = v;
     }
   }
 }
 
-// Backward of the tile above, same ownership (32 grouped rows x a range of 32-column blocks).
+// Backward of the tile above, same ownership and lane roles.
 // With H[t] = W_down^T dy[t] and Vw[row] = w_row * B_down[e]^T dy[t]:
 //   da = w_row * H[t] + s * A_down[e]^T Vw[row]      (rank-r MFMA on the transposed bank AdT)
 //   dg = da * u * sig(g) * (1 + g (1 - sig(g))),  du = da * g * sig(g)   -> dg_grp, du_grp
 //   dw_part[row][split]   = sum over the split's columns of H * a
 //   TG_part[split][row][q] = sum_c dg[row, c] * B_gate[e, c, q]   (and TU with du, B_up)
-// BgT / BuT are the banks re-laid as [N, r, f] so that the column index is contiguous.
+// AdT is A_down re-laid [N, f, r]; BgT / BuT are the B banks re-laid [N, r, f].
 template <int KSR, int NQ>
 __global__ __launch_bounds__(FT_WAVES * 64) void swiglu_bwd_mfma_kernel(
     PairCtx pc, int f, float s, const bf16_t *__restrict__ G, const bf16_t *__restrict__ U,
@@ -227,142 +292,188 @@ __global__ __launch_bounds__(FT_WAVES * 64) void swiglu_bwd_mfma_kernel(
     const bf16_t *__restrict__ AdT, const bf16_t *__restrict__ BgT, const bf16_t *__restrict__ BuT,
     bf16_t *__restrict__ dg_grp, bf16_t *__restrict__ du_grp, float *__restrict__ dw_part,
     float *__restrict__ TG_part, float *__restrict__ TU_part, int nsplit) {
-  __shared__ float red[FT_WAVES][NQ][16][64];
+  constexpr int TILES = 3;
+  constexpr int LDS_BYTES = FT_WAVES * TILES * FT_TILE * 2 > FT_WAVES * NQ * 16 * 64 * 4
+                                ? FT_WAVES * TILES * FT_TILE * 2 : FT_WAVES * NQ * 16 * 64 * 4;
+  __shared__ __align__(16) unsigned char lds[LDS_BYTES];
   __shared__ float dwred[FT_WAVES][32];
   int e, row0, rows;
   if (!fused_tile_rows(pc.offs, pc.N, blockIdx.x, e, row0, rows)) return;
   const int r = pc.r, R = pc.N * r, nP = pc.T * pc.k;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int l31 = lane & 31, hi = lane >> 5;
-  const bool rvalid = l31 < rows;
-  const int row = row0 + (rvalid ? l31 : 0);
-  const int pair = pc.pair_of_row[row];
-  const int64_t t = pair / pc.k;
-  const float wrow = pc.w[pair];
+  const int l31 = lane & 31, hi = lane >> 5, rr = lane >> 3, cc = lane & 7;
+  bf16_t *tg = reinterpret_cast<bf16_t *>(lds) + wave * TILES * FT_TILE;
+  bf16_t *tu = tg + FT_TILE, *td = tu + FT_TILE;
 
   bf16x8_t pg[KSR], pu[KSR], vw[KSR];
+  {
+    const int pair = pc.pair_of_row[row0 + (l31 < rows ? l31 : 0)];
+    const int64_t tm = pair / pc.k;
+    const float wm = pc.w[pair];
 #pragma unroll
-  for (int ks = 0; ks < KSR; ks++) {
-    const int q0 = ks * 16 + hi * 8;
-    const bool v = q0 < r;
-    const int64_t o = t * R + e * r + (v ? q0 : 0);
-    pg[ks] = cvt8(Pg_all + o, v, 1.f);
-    pu[ks] = cvt8(Pu_all + o, v, 1.f);
-    vw[ks] = cvt8(VB_all + o, v, wrow);
+    for (int ks = 0; ks < KSR; ks++) {
+      const int q0 = ks * 16 + hi * 8;
+      const bool v = q0 < r;
+      const int64_t o = tm * R + e * r + (v ? q0 : 0);
+      pg[ks] = cvt8(Pg_all + o, v, 1.f);
+      pu[ks] = cvt8(Pu_all + o, v, 1.f);
+      vw[ks] = cvt8(VB_all + o, v, wm);
+    }
+  }
+  int64_t gsrc[4], odst[4];
+  float wrow[4], dwacc[4];
+  bool rvalid[4];
+#pragma unroll
+  for (int p = 0; p < 4; p++) {
+    const int rl = 8 * p + rr;
+    rvalid[p] = rl < rows;
+    const int row = row0 + (rvalid[p] ? rl : 0);
+    const int pair = pc.pair_of_row[row];
+    gsrc[p] = (int64_t)(pair / pc.k) * f;
+    odst[p] = (int64_t)row * f;
+    wrow[p] = pc.w[pair];
+    dwacc[p] = 0.f;
   }
   f32x16_t acctg[NQ], acctu[NQ];
 #pragma unroll
   for (int j = 0; j < NQ; j++)
 #pragma unroll
     for (int i = 0; i < 16; i++) acctg[j][i] = acctu[j][i] = 0.f;
-  float dwacc = 0.f;
 
-  const int nblk = f / 32;
-  const int per = (nblk + nsplit - 1) / nsplit;
-  const int b_lo = blockIdx.y * per;
-  const int b_hi = b_lo + per < nblk ? b_lo + per : nblk;
+  const int nsb = (f + FT_SB - 1) / FT_SB;
+  const int per = (nsb + nsplit - 1) / nsplit;
+  const int sb_lo = blockIdx.y * per;
+  const int sb_hi = sb_lo + per < nsb ? sb_lo + per : nsb;
   const bf16_t *bg_e = B_gate + (int64_t)e * f * r;
   const bf16_t *bu_e = B_up + (int64_t)e * f * r;
   const bf16_t *ad_e = AdT + (int64_t)e * f * r;
   const bf16_t *bgt_e = BgT + (int64_t)e * r * f;
   const bf16_t *but_e = BuT + (int64_t)e * r * f;
 
-  bf16x4_t gnx[4], unx[4], hnx[4];
-  {
-    const int cbf = b_lo + wave < b_hi ? b_lo + wave : 0;
+  bf16x8_t wg[2][KSR], wu[2][KSR], wd[2][KSR], tgw[4][NQ], tuw[4][NQ], gnx[4], unx[4], hnx[4];
+  auto load_w = [&](int c0) {
 #pragma unroll
-    for (int g = 0; g < 4; g++) {
-      gnx[g] = *reinterpret_cast<const bf16x4_t *>(G + t * f + cbf * 32 + hi * 4 + g * 8);
-      unx[g] = *reinterpret_cast<const bf16x4_t *>(U + t * f + cbf * 32 + hi * 4 + g * 8);
-      hnx[g] = *reinterpret_cast<const bf16x4_t *>(H + t * f + cbf * 32 + hi * 4 + g * 8);
+    for (int b = 0; b < 2; b++) {
+      int col = c0 + 32 * b + l31;
+      col = col < f ? col : f - 1;
+#pragma unroll
+      for (int ks = 0; ks < KSR; ks++) {
+        const int q0 = ks * 16 + hi * 8;
+        const int64_t o = (int64_t)col * r + (q0 < r ? q0 : 0);
+        wg[b][ks] = ld8(bg_e + o);
+        wu[b][ks] = ld8(bu_e + o);
+        wd[b][ks] = ld8(ad_e + o);
+      }
     }
-  }
-  for (int cb = b_lo + wave; cb < b_hi; cb += FT_WAVES) {
-    const int c0 = cb * 32;
-    // weight fragments of this block first, then the next block's gathered runs (see forward)
-    bf16x8_t wg[KSR], wu[KSR], wd[KSR], tg[2][NQ], tu[2][NQ];
+  };
+  auto load_wt = [&](int c0) {
 #pragma unroll
-    for (int ks = 0; ks < KSR; ks++) {
-      const int q0 = ks * 16 + hi * 8;
-      const int64_t o = (int64_t)(c0 + l31) * r + (q0 < r ? q0 : 0);
-      wg[ks] = *reinterpret_cast<const bf16x8_t *>(bg_e + o);
-      wu[ks] = *reinterpret_cast<const bf16x8_t *>(bu_e + o);
-      wd[ks] = *reinterpret_cast<const bf16x8_t *>(ad_e + o);
-    }
-#pragma unroll
-    for (int s2 = 0; s2 < 2; s2++)
+    for (int s4 = 0; s4 < 4; s4++)
 #pragma unroll
       for (int j = 0; j < NQ; j++) {
         const int q = j * 32 + l31;
-        const int64_t o = (int64_t)(q < r ? q : 0) * f + c0 + 16 * s2 + hi * 4;
-        tg[s2][j] = join44(bgt_e + o, bgt_e + o + 8);
-        tu[s2][j] = join44(but_e + o, but_e + o + 8);
+        int col = c0 + 16 * s4 + 8 * hi;
+        col = col < f ? col : f - 8;
+        const int64_t o = (int64_t)(q < r ? q : 0) * f + col;
+        tgw[s4][j] = ld8(bgt_e + o);
+        tuw[s4][j] = ld8(but_e + o);
       }
-    bf16x4_t gcur[4], ucur[4], hcur[4];
+  };
+  auto col_of = [&](int c0) { const int c = c0 + 8 * cc; return c < f ? c : f - 8; };
+  const int sb_first = sb_lo + wave < sb_hi ? sb_lo + wave : (nsb - 1);
+  load_w(sb_first * FT_SB);
 #pragma unroll
-    for (int g = 0; g < 4; g++) { gcur[g] = gnx[g]; ucur[g] = unx[g]; hcur[g] = hnx[g]; }
-    {
-      const int64_t nx = t * f + (cb + FT_WAVES < b_hi ? c0 + FT_WAVES * 32 : c0) + hi * 4;
+  for (int p = 0; p < 4; p++) {
+    const int64_t o = gsrc[p] + col_of(sb_first * FT_SB);
+    gnx[p] = ld8(G + o);
+    unx[p] = ld8(U + o);
+    hnx[p] = ld8(H + o);
+  }
+  load_wt(sb_first * FT_SB);
+
+  for (int sb = sb_lo + wave; sb < sb_hi; sb += FT_WAVES) {
+    const int c0 = sb * FT_SB;
+    const int cn = sb + FT_WAVES < sb_hi ? c0 + FT_WAVES * FT_SB : c0;
 #pragma unroll
-      for (int g = 0; g < 4; g++) {
-        gnx[g] = *reinterpret_cast<const bf16x4_t *>(G + nx + g * 8);
-        unx[g] = *reinterpret_cast<const bf16x4_t *>(U + nx + g * 8);
-        hnx[g] = *reinterpret_cast<const bf16x4_t *>(H + nx + g * 8);
+    for (int b = 0; b < 2; b++) {
+      f32x16_t dgm, dum, ddm;
+#pragma unroll
+      for (int i = 0; i < 16; i++) dgm[i] = dum[i] = ddm[i] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KSR; ks++) {
+        const bool v = ks * 16 + hi * 8 < r;
+        dgm = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v ? wg[b][ks] : zero8(), pg[ks], dgm, 0, 0, 0);
+        dum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v ? wu[b][ks] : zero8(), pu[ks], dum, 0, 0, 0);
+        ddm = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v ? wd[b][ks] : zero8(), vw[ks], ddm, 0, 0, 0);
       }
+      tile_put(tg, l31, hi, 32 * b, dgm, s);
+      tile_put(tu, l31, hi, 32 * b, dum, s);
+      tile_put(td, l31, hi, 32 * b, ddm, s);
     }
-    f32x16_t dgm, dum, ddm;
+    load_w(cn);
+    __builtin_amdgcn_wave_barrier();
+    const int col = c0 + 8 * cc;
+    const bool cvalid = col < f;
 #pragma unroll
-    for (int i = 0; i < 16; i++) dgm[i] = dum[i] = ddm[i] = 0.f;
+    for (int p = 0; p < 4; p++) {
+      const int lo = (8 * p + rr) * FT_PITCH + 8 * cc;
+      const bf16x8_t dgl = ld8(tg + lo), dul = ld8(tu + lo), ddl = ld8(td + lo);
+      const bf16x8_t gv = gnx[p], uv = unx[p], hv = hnx[p];
+      bf16x8_t dgv, duv;
+      float part = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < KSR; ks++) {
-      const bool v = ks * 16 + hi * 8 < r;
-      dgm = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v ? wg[ks] : zero8(), pg[ks], dgm, 0, 0, 0);
-      dum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v ? wu[ks] : zero8(), pu[ks], dum, 0, 0, 0);
-      ddm = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v ? wd[ks] : zero8(), vw[ks], ddm, 0, 0, 0);
-    }
-    const int64_t rout = (int64_t)row * f + c0 + hi * 4;
-    bf16x4_t dgv[4], duv[4];
-#pragma unroll
-    for (int g = 0; g < 4; g++) {
-      const bf16x4_t gv = gcur[g], uv = ucur[g], hv = hcur[g];
-#pragma unroll
-      for (int m = 0; m < 4; m++) {
-        const float gg = (float)gv[m] + s * dgm[g * 4 + m];
-        const float uu = (float)uv[m] + s * dum[g * 4 + m];
+      for (int m = 0; m < 8; m++) {
+        const float gg = (float)gv[m] + (float)dgl[m];
+        const float uu = (float)uv[m] + (float)dul[m];
         const float hh = (float)hv[m];
         const float sg = fsigmoid(gg);
-        const float da = wrow * hh + s * ddm[g * 4 + m];
-        dwacc = fmaf(hh, gg * sg * uu, dwacc);
-        dgv[g][m] = (bf16_t)(da * uu * sg * (1.f + gg * (1.f - sg)));
-        duv[g][m] = (bf16_t)(da * gg * sg);
+        const float da = wrow[p] * hh + (float)ddl[m];
+        part = fmaf(hh, gg * sg * uu, part);
+        dgv[m] = cvalid ? (bf16_t)(da * uu * sg * (1.f + gg * (1.f - sg))) : (bf16_t)0.f;
+        duv[m] = cvalid ? (bf16_t)(da * gg * sg) : (bf16_t)0.f;
       }
-      if (rvalid) {
-        *reinterpret_cast<bf16x4_t *>(dg_grp + rout + g * 8) = dgv[g];
-        *reinterpret_cast<bf16x4_t *>(du_grp + rout + g * 8) = duv[g];
+      if (cvalid) dwacc[p] += part;
+      {
+        const int64_t o = gsrc[p] + col_of(cn);
+        gnx[p] = ld8(G + o);
+        unx[p] = ld8(U + o);
+        hnx[p] = ld8(H + o);
       }
+      if (rvalid[p] && cvalid) {
+        *reinterpret_cast<bf16x8_t *>(dg_grp + odst[p] + col) = dgv;
+        *reinterpret_cast<bf16x8_t *>(du_grp + odst[p] + col) = duv;
+      }
+      *reinterpret_cast<bf16x8_t *>(tg + lo) = dgv;
+      *reinterpret_cast<bf16x8_t *>(tu + lo) = duv;
     }
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int s2 = 0; s2 < 2; s2++) {
-      bf16x8_t fg, fu;
-#pragma unroll
-      for (int m = 0; m < 4; m++) {
-        fg[m] = dgv[2 * s2][m]; fg[4 + m] = dgv[2 * s2 + 1][m];
-        fu[m] = duv[2 * s2][m]; fu[4 + m] = duv[2 * s2 + 1][m];
-      }
+    for (int s4 = 0; s4 < 4; s4++) {
+      const bf16x8_t fg = ld8(tg + l31 * FT_PITCH + 16 * s4 + 8 * hi);
+      const bf16x8_t fu = ld8(tu + l31 * FT_PITCH + 16 * s4 + 8 * hi);
+      const bool kv = c0 + 16 * s4 + 8 * hi < f;
 #pragma unroll
       for (int j = 0; j < NQ; j++) {
-        const bool v = j * 32 + l31 < r;
-        acctg[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fg, v ? tg[s2][j] : zero8(), acctg[j], 0, 0, 0);
-        acctu[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fu, v ? tu[s2][j] : zero8(), acctu[j], 0, 0, 0);
+        const bool v = kv && j * 32 + l31 < r;
+        acctg[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fg, v ? tgw[s4][j] : zero8(), acctg[j], 0, 0, 0);
+        acctu[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fu, v ? tuw[s4][j] : zero8(), acctu[j], 0, 0, 0);
       }
     }
+    load_wt(cn);
+    __builtin_amdgcn_wave_barrier();
   }
-  // <H, a> per row: the two half-waves hold complementary columns of the same row
-  dwacc += __shfl_xor(dwacc, 32, 64);
-  if (hi == 0) dwred[wave][l31] = dwacc;
-  // rank-r sums: add the 4 waves in a fixed order, gate bank first, then up
+  // <H, a> per row: add the 8 column chunks (lanes cc = 0..7 of a row), then the 4 waves
+#pragma unroll
+  for (int p = 0; p < 4; p++) {
+    float v = dwacc[p];
+    v += __shfl_xor(v, 1, 64);
+    v += __shfl_xor(v, 2, 64);
+    v += __shfl_xor(v, 4, 64);
+    if (cc == 0) dwred[wave][8 * p + rr] = v;
+  }
+  float(*red)[NQ][16][64] = reinterpret_cast<float(*)[NQ][16][64]>(lds);
   for (int bank = 0; bank < 2; bank++) {
-    __syncthreads();
+    __syncthreads();   // tiles (first pass) or the previous bank's sums are no longer read
 #pragma unroll
     for (int j = 0; j < NQ; j++)
 #pragma unroll
@@ -372,10 +483,10 @@ __global__ __launch_bounds__(FT_WAVES * 64) void swiglu_bwd_mfma_kernel(
     for (int idx = threadIdx.x; idx < NQ * 16 * 64; idx += FT_WAVES * 64) {
       const int j = idx / (16 * 64), i = (idx / 64) % 16, ln = idx % 64;
       const int q = j * 32 + (ln & 31);
-      const int rr = 8 * (i >> 2) + 4 * (ln >> 5) + (i & 3);
-      if (q < r && rr < rows) {
+      const int rl = 8 * (i >> 2) + 4 * (ln >> 5) + (i & 3);
+      if (q < r && rl < rows) {
         const float v = (red[0][j][i][ln] + red[1][j][i][ln]) + (red[2][j][i][ln] + red[3][j][i][ln]);
-        out[((int64_t)blockIdx.y * nP + row0 + rr) * r + q] = v;
+        out[((int64_t)blockIdx.y * nP + row0 + rl) * r + q] = v;
       }
     }
   }
@@ -398,7 +509,7 @@ __global__ void reduce_rank_parts_kernel(PairCtx pc, const float *__restrict__ p
 }
 
 int fused_splits(int f) {
-  const int nblk = f / 32;
+  const int nblk = (f + FT_SB - 1) / FT_SB;
   int s = 8;
   while (s > 1 && nblk / s < FT_WAVES) s >>= 1;
   return s;
