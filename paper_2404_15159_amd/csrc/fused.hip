@@ -109,7 +109,7 @@ __device__ __forceinline__ void tile_put(bf16_t *tile, int l31, int hi, int cb32
 // Forward: a_grp[row, :] and the per-split partial sums  Q_part[split][row][q] = sum over the
 // split's columns of a[row, c] * A_down[e, q, c].
 template <int KSR, int NQ>
-__global__ __launch_bounds__(FT_WAVES * 64) void swiglu_fwd_mfma_kernel(
+__global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 3 : 1) void swiglu_fwd_mfma_kernel(
     PairCtx pc, int f, float s, const bf16_t *__restrict__ G, const bf16_t *__restrict__ U,
     const float *__restrict__ Pg_all, const float *__restrict__ Pu_all,
     const bf16_t *__restrict__ B_gate, const bf16_t *__restrict__ B_up,
@@ -284,7 +284,7 @@ __global__ __launch_bounds__(FT_WAVES * 64) void swiglu_fwd_mfma_kernel(
 //   TG_part[split][row][q] = sum_c dg[row, c] * B_gate[e, c, q]   (and TU with du, B_up)
 // AdT is A_down re-laid [N, f, r]; BgT / BuT are the B banks re-laid [N, r, f].
 template <int KSR, int NQ>
-__global__ __launch_bounds__(FT_WAVES * 64) void swiglu_bwd_mfma_kernel(
+__global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 2 : 1) void swiglu_bwd_mfma_kernel(
     PairCtx pc, int f, float s, const bf16_t *__restrict__ G, const bf16_t *__restrict__ U,
     const bf16_t *__restrict__ H, const float *__restrict__ Pg_all,
     const float *__restrict__ Pu_all, const float *__restrict__ VB_all,
