@@ -209,19 +209,16 @@ int mixlora_ffn_forward(const mixlora_dims *dims, const mixlora_weights *w, cons
   hipLaunchKernelGGL(set_pair_kernel, dim3(1), dim3(64), 0, st, (int32_t *)(ws + L.tok_offs), 0, T);
   HIP_TRY(hipGetLastError());
 
-  // shared frozen projections, once for all tokens (Algorithm 1 lines 7-8)
+  // shared frozen projections, once for all tokens (Algorithm 1 lines 7-8), and in the same
+  // launch the LoRA A projections of every expert (rank-r, N*r output columns per bank)
   {
-    GemmProblem p[2] = {problem(T, f, ws + L.G, f, 0), problem(T, f, ws + L.U, f, 0)};
+    GemmProblem p[4] = {problem(T, f, ws + L.G, f, 0), problem(T, f, ws + L.U, f, 0),
+                        problem(T, R, ws + L.Pg_all, R, 1), problem(T, R, ws + L.Pu_all, R, 1)};
     add_seg(p[0], x, d, w->W_gate, d, d);
     add_seg(p[1], x, d, w->W_up, d, d);
-    HIP_TRY(launch_gemm(dt, p, 2, st));
-  }
-  // LoRA A projections of every expert (rank-r, N*r output columns per bank)
-  {
-    GemmProblem p[2] = {problem(T, R, ws + L.Pg_all, R, 1), problem(T, R, ws + L.Pu_all, R, 1)};
-    add_seg(p[0], x, d, w->A_gate, d, d);
-    add_seg(p[1], x, d, w->A_up, d, d);
-    HIP_TRY(launch_gemm(dt, p, 2, st));
+    add_seg(p[2], x, d, w->A_gate, d, d);
+    add_seg(p[3], x, d, w->A_up, d, d);
+    HIP_TRY(launch_gemm(dt, p, 4, st));
   }
   PairCtx pc{offs, pair_of_row, row_of_pair, wts, idx, T, N, k, r};
   // Algorithm 1 lines 11-13 on the routed pairs, expert-grouped rows
@@ -294,18 +291,14 @@ int mixlora_ffn_backward(const mixlora_dims *dims, const mixlora_weights *w, con
   if (!WgT) { HIP_TRY(launch_transpose(dt, w->W_gate, ws + L.WgT, f, d, st)); WgT = ws + L.WgT; }
   if (!WuT) { HIP_TRY(launch_transpose(dt, w->W_up, ws + L.WuT, f, d, st)); WuT = ws + L.WuT; }
 
-  // H = dy W_down  (once per token: the frozen down projection is shared and linear)
-  {
-    GemmProblem p = problem(T, f, ws + L.H, f, 0);
-    add_seg(p, dy, d, WdT, d, d);
-    HIP_TRY(launch_gemm(dt, &p, 1, st));
-  }
-  // VB[t, e, :] = B_down[e]^T dy[t]
+  // H = dy W_down  (once per token: the frozen down projection is shared and linear) and, in
+  // the same launch, VB[t, e, :] = B_down[e]^T dy[t]
   HIP_TRY(launch_pack_bank_T(dt, w->B_down, N, d, r, ws + L.Bd_T, st));
   {
-    GemmProblem p = problem(T, R, ws + L.VB_all, R, 1);
-    add_seg(p, dy, d, ws + L.Bd_T, d, d);
-    HIP_TRY(launch_gemm(dt, &p, 1, st));
+    GemmProblem p[2] = {problem(T, f, ws + L.H, f, 0), problem(T, R, ws + L.VB_all, R, 1)};
+    add_seg(p[0], dy, d, WdT, d, d);
+    add_seg(p[1], dy, d, ws + L.Bd_T, d, d);
+    HIP_TRY(launch_gemm(dt, p, 2, st));
   }
   // through SiLU * up and the LoRA deltas, per pair; TG[row, e, :] = B_gate[e]^T dg[row] (and up)
   HIP_TRY(launch_pack_bank_T(dt, w->B_gate, N, f, r, ws + L.Bg_T, st));

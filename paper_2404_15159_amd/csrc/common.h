@@ -65,7 +65,8 @@ struct GemmProblem {
   int64_t ldc;
   int c_f32;  // 1: C is float32 regardless of the storage dtype
 };
-// Enqueue up to two independent problems of identical M, N in one launch.
+// Enqueue up to four independent problems of identical M in one launch (N and the output type
+// may differ per problem).
 hipError_t launch_gemm(int dtype, const GemmProblem *probs, int nprob, hipStream_t st);
 
 // Measurement hook: HIP-event timing of every launch of the large-tile bf16 kernel between

@@ -11,10 +11,12 @@
 // K segments (low-rank K-extension) or through the element-wise kernels.
 #include "common.h"
 
+#include <type_traits>
+
 namespace mixlora {
 
 struct GemmBatch {
-  GemmProblem p[2];
+  GemmProblem p[4];
 };
 
 // Map the hardware block id to a tile so that (a) blocks that land on the same XCD (id % 8)
@@ -225,7 +227,7 @@ __device__ __forceinline__ const void *uniform_ptr(const void *p) {
   return reinterpret_cast<const void *>(((uint64_t)hi << 32) | lo);
 }
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, typename OutT, bool PIPE = false>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool PIPE = false>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_dl_kernel(GemmBatch args) {
   constexpr int NW = WGM * WGN;
   constexpr int ROWB = BK * 2;            // bytes per tile row in LDS
@@ -245,6 +247,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_dl_kernel(GemmBatch a
   const GemmProblem &P = args.p[blockIdx.z];
   const int M = P.M, N = P.N;
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  if ((int)blockIdx.x >= tiles_m * tiles_n) return;   // problems of one launch may differ in N
   int tm, tn;
   tile_of_block(blockIdx.x, tiles_m, tiles_n, tm, tn);
   const int row0 = tm * BM, col0 = tn * BN;
@@ -401,30 +404,34 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_dl_kernel(GemmBatch a
 
   // The weight fragment is the FIRST MFMA operand, so a lane holds, for its row (lane % 32),
   // the columns 8g + 4*(lane/32) + m: four runs of 4 consecutive outputs -> 8/16-byte stores.
-  OutT *C = reinterpret_cast<OutT *>(P.C);
   const int cbase = col0 + wn * TN + hi * 4;
   const int rbase = row0 + wm * TM + l31;
+  auto store_all = [&](auto *C) {
+    typedef typename std::remove_pointer<decltype(C)>::type OutT;
 #pragma unroll
-  for (int i = 0; i < MI; i++) {
-    const int r = rbase + i * 32;
-    if (r < M) {
+    for (int i = 0; i < MI; i++) {
+      const int r = rbase + i * 32;
+      if (r < M) {
 #pragma unroll
-      for (int j = 0; j < NI; j++)
+        for (int j = 0; j < NI; j++)
 #pragma unroll
-        for (int g = 0; g < 4; g++) {
-          const int c = cbase + j * 32 + g * 8;
-          OutT *o = C + (int64_t)r * P.ldc + c;
-          if (c + 3 < N && (P.ldc & 3) == 0) {
-            store_c4<OutT>(o, acc[i][j][g * 4], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2],
-                           acc[i][j][g * 4 + 3]);
-          } else {
+          for (int g = 0; g < 4; g++) {
+            const int c = cbase + j * 32 + g * 8;
+            OutT *o = C + (int64_t)r * P.ldc + c;
+            if (c + 3 < N && (P.ldc & 3) == 0) {
+              store_c4<OutT>(o, acc[i][j][g * 4], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2],
+                             acc[i][j][g * 4 + 3]);
+            } else {
 #pragma unroll
-            for (int m = 0; m < 4; m++)
-              if (c + m < N) store_c<OutT>(o + m, acc[i][j][g * 4 + m]);
+              for (int m = 0; m < 4; m++)
+                if (c + m < N) store_c<OutT>(o + m, acc[i][j][g * 4 + m]);
+            }
           }
-        }
+      }
     }
-  }
+  };
+  if (P.c_f32) store_all(reinterpret_cast<float *>(P.C));
+  else store_all(reinterpret_cast<bf16_t *>(P.C));
 }
 
 // ---- fp32 storage: 64x64 tile, 256 threads, 4x4 outputs per thread ----------------------
@@ -549,10 +556,10 @@ static hipError_t launch_bf16(const GemmBatch &b, int nprob, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, typename OutT, bool PIPE = false>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool PIPE = false>
 static hipError_t launch_bf16_dl(const GemmBatch &b, int nprob, hipStream_t st) {
   constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * sizeof(bf16_t);
-  auto kern = gemm_bf16_dl_kernel<BM, BN, BK, STAGES, WGM, WGN, OutT, PIPE>;
+  auto kern = gemm_bf16_dl_kernel<BM, BN, BK, STAGES, WGM, WGN, PIPE>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -560,7 +567,11 @@ static hipError_t launch_bf16_dl(const GemmBatch &b, int nprob, hipStream_t st) 
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int tiles = ((b.p[0].M + BM - 1) / BM) * ((b.p[0].N + BN - 1) / BN);
+  int tiles = 0;
+  for (int i = 0; i < nprob; i++) {
+    const int t = ((b.p[i].M + BM - 1) / BM) * ((b.p[i].N + BN - 1) / BN);
+    tiles = t > tiles ? t : tiles;
+  }
   const bool timed = BM == 256 && g_timer.on && g_timer.used < g_timer.cap;
   if (timed) (void)hipEventRecord(g_timer.beg[g_timer.used], st);
   hipLaunchKernelGGL(kern, dim3(tiles, 1, nprob), dim3(WGM * WGN * 64), smem, st, b);
@@ -588,12 +599,32 @@ static bool dl_eligible(const GemmBatch &b, int nprob, int BK) {
 }
 
 hipError_t launch_gemm(int dtype, const GemmProblem *probs, int nprob, hipStream_t st) {
-  if (nprob < 1 || nprob > 2) return hipErrorInvalidValue;
+  if (nprob < 1 || nprob > 4) return hipErrorInvalidValue;
   GemmBatch b;
-  for (int i = 0; i < nprob; i++) b.p[i] = probs[i];
-  if (nprob == 1) b.p[1] = probs[0];
+  for (int i = 0; i < 4; i++) b.p[i] = probs[i < nprob ? i : 0];
   const int M = probs[0].M, N = probs[0].N;
-  if (M <= 0 || N <= 0) return hipSuccess;
+  bool uniform = true, any_big = false;
+  for (int i = 0; i < nprob; i++) {
+    if (probs[i].M != M) return hipErrorInvalidValue;
+    if (probs[i].N != N || probs[i].c_f32 != probs[0].c_f32) uniform = false;
+    if (probs[i].N > 128) any_big = true;
+    if (probs[i].N <= 0) return hipErrorInvalidValue;
+  }
+  if (M <= 0) return hipSuccess;
+  if (dtype == MIXLORA_BF16 && M > 128 && any_big) {
+    // large tiles: direct-to-LDS ring; BK = 64 needs whole 64-wide K tiles, else BK = 32.
+    // Problems of one launch may differ in N and output type (narrow ones ride in the slack
+    // of the last, partially filled round of workgroups).
+    if (dl_eligible(b, nprob, 64)) return launch_bf16_dl<256, 256, 64, 2, 2, 4, true>(b, nprob, st);
+    if (dl_eligible(b, nprob, 32)) return launch_bf16_dl<256, 256, 32, 4, 2, 4, false>(b, nprob, st);
+  }
+  if (!uniform || nprob > 2) {   // the generic kernels take uniform batches of at most two
+    for (int i = 0; i < nprob; i++) {
+      const hipError_t e = launch_gemm(dtype, probs + i, 1, st);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }
   if (dtype == MIXLORA_F32) {
     const int tiles = ((M + 63) / 64) * ((N + 63) / 64);
     hipLaunchKernelGGL(gemm_f32_kernel, dim3(tiles, 1, nprob), dim3(256), 0, st, b);
@@ -603,11 +634,6 @@ hipError_t launch_gemm(int dtype, const GemmProblem *probs, int nprob, hipStream
   if (N <= 128 || M <= 128) {
     return f32out ? launch_bf16<128, 128, 64, 2, 2, float>(b, nprob, st)
                   : launch_bf16<128, 128, 64, 2, 2, bf16_t>(b, nprob, st);
-  }
-  if (!f32out) {
-    // large tiles: direct-to-LDS ring; BK = 64 needs whole 64-wide K tiles, else BK = 32
-    if (dl_eligible(b, nprob, 64)) return launch_bf16_dl<256, 256, 64, 2, 2, 4, bf16_t, true>(b, nprob, st);
-    if (dl_eligible(b, nprob, 32)) return launch_bf16_dl<256, 256, 32, 4, 2, 4, bf16_t, false>(b, nprob, st);
   }
   return f32out ? launch_bf16<256, 256, 64, 2, 4, float>(b, nprob, st)
                 : launch_bf16<256, 256, 64, 2, 4, bf16_t>(b, nprob, st);

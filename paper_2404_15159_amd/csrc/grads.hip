@@ -137,7 +137,6 @@ hipError_t launch_group_outer(int dtype, const int32_t *offs, int G, int max_row
 // lane, read as 2-byte-pair loads whose even/odd halves feed two column-interleaved MFMA
 // blocks), second operand = smallT (index = q, 8 consecutive rows = one 16-byte load from the
 // transposed bf16 copy).  Rows outside the group are masked in the small operand.
-constexpr int GOM_NQ = 2;     // q <= 64
 constexpr int GOM_CB = 8;     // column blocks per wave: a lane reads 8 adjacent columns (16 bytes)
 
 // A wave covers 256 columns: lane (l31, hi) reads, for each of its 8 rows, the 16-byte run of
