@@ -374,36 +374,58 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_dl_kernel(GemmBatch a
 #pragma unroll
       for (int j = 0; j < NI; j++) bfr[buf][j] = *reinterpret_cast<const bf16x8_t *>(b + j * 32 * ROWB);
     };
+    auto mfma_step = [&](int cur) {
+#pragma unroll
+      for (int i = 0; i < MI; i++)
+#pragma unroll
+        for (int j = 0; j < NI; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][j], af[cur][i], acc[i][j], 0, 0, 0);
+    };
     wait_tile(0);
     __syncthreads();
     issue_next();
     load_frags(0, 0, 0);
-    for (int it = 0; it < total_tiles; it++) {
+    // All tiles but the last: no data-dependent branch inside, so that the wait counts the
+    // compiler derives for the fragment reads are exact (a merge with a path that skips the
+    // tile switch would make every post-barrier MFMA wait for the reads just issued).
+    for (int it = 0; it + 1 < total_tiles; it++) {
       const int st = it % STAGES;
 #pragma unroll
       for (int ks = 0; ks < KS; ks++) {
         const int cur = ks & 1, nxt = cur ^ 1;   // KS is even, so step 0 always uses buffer 0
         if (ks + 1 < KS) {
           load_frags(nxt, st, ks + 1);
-        } else if (it + 1 < total_tiles) {
+        } else {
           wait_tile(it + 1);
           __syncthreads();
           issue_next();
           load_frags(nxt, (it + 1) % STAGES, 0);
         }
+        // issue order within the step: one LDS read between consecutive MFMAs, so the reads of
+        // the next step trickle out while the matrix pipe is busy
+        mfma_step(cur);
+#pragma unroll
+        for (int q = 0; q < MI + NI; q++) {
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read ...
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // ... then one MFMA
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - MI - NI, 0);
         __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    {
+      const int st = (total_tiles - 1) % STAGES;
 #pragma unroll
-        for (int i = 0; i < MI; i++)
-#pragma unroll
-          for (int j = 0; j < NI; j++)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][j], af[cur][i], acc[i][j], 0, 0, 0);
+      for (int ks = 0; ks < KS; ks++) {
+        const int cur = ks & 1;
+        if (ks + 1 < KS) load_frags(cur ^ 1, st, ks + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_step(cur);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
 
-  // The weight fragment is the FIRST MFMA operand, so a lane holds, for its row (lane % 32),
-  // the columns 8g + 4*(lane/32) + m: four runs of 4 consecutive outputs -> 8/16-byte stores.
   const int cbase = col0 + wn * TN + hi * 4;
   const int rbase = row0 + wm * TM + l31;
   auto store_all = [&](auto *C) {
