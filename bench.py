@@ -78,6 +78,9 @@ def main():
     ap.add_argument("--cpu-tokens", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--forward-only", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB device copy (a kernel of known HBM traffic, used to "
+                         "scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -124,6 +127,14 @@ def main():
         step()
     torch.cuda.synchronize()
     k_ms, k_launches, k_flops_exec = B.mixlora_profile_end()
+
+    if args.copy_calibration:
+        src = torch.zeros(1 << 28, dtype=torch.int32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     unit, fwd_fl, bwd_fl = flop_model(cfg, 3, 3)
     _, fwd_paper, bwd_paper = flop_model(cfg, 2 + cfg.k, 2 + cfg.k)
