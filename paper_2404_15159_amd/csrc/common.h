@@ -110,15 +110,14 @@ hipError_t launch_swiglu_bwd(int dtype, const PairCtx &pc, int f, float s, const
                              void *du_grp, float *dw_part, int n_col_tiles, hipStream_t st);
 int swiglu_col_tiles(int f);
 
-// bf16 MFMA fusion of the above with the A_down projection of the row's expert (needs
-// f % 32 == 0): writes a_grp and Q_all[row, e(row)*r + q]; Q_part is scratch of
+// bf16 MFMA fusion of the above with the A_down projection of the row's expert: writes a_grp and Q_all[row, e(row)*r + q]; Q_part is scratch of
 // 8 * kT * r floats.
 hipError_t launch_swiglu_fwd_mfma(const PairCtx &pc, int f, float s, const void *G, const void *U,
                                   const float *Pg_all, const float *Pu_all, const void *B_gate,
                                   const void *B_up, const void *A_down, void *a_grp,
                                   float *Q_part, float *Q_all, hipStream_t st);
 
-// bf16 MFMA backward of the same stage (f % 32 == 0): dg_grp, du_grp, dw_part[row][split]
+// bf16 MFMA backward of the same stage: dg_grp, du_grp, dw_part[row][split]
 // (split count = fused_splits(f)), TG_all / TU_all at [row, e(row)*r + q].  AdT = A_down re-laid
 // [N, f, r]; BgT / BuT = B banks re-laid [N, r, f]; rank_part is scratch of 16 * kT * r floats.
 hipError_t launch_swiglu_bwd_mfma(const PairCtx &pc, int f, float s, const void *G, const void *U,

@@ -1,18 +1,18 @@
 // bf16 MFMA versions of the per-pair (token, expert) stages, on expert-grouped rows.
 //
-// A workgroup owns one tile of 32 grouped rows (all of one expert) and a range of 32-column
-// blocks; each of its 4 wavefronts walks every 4th block.  Per block the LoRA deltas of
-// Algorithm 1 lines 11-12 are one rank-r MFMA each (B_e[cols, r] x P[rows, r]^T added to the
-// shared gate/up projections gathered by token), SiLU * up follows in registers (line 13), and
-// the activation tile - still in registers, whose MFMA result layout is also a valid MFMA
-// operand layout with the columns as the contraction index - is multiplied by A_down_e to
-// accumulate the rank-r input of the down projection's LoRA (line 14) without re-reading it.
+// A workgroup owns one tile of 32 grouped rows (all of one expert) and a range of 64-column
+// super-blocks; each of its 4 wavefronts walks every 4th super-block.  Per 32x32 block the LoRA
+// deltas of Algorithm 1 lines 11-12 are one rank-r MFMA each (B_e[cols, r] x P[rows, r]^T, added
+// to the shared gate/up projections gathered by token), SiLU * up follows (line 13), and the
+// activation tile is multiplied by A_down_e to accumulate the rank-r input of the down
+// projection's LoRA (line 14) without re-reading it from memory.
 //
 // MFMA 32x32x16 layout used throughout: operand lanes carry index (lane % 32) and the 8
 // contraction elements of half (lane / 32); result register e of a lane holds
-// D[8*(e/4) + 4*(lane/32) + e%4][lane % 32].  Here the FIRST operand is the weight fragment
-// (index = column), the SECOND the per-row fragment (index = row), so a lane holds, for its row,
-// the 16 columns c0 + 8g + 4*(lane/32) + m (g, m < 4): four 8-byte runs.
+// D[8*(e/4) + 4*(lane/32) + e%4][lane % 32].  For the deltas the FIRST operand is the weight
+// fragment (index = column), the SECOND the per-row fragment (index = row), so a lane holds, for
+// its row, the 16 columns c0 + 8g + 4*(lane/32) + m (g, m < 4): four 8-byte runs, which go into
+// an LDS tile (see below).
 #include "common.h"
 
 namespace mixlora {
@@ -65,20 +65,10 @@ __device__ __forceinline__ bf16x8_t zero8() {
   return o;
 }
 
-// two 8-byte runs -> one 8-element fragment
-__device__ __forceinline__ bf16x8_t join44(const bf16_t *p0, const bf16_t *p1) {
-  const bf16x4_t a = *reinterpret_cast<const bf16x4_t *>(p0);
-  const bf16x4_t b = *reinterpret_cast<const bf16x4_t *>(p1);
-  bf16x8_t o;
-  o[0] = a[0]; o[1] = a[1]; o[2] = a[2]; o[3] = a[3];
-  o[4] = b[0]; o[5] = b[1]; o[6] = b[2]; o[7] = b[3];
-  return o;
-}
-
-// ---- version 2 of the fused stages: coalesced global traffic ---------------------------------
-// The MFMA result layout gives a lane 4-column runs of 32 different rows, which makes every
-// gathered load and every store an 8-byte piece.  Here the rank-r MFMA results go through a
-// small per-wave LDS tile ([32 rows][64 columns] bf16, padded pitch) instead, and all global
+// ---- coalesced global traffic -------------------------------------------------------------------
+// The MFMA result layout gives a lane 4-column runs of 32 different rows; used directly it would
+// make every gathered load and every store an 8-byte piece.  The rank-r MFMA results therefore
+// go through a small per-wave LDS tile ([32 rows][64 columns] bf16, padded pitch) instead, and all global
 // traffic uses the "row-major" lane role: lane = (row 8p + lane/8, 8-column chunk lane%8), i.e.
 // 16 bytes per lane and 128 contiguous bytes per row per instruction.  The activation (or
 // gradient) tile is written back into the same LDS tile and read once more as MFMA first
@@ -87,10 +77,6 @@ __device__ __forceinline__ bf16x8_t join44(const bf16_t *p0, const bf16_t *p1) {
 constexpr int FT_SB = 64;                 // columns per super-block
 constexpr int FT_PITCH = FT_SB + 8;       // bf16 elements per LDS tile row (144 bytes)
 constexpr int FT_TILE = FT_ROWS * FT_PITCH;
-
-struct FusedRoles {
-  int lane, wave, l31, hi, rr, cc;
-};
 
 __device__ __forceinline__ bf16x8_t ld8(const bf16_t *p) { return *reinterpret_cast<const bf16x8_t *>(p); }
 
