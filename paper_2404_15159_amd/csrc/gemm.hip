@@ -26,7 +26,7 @@ __device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n,
   const int q = nb >> 3, rem = nb & 7;
   const int xcd = bid & 7, local = bid >> 3;
   const int lid = xcd * q + (xcd < rem ? xcd : rem) + local;
-  constexpr int GROUP = 8;
+  constexpr int GROUP = 4;   // measured: 4 slightly ahead of 2, 8, 16 (all within 3 %)
   const int width = GROUP * tiles_n;
   const int group_id = lid / width;
   const int first_m = group_id * GROUP;

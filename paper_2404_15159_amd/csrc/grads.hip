@@ -225,8 +225,9 @@ __global__ __launch_bounds__(256) void group_outer_mfma_kernel(
 }
 
 static int gom_splits(int G, int C) {
+  // one resident round: 256 CUs x 2 workgroups of 4 waves (the kernel runs 2 waves per SIMD)
   const int col_groups = (C + 1023) / 1024;
-  int s = 1024 / (col_groups * G);
+  int s = 512 / (col_groups * G);
   if (s < 1) s = 1;
   if (s > 8 && G > 1) s = 8;     // partial sums cost HBM traffic: nsplit * G * r * C floats
   if (s > 32) s = 32;
