@@ -19,7 +19,7 @@ inline int up64(int v) { return (v + 63) / 64 * 64; }
 
 struct Layout {
   // saved by forward
-  size_t probs, idx, w, counts, first_counts, offs, row_of_pair, pair_of_row, F, P, tok_offs;
+  size_t probs, Z, idx, w, counts, first_counts, offs, row_of_pair, pair_of_row, F, P, tok_offs;
   size_t G, U, Pg_all, Pu_all, a_grp, Q_all;
   // forward scratch
   size_t a_comb, Qw, Bd_cat, rank_part;
@@ -41,6 +41,7 @@ Layout make_layout(const mixlora_dims &D) {
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o = up(o + bytes); return at; };
   L.probs = take(T * N * 4);
+  L.Z = take(T * N * 4);
   L.idx = take(kT * 4);
   L.w = take(kT * 4);
   L.counts = take(N * 4);
@@ -199,8 +200,27 @@ int mixlora_ffn_forward(const mixlora_dims *dims, const mixlora_weights *w, cons
   int32_t *row_of_pair = (int32_t *)(ws + L.row_of_pair);
   int32_t *pair_of_row = (int32_t *)(ws + L.pair_of_row);
 
+  // Shared frozen projections, once for all tokens (Algorithm 1 lines 7-8), and in the same
+  // launch the LoRA A projections of every expert (rank-r, N*r output columns per bank).  None
+  // of them depends on the routing; in bf16 the router logits (Eq. 7) ride along as a fifth,
+  // N-column problem, so x is not read a second time.
+  {
+    GemmProblem p[5] = {problem(T, f, ws + L.G, f, 0), problem(T, f, ws + L.U, f, 0),
+                        problem(T, R, ws + L.Pg_all, R, 1), problem(T, R, ws + L.Pu_all, R, 1),
+                        problem(T, N, ws + L.Z, N, 1)};
+    add_seg(p[0], x, d, w->W_gate, d, d);
+    add_seg(p[1], x, d, w->W_up, d, d);
+    add_seg(p[2], x, d, w->A_gate, d, d);
+    add_seg(p[3], x, d, w->A_up, d, d);
+    add_seg(p[4], x, d, w->W_router, d, d);
+    HIP_TRY(launch_gemm(dt, p, dt == MIXLORA_BF16 ? 5 : 4, st));
+  }
   // Eq. 7 + Norm (Algorithm 1 lines 4-5)
-  HIP_TRY(launch_router(dt, x, w->W_router, T, d, N, k, probs, topk_idx, topk_w, idx, wts, st));
+  if (dt == MIXLORA_BF16)
+    HIP_TRY(launch_route_logits((const float *)(ws + L.Z), N, T, N, k, probs, topk_idx, topk_w, idx,
+                                wts, st));
+  else
+    HIP_TRY(launch_router(dt, x, w->W_router, T, d, N, k, probs, topk_idx, topk_w, idx, wts, st));
   HIP_TRY(launch_group_pairs(idx, T, N, k, (int32_t *)(ws + L.counts), expert_counts,
                              (int32_t *)(ws + L.first_counts), offs, row_of_pair, pair_of_row, st));
   // Eq. 8-9
@@ -208,18 +228,6 @@ int mixlora_ffn_forward(const mixlora_dims *dims, const mixlora_weights *w, cons
                           (float *)(ws + L.F), (float *)(ws + L.P), nullptr, st));
   hipLaunchKernelGGL(set_pair_kernel, dim3(1), dim3(64), 0, st, (int32_t *)(ws + L.tok_offs), 0, T);
   HIP_TRY(hipGetLastError());
-
-  // shared frozen projections, once for all tokens (Algorithm 1 lines 7-8), and in the same
-  // launch the LoRA A projections of every expert (rank-r, N*r output columns per bank)
-  {
-    GemmProblem p[4] = {problem(T, f, ws + L.G, f, 0), problem(T, f, ws + L.U, f, 0),
-                        problem(T, R, ws + L.Pg_all, R, 1), problem(T, R, ws + L.Pu_all, R, 1)};
-    add_seg(p[0], x, d, w->W_gate, d, d);
-    add_seg(p[1], x, d, w->W_up, d, d);
-    add_seg(p[2], x, d, w->A_gate, d, d);
-    add_seg(p[3], x, d, w->A_up, d, d);
-    HIP_TRY(launch_gemm(dt, p, 4, st));
-  }
   PairCtx pc{offs, pair_of_row, row_of_pair, wts, idx, T, N, k, r};
   // Algorithm 1 lines 11-13 on the routed pairs, expert-grouped rows
   if (dt == MIXLORA_BF16) {
@@ -240,8 +248,11 @@ int mixlora_ffn_forward(const mixlora_dims *dims, const mixlora_weights *w, cons
   // weighted combine of the pair activations (Algorithm 1 line 15, moved in front of the linear
   // frozen down projection) and the block-sparse low-rank operand
   HIP_TRY(launch_pair_combine(dt, pc, f, ws + L.a_grp, ws + L.a_comb, 1, st));
-  HIP_TRY(launch_scatter_blocks(dt, pc, (float *)(ws + L.Q_all), R, 1, 1, ws + L.Qw, R, 0, st));
-  HIP_TRY(launch_pack_bank_cat(dt, w->B_down, N, d, r, D.lora_scale, ws + L.Bd_cat, R, 0, st));
+  HIP_TRY(launch_scatter_blocks(dt, pc, (float *)(ws + L.Q_all), 0, 1, R, 1, 1, ws + L.Qw, R, 0, st));
+  {
+    const RelayoutJob j = job_bank_cat(w->B_down, N, d, r, D.lora_scale, ws + L.Bd_cat, R, 0);
+    HIP_TRY(launch_relayout(dt, &j, 1, st));
+  }
   // down projection (Algorithm 1 line 14): y = a_comb W_down^T + Qw (s B_down)^T
   {
     GemmProblem p = problem(T, d, y, d, 0);
@@ -291,9 +302,20 @@ int mixlora_ffn_backward(const mixlora_dims *dims, const mixlora_weights *w, con
   if (!WgT) { HIP_TRY(launch_transpose(dt, w->W_gate, ws + L.WgT, f, d, st)); WgT = ws + L.WgT; }
   if (!WuT) { HIP_TRY(launch_transpose(dt, w->W_up, ws + L.WuT, f, d, st)); WuT = ws + L.WuT; }
 
+  // every re-layout of the LoRA banks and the router that the pass needs, in one launch
+  {
+    const RelayoutJob jobs[7] = {
+        job_bank_T(w->B_down, N, d, r, ws + L.Bd_T),
+        job_bank_T(w->B_gate, N, f, r, ws + L.Bg_T),
+        job_bank_T(w->B_up, N, f, r, ws + L.Bu_T),
+        job_A_cat(w->A_gate, N, r, d, s, ws + L.Bx, Kx, 0),
+        job_A_cat(w->A_up, N, r, d, s, ws + L.Bx, Kx, R),
+        job_router_T(w->W_router, N, d, ws + L.Bx, Kx, 2 * R, Kx - 2 * R),
+        job_bank_T(w->A_down, N, r, f, ws + L.AdT)};   // [N,r,f] -> [N,f,r], bf16 path only
+    HIP_TRY(launch_relayout(dt, jobs, dt == MIXLORA_BF16 ? 7 : 6, st));
+  }
   // H = dy W_down  (once per token: the frozen down projection is shared and linear) and, in
   // the same launch, VB[t, e, :] = B_down[e]^T dy[t]
-  HIP_TRY(launch_pack_bank_T(dt, w->B_down, N, d, r, ws + L.Bd_T, st));
   {
     GemmProblem p[2] = {problem(T, f, ws + L.H, f, 0), problem(T, R, ws + L.VB_all, R, 1)};
     add_seg(p[0], dy, d, WdT, d, d);
@@ -301,12 +323,9 @@ int mixlora_ffn_backward(const mixlora_dims *dims, const mixlora_weights *w, con
     HIP_TRY(launch_gemm(dt, p, 2, st));
   }
   // through SiLU * up and the LoRA deltas, per pair; TG[row, e, :] = B_gate[e]^T dg[row] (and up)
-  HIP_TRY(launch_pack_bank_T(dt, w->B_gate, N, f, r, ws + L.Bg_T, st));
-  HIP_TRY(launch_pack_bank_T(dt, w->B_up, N, f, r, ws + L.Bu_T, st));
   int nct = L.nct;
   if (dt == MIXLORA_BF16) {
     nct = fused_splits(f);
-    HIP_TRY(launch_pack_bank_T(dt, w->A_down, N, r, f, ws + L.AdT, st));   // [N,r,f] -> [N,f,r]
     HIP_TRY(launch_swiglu_bwd_mfma(pc, f, s, ws + L.G, ws + L.U, ws + L.H, (float *)(ws + L.Pg_all),
                                    (float *)(ws + L.Pu_all), (float *)(ws + L.VB_all), w->B_gate,
                                    w->B_up, ws + L.AdT, ws + L.Bg_T, ws + L.Bu_T, ws + L.dg_grp,
@@ -345,8 +364,10 @@ int mixlora_ffn_backward(const mixlora_dims *dims, const mixlora_weights *w, con
                             s, d_aux, D.aux_coeff, (float *)(ws + L.dw), (float *)(ws + L.dz),
                             ws + L.S, Kx, 2 * R, Kx - 2 * R, st));
   if (dt == MIXLORA_BF16) {
+    GatherJob gj[6];
+    for (int i = 0; i < 6; i++) gj[i] = GatherJob{fsrc[i], ws + L.small[i], by_token[i], weighted[i]};
+    HIP_TRY(launch_gather_small_T(pc, gj, 6, L.ldT, st));
     for (int i = 0; i < 6; i++) {
-      HIP_TRY(launch_gather_small_T(pc, fsrc[i], by_token[i], weighted[i], ws + L.small[i], L.ldT, st));
       HIP_TRY(launch_group_outer_mfma(offs, N, kT, gat[i], k, ws + L.small[i], L.ldT, r, wide[i],
                                       width[i], s, layout_qc[i], gout[i], part, pfl, st));
     }
@@ -364,11 +385,9 @@ int mixlora_ffn_backward(const mixlora_dims *dims, const mixlora_weights *w, con
                                (float *)(ws + L.dz), N, x, d, 1.f, 1, grads->dW_router, part, pfl, st));
   }
   // dx = dgsum W_gate + dusum W_up + [TG | TU | dz] [s A_gate ; s A_up ; W_router]
-  HIP_TRY(launch_scatter_blocks(dt, pc, (float *)(ws + L.TG_all), R, 1, 0, ws + L.S, Kx, 0, st));
-  HIP_TRY(launch_scatter_blocks(dt, pc, (float *)(ws + L.TU_all), R, 1, 0, ws + L.S, Kx, R, st));
-  HIP_TRY(launch_pack_A_cat(dt, w->A_gate, N, r, d, s, ws + L.Bx, Kx, 0, st));
-  HIP_TRY(launch_pack_A_cat(dt, w->A_up, N, r, d, s, ws + L.Bx, Kx, R, st));
-  HIP_TRY(launch_pack_router_T(dt, w->W_router, N, d, ws + L.Bx, Kx, 2 * R, Kx - 2 * R, st));
+  HIP_TRY(launch_scatter_blocks(dt, pc, (float *)(ws + L.TG_all),
+                                (int64_t)((float *)(ws + L.TU_all) - (float *)(ws + L.TG_all)), 2, R,
+                                1, 0, ws + L.S, Kx, 0, st));
   {
     GemmProblem p = problem(T, d, dx, d, 0);
     add_seg(p, ws + L.dgsum, f, WgT, f, f);

@@ -65,8 +65,9 @@ struct GemmProblem {
   int64_t ldc;
   int c_f32;  // 1: C is float32 regardless of the storage dtype
 };
-// Enqueue up to four independent problems of identical M in one launch (N and the output type
-// may differ per problem).
+// Enqueue up to GEMM_MAX_PROBLEMS independent problems of identical M in one launch (N and the
+// output type may differ per problem).
+constexpr int GEMM_MAX_PROBLEMS = 5;
 hipError_t launch_gemm(int dtype, const GemmProblem *probs, int nprob, hipStream_t st);
 
 // Measurement hook: HIP-event timing of every launch of the large-tile bf16 kernel between
@@ -78,6 +79,10 @@ int gemm_timer_end(double *ms_total, int *launches, double *flops_total);
 hipError_t launch_router(int dtype, const void *x, const void *W_router, int T, int d, int N,
                          int k, float *probs, int32_t *idx_out, float *w_out, int32_t *idx_ws,
                          float *w_ws, hipStream_t st);
+// Same routing from logits Z[t, n] (row pitch ldz) that a GEMM launch produced.
+hipError_t launch_route_logits(const float *Z, int ldz, int T, int N, int k, float *probs,
+                               int32_t *idx_out, float *w_out, int32_t *idx_ws, float *w_ws,
+                               hipStream_t st);
 // Stable grouping of the k*T pairs by expert: counts[N], first_counts[N] (slot-0 histogram),
 // offs[N+1], row_of_pair[kT], pair_of_row[kT].  counts_out may be NULL.
 hipError_t launch_group_pairs(const int32_t *idx, int T, int N, int k, int32_t *counts,
@@ -131,24 +136,41 @@ int fused_splits(int f);
 // out[t,:] = sum_j (weighted ? w[t,j] : 1) * in_grp[row_of_pair[t,j], :]
 hipError_t launch_pair_combine(int dtype, const PairCtx &pc, int width, const void *in_grp,
                                void *out, int weighted, hipStream_t st);
-// dst[t, e_j*r + q] = scale_j * src[row_j, src_col0 + q] for the kept experts, 0 elsewhere;
-// dst is in the storage dtype with leading dimension ldd, columns [col0, col0 + N*r).
-hipError_t launch_scatter_blocks(int dtype, const PairCtx &pc, const float *src, int lds_,
-                                 int src_dense, int weighted, void *dst, int ldd, int col0,
-                                 hipStream_t st);
+// dst[t, col0 + e_j*r + q] = scale_j * src[row_j, (src_dense ? e_j*r : 0) + q] for the kept
+// experts, 0 elsewhere; dst is in the storage dtype with leading dimension ldd.  nsrc sources
+// (src + b*src_stride, b < nsrc) fill consecutive N*r-column blocks in one launch.
+hipError_t launch_scatter_blocks(int dtype, const PairCtx &pc, const float *src, int64_t src_stride,
+                                 int nsrc, int lds_, int src_dense, int weighted, void *dst,
+                                 int ldd, int col0, hipStream_t st);
 // small_grp[row, q] = scale * src[(by_token ? t(row) : row), e(row)*r + q]   (float32)
 hipError_t launch_gather_small(const PairCtx &pc, const float *src, int by_token, int weighted,
                                float *small_grp, hipStream_t st);
 
-// Weight re-layouts (tiny): see the definitions for the index maps.
-hipError_t launch_pack_bank_cat(int dtype, const void *bank, int N, int rows, int r, float scale,
-                                void *out, int ldo, int col0, hipStream_t st);
-hipError_t launch_pack_bank_T(int dtype, const void *bank, int N, int rows, int r, void *out,
-                              hipStream_t st);
-hipError_t launch_pack_A_cat(int dtype, const void *A, int N, int r, int cols, float scale,
-                             void *out, int ldo, int col0, hipStream_t st);
-hipError_t launch_pack_router_T(int dtype, const void *W_router, int N, int d, void *out,
-                                int ldo, int col0, int ncols, hipStream_t st);
+// Weight re-layouts (tiny index permutations), batched into one launch:
+//   dst[dst0 + i0*d0 + i1*d1 + i2*d2] = scale * src[i0*s0 + i1*s1 + i2*s2]   (0 where i2 >= valid2)
+// or, with batched_transpose set,  dst[dst0 + b*d0 + q*d1 + p] = scale * src[b*s0 + p*n2 + q]  for
+// b < n0, p < n1, q < n2 (0 where p >= valid2), tiled through LDS.
+struct RelayoutJob {
+  const void *src;
+  void *dst;
+  int64_t s0, s1, s2, dst0, d0, d1, d2;
+  int n0, n1, n2, valid2;
+  float scale;
+  int batched_transpose;
+};
+constexpr int RELAYOUT_MAX_JOBS = 8;
+hipError_t launch_relayout(int dtype, const RelayoutJob *jobs, int njobs, hipStream_t st);
+// bank [N, rows, r] -> out[i, col0 + e*r + q] = scale * bank[e, i, q]   (out pitch ldo)
+RelayoutJob job_bank_cat(const void *bank, int N, int rows, int r, float scale, void *out,
+                         int ldo, int col0);
+// bank [N, rows, r] -> out[e*r + q, i]                                   (out is [N*r, rows])
+RelayoutJob job_bank_T(const void *bank, int N, int rows, int r, void *out);
+// A [N, r, cols] -> out[c, col0 + e*r + q] = scale * A[e, q, c]
+RelayoutJob job_A_cat(const void *A, int N, int r, int cols, float scale, void *out, int ldo,
+                      int col0);
+// W_router [N, d] -> out[c, col0 + n] = W_router[n, c] for n < N, 0 for N <= n < ncols
+RelayoutJob job_router_T(const void *W_router, int N, int d, void *out, int ldo, int col0,
+                         int ncols);
 hipError_t launch_transpose(int dtype, const void *in, void *out, int rows, int cols,
                             hipStream_t st);
 
@@ -169,8 +191,16 @@ hipError_t launch_group_outer_mfma(const int32_t *offs, int G, int nrows,
                                    float *out, float *partials, size_t partial_floats,
                                    hipStream_t st);
 size_t group_outer_mfma_partial_floats(int G, int r, int C);
-hipError_t launch_gather_small_T(const PairCtx &pc, const float *src, int by_token, int weighted,
-                                 void *outT, int ldT, hipStream_t st);
+// outT[q, row] = (w_row or 1) * src[(by_token ? t(row) : row), e(row)*r + q] as bf16, pitch ldT;
+// up to GATHER_MAX_JOBS factors in one launch
+struct GatherJob {
+  const float *src;
+  void *outT;
+  int by_token, weighted;
+};
+constexpr int GATHER_MAX_JOBS = 6;
+hipError_t launch_gather_small_T(const PairCtx &pc, const GatherJob *jobs, int njobs, int ldT,
+                                 hipStream_t st);
 hipError_t launch_f32_to_bf16T(const float *src, int rows, int r, void *outT, int ldT,
                                hipStream_t st);
 

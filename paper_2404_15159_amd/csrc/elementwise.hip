@@ -288,11 +288,14 @@ hipError_t launch_pair_combine(int dtype, const PairCtx &pc, int width, const vo
 
 // dst[t, col0 + e*r + q] = (w[t,j] or 1) * src[row_j, (src_dense ? e*r : 0) + q] when expert e is
 // slot j of token t, else 0.  Builds the block-sparse low-rank operand of a K-extension.
+// blockIdx.y = b handles a further source src + b*src_stride into columns col0 + b*N*r.
 template <typename E>
-__global__ void scatter_blocks_kernel(PairCtx pc, const float *__restrict__ src, int lds_,
-                                      int src_dense, int weighted, E *__restrict__ dst, int ldd,
-                                      int col0) {
+__global__ void scatter_blocks_kernel(PairCtx pc, const float *__restrict__ src0,
+                                      int64_t src_stride, int lds_, int src_dense, int weighted,
+                                      E *__restrict__ dst, int ldd, int col00) {
   const int R = pc.N * pc.r;
+  const float *__restrict__ src = src0 + blockIdx.y * src_stride;
+  const int col0 = col00 + blockIdx.y * R;
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (int64_t)pc.T * R) return;
   const int t = (int)(i / R), er = (int)(i % R);
@@ -308,17 +311,17 @@ __global__ void scatter_blocks_kernel(PairCtx pc, const float *__restrict__ src,
   dst[(int64_t)t * ldd + col0 + er] = from_f32<E>(v);
 }
 
-hipError_t launch_scatter_blocks(int dtype, const PairCtx &pc, const float *src, int lds_,
-                                 int src_dense, int weighted, void *dst, int ldd, int col0,
-                                 hipStream_t st) {
+hipError_t launch_scatter_blocks(int dtype, const PairCtx &pc, const float *src, int64_t src_stride,
+                                 int nsrc, int lds_, int src_dense, int weighted, void *dst,
+                                 int ldd, int col0, hipStream_t st) {
   const int64_t n = (int64_t)pc.T * pc.N * pc.r;
-  const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+  const dim3 grid((unsigned)((n + 255) / 256), nsrc), block(256);
   if (dtype == MIXLORA_BF16)
-    hipLaunchKernelGGL(scatter_blocks_kernel<bf16_t>, grid, block, 0, st, pc, src, lds_, src_dense,
-                       weighted, (bf16_t *)dst, ldd, col0);
+    hipLaunchKernelGGL(scatter_blocks_kernel<bf16_t>, grid, block, 0, st, pc, src, src_stride, lds_,
+                       src_dense, weighted, (bf16_t *)dst, ldd, col0);
   else
-    hipLaunchKernelGGL(scatter_blocks_kernel<float>, grid, block, 0, st, pc, src, lds_, src_dense,
-                       weighted, (float *)dst, ldd, col0);
+    hipLaunchKernelGGL(scatter_blocks_kernel<float>, grid, block, 0, st, pc, src, src_stride, lds_,
+                       src_dense, weighted, (float *)dst, ldd, col0);
   return hipGetLastError();
 }
 
@@ -345,93 +348,119 @@ hipError_t launch_gather_small(const PairCtx &pc, const float *src, int by_token
 }
 
 // ---- weight re-layouts (all tiny next to the frozen matrices) -------------------------------
-// bank [N, rows, r]  ->  out[i, col0 + e*r + q] = scale * bank[e, i, q]
+// Every re-layout is an index permutation of at most three loop dimensions (i2 fastest over the
+// threads):  dst[dst0 + i0*d0 + i1*d1 + i2*d2] = scale * src[i0*s0 + i1*s1 + i2*s2], with zeros
+// written where i2 >= valid2.  Up to RELAYOUT_MAX_JOBS of them run in one launch (blockIdx.y
+// picks the job), since each alone is dominated by its launch.
+struct RelayoutBatch {
+  RelayoutJob job[RELAYOUT_MAX_JOBS];
+};
+
 template <typename E>
-__global__ void pack_bank_cat_kernel(const E *__restrict__ bank, int N, int rows, int r,
-                                     float scale, E *__restrict__ out, int ldo, int col0) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= (int64_t)N * rows * r) return;
-  const int q = (int)(i % r);
-  const int row = (int)((i / r) % rows);
-  const int e = (int)(i / ((int64_t)r * rows));
-  out[(int64_t)row * ldo + col0 + e * r + q] = from_f32<E>(scale * to_f32(bank[i]));
-}
-// bank [N, rows, r]  ->  out[e*r + q, i] = bank[e, i, q]      (out is [N*r, rows])
-template <typename E>
-__global__ void pack_bank_T_kernel(const E *__restrict__ bank, int N, int rows, int r,
-                                   E *__restrict__ out) {
-  const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (o >= (int64_t)N * rows * r) return;
-  const int i = (int)(o % rows);
-  const int er = (int)(o / rows);
-  const int e = er / r, q = er % r;
-  out[o] = bank[((int64_t)e * rows + i) * r + q];
-}
-// A [N, r, cols]  ->  out[c, col0 + e*r + q] = scale * A[e, q, c]
-template <typename E>
-__global__ void pack_A_cat_kernel(const E *__restrict__ A, int N, int r, int cols, float scale,
-                                  E *__restrict__ out, int ldo, int col0) {
-  const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int R = N * r;
-  if (o >= (int64_t)cols * R) return;
-  const int er = (int)(o % R);
-  const int c = (int)(o / R);
-  out[(int64_t)c * ldo + col0 + er] = from_f32<E>(scale * to_f32(A[(int64_t)er * cols + c]));
-}
-// W_router [N, d]  ->  out[c, col0 + n] = W_router[n, c] for n < N, 0 for N <= n < ncols
-template <typename E>
-__global__ void pack_router_T_kernel(const E *__restrict__ Wr, int N, int d, E *__restrict__ out,
-                                     int ldo, int col0, int ncols) {
-  const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (o >= (int64_t)d * ncols) return;
-  const int n = (int)(o % ncols);
-  const int c = (int)(o / ncols);
-  out[(int64_t)c * ldo + col0 + n] = n < N ? Wr[(int64_t)n * d + c] : from_f32<E>(0.f);
+__global__ __launch_bounds__(256) void relayout_kernel(RelayoutBatch batch) {
+  const RelayoutJob &J = batch.job[blockIdx.y];
+  const E *__restrict__ src = reinterpret_cast<const E *>(J.src);
+  E *__restrict__ dst = reinterpret_cast<E *>(J.dst);
+  if (J.batched_transpose) {
+    // dst[dst0 + b*d0 + q*d1 + p] = scale * src[b*s0 + p*n2 + q] for b < n0, p < n1, q < n2
+    // (zeros where p >= valid2): 64x64 tiles through LDS so that both the reads and the writes
+    // run along a contiguous dimension
+    __shared__ float tile[64][64 + 1];
+    const int P = J.n1, Q = J.n2, PV = J.valid2;
+    const int tp = (P + 63) / 64, tq = (Q + 63) / 64;
+    const int ntiles = J.n0 * tp * tq;
+    for (int tid = blockIdx.x; tid < ntiles; tid += gridDim.x) {
+      const int b = tid / (tp * tq), rem = tid % (tp * tq);
+      const int p0 = (rem / tq) * 64, q0 = (rem % tq) * 64;
+      const int hp = P - p0 < 64 ? P - p0 : 64, hq = Q - q0 < 64 ? Q - q0 : 64;
+      // reads walk the source rows (hq contiguous elements each; one contiguous block when the
+      // whole row fits), writes walk the destination rows (hp contiguous elements each)
+      for (int x = threadIdx.x; x < hp * hq; x += 256) {
+        const int i = x / hq, j = x - i * hq;
+        tile[i][j] = p0 + i < PV ? J.scale * to_f32(src[b * J.s0 + (int64_t)(p0 + i) * Q + q0 + j]) : 0.f;
+      }
+      __syncthreads();
+      for (int x = threadIdx.x; x < hp * hq; x += 256) {
+        const int j = x / hp, i = x - j * hp;
+        dst[J.dst0 + b * J.d0 + (q0 + j) * J.d1 + p0 + i] = from_f32<E>(tile[i][j]);
+      }
+      __syncthreads();
+    }
+    return;
+  }
+  // element counts are below 2^31 (checked by the launcher): 32-bit index arithmetic
+  const unsigned n2 = J.n2, n1 = J.n1, total = (unsigned)J.n0 * n1 * n2;
+  for (unsigned o = blockIdx.x * blockDim.x + threadIdx.x; o < total; o += gridDim.x * blockDim.x) {
+    const unsigned i2 = o % n2, t = o / n2;
+    const unsigned i1 = t % n1, i0 = t / n1;
+    const float v = (int)i2 < J.valid2 ? J.scale * to_f32(src[i0 * J.s0 + i1 * J.s1 + i2 * J.s2]) : 0.f;
+    dst[J.dst0 + i0 * J.d0 + i1 * J.d1 + i2 * J.d2] = from_f32<E>(v);
+  }
 }
 
-hipError_t launch_pack_bank_cat(int dtype, const void *bank, int N, int rows, int r, float scale,
-                                void *out, int ldo, int col0, hipStream_t st) {
-  const int64_t n = (int64_t)N * rows * r;
-  if (dtype == MIXLORA_BF16)
-    hipLaunchKernelGGL(pack_bank_cat_kernel<bf16_t>, dim3((unsigned)((n + 255) / 256)), dim3(256),
-                       0, st, (const bf16_t *)bank, N, rows, r, scale, (bf16_t *)out, ldo, col0);
-  else
-    hipLaunchKernelGGL(pack_bank_cat_kernel<float>, dim3((unsigned)((n + 255) / 256)), dim3(256),
-                       0, st, (const float *)bank, N, rows, r, scale, (float *)out, ldo, col0);
+hipError_t launch_relayout(int dtype, const RelayoutJob *jobs, int njobs, hipStream_t st) {
+  if (njobs < 1 || njobs > RELAYOUT_MAX_JOBS) return hipErrorInvalidValue;
+  RelayoutBatch b;
+  int64_t most = 1;
+  for (int i = 0; i < RELAYOUT_MAX_JOBS; i++) {
+    b.job[i] = jobs[i < njobs ? i : 0];
+    const int64_t n = (int64_t)b.job[i].n0 * b.job[i].n1 * b.job[i].n2;
+    if (n >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
+    // blocks wanted: one per 256 elements, or one per 64x64 tile
+    const int64_t want = b.job[i].batched_transpose
+                             ? (int64_t)b.job[i].n0 * ((b.job[i].n1 + 63) / 64) * ((b.job[i].n2 + 63) / 64)
+                             : (n + 255) / 256;
+    most = want > most ? want : most;
+  }
+  int64_t blocks = most;
+  if (blocks > 8192) blocks = 8192;   // grid-stride beyond that
+  const dim3 grid((unsigned)blocks, njobs), block(256);
+  if (dtype == MIXLORA_BF16) hipLaunchKernelGGL(relayout_kernel<bf16_t>, grid, block, 0, st, b);
+  else hipLaunchKernelGGL(relayout_kernel<float>, grid, block, 0, st, b);
   return hipGetLastError();
 }
-hipError_t launch_pack_bank_T(int dtype, const void *bank, int N, int rows, int r, void *out,
-                              hipStream_t st) {
-  const int64_t n = (int64_t)N * rows * r;
-  if (dtype == MIXLORA_BF16)
-    hipLaunchKernelGGL(pack_bank_T_kernel<bf16_t>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
-                       st, (const bf16_t *)bank, N, rows, r, (bf16_t *)out);
-  else
-    hipLaunchKernelGGL(pack_bank_T_kernel<float>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
-                       st, (const float *)bank, N, rows, r, (float *)out);
-  return hipGetLastError();
+
+// bank [N, rows, r]  ->  out[i, col0 + e*r + q] = scale * bank[e, i, q]     (out pitch ldo)
+RelayoutJob job_bank_cat(const void *bank, int N, int rows, int r, float scale, void *out,
+                         int ldo, int col0) {
+  RelayoutJob j{};
+  j.src = bank; j.dst = out; j.scale = scale;
+  j.n0 = N; j.n1 = rows; j.n2 = r; j.valid2 = r;
+  j.s0 = (int64_t)rows * r; j.s1 = r; j.s2 = 1;
+  j.dst0 = col0; j.d0 = r; j.d1 = ldo; j.d2 = 1;
+  return j;
 }
-hipError_t launch_pack_A_cat(int dtype, const void *A, int N, int r, int cols, float scale,
-                             void *out, int ldo, int col0, hipStream_t st) {
-  const int64_t n = (int64_t)N * r * cols;
-  if (dtype == MIXLORA_BF16)
-    hipLaunchKernelGGL(pack_A_cat_kernel<bf16_t>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
-                       st, (const bf16_t *)A, N, r, cols, scale, (bf16_t *)out, ldo, col0);
-  else
-    hipLaunchKernelGGL(pack_A_cat_kernel<float>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
-                       st, (const float *)A, N, r, cols, scale, (float *)out, ldo, col0);
-  return hipGetLastError();
+// bank [N, rows, r]  ->  out[e*r + q, i] = bank[e, i, q]                     (out is [N*r, rows])
+RelayoutJob job_bank_T(const void *bank, int N, int rows, int r, void *out) {
+  RelayoutJob j{};
+  j.src = bank; j.dst = out; j.scale = 1.f;
+  j.batched_transpose = 1;
+  j.n0 = N; j.n1 = rows; j.n2 = r; j.valid2 = rows;
+  j.s0 = (int64_t)rows * r;
+  j.dst0 = 0; j.d0 = (int64_t)r * rows; j.d1 = rows;
+  return j;
 }
-hipError_t launch_pack_router_T(int dtype, const void *W_router, int N, int d, void *out,
-                                int ldo, int col0, int ncols, hipStream_t st) {
-  const int64_t n = (int64_t)d * ncols;
-  if (dtype == MIXLORA_BF16)
-    hipLaunchKernelGGL(pack_router_T_kernel<bf16_t>, dim3((unsigned)((n + 255) / 256)), dim3(256),
-                       0, st, (const bf16_t *)W_router, N, d, (bf16_t *)out, ldo, col0, ncols);
-  else
-    hipLaunchKernelGGL(pack_router_T_kernel<float>, dim3((unsigned)((n + 255) / 256)), dim3(256),
-                       0, st, (const float *)W_router, N, d, (float *)out, ldo, col0, ncols);
-  return hipGetLastError();
+// A [N, r, cols]  ->  out[c, col0 + e*r + q] = scale * A[e, q, c]
+RelayoutJob job_A_cat(const void *A, int N, int r, int cols, float scale, void *out, int ldo,
+                      int col0) {
+  RelayoutJob j{};
+  j.src = A; j.dst = out; j.scale = scale;
+  j.batched_transpose = 1;   // one [N*r, cols] matrix -> [cols, N*r] at pitch ldo
+  j.n0 = 1; j.n1 = N * r; j.n2 = cols; j.valid2 = N * r;
+  j.s0 = 0;
+  j.dst0 = col0; j.d0 = 0; j.d1 = ldo;
+  return j;
+}
+// W_router [N, d]  ->  out[c, col0 + n] = W_router[n, c] for n < N, 0 for N <= n < ncols
+RelayoutJob job_router_T(const void *W_router, int N, int d, void *out, int ldo, int col0,
+                         int ncols) {
+  RelayoutJob j{};
+  j.src = W_router; j.dst = out; j.scale = 1.f;
+  j.batched_transpose = 1;   // [N, d] -> [d, ncols] at pitch ldo, zero-filled past N
+  j.n0 = 1; j.n1 = ncols; j.n2 = d; j.valid2 = N;
+  j.s0 = 0;
+  j.dst0 = col0; j.d0 = 0; j.d1 = ldo;
+  return j;
 }
 
 // out[cols, rows] = in[rows, cols]^T through a padded 64x64 LDS tile

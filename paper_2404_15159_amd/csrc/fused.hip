@@ -481,12 +481,16 @@ __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 2 : 1) void swiglu_bwd_mf
         (dwred[0][threadIdx.x] + dwred[1][threadIdx.x]) + (dwred[2][threadIdx.x] + dwred[3][threadIdx.x]);
 }
 
-// dense[row, e(row)*r + q] = sum over splits of part[split][row][q]   (fixed order)
-__global__ void reduce_rank_parts_kernel(PairCtx pc, const float *__restrict__ part, int nsplit,
-                                         float *__restrict__ dense) {
+// dense[row, e(row)*r + q] = sum over splits of part[split][row][q]   (fixed order); blockIdx.y
+// picks the bank (partials bank_stride floats apart, outputs dense0 / dense1)
+__global__ void reduce_rank_parts_kernel(PairCtx pc, const float *__restrict__ part0,
+                                         int64_t bank_stride, int nsplit,
+                                         float *__restrict__ dense0, float *__restrict__ dense1) {
   const int nP = pc.T * pc.k, r = pc.r;
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (int64_t)nP * r) return;
+  const float *part = part0 + blockIdx.y * bank_stride;
+  float *dense = blockIdx.y ? dense1 : dense0;
   const int row = (int)(i / r), q = (int)(i % r);
   float acc = 0.f;
   for (int sp = 0; sp < nsplit; sp++) acc += part[(int64_t)sp * nP * r + i];
@@ -519,7 +523,7 @@ hipError_t launch_swiglu_fwd_mfma(const PairCtx &pc, int f, float s, const void 
   if (e != hipSuccess) return e;
   const int64_t n = (int64_t)nP * pc.r;
   hipLaunchKernelGGL(reduce_rank_parts_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                     pc, Q_part, nsplit, Q_all);
+                     pc, Q_part, (int64_t)0, nsplit, Q_all, Q_all);
   return hipGetLastError();
 }
 
@@ -545,9 +549,9 @@ hipError_t launch_swiglu_bwd_mfma(const PairCtx &pc, int f, float s, const void 
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int64_t n = (int64_t)nP * pc.r;
-  const dim3 rgrid((unsigned)((n + 255) / 256));
-  hipLaunchKernelGGL(reduce_rank_parts_kernel, rgrid, dim3(256), 0, st, pc, TG_part, nsplit, TG_all);
-  hipLaunchKernelGGL(reduce_rank_parts_kernel, rgrid, dim3(256), 0, st, pc, TU_part, nsplit, TU_all);
+  const dim3 rgrid((unsigned)((n + 255) / 256), 2);
+  hipLaunchKernelGGL(reduce_rank_parts_kernel, rgrid, dim3(256), 0, st, pc, TG_part,
+                     (int64_t)(TU_part - TG_part), nsplit, TG_all, TU_all);
   return hipGetLastError();
 }
 

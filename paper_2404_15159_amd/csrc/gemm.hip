@@ -16,7 +16,7 @@
 namespace mixlora {
 
 struct GemmBatch {
-  GemmProblem p[4];
+  GemmProblem p[GEMM_MAX_PROBLEMS];
 };
 
 // Map the hardware block id to a tile so that (a) blocks that land on the same XCD (id % 8)
@@ -621,9 +621,9 @@ static bool dl_eligible(const GemmBatch &b, int nprob, int BK) {
 }
 
 hipError_t launch_gemm(int dtype, const GemmProblem *probs, int nprob, hipStream_t st) {
-  if (nprob < 1 || nprob > 4) return hipErrorInvalidValue;
+  if (nprob < 1 || nprob > GEMM_MAX_PROBLEMS) return hipErrorInvalidValue;
   GemmBatch b;
-  for (int i = 0; i < 4; i++) b.p[i] = probs[i < nprob ? i : 0];
+  for (int i = 0; i < GEMM_MAX_PROBLEMS; i++) b.p[i] = probs[i < nprob ? i : 0];
   const int M = probs[0].M, N = probs[0].N;
   bool uniform = true, any_big = false;
   for (int i = 0; i < nprob; i++) {

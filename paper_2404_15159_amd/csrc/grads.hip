@@ -261,25 +261,34 @@ hipError_t launch_group_outer_mfma(const int32_t *offs, int G, int nrows,
   return hipGetLastError();
 }
 
-// smallT[q][row] (bf16, leading dimension ldT) = (w_row or 1) * src[(by_token ? t : row), e*r + q]
-__global__ void gather_small_T_kernel(PairCtx pc, const float *__restrict__ src, int by_token,
-                                      int weighted, bf16_t *__restrict__ outT, int ldT) {
+// Transposed bf16 row factors for the MFMA gradient sums, several factors per launch:
+//   outT[q, row] = (w_row or 1) * src[(by_token ? t(row) : row), e(row)*r + q]
+struct GatherBatch {
+  GatherJob job[GATHER_MAX_JOBS];
+};
+
+__global__ void gather_small_T_kernel(PairCtx pc, GatherBatch batch, int ldT) {
+  const GatherJob &J = batch.job[blockIdx.y];
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int nP = pc.T * pc.k;
   if (i >= (int64_t)nP * pc.r) return;
   const int q = (int)(i / nP), row = (int)(i % nP);
   const int p = pc.pair_of_row[row];
   const int e = pc.idx[p];
-  const int64_t srow = by_token ? p / pc.k : row;
-  const float w = weighted ? pc.w[p] : 1.f;
-  outT[(int64_t)q * ldT + row] = (bf16_t)(w * src[srow * (pc.N * pc.r) + e * pc.r + q]);
+  const int64_t srow = J.by_token ? p / pc.k : row;
+  const float w = J.weighted ? pc.w[p] : 1.f;
+  reinterpret_cast<bf16_t *>(J.outT)[(int64_t)q * ldT + row] =
+      (bf16_t)(w * J.src[srow * (pc.N * pc.r) + e * pc.r + q]);
 }
 
-hipError_t launch_gather_small_T(const PairCtx &pc, const float *src, int by_token, int weighted,
-                                 void *outT, int ldT, hipStream_t st) {
+hipError_t launch_gather_small_T(const PairCtx &pc, const GatherJob *jobs, int njobs, int ldT,
+                                 hipStream_t st) {
+  if (njobs < 1 || njobs > GATHER_MAX_JOBS) return hipErrorInvalidValue;
+  GatherBatch b;
+  for (int i = 0; i < GATHER_MAX_JOBS; i++) b.job[i] = jobs[i < njobs ? i : 0];
   const int64_t n = (int64_t)pc.T * pc.k * pc.r;
-  hipLaunchKernelGGL(gather_small_T_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, pc,
-                     src, by_token, weighted, (bf16_t *)outT, ldT);
+  hipLaunchKernelGGL(gather_small_T_kernel, dim3((unsigned)((n + 255) / 256), njobs), dim3(256), 0,
+                     st, pc, b, ldT);
   return hipGetLastError();
 }
 
@@ -301,63 +310,71 @@ hipError_t launch_f32_to_bf16T(const float *src, int rows, int r, void *outT, in
 }
 
 // ---- router backward -------------------------------------------------------------------------
-// One thread per token.  dw_j = <dy_t, o_pair> is assembled from the column-tile partials of
-// <H[t], a_row> plus the low-rank part  s <B_down[e]^T dy_t, A_down[e] a_row>.  Then, with
-// w_j = p_j / sum_kept p (Norm of Algorithm 1):  dp_j = (dw_j - sum_i w_i dw_i) / sum_kept p on
-// the kept experts, plus the auxiliary term  d_aux * a * N * F_e / T  on every expert (Eq. 8-9;
-// F is piecewise constant), and dz = p * (dp - <p, dp>) through the softmax of Eq. 7.
+// One wavefront per token.  dw_j = <dy_t, o_pair> is assembled from the column-tile partials of
+// <H[t], a_row> plus the low-rank part  s <B_down[e]^T dy_t, A_down[e] a_row>  (lanes split the
+// terms, a butterfly adds them).  Then, with w_j = p_j / sum_kept p (Norm of Algorithm 1):
+// dp_j = (dw_j - sum_i w_i dw_i) / sum_kept p on the kept experts, plus the auxiliary term
+// d_aux * a * N * F_e / T  on every expert (Eq. 8-9; F is piecewise constant), and
+// dz = p * (dp - <p, dp>) through the softmax of Eq. 7 (lane e holds expert e).
+__device__ __forceinline__ float rb_wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
 template <typename E>
-__global__ void router_bwd_kernel(PairCtx pc, const float *__restrict__ probs,
-                                  const float *__restrict__ dw_part, int n_col_tiles,
-                                  const float *__restrict__ VB_all, const float *__restrict__ Q_all,
-                                  const float *__restrict__ F, float s, float d_aux,
-                                  float aux_coeff, float *__restrict__ dw_ws,
-                                  float *__restrict__ dz, E *__restrict__ S, int lds_, int col0,
-                                  int ncols) {
-  const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= pc.T) return;
+__global__ __launch_bounds__(256) void router_bwd_kernel(
+    PairCtx pc, const float *__restrict__ probs, const float *__restrict__ dw_part,
+    int n_col_tiles, const float *__restrict__ VB_all, const float *__restrict__ Q_all,
+    const float *__restrict__ F, float s, float d_aux, float aux_coeff,
+    float *__restrict__ dw_ws, float *__restrict__ dz, E *__restrict__ S, int lds_, int col0,
+    int ncols) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= pc.T) return;   // whole wave leaves together
   const int N = pc.N, k = pc.k, r = pc.r, R = N * r;
-  float wdw = 0.f, ssum = 0.f;
+  float my_dw = 0.f, my_w = 0.f, my_p = 0.f;   // lane j < k: slot j of the token
+  int my_e = -1;
   for (int j = 0; j < k; j++) {
     const int p = t * k + j;
     const int row = pc.row_of_pair[p];
     const int e = pc.idx[p];
-    float acc = 0.f;
-    for (int ct = 0; ct < n_col_tiles; ct++) acc += dw_part[(int64_t)row * n_col_tiles + ct];
+    float part = 0.f;
+    for (int ct = lane; ct < n_col_tiles; ct += 64) part += dw_part[(int64_t)row * n_col_tiles + ct];
     float lr = 0.f;
-    for (int q = 0; q < r; q++)
+    for (int q = lane; q < r; q += 64)
       lr = fmaf(VB_all[(int64_t)t * R + e * r + q], Q_all[(int64_t)row * R + e * r + q], lr);
-    const float dwj = acc + s * lr;
-    dw_ws[p] = dwj;
-    wdw = fmaf(pc.w[p], dwj, wdw);
-    ssum += probs[(int64_t)t * N + e];
-  }
-  const float auxg = d_aux * aux_coeff * (float)N / (float)pc.T;
-  float dot = 0.f;
-  for (int e = 0; e < N; e++) {
-    float dp = auxg * F[e];
-    for (int j = 0; j < k; j++)
-      if (pc.idx[t * k + j] == e) dp += (dw_ws[t * k + j] - wdw) / ssum;
-    dot = fmaf(probs[(int64_t)t * N + e], dp, dot);
-  }
-  for (int e = 0; e < ncols; e++) {
-    float v = 0.f;
-    if (e < N) {
-      float dp = auxg * F[e];
-      for (int j = 0; j < k; j++)
-        if (pc.idx[t * k + j] == e) dp += (dw_ws[t * k + j] - wdw) / ssum;
-      v = probs[(int64_t)t * N + e] * (dp - dot);
-      dz[(int64_t)t * N + e] = v;
+    const float dwj = rb_wave_sum(part + s * lr);
+    if (lane == j) {
+      my_dw = dwj;
+      my_e = e;
+      my_w = pc.w[p];
+      my_p = probs[(int64_t)t * N + e];
+      dw_ws[p] = dwj;
     }
-    S[(int64_t)t * lds_ + col0 + e] = from_f32<E>(v);
   }
+  const float wdw = rb_wave_sum(my_w * my_dw);
+  const float ssum = rb_wave_sum(my_p);
+  const float auxg = d_aux * aux_coeff * (float)N / (float)pc.T;
+  float dp = lane < N ? auxg * F[lane] : 0.f;
+  for (int j = 0; j < k; j++) {
+    const int ej = __shfl(my_e, j, 64);
+    const float dwj = __shfl(my_dw, j, 64);
+    if (ej == lane) dp += (dwj - wdw) / ssum;
+  }
+  const float pe = lane < N ? probs[(int64_t)t * N + lane] : 0.f;
+  const float dot = rb_wave_sum(pe * dp);
+  const float v = pe * (dp - dot);   // 0 on lanes >= N
+  if (lane < N) dz[(int64_t)t * N + lane] = v;
+  for (int e = lane; e < ncols; e += 64)
+    S[(int64_t)t * lds_ + col0 + e] = from_f32<E>(e < N ? v : 0.f);
 }
 
 hipError_t launch_router_bwd(int dtype, const PairCtx &pc, const float *probs, const float *dw_part,
                              int n_col_tiles, const float *VB_all, const float *Q_all,
                              const float *F, float s, float d_aux, float aux_coeff, float *dw_ws,
                              float *dz, void *S, int lds_, int col0, int ncols, hipStream_t st) {
-  const dim3 grid((pc.T + 127) / 128), block(128);
+  const dim3 grid((pc.T + 3) / 4), block(256);
   if (dtype == MIXLORA_BF16)
     hipLaunchKernelGGL(router_bwd_kernel<bf16_t>, grid, block, 0, st, pc, probs, dw_part,
                        n_col_tiles, VB_all, Q_all, F, s, d_aux, aux_coeff, dw_ws, dz, (bf16_t *)S,

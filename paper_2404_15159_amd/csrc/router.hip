@@ -16,10 +16,45 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// Softmax over the N logits of token t (lane n holds logit n, lanes >= N hold -inf), top-k on
+// the logits (monotone with the probabilities; equal logits go to the lower expert index; slots
+// in descending order) and renormalisation of the kept probabilities.
+__device__ __forceinline__ void route_token(float z, int lane, int t, int N, int k,
+                                            float *__restrict__ probs,
+                                            int32_t *__restrict__ idx_out,
+                                            float *__restrict__ w_out,
+                                            int32_t *__restrict__ idx_ws,
+                                            float *__restrict__ w_ws) {
+  const float zmax = wave_max(z);
+  const float ez = lane < N ? expf(z - zmax) : 0.f;
+  const float p = ez / wave_sum(ez);
+  if (lane < N) probs[(int64_t)t * N + lane] = p;
+  // k rounds of arg-max with ties to the lowest lane
+  float zc = z;
+  float psel = 0.f;     // lane j keeps the probability of slot j
+  int esel = 0;
+  float ksum = 0.f;
+  for (int j = 0; j < k; j++) {
+    const float m = wave_max(zc);
+    const unsigned long long b = __ballot(zc == m && lane < N);
+    const int e = __ffsll((long long)b) - 1;
+    const float pe = __shfl(p, e, 64);
+    ksum += pe;
+    if (lane == j) { psel = pe; esel = e; }
+    if (lane == e) zc = -INFINITY;
+  }
+  if (lane < k) {
+    const float w = psel / ksum;
+    const int64_t o = (int64_t)t * k + lane;
+    idx_out[o] = esel;
+    w_out[o] = w;
+    idx_ws[o] = esel;
+    w_ws[o] = w;
+  }
+}
+
 // One wavefront per token.  Lane l accumulates, for every expert, the products of the 8-wide
 // chunks l, l+64, ... of the row; a butterfly then gives every lane the full logit.
-// Selection is on the logits (monotone with the probabilities); equal logits go to the lower
-// expert index; slots are in descending order.
 template <typename E, int NMAX>
 __global__ __launch_bounds__(256) void router_kernel(const E *__restrict__ x,
                                                      const E *__restrict__ Wr, int T, int d,
@@ -56,32 +91,22 @@ __global__ __launch_bounds__(256) void router_kernel(const E *__restrict__ x,
   }
   __builtin_amdgcn_wave_barrier();
   const float z = lane < N ? zbuf[wave][lane] : -INFINITY;
-  const float zmax = wave_max(z);
-  const float ez = lane < N ? expf(z - zmax) : 0.f;
-  const float p = ez / wave_sum(ez);
-  if (lane < N) probs[(int64_t)t * N + lane] = p;
-  // k rounds of arg-max with ties to the lowest lane
-  float zc = z;
-  float psel = 0.f;     // lane j keeps the probability of slot j
-  int esel = 0;
-  float ksum = 0.f;
-  for (int j = 0; j < k; j++) {
-    const float m = wave_max(zc);
-    const unsigned long long b = __ballot(zc == m && lane < N);
-    const int e = __ffsll((long long)b) - 1;
-    const float pe = __shfl(p, e, 64);
-    ksum += pe;
-    if (lane == j) { psel = pe; esel = e; }
-    if (lane == e) zc = -INFINITY;
-  }
-  if (lane < k) {
-    const float w = psel / ksum;
-    const int64_t o = (int64_t)t * k + lane;
-    idx_out[o] = esel;
-    w_out[o] = w;
-    idx_ws[o] = esel;
-    w_ws[o] = w;
-  }
+  route_token(z, lane, t, N, k, probs, idx_out, w_out, idx_ws, w_ws);
+}
+
+// Routing from logits that a GEMM launch has already produced: Z[t, n], row pitch ldz.
+__global__ __launch_bounds__(256) void route_logits_kernel(const float *__restrict__ Z, int ldz,
+                                                           int T, int N, int k,
+                                                           float *__restrict__ probs,
+                                                           int32_t *__restrict__ idx_out,
+                                                           float *__restrict__ w_out,
+                                                           int32_t *__restrict__ idx_ws,
+                                                           float *__restrict__ w_ws) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  const float z = lane < N ? Z[(int64_t)t * ldz + lane] : -INFINITY;
+  route_token(z, lane, t, N, k, probs, idx_out, w_out, idx_ws, w_ws);
 }
 
 template <typename E>
@@ -107,6 +132,14 @@ hipError_t launch_router(int dtype, const void *x, const void *W_router, int T, 
   return dtype == MIXLORA_BF16
              ? launch_router_t<bf16_t>(x, W_router, T, d, N, k, probs, idx_out, w_out, idx_ws, w_ws, st)
              : launch_router_t<float>(x, W_router, T, d, N, k, probs, idx_out, w_out, idx_ws, w_ws, st);
+}
+
+hipError_t launch_route_logits(const float *Z, int ldz, int T, int N, int k, float *probs,
+                               int32_t *idx_out, float *w_out, int32_t *idx_ws, float *w_ws,
+                               hipStream_t st) {
+  hipLaunchKernelGGL(route_logits_kernel, dim3((T + 3) / 4), dim3(256), 0, st, Z, ldz, T, N, k,
+                     probs, idx_out, w_out, idx_ws, w_ws);
+  return hipGetLastError();
 }
 
 // ---- grouping of pairs by expert ---------------------------------------------------------
