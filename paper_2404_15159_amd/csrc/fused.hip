@@ -493,7 +493,13 @@ __global__ void reduce_rank_parts_kernel(PairCtx pc, const float *__restrict__ p
   float *dense = blockIdx.y ? dense1 : dense0;
   const int row = (int)(i / r), q = (int)(i % r);
   float acc = 0.f;
-  for (int sp = 0; sp < nsplit; sp++) acc += part[(int64_t)sp * nP * r + i];
+  int sp = 0;
+  for (; sp + 4 <= nsplit; sp += 4) {   // four loads in flight; additions in split order
+    const float a0 = part[(int64_t)sp * nP * r + i], a1 = part[(int64_t)(sp + 1) * nP * r + i];
+    const float a2 = part[(int64_t)(sp + 2) * nP * r + i], a3 = part[(int64_t)(sp + 3) * nP * r + i];
+    acc += a0; acc += a1; acc += a2; acc += a3;
+  }
+  for (; sp < nsplit; sp++) acc += part[(int64_t)sp * nP * r + i];
   const int e = pc.idx[pc.pair_of_row[row]];
   dense[(int64_t)row * (pc.N * r) + e * r + q] = acc;
 }

@@ -80,8 +80,15 @@ __global__ void group_outer_reduce_kernel(const float *__restrict__ partial, int
   const int64_t n = (int64_t)G * r * C;
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
+  // four loads in flight at a time; the additions keep the split order
   float acc = 0.f;
-  for (int sp = 0; sp < nsplit; sp++) acc += partial[(int64_t)sp * n + i];
+  int sp = 0;
+  for (; sp + 4 <= nsplit; sp += 4) {
+    const float a0 = partial[(int64_t)sp * n + i], a1 = partial[(int64_t)(sp + 1) * n + i];
+    const float a2 = partial[(int64_t)(sp + 2) * n + i], a3 = partial[(int64_t)(sp + 3) * n + i];
+    acc += a0; acc += a1; acc += a2; acc += a3;
+  }
+  for (; sp < nsplit; sp++) acc += partial[(int64_t)sp * n + i];
   acc *= scale;
   if (layout_qc) {
     out[i] = acc;
