@@ -29,9 +29,19 @@ expert index; slots are ordered by descending logit; F_i of Eq. 9 counts the
 first-choice expert ("top1", as printed) or all k choices divided by k
 ("topk"); P_i uses the full softmax; no gradient flows through F_i.
 
+* Several adapters on one frozen base (Section 3.3, "Optimizing Multi-MixLoRA
+  Training and Inference (II)", outer loop of Algorithm 1): every token belongs
+  to one adapter and is routed and processed by that adapter's router and
+  experts only; multi_forward / multi_backward are that definition, adapter by
+  adapter, on top of the single-adapter functions.
+
 Pinned by tests/test_oracle_pins.py (dense-FFN special case, k = N mixture,
 merged-weight identity, brute-force loops, closed-form auxiliary losses,
-finite differences, autograd of an independent formulation).
+finite differences, autograd of an independent formulation) and, for the
+multi-adapter functions, tests/test_oracle_multi_pins.py (one adapter reduces
+to the single-adapter block, equality with one large block whose router is
+blocked by indicator channels, independence of the adapters, token-order
+equivariance, empty adapter).
 """
 from __future__ import annotations
 
@@ -183,3 +193,64 @@ def backward(x, W, k, lora_scale, dy, d_aux=1.0, aux_coeff=0.01, aux_mode="top1"
     out = {"d" + n: v for n, v in G.items()}
     out.update(dx=dx, dw=dw, dz=dz, forward=fw)
     return out
+
+
+def multi_forward(x, token_model, Ws, k, lora_scale, aux_coeff=0.01, aux_mode="top1"):
+    """M adapters sharing the frozen base (Section 3.3, optimisation II; outer loop of
+    Algorithm 1).  token_model [T] gives the adapter of every token; Ws is a list of M weight
+    dicts with identical W_gate / W_up / W_down.  Adapter m sees only its own tokens.
+
+    Returns y [T,d]; topk_idx [T,k] (expert index inside the token's adapter), topk_w [T,k];
+    probs [T,N] over the token's own adapter's experts; counts [M,N]; aux_loss [M] (Eq. 8-9 per
+    adapter over its own tokens; 0 for an adapter without tokens)."""
+    x = _f64(x)
+    token_model = np.asarray(token_model)
+    M = len(Ws)
+    T, d = x.shape
+    N = np.asarray(Ws[0]["W_router"]).shape[0]
+    y = np.zeros((T, d), dtype=F64)
+    idx = np.zeros((T, k), dtype=np.int64)
+    w = np.zeros((T, k), dtype=F64)
+    probs = np.zeros((T, N), dtype=F64)
+    counts = np.zeros((M, N), dtype=np.int64)
+    aux = np.zeros(M, dtype=F64)
+    for m in range(M):
+        tok = np.nonzero(token_model == m)[0]
+        if tok.size == 0:
+            continue
+        fw = forward(x[tok], Ws[m], k, lora_scale, aux_coeff, aux_mode)
+        y[tok] = fw["y"]
+        idx[tok] = fw["topk_idx"]
+        w[tok] = fw["topk_w"]
+        probs[tok] = fw["probs"]
+        counts[m] = fw["counts"]
+        aux[m] = fw["aux_loss"]
+    return dict(y=y, topk_idx=idx, topk_w=w, probs=probs, counts=counts, aux_loss=aux)
+
+
+def multi_backward(x, token_model, Ws, k, lora_scale, dy, d_aux=None, aux_coeff=0.01,
+                   aux_mode="top1"):
+    """Gradients of  <y, dy> + sum_m d_aux[m] * L_aux[m]  for the M-adapter block.
+
+    Returns dx [T,d] and, per adapter, the gradient dicts of `backward` in the list "grads"
+    (all zeros for an adapter without tokens); dz [T,N] over the token's own adapter."""
+    x = _f64(x)
+    dy = _f64(dy)
+    token_model = np.asarray(token_model)
+    M = len(Ws)
+    d_aux = np.ones(M) if d_aux is None else np.asarray(d_aux, dtype=F64)
+    N = np.asarray(Ws[0]["W_router"]).shape[0]
+    dx = np.zeros_like(x)
+    dz = np.zeros((x.shape[0], N), dtype=F64)
+    grads = []
+    names = ("A_gate", "B_gate", "A_up", "B_up", "A_down", "B_down", "W_router")
+    for m in range(M):
+        tok = np.nonzero(token_model == m)[0]
+        if tok.size == 0:
+            grads.append({"d" + n: np.zeros_like(_f64(Ws[m][n])) for n in names})
+            continue
+        bw = backward(x[tok], Ws[m], k, lora_scale, dy[tok], float(d_aux[m]), aux_coeff, aux_mode)
+        dx[tok] = bw["dx"]
+        dz[tok] = bw["dz"]
+        grads.append({"d" + n: bw["d" + n] for n in names})
+    return dict(dx=dx, dz=dz, grads=grads)

@@ -104,6 +104,7 @@ class Config:
     backward: bool = True
     structure: str = "uniform"   # "uniform" | "skew0" | "clusters4"
     seq_len: int = 1024
+    M: int = 1            # adapters sharing the frozen base; banks then hold M*N experts
 
     @property
     def lora_scale(self) -> float:
@@ -126,6 +127,10 @@ CONFIGS = {
     "llama3_8b_clusters": Config("llama3_8b_clusters", 5, T=16384, d=4096, d_ff=14336, N=16, k=2,
                                  r=8, alpha=16.0, dtype="bf16", b_std=0.01,
                                  structure="clusters4"),
+    # two adapters trained together on one frozen base (the multi-adapter setting of the
+    # paper's efficiency table): 4 sequences of 1024 tokens, alternating between the adapters
+    "llama2_7b_multi2": Config("llama2_7b_multi2", 6, T=4096, d=4096, d_ff=11008, N=8, k=2, r=16,
+                               alpha=32.0, dtype="bf16", b_std=0.01, M=2),
 }
 
 
@@ -145,7 +150,8 @@ def make_inputs(cfg: Config, only: Optional[tuple] = None) -> Dict[str, np.ndarr
     Returns fp32 arrays whose values are exactly representable in cfg.dtype:
       x [T,d], W_gate/W_up [d_ff,d], W_down [d,d_ff], A_gate/A_up [N,r,d],
       B_gate/B_up [N,d_ff,r], A_down [N,r,d_ff], B_down [N,d,r], W_router [N,d],
-      dy [T,d].
+      dy [T,d].  With cfg.M adapters the banks and the router hold M*N experts, adapter m's
+      expert e at index m*N + e.
     Distributions: x, dy ~ N(0,1); frozen W ~ N(0,0.02^2); A ~ U(+-1/sqrt(fan_in));
     B ~ N(0,b_std^2) (non-zero so that every LoRA path is exercised);
     W_router ~ N(0,0.02^2).
@@ -155,7 +161,7 @@ def make_inputs(cfg: Config, only: Optional[tuple] = None) -> Dict[str, np.ndarr
       clusters4 - sequence s (seq_len tokens) belongs to cluster s mod 4 and its tokens
                   are shifted by 0.5 * (random sign vector of the cluster).
     """
-    T, d, f, N, r = cfg.T, cfg.d, cfg.d_ff, cfg.N, cfg.r
+    T, d, f, N, r = cfg.T, cfg.d, cfg.d_ff, cfg.N * cfg.M, cfg.r
     seed = cfg.seed
     sid = {n: i for i, n in enumerate(TENSOR_ORDER)}
     want = set(only) if only is not None else set(TENSOR_ORDER)
@@ -200,3 +206,34 @@ def make_inputs(cfg: Config, only: Optional[tuple] = None) -> Dict[str, np.ndarr
 
 WEIGHT_NAMES = ("W_gate", "W_up", "W_down", "A_gate", "B_gate", "A_up", "B_up",
                 "A_down", "B_down", "W_router")
+
+
+def token_model(cfg: Config, pattern: str = "round_robin") -> np.ndarray:
+    """Adapter of every token, int32 [T].  Whole sequences (cfg.seq_len tokens) belong to one
+    adapter, as in a batch that mixes the training sequences of several adapters.
+      round_robin - sequence s goes to adapter s mod M;
+      uneven      - adapter 0 gets every second sequence, the others share the rest in turn;
+      skip_last   - round robin over the first M-1 adapters: the last adapter gets no token."""
+    seq = np.arange(cfg.T) // cfg.seq_len
+    M = cfg.M
+    if pattern == "round_robin":
+        m = seq % M
+    elif pattern == "uneven":
+        m = np.where(seq % 2 == 0, 0, 1 + (seq // 2) % max(M - 1, 1)) if M > 1 else seq * 0
+    elif pattern == "skip_last":
+        m = seq % max(M - 1, 1)
+    else:
+        raise ValueError(pattern)
+    return m.astype(np.int32)
+
+
+def split_adapters(cfg: Config, host: Dict[str, np.ndarray]):
+    """The M per-adapter weight dicts (views) of a multi-adapter input set."""
+    N = cfg.N
+    out = []
+    for m in range(cfg.M):
+        Wm = {n: host[n] for n in ("W_gate", "W_up", "W_down")}
+        for n in ("A_gate", "B_gate", "A_up", "B_up", "A_down", "B_down", "W_router"):
+            Wm[n] = host[n][m * N:(m + 1) * N]
+        out.append(Wm)
+    return out
