@@ -62,7 +62,12 @@ def cpu_baseline(cfg, host, n_tokens):
     x = np.asarray(host["x"][:n_tokens], dtype=np.float64)
     dy = np.asarray(host["dy"][:n_tokens], dtype=np.float64)
     t0 = time.perf_counter()
-    orc.backward(x, W, cfg.k, cfg.lora_scale, dy, 1.0, cfg.aux_coeff, "top1")
+    if cfg.M > 1:
+        tm = synth.token_model(cfg)[:n_tokens]
+        orc.multi_backward(x, tm, synth.split_adapters(cfg, W), cfg.k, cfg.lora_scale, dy, None,
+                           cfg.aux_coeff, "top1")
+    else:
+        orc.backward(x, W, cfg.k, cfg.lora_scale, dy, 1.0, cfg.aux_coeff, "top1")
     dt = time.perf_counter() - t0
     return {"value": n_tokens / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
             "sample": f"first {n_tokens} of {cfg.T} tokens, forward+backward, float64 NumPy, "
@@ -104,7 +109,8 @@ def main():
     t0 = time.perf_counter()
     host = synth.make_inputs(cfg)
     t_inputs = time.perf_counter() - t0
-    m = MixLoraFFN(cfg, host, with_backward=do_bwd)
+    m = MixLoraFFN(cfg, host, with_backward=do_bwd,
+                   token_model=synth.token_model(cfg) if cfg.M > 1 else None)
 
     def step():
         m.forward()
@@ -155,7 +161,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} d_ff={cfg.d_ff} N={cfg.N} "
-                               f"top-{cfg.k} r={cfg.r} bf16 "
+                               f"top-{cfg.k} r={cfg.r} {'adapters=%d ' % cfg.M if cfg.M > 1 else ''}bf16 "
                                f"{'forward+backward' if do_bwd else 'forward'}",
                    "schedule": "shared gate/up (2 units) + linear frozen down (1 unit) per "
                                "direction; LoRA as rank-r terms on routed pairs",

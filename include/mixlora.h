@@ -120,6 +120,45 @@ MIXLORA_API int mixlora_ffn_backward(const mixlora_dims *dims, const mixlora_wei
                          size_t workspace_bytes, void *dx, const mixlora_grads *grads,
                          void *stream);
 
+/* ---- Several adapters on one frozen base (Section 3.3, "Optimizing Multi-MixLoRA Training and
+ * Inference (II)"; outer loop of Algorithm 1) -------------------------------------------------
+ * M MixLoRA adapters, each with its own router and N LoRA experts, share W_gate / W_up / W_down.
+ * Every token belongs to one adapter and is routed and processed by that adapter only; the shared
+ * projections run once over the tokens of all adapters.
+ *   dims->N is the number of experts PER ADAPTER (k <= N); M*N <= 64 and M*N*r <= 512.
+ *   The LoRA banks, the router and their gradients hold M*N experts, adapter m's expert e at
+ *   index m*N + e: A_gate [M*N,r,d], ..., W_router [M*N,d].
+ *   token_model: device int32 [T], adapter of every token, values in [0, M) (not checked on the
+ *   device: out-of-range values are undefined behaviour).
+ *   d_aux: HOST float [M], upstream gradient of each adapter's auxiliary loss (backward only;
+ *   NULL = all 1).  Read during the call, not retained. */
+typedef struct {
+  int32_t M;
+  const int32_t *token_model;
+  const float *d_aux;
+} mixlora_multi;
+
+/* Workspace bytes of the multi-adapter calls (0 for invalid dims or M). */
+MIXLORA_API size_t mixlora_multi_workspace_bytes(const mixlora_dims *dims, int32_t M,
+                                                 int for_backward);
+
+/* As mixlora_ffn_forward, with: topk_idx [T,k] = expert index inside the token's adapter;
+ * expert_counts [M*N] (pairs per expert of every adapter); aux_loss [M] (Eq. 8-9 per adapter,
+ * over the adapter's own tokens; 0 for an adapter without tokens).  Errors as
+ * mixlora_ffn_forward; MIXLORA_E_SHAPE also for M < 1 or M*N > 64. */
+MIXLORA_API int mixlora_multi_forward(const mixlora_dims *dims, const mixlora_multi *multi,
+                                      const mixlora_weights *w, const void *x, void *y,
+                                      int32_t *topk_idx, float *topk_w, int32_t *expert_counts,
+                                      float *aux_loss, void *workspace, size_t workspace_bytes,
+                                      void *stream);
+
+/* As mixlora_ffn_backward on the workspace mixlora_multi_forward filled; gradients of
+ * <y, dy> + sum_m d_aux[m] * aux_loss[m].  An adapter without tokens gets zero gradients. */
+MIXLORA_API int mixlora_multi_backward(const mixlora_dims *dims, const mixlora_multi *multi,
+                                       const mixlora_weights *w, const void *x, const void *dy,
+                                       void *workspace, size_t workspace_bytes, void *dx,
+                                       const mixlora_grads *grads, void *stream);
+
 /* Auxiliary load-balance loss alone (Eq. 8-9) from router probabilities and kept experts.
  * in : probs [T,N] float32 (full softmax), topk_idx [T,k] int32.
  * out: loss [1]; F [N], P [N] (each may be NULL); dprobs [T,N] = d loss / d probs (may be

@@ -201,7 +201,7 @@ def multi_forward(x, token_model, Ws, k, lora_scale, aux_coeff=0.01, aux_mode="t
     dicts with identical W_gate / W_up / W_down.  Adapter m sees only its own tokens.
 
     Returns y [T,d]; topk_idx [T,k] (expert index inside the token's adapter), topk_w [T,k];
-    probs [T,N] over the token's own adapter's experts; counts [M,N]; aux_loss [M] (Eq. 8-9 per
+    probs, logits [T,N] over the token's own adapter's experts; counts [M,N]; aux_loss [M] (Eq. 8-9 per
     adapter over its own tokens; 0 for an adapter without tokens)."""
     x = _f64(x)
     token_model = np.asarray(token_model)
@@ -212,6 +212,7 @@ def multi_forward(x, token_model, Ws, k, lora_scale, aux_coeff=0.01, aux_mode="t
     idx = np.zeros((T, k), dtype=np.int64)
     w = np.zeros((T, k), dtype=F64)
     probs = np.zeros((T, N), dtype=F64)
+    logits = np.zeros((T, N), dtype=F64)
     counts = np.zeros((M, N), dtype=np.int64)
     aux = np.zeros(M, dtype=F64)
     for m in range(M):
@@ -223,9 +224,11 @@ def multi_forward(x, token_model, Ws, k, lora_scale, aux_coeff=0.01, aux_mode="t
         idx[tok] = fw["topk_idx"]
         w[tok] = fw["topk_w"]
         probs[tok] = fw["probs"]
+        logits[tok] = fw["logits"]
         counts[m] = fw["counts"]
         aux[m] = fw["aux_loss"]
-    return dict(y=y, topk_idx=idx, topk_w=w, probs=probs, counts=counts, aux_loss=aux)
+    return dict(y=y, topk_idx=idx, topk_w=w, probs=probs, logits=logits, counts=counts,
+                aux_loss=aux)
 
 
 def multi_backward(x, token_model, Ws, k, lora_scale, dy, d_aux=None, aux_coeff=0.01,

@@ -21,7 +21,8 @@ STATUS = {0: "OK", -1: "E_NULL", -2: "E_SHAPE", -3: "E_DTYPE", -4: "E_ALIGN", -5
 
 EXPORTS = ("mixlora_workspace_bytes", "mixlora_ffn_forward", "mixlora_ffn_backward",
            "mixlora_aux_loss", "mixlora_transpose", "mixlora_version",
-           "mixlora_profile_begin", "mixlora_profile_end")
+           "mixlora_profile_begin", "mixlora_profile_end",
+           "mixlora_multi_workspace_bytes", "mixlora_multi_forward", "mixlora_multi_backward")
 
 
 class Dims(C.Structure):
@@ -41,6 +42,10 @@ class Weights(C.Structure):
 
 class Grads(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in GRAD_FIELDS]
+
+
+class Multi(C.Structure):
+    _fields_ = [("M", C.c_int32), ("token_model", C.c_void_p), ("d_aux", C.POINTER(C.c_float))]
 
 
 class MixLoraError(RuntimeError):
@@ -80,6 +85,14 @@ def load():
     lib.mixlora_profile_end.restype = C.c_int
     lib.mixlora_profile_end.argtypes = [C.POINTER(C.c_double), C.POINTER(i32),
                                         C.POINTER(C.c_double)]
+    lib.mixlora_multi_workspace_bytes.restype = sz
+    lib.mixlora_multi_workspace_bytes.argtypes = [C.POINTER(Dims), i32, C.c_int]
+    lib.mixlora_multi_forward.restype = C.c_int
+    lib.mixlora_multi_forward.argtypes = [C.POINTER(Dims), C.POINTER(Multi), C.POINTER(Weights), vp,
+                                          vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.mixlora_multi_backward.restype = C.c_int
+    lib.mixlora_multi_backward.argtypes = [C.POINTER(Dims), C.POINTER(Multi), C.POINTER(Weights),
+                                           vp, vp, vp, sz, vp, C.POINTER(Grads), vp]
     _lib = lib
     return lib
 
@@ -141,6 +154,42 @@ def mixlora_ffn_backward(dims: Dims, weights: Weights, x, dy, d_aux: float, work
                                      C.byref(grads), _stream(stream))
     if rc != 0:
         raise MixLoraError("mixlora_ffn_backward", rc)
+
+
+def make_multi(M: int, token_model, d_aux=None) -> Multi:
+    """token_model: device int32 tensor [T] (or raw pointer); d_aux: M host floats or None."""
+    m = Multi()
+    m.M = M
+    m.token_model = _ptr(token_model)
+    if d_aux is not None:
+        arr = (C.c_float * M)(*[float(v) for v in d_aux])
+        m._keep = arr                       # keeps the host array alive with the struct
+        m.d_aux = C.cast(arr, C.POINTER(C.c_float))
+    return m
+
+
+def mixlora_multi_workspace_bytes(dims: Dims, M: int, for_backward: bool) -> int:
+    return int(load().mixlora_multi_workspace_bytes(C.byref(dims), M, int(bool(for_backward))))
+
+
+def mixlora_multi_forward(dims: Dims, multi: Multi, weights: Weights, x, y, topk_idx, topk_w,
+                          expert_counts, aux_loss, workspace, workspace_bytes: int,
+                          stream=None) -> None:
+    rc = load().mixlora_multi_forward(C.byref(dims), C.byref(multi), C.byref(weights), _ptr(x),
+                                      _ptr(y), _ptr(topk_idx), _ptr(topk_w), _ptr(expert_counts),
+                                      _ptr(aux_loss), _ptr(workspace), workspace_bytes,
+                                      _stream(stream))
+    if rc != 0:
+        raise MixLoraError("mixlora_multi_forward", rc)
+
+
+def mixlora_multi_backward(dims: Dims, multi: Multi, weights: Weights, x, dy, workspace,
+                           workspace_bytes: int, dx, grads: Grads, stream=None) -> None:
+    rc = load().mixlora_multi_backward(C.byref(dims), C.byref(multi), C.byref(weights), _ptr(x),
+                                       _ptr(dy), _ptr(workspace), workspace_bytes, _ptr(dx),
+                                       C.byref(grads), _stream(stream))
+    if rc != 0:
+        raise MixLoraError("mixlora_multi_backward", rc)
 
 
 def mixlora_aux_loss(probs, topk_idx, T: int, N: int, k: int, coeff: float, mode: int, loss,

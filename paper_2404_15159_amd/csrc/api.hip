@@ -19,7 +19,8 @@ inline int up64(int v) { return (v + 63) / 64 * 64; }
 
 struct Layout {
   // saved by forward
-  size_t probs, Z, idx, w, counts, first_counts, offs, row_of_pair, pair_of_row, F, P, tok_offs;
+  size_t probs, Z, idx, w, counts, first_counts, offs, row_of_pair, pair_of_row, F, P, tok_offs,
+      model_tokens;
   size_t G, U, Pg_all, Pu_all, a_grp, Q_all;
   // forward scratch
   size_t a_comb, Qw, Bd_cat, rank_part;
@@ -52,6 +53,7 @@ Layout make_layout(const mixlora_dims &D) {
   L.F = take(N * 4);
   L.P = take(N * 4);
   L.tok_offs = take(2 * 4);
+  L.model_tokens = take(64 * 4);
   L.G = take(T * f * E);
   L.U = take(T * f * E);
   L.Pg_all = take(T * R * 4);
@@ -174,18 +176,12 @@ size_t mixlora_workspace_bytes(const mixlora_dims *dims, int for_backward) {
   return for_backward ? L.bwd_end : L.fwd_end;
 }
 
-int mixlora_ffn_forward(const mixlora_dims *dims, const mixlora_weights *w, const void *x,
-                        void *y, int32_t *topk_idx, float *topk_w, int32_t *expert_counts,
-                        float *aux_loss, void *workspace, size_t workspace_bytes,
-                        void *stream) {
-  int rc = check_dims(dims);
-  if (rc) return rc;
-  rc = check_weights(w);
-  if (rc) return rc;
-  if (!x || !y || !topk_idx || !topk_w || !expert_counts || !aux_loss || !workspace)
-    return MIXLORA_E_NULL;
-  if (misaligned(x) || misaligned(y) || misaligned(workspace)) return MIXLORA_E_ALIGN;
-  const mixlora_dims &D = *dims;
+// Forward pass on D.N experts in all, of which every adapter owns Nl consecutive ones
+// (token_model == NULL: one adapter).  Arguments are already validated.
+static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_model,
+                        const mixlora_weights *w, const void *x, void *y, int32_t *topk_idx,
+                        float *topk_w, int32_t *expert_counts, float *aux_loss, void *workspace,
+                        size_t workspace_bytes, void *stream) {
   const Layout L = make_layout(D);
   if (workspace_bytes < L.fwd_end) return MIXLORA_E_WORKSPACE;
 
@@ -218,14 +214,16 @@ int mixlora_ffn_forward(const mixlora_dims *dims, const mixlora_weights *w, cons
   // Eq. 7 + Norm (Algorithm 1 lines 4-5)
   if (dt == MIXLORA_BF16)
     HIP_TRY(launch_route_logits((const float *)(ws + L.Z), N, T, N, k, probs, topk_idx, topk_w, idx,
-                                wts, st));
+                                wts, Nl, token_model, st));
   else
-    HIP_TRY(launch_router(dt, x, w->W_router, T, d, N, k, probs, topk_idx, topk_w, idx, wts, st));
+    HIP_TRY(launch_router(dt, x, w->W_router, T, d, N, k, probs, topk_idx, topk_w, idx, wts, Nl,
+                          token_model, st));
   HIP_TRY(launch_group_pairs(idx, T, N, k, (int32_t *)(ws + L.counts), expert_counts,
                              (int32_t *)(ws + L.first_counts), offs, row_of_pair, pair_of_row, st));
   // Eq. 8-9
   HIP_TRY(launch_aux_loss(probs, idx, T, N, k, D.aux_coeff, D.aux_mode, aux_loss,
-                          (float *)(ws + L.F), (float *)(ws + L.P), nullptr, st));
+                          (float *)(ws + L.F), (float *)(ws + L.P), nullptr, Nl, token_model,
+                          (int32_t *)(ws + L.model_tokens), st));
   hipLaunchKernelGGL(set_pair_kernel, dim3(1), dim3(64), 0, st, (int32_t *)(ws + L.tok_offs), 0, T);
   HIP_TRY(hipGetLastError());
   PairCtx pc{offs, pair_of_row, row_of_pair, wts, idx, T, N, k, r};
@@ -263,10 +261,65 @@ int mixlora_ffn_forward(const mixlora_dims *dims, const mixlora_weights *w, cons
   return MIXLORA_OK;
 }
 
-int mixlora_ffn_backward(const mixlora_dims *dims, const mixlora_weights *w, const void *x,
-                         const void *dy, float d_aux, void *workspace,
-                         size_t workspace_bytes, void *dx, const mixlora_grads *grads,
-                         void *stream) {
+// Validation shared by the forward entry points; D.N is the number of experts in all.
+static int check_forward_args(const mixlora_dims *dims, const mixlora_weights *w, const void *x,
+                              const void *y, const int32_t *topk_idx, const float *topk_w,
+                              const int32_t *expert_counts, const float *aux_loss,
+                              const void *workspace) {
+  int rc = check_dims(dims);
+  if (rc) return rc;
+  rc = check_weights(w);
+  if (rc) return rc;
+  if (!x || !y || !topk_idx || !topk_w || !expert_counts || !aux_loss || !workspace)
+    return MIXLORA_E_NULL;
+  if (misaligned(x) || misaligned(y) || misaligned(workspace)) return MIXLORA_E_ALIGN;
+  return MIXLORA_OK;
+}
+
+int mixlora_ffn_forward(const mixlora_dims *dims, const mixlora_weights *w, const void *x,
+                        void *y, int32_t *topk_idx, float *topk_w, int32_t *expert_counts,
+                        float *aux_loss, void *workspace, size_t workspace_bytes,
+                        void *stream) {
+  const int rc = check_forward_args(dims, w, x, y, topk_idx, topk_w, expert_counts, aux_loss, workspace);
+  if (rc) return rc;
+  return forward_impl(*dims, dims->N, nullptr, w, x, y, topk_idx, topk_w, expert_counts, aux_loss,
+                      workspace, workspace_bytes, stream);
+}
+
+// dims with N replaced by the number of experts of all adapters together
+static int multi_dims(const mixlora_dims *dims, const mixlora_multi *multi, mixlora_dims *all) {
+  if (!dims || !multi) return MIXLORA_E_NULL;
+  if (multi->M < 1 || multi->M > 64 || dims->N < 1 || dims->k > dims->N) return MIXLORA_E_SHAPE;
+  if ((int64_t)multi->M * dims->N > 64) return MIXLORA_E_SHAPE;
+  if (!multi->token_model) return MIXLORA_E_NULL;
+  *all = *dims;
+  all->N = multi->M * dims->N;
+  return check_dims(all);
+}
+
+size_t mixlora_multi_workspace_bytes(const mixlora_dims *dims, int32_t M, int for_backward) {
+  if (!dims || M < 1 || (int64_t)M * dims->N > 64 || dims->k > dims->N) return 0;
+  mixlora_dims all = *dims;
+  all.N = M * dims->N;
+  return mixlora_workspace_bytes(&all, for_backward);
+}
+
+int mixlora_multi_forward(const mixlora_dims *dims, const mixlora_multi *multi,
+                          const mixlora_weights *w, const void *x, void *y, int32_t *topk_idx,
+                          float *topk_w, int32_t *expert_counts, float *aux_loss, void *workspace,
+                          size_t workspace_bytes, void *stream) {
+  mixlora_dims all;
+  int rc = multi_dims(dims, multi, &all);
+  if (rc) return rc;
+  rc = check_forward_args(&all, w, x, y, topk_idx, topk_w, expert_counts, aux_loss, workspace);
+  if (rc) return rc;
+  return forward_impl(all, dims->N, multi->token_model, w, x, y, topk_idx, topk_w, expert_counts,
+                      aux_loss, workspace, workspace_bytes, stream);
+}
+
+static int check_backward_args(const mixlora_dims *dims, const mixlora_weights *w, const void *x,
+                               const void *dy, const void *workspace, const void *dx,
+                               const mixlora_grads *grads) {
   int rc = check_dims(dims);
   if (rc) return rc;
   rc = check_weights(w);
@@ -280,7 +333,14 @@ int mixlora_ffn_backward(const mixlora_dims *dims, const mixlora_weights *w, con
   }
   if (misaligned(x) || misaligned(dy) || misaligned(dx) || misaligned(workspace))
     return MIXLORA_E_ALIGN;
-  const mixlora_dims &D = *dims;
+  return MIXLORA_OK;
+}
+
+// Backward pass; same conventions as forward_impl.
+static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_model,
+                         const AuxUpstream &d_aux, const mixlora_weights *w, const void *x,
+                         const void *dy, void *workspace, size_t workspace_bytes, void *dx,
+                         const mixlora_grads *grads, void *stream) {
   const Layout L = make_layout(D);
   if (workspace_bytes < L.bwd_end) return MIXLORA_E_WORKSPACE;
 
@@ -362,7 +422,8 @@ int mixlora_ffn_backward(const mixlora_dims *dims, const mixlora_weights *w, con
   HIP_TRY(launch_router_bwd(dt, pc, probs, (float *)(ws + L.dw_part), nct,
                             (float *)(ws + L.VB_all), (float *)(ws + L.Q_all), (float *)(ws + L.F),
                             s, d_aux, D.aux_coeff, (float *)(ws + L.dw), (float *)(ws + L.dz),
-                            ws + L.S, Kx, 2 * R, Kx - 2 * R, st));
+                            ws + L.S, Kx, 2 * R, Kx - 2 * R, Nl, token_model,
+                            (const int32_t *)(ws + L.model_tokens), st));
   if (dt == MIXLORA_BF16) {
     GatherJob gj[6];
     for (int i = 0; i < 6; i++) gj[i] = GatherJob{fsrc[i], ws + L.small[i], by_token[i], weighted[i]};
@@ -398,6 +459,33 @@ int mixlora_ffn_backward(const mixlora_dims *dims, const mixlora_weights *w, con
   return MIXLORA_OK;
 }
 
+int mixlora_ffn_backward(const mixlora_dims *dims, const mixlora_weights *w, const void *x,
+                         const void *dy, float d_aux, void *workspace,
+                         size_t workspace_bytes, void *dx, const mixlora_grads *grads,
+                         void *stream) {
+  const int rc = check_backward_args(dims, w, x, dy, workspace, dx, grads);
+  if (rc) return rc;
+  AuxUpstream up{};
+  up.v[0] = d_aux;
+  return backward_impl(*dims, dims->N, nullptr, up, w, x, dy, workspace, workspace_bytes, dx, grads,
+                       stream);
+}
+
+int mixlora_multi_backward(const mixlora_dims *dims, const mixlora_multi *multi,
+                           const mixlora_weights *w, const void *x, const void *dy,
+                           void *workspace, size_t workspace_bytes, void *dx,
+                           const mixlora_grads *grads, void *stream) {
+  mixlora_dims all;
+  int rc = multi_dims(dims, multi, &all);
+  if (rc) return rc;
+  rc = check_backward_args(&all, w, x, dy, workspace, dx, grads);
+  if (rc) return rc;
+  AuxUpstream up{};
+  for (int m = 0; m < multi->M; m++) up.v[m] = multi->d_aux ? multi->d_aux[m] : 1.f;
+  return backward_impl(all, dims->N, multi->token_model, up, w, x, dy, workspace, workspace_bytes,
+                       dx, grads, stream);
+}
+
 int mixlora_aux_loss(const float *probs, const int32_t *topk_idx, int32_t T, int32_t N,
                      int32_t k, float coeff, int32_t mode, float *loss, float *F, float *P,
                      float *dprobs, void *stream) {
@@ -405,8 +493,8 @@ int mixlora_aux_loss(const float *probs, const int32_t *topk_idx, int32_t T, int
   if (mode != MIXLORA_AUX_TOP1 && mode != MIXLORA_AUX_TOPK) return MIXLORA_E_DTYPE;
   if (T < 1 || N < 1 || N > 64 || k < 1 || k > N || (int64_t)T * k >= (1 << 24))
     return MIXLORA_E_SHAPE;
-  HIP_TRY(launch_aux_loss(probs, topk_idx, T, N, k, coeff, mode, loss, F, P, dprobs,
-                          reinterpret_cast<hipStream_t>(stream)));
+  HIP_TRY(launch_aux_loss(probs, topk_idx, T, N, k, coeff, mode, loss, F, P, dprobs, N, nullptr,
+                          nullptr, reinterpret_cast<hipStream_t>(stream)));
   return MIXLORA_OK;
 }
 

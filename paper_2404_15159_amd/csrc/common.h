@@ -76,21 +76,27 @@ int gemm_timer_begin(int max_launches);
 int gemm_timer_end(double *ms_total, int *launches, double *flops_total);
 
 // ---- routing -----------------------------------------------------------------------------
+// N experts in all; with several adapters (token_model != NULL) token t is routed among the Nl
+// experts [token_model[t] * Nl, ... + Nl) of its adapter: probs is 0 elsewhere, idx_out is the
+// index inside the adapter, idx_ws the index among all N.
 hipError_t launch_router(int dtype, const void *x, const void *W_router, int T, int d, int N,
                          int k, float *probs, int32_t *idx_out, float *w_out, int32_t *idx_ws,
-                         float *w_ws, hipStream_t st);
+                         float *w_ws, int Nl, const int32_t *token_model, hipStream_t st);
 // Same routing from logits Z[t, n] (row pitch ldz) that a GEMM launch produced.
 hipError_t launch_route_logits(const float *Z, int ldz, int T, int N, int k, float *probs,
                                int32_t *idx_out, float *w_out, int32_t *idx_ws, float *w_ws,
-                               hipStream_t st);
+                               int Nl, const int32_t *token_model, hipStream_t st);
 // Stable grouping of the k*T pairs by expert: counts[N], first_counts[N] (slot-0 histogram),
 // offs[N+1], row_of_pair[kT], pair_of_row[kT].  counts_out may be NULL.
 hipError_t launch_group_pairs(const int32_t *idx, int T, int N, int k, int32_t *counts,
                               int32_t *counts_out, int32_t *first_counts, int32_t *offs,
                               int32_t *row_of_pair, int32_t *pair_of_row, hipStream_t st);
+// loss[N / Nl], one per adapter (statistics over the adapter's own tokens); model_tokens (may be
+// NULL) receives the token count of every adapter.
 hipError_t launch_aux_loss(const float *probs, const int32_t *idx, int T, int N, int k,
                            float coeff, int mode, float *loss, float *F, float *P,
-                           float *dprobs, hipStream_t st);
+                           float *dprobs, int Nl, const int32_t *token_model,
+                           int32_t *model_tokens, hipStream_t st);
 
 // ---- element-wise / rank-r pieces -------------------------------------------------------
 struct PairCtx {  // device pointers describing the grouped pairs
@@ -204,9 +210,14 @@ hipError_t launch_gather_small_T(const PairCtx &pc, const GatherJob *jobs, int n
 hipError_t launch_f32_to_bf16T(const float *src, int rows, int r, void *outT, int ldT,
                                hipStream_t st);
 
+struct AuxUpstream {   // upstream gradient of every adapter's auxiliary loss
+  float v[64];
+};
 hipError_t launch_router_bwd(int dtype, const PairCtx &pc, const float *probs, const float *dw_part,
                              int n_col_tiles, const float *VB_all, const float *Q_all,
-                             const float *F, float s, float d_aux, float aux_coeff, float *dw_ws,
-                             float *dz, void *S, int lds_, int col0, int ncols, hipStream_t st);
+                             const float *F, float s, const AuxUpstream &d_aux, float aux_coeff,
+                             float *dw_ws, float *dz, void *S, int lds_, int col0, int ncols,
+                             int Nl, const int32_t *token_model, const int32_t *model_tokens,
+                             hipStream_t st);
 
 }  // namespace mixlora

@@ -322,7 +322,9 @@ hipError_t launch_f32_to_bf16T(const float *src, int rows, int r, void *outT, in
 // terms, a butterfly adds them).  Then, with w_j = p_j / sum_kept p (Norm of Algorithm 1):
 // dp_j = (dw_j - sum_i w_i dw_i) / sum_kept p on the kept experts, plus the auxiliary term
 // d_aux * a * N * F_e / T  on every expert (Eq. 8-9; F is piecewise constant), and
-// dz = p * (dp - <p, dp>) through the softmax of Eq. 7 (lane e holds expert e).
+// dz = p * (dp - <p, dp>) through the softmax of Eq. 7 (lane e holds expert e).  With several
+// adapters p is zero outside the token's adapter, so dz is too; T and the upstream gradient of
+// the auxiliary loss are those of the token's adapter.
 __device__ __forceinline__ float rb_wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
@@ -333,9 +335,10 @@ template <typename E>
 __global__ __launch_bounds__(256) void router_bwd_kernel(
     PairCtx pc, const float *__restrict__ probs, const float *__restrict__ dw_part,
     int n_col_tiles, const float *__restrict__ VB_all, const float *__restrict__ Q_all,
-    const float *__restrict__ F, float s, float d_aux, float aux_coeff,
+    const float *__restrict__ F, float s, AuxUpstream d_aux, float aux_coeff,
     float *__restrict__ dw_ws, float *__restrict__ dz, E *__restrict__ S, int lds_, int col0,
-    int ncols) {
+    int ncols, int Nl, const int32_t *__restrict__ token_model,
+    const int32_t *__restrict__ model_tokens) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= pc.T) return;   // whole wave leaves together
@@ -362,7 +365,9 @@ __global__ __launch_bounds__(256) void router_bwd_kernel(
   }
   const float wdw = rb_wave_sum(my_w * my_dw);
   const float ssum = rb_wave_sum(my_p);
-  const float auxg = d_aux * aux_coeff * (float)N / (float)pc.T;
+  // auxiliary term of the token's adapter: statistics over that adapter's own tokens
+  const int m = __builtin_amdgcn_readfirstlane(token_model ? token_model[t] : 0);   // wave-uniform
+  const float auxg = d_aux.v[m] * aux_coeff * (float)Nl / (float)model_tokens[m];
   float dp = lane < N ? auxg * F[lane] : 0.f;
   for (int j = 0; j < k; j++) {
     const int ej = __shfl(my_e, j, 64);
@@ -379,17 +384,19 @@ __global__ __launch_bounds__(256) void router_bwd_kernel(
 
 hipError_t launch_router_bwd(int dtype, const PairCtx &pc, const float *probs, const float *dw_part,
                              int n_col_tiles, const float *VB_all, const float *Q_all,
-                             const float *F, float s, float d_aux, float aux_coeff, float *dw_ws,
-                             float *dz, void *S, int lds_, int col0, int ncols, hipStream_t st) {
+                             const float *F, float s, const AuxUpstream &d_aux, float aux_coeff,
+                             float *dw_ws, float *dz, void *S, int lds_, int col0, int ncols,
+                             int Nl, const int32_t *token_model, const int32_t *model_tokens,
+                             hipStream_t st) {
   const dim3 grid((pc.T + 3) / 4), block(256);
   if (dtype == MIXLORA_BF16)
     hipLaunchKernelGGL(router_bwd_kernel<bf16_t>, grid, block, 0, st, pc, probs, dw_part,
                        n_col_tiles, VB_all, Q_all, F, s, d_aux, aux_coeff, dw_ws, dz, (bf16_t *)S,
-                       lds_, col0, ncols);
+                       lds_, col0, ncols, Nl, token_model, model_tokens);
   else
     hipLaunchKernelGGL(router_bwd_kernel<float>, grid, block, 0, st, pc, probs, dw_part,
                        n_col_tiles, VB_all, Q_all, F, s, d_aux, aux_coeff, dw_ws, dz, (float *)S,
-                       lds_, col0, ncols);
+                       lds_, col0, ncols, Nl, token_model, model_tokens);
   return hipGetLastError();
 }
 

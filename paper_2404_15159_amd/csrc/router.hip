@@ -16,19 +16,23 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
-// Softmax over the N logits of token t (lane n holds logit n, lanes >= N hold -inf), top-k on
-// the logits (monotone with the probabilities; equal logits go to the lower expert index; slots
-// in descending order) and renormalisation of the kept probabilities.
-__device__ __forceinline__ void route_token(float z, int lane, int t, int N, int k,
-                                            float *__restrict__ probs,
+// Softmax over the logits of token t (lane n holds logit n), restricted to the experts
+// [lo, lo + N) of the token's adapter, top-k on the logits (monotone with the probabilities; equal
+// logits go to the lower expert index; slots in descending order) and renormalisation of the kept
+// probabilities.  probs gets all Ntot columns (0 outside the adapter); idx_out is the index
+// inside the adapter, idx_ws the index among all Ntot experts.
+__device__ __forceinline__ void route_token(float z, int lane, int t, int lo, int N, int Ntot,
+                                            int k, float *__restrict__ probs,
                                             int32_t *__restrict__ idx_out,
                                             float *__restrict__ w_out,
                                             int32_t *__restrict__ idx_ws,
                                             float *__restrict__ w_ws) {
+  const bool own = lane >= lo && lane < lo + N;
+  if (!own) z = -INFINITY;
   const float zmax = wave_max(z);
-  const float ez = lane < N ? expf(z - zmax) : 0.f;
+  const float ez = own ? expf(z - zmax) : 0.f;
   const float p = ez / wave_sum(ez);
-  if (lane < N) probs[(int64_t)t * N + lane] = p;
+  if (lane < Ntot) probs[(int64_t)t * Ntot + lane] = p;
   // k rounds of arg-max with ties to the lowest lane
   float zc = z;
   float psel = 0.f;     // lane j keeps the probability of slot j
@@ -36,7 +40,7 @@ __device__ __forceinline__ void route_token(float z, int lane, int t, int N, int
   float ksum = 0.f;
   for (int j = 0; j < k; j++) {
     const float m = wave_max(zc);
-    const unsigned long long b = __ballot(zc == m && lane < N);
+    const unsigned long long b = __ballot(zc == m && own);
     const int e = __ffsll((long long)b) - 1;
     const float pe = __shfl(p, e, 64);
     ksum += pe;
@@ -46,7 +50,7 @@ __device__ __forceinline__ void route_token(float z, int lane, int t, int N, int
   if (lane < k) {
     const float w = psel / ksum;
     const int64_t o = (int64_t)t * k + lane;
-    idx_out[o] = esel;
+    idx_out[o] = esel - lo;
     w_out[o] = w;
     idx_ws[o] = esel;
     w_ws[o] = w;
@@ -62,7 +66,8 @@ __global__ __launch_bounds__(256) void router_kernel(const E *__restrict__ x,
                                                      int32_t *__restrict__ idx_out,
                                                      float *__restrict__ w_out,
                                                      int32_t *__restrict__ idx_ws,
-                                                     float *__restrict__ w_ws) {
+                                                     float *__restrict__ w_ws, int Nl,
+                                                     const int32_t *__restrict__ token_model) {
   __shared__ float zbuf[4][64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int t = blockIdx.x * 4 + wave;
@@ -91,7 +96,8 @@ __global__ __launch_bounds__(256) void router_kernel(const E *__restrict__ x,
   }
   __builtin_amdgcn_wave_barrier();
   const float z = lane < N ? zbuf[wave][lane] : -INFINITY;
-  route_token(z, lane, t, N, k, probs, idx_out, w_out, idx_ws, w_ws);
+  const int lo = token_model ? token_model[t] * Nl : 0;
+  route_token(z, lane, t, lo, Nl, N, k, probs, idx_out, w_out, idx_ws, w_ws);
 }
 
 // Routing from logits that a GEMM launch has already produced: Z[t, n], row pitch ldz.
@@ -101,23 +107,26 @@ __global__ __launch_bounds__(256) void route_logits_kernel(const float *__restri
                                                            int32_t *__restrict__ idx_out,
                                                            float *__restrict__ w_out,
                                                            int32_t *__restrict__ idx_ws,
-                                                           float *__restrict__ w_ws) {
+                                                           float *__restrict__ w_ws, int Nl,
+                                                           const int32_t *__restrict__ token_model) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;
   const float z = lane < N ? Z[(int64_t)t * ldz + lane] : -INFINITY;
-  route_token(z, lane, t, N, k, probs, idx_out, w_out, idx_ws, w_ws);
+  const int lo = token_model ? token_model[t] * Nl : 0;
+  route_token(z, lane, t, lo, Nl, N, k, probs, idx_out, w_out, idx_ws, w_ws);
 }
 
 template <typename E>
 static hipError_t launch_router_t(const void *x, const void *Wr, int T, int d, int N, int k,
                                   float *probs, int32_t *idx_out, float *w_out, int32_t *idx_ws,
-                                  float *w_ws, hipStream_t st) {
+                                  float *w_ws, int Nl, const int32_t *token_model,
+                                  hipStream_t st) {
   const dim3 grid((T + 3) / 4), block(256);
   const E *xe = reinterpret_cast<const E *>(x), *we = reinterpret_cast<const E *>(Wr);
 #define MIXLORA_ROUTER(NM)                                                                    \
   hipLaunchKernelGGL((router_kernel<E, NM>), grid, block, 0, st, xe, we, T, d, N, k, probs,   \
-                     idx_out, w_out, idx_ws, w_ws)
+                     idx_out, w_out, idx_ws, w_ws, Nl, token_model)
   if (N <= 8) MIXLORA_ROUTER(8);
   else if (N <= 16) MIXLORA_ROUTER(16);
   else if (N <= 32) MIXLORA_ROUTER(32);
@@ -128,17 +137,19 @@ static hipError_t launch_router_t(const void *x, const void *Wr, int T, int d, i
 
 hipError_t launch_router(int dtype, const void *x, const void *W_router, int T, int d, int N,
                          int k, float *probs, int32_t *idx_out, float *w_out, int32_t *idx_ws,
-                         float *w_ws, hipStream_t st) {
+                         float *w_ws, int Nl, const int32_t *token_model, hipStream_t st) {
   return dtype == MIXLORA_BF16
-             ? launch_router_t<bf16_t>(x, W_router, T, d, N, k, probs, idx_out, w_out, idx_ws, w_ws, st)
-             : launch_router_t<float>(x, W_router, T, d, N, k, probs, idx_out, w_out, idx_ws, w_ws, st);
+             ? launch_router_t<bf16_t>(x, W_router, T, d, N, k, probs, idx_out, w_out, idx_ws, w_ws,
+                                       Nl, token_model, st)
+             : launch_router_t<float>(x, W_router, T, d, N, k, probs, idx_out, w_out, idx_ws, w_ws,
+                                      Nl, token_model, st);
 }
 
 hipError_t launch_route_logits(const float *Z, int ldz, int T, int N, int k, float *probs,
                                int32_t *idx_out, float *w_out, int32_t *idx_ws, float *w_ws,
-                               hipStream_t st) {
+                               int Nl, const int32_t *token_model, hipStream_t st) {
   hipLaunchKernelGGL(route_logits_kernel, dim3((T + 3) / 4), dim3(256), 0, st, Z, ldz, T, N, k,
-                     probs, idx_out, w_out, idx_ws, w_ws);
+                     probs, idx_out, w_out, idx_ws, w_ws, Nl, token_model);
   return hipGetLastError();
 }
 
@@ -233,23 +244,34 @@ hipError_t launch_group_pairs(const int32_t *idx, int T, int N, int k, int32_t *
 // One workgroup.  F from an integer histogram of the kept experts (first slot only, or all k
 // slots divided by k); P from column sums taken in a fixed order (thread (g, e) sums rows
 // g, g + G, ...; thread e then adds the G partials in ascending g), so the result is
-// bit-reproducible.
+// bit-reproducible.  With several adapters (N = M * Nl experts, expert e belongs to adapter
+// e / Nl, probs is zero outside a token's adapter) every adapter's F, P and loss are taken over
+// its own T_m tokens; an adapter without tokens has loss 0.
 __global__ __launch_bounds__(1024) void aux_loss_kernel(const float *__restrict__ probs,
                                                         const int32_t *__restrict__ idx, int T,
                                                         int N, int k, float coeff, int mode,
                                                         float *__restrict__ loss,
                                                         float *__restrict__ F_out,
-                                                        float *__restrict__ P_out) {
+                                                        float *__restrict__ P_out, int Nl,
+                                                        const int32_t *__restrict__ token_model,
+                                                        int32_t *__restrict__ model_tokens) {
   __shared__ int hist[64];
+  __shared__ int tm[64];
   __shared__ float part[1024];
   __shared__ float fp[64];
   const int tid = threadIdx.x;
-  if (tid < 64) hist[tid] = 0;
+  const int M = N / Nl;
+  if (tid < 64) { hist[tid] = 0; tm[tid] = 0; }
   __syncthreads();
   if (mode == MIXLORA_AUX_TOP1) {
     for (int t = tid; t < T; t += 1024) atomicAdd(&hist[idx[(int64_t)t * k]], 1);
   } else {
     for (int64_t p = tid; p < (int64_t)T * k; p += 1024) atomicAdd(&hist[idx[p]], 1);
+  }
+  if (token_model) {
+    for (int t = tid; t < T; t += 1024) atomicAdd(&tm[token_model[t]], 1);
+  } else if (tid == 0) {
+    tm[0] = T;
   }
   const int G = 1024 / N;
   const int e = tid % N, g = tid / N;
@@ -261,17 +283,20 @@ __global__ __launch_bounds__(1024) void aux_loss_kernel(const float *__restrict_
   if (tid < N) {
     float ps = 0.f;
     for (int gg = 0; gg < G; gg++) ps += part[gg * N + tid];
-    const float P = ps / (float)T;
-    const float F = (float)hist[tid] / (mode == MIXLORA_AUX_TOP1 ? (float)T : (float)T * (float)k);
+    const int Tm = tm[tid / Nl];
+    const float denom = mode == MIXLORA_AUX_TOP1 ? (float)Tm : (float)Tm * (float)k;
+    const float P = Tm > 0 ? ps / (float)Tm : 0.f;
+    const float F = Tm > 0 ? (float)hist[tid] / denom : 0.f;
     if (P_out) P_out[tid] = P;
     if (F_out) F_out[tid] = F;
     fp[tid] = F * P;
   }
   __syncthreads();
-  if (tid == 0) {
+  if (tid < M) {
     float acc = 0.f;
-    for (int n = 0; n < N; n++) acc += fp[n];
-    *loss = coeff * (float)N * acc;
+    for (int n = 0; n < Nl; n++) acc += fp[tid * Nl + n];
+    loss[tid] = coeff * (float)Nl * acc;
+    if (model_tokens) model_tokens[tid] = tm[tid];
   }
 }
 
@@ -299,9 +324,10 @@ __global__ void aux_dprobs_kernel(const int32_t *__restrict__ idx, int T, int N,
 
 hipError_t launch_aux_loss(const float *probs, const int32_t *idx, int T, int N, int k,
                            float coeff, int mode, float *loss, float *F, float *P,
-                           float *dprobs, hipStream_t st) {
+                           float *dprobs, int Nl, const int32_t *token_model,
+                           int32_t *model_tokens, hipStream_t st) {
   hipLaunchKernelGGL(aux_loss_kernel, dim3(1), dim3(1024), 0, st, probs, idx, T, N, k, coeff,
-                     mode, loss, F, P);
+                     mode, loss, F, P, Nl, token_model, model_tokens);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (dprobs) {

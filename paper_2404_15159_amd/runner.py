@@ -23,9 +23,15 @@ class MixLoraFFN:
     """One problem instance on cuda:0: weights, workspace and output buffers."""
 
     def __init__(self, cfg: synth.Config, host: Dict[str, np.ndarray], aux_mode: int = B.AUX_TOP1,
-                 pretransposed: bool = True, with_backward: bool = True, device: str = "cuda:0"):
+                 pretransposed: bool = True, with_backward: bool = True, device: str = "cuda:0",
+                 token_model: Optional[np.ndarray] = None, d_aux=None):
+        """With cfg.M > 1 (several adapters on one frozen base) token_model [T] is required and
+        the multi-adapter entry points are used; the banks then hold M*N experts."""
         B.load()
         self.cfg = cfg
+        self.M = cfg.M
+        if (cfg.M > 1) != (token_model is not None):
+            raise ValueError("token_model goes with cfg.M > 1")
         self.dev = torch.device(device)
         self.with_backward = with_backward
         td = _tdtype(cfg.dtype)
@@ -34,14 +40,19 @@ class MixLoraFFN:
         self.t: Dict[str, torch.Tensor] = {}
         for n in synth.WEIGHT_NAMES + ("x",) + (("dy",) if with_backward and "dy" in host else ()):
             self.t[n] = torch.from_numpy(np.ascontiguousarray(host[n])).to(self.dev).to(td).contiguous()
-        T, d, f, N, k, r = cfg.T, cfg.d, cfg.d_ff, cfg.N, cfg.k, cfg.r
+        T, d, f, N, k, r = cfg.T, cfg.d, cfg.d_ff, cfg.N * cfg.M, cfg.k, cfg.r
+        self.multi = None
+        if cfg.M > 1:
+            self.token_model = torch.from_numpy(np.ascontiguousarray(token_model, dtype=np.int32)).to(self.dev)
+            self.multi = B.make_multi(cfg.M, self.token_model, d_aux)
         if with_backward and pretransposed:
             for n, (rows, cols) in (("W_gate", (f, d)), ("W_up", (f, d)), ("W_down", (d, f))):
                 out = torch.empty((cols, rows), dtype=td, device=self.dev)
                 B.mixlora_transpose(self.t[n], out, rows, cols, self.dims.dtype)
                 self.t[n + "_T"] = out
         self.weights = B.make_weights(self.t)
-        self.ws_bytes = B.mixlora_workspace_bytes(self.dims, with_backward)
+        self.ws_bytes = (B.mixlora_multi_workspace_bytes(self.dims, cfg.M, with_backward)
+                         if self.multi else B.mixlora_workspace_bytes(self.dims, with_backward))
         if self.ws_bytes == 0:
             raise ValueError("dims rejected by mixlora_workspace_bytes")
         self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.dev)
@@ -49,7 +60,7 @@ class MixLoraFFN:
         self.topk_idx = torch.empty((T, k), dtype=torch.int32, device=self.dev)
         self.topk_w = torch.empty((T, k), dtype=torch.float32, device=self.dev)
         self.counts = torch.empty((N,), dtype=torch.int32, device=self.dev)
-        self.aux = torch.empty((1,), dtype=torch.float32, device=self.dev)
+        self.aux = torch.empty((cfg.M,), dtype=torch.float32, device=self.dev)
         if with_backward:
             self.dx = torch.empty((T, d), dtype=td, device=self.dev)
             shapes = dict(dA_gate=(N, r, d), dB_gate=(N, f, r), dA_up=(N, r, d), dB_up=(N, f, r),
@@ -59,11 +70,22 @@ class MixLoraFFN:
             self.grads = B.make_grads(self.g)
 
     def forward(self, x: Optional[torch.Tensor] = None, stream=None) -> None:
+        if self.multi:
+            B.mixlora_multi_forward(self.dims, self.multi, self.weights,
+                                    self.t["x"] if x is None else x, self.y, self.topk_idx,
+                                    self.topk_w, self.counts, self.aux, self.workspace,
+                                    self.ws_bytes, stream)
+            return
         B.mixlora_ffn_forward(self.dims, self.weights, self.t["x"] if x is None else x, self.y,
                               self.topk_idx, self.topk_w, self.counts, self.aux, self.workspace,
                               self.ws_bytes, stream)
 
     def backward(self, dy: Optional[torch.Tensor] = None, d_aux: float = 1.0, stream=None) -> None:
+        if self.multi:   # per-adapter upstream gradients were given at construction
+            B.mixlora_multi_backward(self.dims, self.multi, self.weights, self.t["x"],
+                                     self.t["dy"] if dy is None else dy, self.workspace,
+                                     self.ws_bytes, self.dx, self.grads, stream)
+            return
         B.mixlora_ffn_backward(self.dims, self.weights, self.t["x"],
                                self.t["dy"] if dy is None else dy, d_aux, self.workspace,
                                self.ws_bytes, self.dx, self.grads, stream)
@@ -72,7 +94,7 @@ class MixLoraFFN:
         torch.cuda.synchronize()
         out = dict(y=self.y.float().cpu().numpy(), topk_idx=self.topk_idx.cpu().numpy(),
                    topk_w=self.topk_w.cpu().numpy(), counts=self.counts.cpu().numpy(),
-                   aux_loss=float(self.aux.cpu().item()))
+                   aux_loss=(self.aux.cpu().numpy() if self.multi else float(self.aux.cpu().item())))
         if self.with_backward:
             out["dx"] = self.dx.float().cpu().numpy()
             for n, v in self.g.items():

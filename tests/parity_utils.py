@@ -44,12 +44,18 @@ def routing_masks(logits, k):
     return set_safe, order_safe
 
 
-def check_routing(res, ref, cfg, tol_w):
-    """Returns the mask of tokens whose routing agrees completely with the oracle."""
+def check_routing(res, ref, cfg, tol_w, token_model=None):
+    """Returns the mask of tokens whose routing agrees completely with the oracle.  With several
+    adapters (token_model given) the indices are those inside the token's adapter and the counts
+    cover the M*N experts of all adapters."""
     k, N, T = cfg.k, cfg.N, cfg.T
     set_safe, order_safe = routing_masks(ref["logits"], k)
     gi, ri = res["topk_idx"].astype(np.int64), ref["topk_idx"]
     assert gi.shape == (T, k) and gi.min() >= 0 and gi.max() < N
+    if token_model is not None:   # index among all experts from here on
+        off = (np.asarray(token_model, dtype=np.int64) * N)[:, None]
+        gi, ri = gi + off, ri + off
+        N = N * cfg.M
     # bit-exact on margin-safe tokens: kept sets, and slot order where the order is safe too
     assert (np.sort(gi[set_safe], axis=1) == np.sort(ri[set_safe], axis=1)).all()
     assert (gi[order_safe] == ri[order_safe]).all()

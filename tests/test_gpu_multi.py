@@ -1,0 +1,143 @@
+"""GPU parity of the multi-adapter calls (several MixLoRA adapters on one frozen base, Section
+3.3 optimisation II) against the CPU oracle's adapter-by-adapter definition."""
+import numpy as np
+import pytest
+
+from oracle import mixlora_oracle as orc
+from paper_2404_15159_amd import binding as B
+from paper_2404_15159_amd import synth
+from paper_2404_15159_amd.runner import MixLoraFFN
+
+import parity_utils as pu
+
+pytestmark = pytest.mark.gpu
+
+BASE_BF16 = synth.CONFIGS["llama2_7b"]
+BASE_F32 = synth.CONFIGS["tiny_f32"]
+
+
+def run_multi(cfg, host, pattern, d_aux=None, aux_mode="top1"):
+    tm = synth.token_model(cfg, pattern)
+    print(f"\nmulti case {cfg.name}: M={cfg.M} T={cfg.T} d={cfg.d} f={cfg.d_ff} N={cfg.N} k={cfg.k} "
+          f"r={cfg.r} {cfg.dtype} pattern={pattern} tokens/adapter={np.bincount(tm, minlength=cfg.M)}",
+          flush=True)
+    mode = B.AUX_TOP1 if aux_mode == "top1" else B.AUX_TOPK
+    m = MixLoraFFN(cfg, host, aux_mode=mode, token_model=tm, d_aux=d_aux)
+    m.forward()
+    m.backward()
+    res = m.results()
+    Ws = synth.split_adapters(cfg, host)
+    fw = orc.multi_forward(host["x"], tm, Ws, cfg.k, cfg.lora_scale, cfg.aux_coeff, aux_mode)
+    bw = orc.multi_backward(host["x"], tm, Ws, cfg.k, cfg.lora_scale, host["dy"], d_aux,
+                            cfg.aux_coeff, aux_mode)
+    return res, fw, bw, tm
+
+
+def compare_multi(res, fw, bw, cfg, tm):
+    tol = pu.TOL[cfg.dtype]
+    same = pu.check_routing(res, fw, cfg, 1e-5 if cfg.dtype == "f32" else 2e-5, token_model=tm)
+    rep = {"routing_mismatch_tokens": int((~same).sum())}
+    rep["y"] = pu.assert_close("y", res["y"][same], fw["y"][same], tol)
+    rep["dx"] = pu.assert_close("dx", res["dx"][same], bw["dx"][same], tol)
+    assert (res["counts"].reshape(cfg.M, cfg.N)[:, :].sum(axis=1)
+            == cfg.k * np.bincount(tm, minlength=cfg.M)).all()
+    all_same = bool(same.all())
+    if all_same:
+        den = np.maximum(np.abs(fw["aux_loss"]), 1e-30)
+        a = np.abs(res["aux_loss"] - fw["aux_loss"]) / den
+        a[fw["aux_loss"] == 0.0] = np.abs(res["aux_loss"][fw["aux_loss"] == 0.0])
+        assert a.max() <= 1e-5, f"aux_loss rel err {a}"
+        rep["aux_loss"] = float(a.max())
+    for n in pu.GRAD_NAMES:
+        ref = np.concatenate([g[n] for g in bw["grads"]], axis=0)
+        if all_same or cfg.dtype == "bf16":
+            rep[n] = pu.assert_close(n, res[n], ref, tol)
+        # an adapter without tokens gets exactly zero gradients
+        for m_ in range(cfg.M):
+            if not (tm == m_).any():
+                assert not res[n][m_ * cfg.N:(m_ + 1) * cfg.N].any(), n
+    print({k: (tuple(f"{x:.2e}" for x in v) if isinstance(v, tuple) else v) for k, v in rep.items()},
+          flush=True)
+    return rep
+
+
+MULTI_CASES = [
+    # name, base, overrides, token pattern, d_aux
+    ("f32_m3", BASE_F32, dict(T=264, d=72, d_ff=200, N=4, k=2, r=8, M=3, seq_len=24), "round_robin", None),
+    ("f32_m2_uneven_daux", BASE_F32, dict(T=250, d=64, d_ff=136, N=6, k=3, r=8, M=2, seq_len=10),
+     "uneven", (0.5, 2.0)),
+    ("bf16_m2", BASE_BF16, dict(T=600, d=256, d_ff=520, N=8, k=2, r=16, M=2, seq_len=50), "round_robin", None),
+    ("bf16_m4_uneven", BASE_BF16, dict(T=777, d=192, d_ff=544, N=4, k=2, r=8, alpha=16.0, M=4, seq_len=37),
+     "uneven", (1.0, 0.0, 3.0, 1.0)),
+    ("bf16_m3_empty_adapter", BASE_BF16, dict(T=300, d=128, d_ff=264, N=5, k=2, r=16, M=3, seq_len=30),
+     "skip_last", None),
+    ("bf16_m8_top1", BASE_BF16, dict(T=512, d=128, d_ff=256, N=8, k=1, r=8, alpha=16.0, M=8, seq_len=16),
+     "round_robin", None),
+]
+
+
+@pytest.mark.parametrize("name,base,over,pattern,d_aux", MULTI_CASES, ids=[c[0] for c in MULTI_CASES])
+def test_multi_small_cases(name, base, over, pattern, d_aux):
+    cfg = synth.scaled(base, name=name, **over)
+    host = synth.make_inputs(cfg)
+    for n in ("B_gate", "B_up", "B_down"):
+        host[n] = synth._store(host[n] * 4.0, cfg.dtype)
+    host["W_router"] = synth._store(host["W_router"] * 8.0, cfg.dtype)
+    res, fw, bw, tm = run_multi(cfg, host, pattern, d_aux)
+    compare_multi(res, fw, bw, cfg, tm)
+
+
+def test_multi_one_adapter_matches_single_entry_point():
+    """M = 1 through the multi-adapter entry points gives bit-identical results to the
+    single-adapter entry points (same kernels, same launch shapes)."""
+    cfg1 = synth.scaled(BASE_BF16, name="m1", T=300, d=256, d_ff=520, N=8, k=2, r=16)
+    host = synth.make_inputs(cfg1)
+    a = MixLoraFFN(cfg1, host)
+    a.forward(); a.backward()
+    ra = a.results()
+    import torch
+    tm = torch.zeros(cfg1.T, dtype=torch.int32, device="cuda:0")
+    multi = B.make_multi(1, tm, None)
+    ws_bytes = B.mixlora_multi_workspace_bytes(a.dims, 1, True)
+    assert ws_bytes == a.ws_bytes
+    y = torch.empty_like(a.y); dx = torch.empty_like(a.dx)
+    B.mixlora_multi_forward(a.dims, multi, a.weights, a.t["x"], y, a.topk_idx, a.topk_w, a.counts,
+                            a.aux, a.workspace, a.ws_bytes)
+    B.mixlora_multi_backward(a.dims, multi, a.weights, a.t["x"], a.t["dy"], a.workspace, a.ws_bytes,
+                             dx, a.grads)
+    torch.cuda.synchronize()
+    assert np.array_equal(y.float().cpu().numpy(), ra["y"])
+    assert np.array_equal(dx.float().cpu().numpy(), ra["dx"])
+    for n, v in a.g.items():
+        assert np.array_equal(v.cpu().numpy(), ra[n]), n
+
+
+def test_multi_full_size_two_adapters():
+    """Two adapters at the LLaMA-2-7B shape, in the configuration bench.py --workload
+    llama2_7b_multi2 times: y / dx on sampled tokens and the gradients of the experts through
+    the per-adapter oracle on each adapter's tokens."""
+    cfg = synth.CONFIGS["llama2_7b_multi2"]
+    host = synth.make_inputs(cfg)
+    tm = synth.token_model(cfg)
+    m = MixLoraFFN(cfg, host, token_model=tm)
+    m.forward(); m.backward()
+    res = m.results()
+    Ws = synth.split_adapters(cfg, host)
+    tol = pu.TOL["bf16"]
+    # sampled tokens: per-token outputs are independent of the rest of the batch except for the
+    # auxiliary term (batch statistics), which needs the adapter's full routing
+    rng = np.random.default_rng(11)
+    for a in range(cfg.M):
+        tok = np.nonzero(tm == a)[0]
+        z, p, idx, w = orc.router(host["x"][tok], Ws[a]["W_router"], cfg.k)
+        set_safe, order_safe = pu.routing_masks(z, cfg.k)
+        gi = res["topk_idx"][tok].astype(np.int64)
+        assert (gi[order_safe] == idx[order_safe]).all()
+        loss, F, P = orc.aux_loss(p, idx, cfg.N, cfg.aux_coeff)
+        if (gi == idx).all():
+            assert abs(res["aux_loss"][a] - loss) / loss < 1e-5
+        sub = rng.choice(tok.size, size=96, replace=False)
+        sub = sub[(gi[sub] == idx[sub]).all(axis=1)]
+        fw = orc.forward(host["x"][tok[sub]], Ws[a], cfg.k, cfg.lora_scale, 0.0)
+        pu.assert_close(f"y[adapter {a}]", res["y"][tok[sub]], fw["y"], tol)
+    assert (res["counts"].reshape(cfg.M, cfg.N).sum(axis=1) == cfg.k * np.bincount(tm)).all()
