@@ -117,6 +117,37 @@ def test_aux_and_transpose_argument_errors(lib):
     assert ei.value.code == -3
 
 
+def test_multi_adapter_argument_errors(lib):
+    d = dims()
+    assert B.mixlora_multi_workspace_bytes(d, 1, True) == B.mixlora_workspace_bytes(d, True)
+    assert B.mixlora_multi_workspace_bytes(d, 2, True) == B.mixlora_workspace_bytes(dims(N=16), True)
+    for M in (0, -1, 9):          # 9 * 8 experts > 64
+        assert B.mixlora_multi_workspace_bytes(d, M, True) == 0
+    assert B.mixlora_multi_workspace_bytes(d, 5, True) == 0          # 5 * 8 * 16 > 512 rank columns
+    assert B.mixlora_multi_workspace_bytes(dims(N=2, k=3), 4, True) == 0   # k > experts per adapter
+
+    def fcode(d_, multi, w=None, **kw):
+        with pytest.raises(B.MixLoraError) as ei:
+            B.mixlora_multi_forward(d_, multi, w or fake_weights(), stream=0, **fwd_args(**kw))
+        return ei.value.code
+
+    assert fcode(d, B.make_multi(0, FAKE)) == -2
+    assert fcode(d, B.make_multi(9, FAKE)) == -2
+    assert fcode(d, B.make_multi(2, None)) == -1
+    assert fcode(dims(N=2, k=3), B.make_multi(4, FAKE)) == -2
+    assert fcode(d, B.make_multi(2, FAKE), y=None) == -1
+    assert fcode(d, B.make_multi(2, FAKE), workspace_bytes=1024) == -5
+    g = B.make_grads({n: FAKE for n in B.GRAD_FIELDS})
+    with pytest.raises(B.MixLoraError) as ei:
+        B.mixlora_multi_backward(d, B.make_multi(2, FAKE, (1.0, 2.0)), fake_weights(), FAKE, None,
+                                 FAKE, 1 << 40, FAKE, g, stream=0)
+    assert ei.value.code == -1
+    with pytest.raises(B.MixLoraError) as ei:
+        B.mixlora_multi_backward(d, B.make_multi(2, FAKE), fake_weights(), FAKE, FAKE, FAKE,
+                                 B.mixlora_multi_workspace_bytes(d, 2, False), FAKE, g, stream=0)
+    assert ei.value.code == -5
+
+
 def test_binding_refuses_missing_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
