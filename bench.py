@@ -22,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK = 2.5e15     # dense bf16 MFMA, FLOP/s (MI355X published)
+HBM_PEAK = 8.0e12           # HBM3E, B/s (MI355X published)
 
 
 def flop_model(cfg, units_fwd, units_bwd):
@@ -148,9 +149,28 @@ def main():
     units_per_step = 3 + (3 if do_bwd else 0)
     launches_per_step = k_launches / args.steps
     avg_launch_s = k_ms / 1e3 / max(k_launches, 1)
-    alg_flops_per_launch = units_per_step * unit / launches_per_step
-    achieved = alg_flops_per_launch / avg_launch_s
     traffic = read_traffic(args.workload)
+    if cfg.T <= 128:
+        # decode-shaped call: the frozen-projection launches stream every weight once and do
+        # little arithmetic per byte, so their roofline is HBM bandwidth.  Algorithmic bytes per
+        # launch: the frozen matrices (units_per_step * d * d_ff * 2 B) over the launches.
+        alg_bytes_per_launch = units_per_step * cfg.d * cfg.d_ff * 2.0 / max(launches_per_step, 1e-9)
+        achieved = alg_bytes_per_launch / avg_launch_s if k_launches else 0.0
+        roofline = {"bound": "hbm",
+                    "kernel": "gemm_bf16_dl_kernel<64 or 128 rows,64,64,4 stages> (weight streaming)",
+                    "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK, "launches_per_step": launches_per_step,
+                    "avg_launch_ms": avg_launch_s * 1e3, "traffic": traffic}
+    else:
+        alg_flops_per_launch = units_per_step * unit / max(launches_per_step, 1e-9)
+        achieved = alg_flops_per_launch / avg_launch_s if k_launches else 0.0
+        roofline = {"bound": "mfma", "kernel": "gemm_bf16_dl_kernel<256,256,64,2 stages,8 waves>",
+                    "achieved": achieved / 1e12, "peak": MFMA_BF16_PEAK / 1e12,
+                    "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK,
+                    "launches_per_step": launches_per_step,
+                    "avg_launch_ms": avg_launch_s * 1e3,
+                    "executed_tflop_per_launch": k_flops_exec / max(k_launches, 1) / 1e12,
+                    "traffic": traffic}
 
     out = {
         "metric": "MixLoRA FFN fwd+bwd tokens/sec on 1 MI355X + % bf16 MFMA peak",
@@ -170,13 +190,7 @@ def main():
                    "paper_schedule_tflop_per_step": (fwd_paper + (bwd_paper if do_bwd else 0)) / 1e12,
                    "mfma_frac_whole_step": step_flops / (ms_per_step / 1e3) / MFMA_BF16_PEAK,
                    "input_generation_s": round(t_inputs, 1)},
-        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_dl_kernel<256,256,64,2 stages,8 waves>",
-                     "achieved": achieved / 1e12, "peak": MFMA_BF16_PEAK / 1e12,
-                     "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK,
-                     "launches_per_step": launches_per_step,
-                     "avg_launch_ms": avg_launch_s * 1e3,
-                     "executed_tflop_per_launch": k_flops_exec / max(k_launches, 1) / 1e12,
-                     "traffic": traffic},
+        "roofline": roofline,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, host, min(args.cpu_tokens, cfg.T))

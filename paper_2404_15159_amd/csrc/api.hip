@@ -14,6 +14,7 @@ using namespace mixlora;
 namespace {
 
 constexpr size_t ALIGN = 256;
+constexpr size_t SPLITK_MAX_ROWS = 128;   // at most this many tokens: the down GEMM is split along K
 inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 inline int up64(int v) { return (v + 63) / 64 * 64; }
 
@@ -23,7 +24,7 @@ struct Layout {
       model_tokens;
   size_t G, U, Pg_all, Pu_all, a_grp, Q_all;
   // forward scratch
-  size_t a_comb, Qw, Bd_cat, rank_part;
+  size_t a_comb, Qw, Bd_cat, rank_part, splitk;
   size_t fwd_end;
   // backward scratch
   size_t WdT, WgT, WuT, H, Bd_T, VB_all, dg_grp, du_grp, dgsum, dusum, dw_part, dw, Bg_T, Bu_T, AdT,
@@ -64,6 +65,8 @@ Layout make_layout(const mixlora_dims &D) {
   L.Qw = take(T * R * E);
   L.Bd_cat = take(d * R * E);
   L.rank_part = take(2 * 8 * kT * r * 4);   // per-split rank-r partial sums (two banks)
+  // few tokens (decode-shaped calls): partial outputs of the K-split down projection
+  L.splitk = take(T <= SPLITK_MAX_ROWS ? (size_t)GEMM_MAX_PROBLEMS * T * d * 4 : 0);
   L.fwd_end = o;
   L.Kx = up64((int)(2 * R) + (int)N);   // whole K tiles of the GEMM's DMA path
   L.nct = swiglu_col_tiles((int)f);
@@ -252,7 +255,28 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
     HIP_TRY(launch_relayout(dt, &j, 1, st));
   }
   // down projection (Algorithm 1 line 14): y = a_comb W_down^T + Qw (s B_down)^T
-  {
+  if (dt == MIXLORA_BF16 && (size_t)T <= SPLITK_MAX_ROWS) {
+    // Few rows: the d output columns alone give too few tiles to stream W_down at full rate, so
+    // the K range is cut into S slices (whole 64-wide K tiles), one GEMM problem each with an
+    // fp32 partial output, and the partial outputs are added in slice order.
+    const int tiles_n = (d + 63) / 64, ktiles = (f + 63) / 64;
+    int S = 256 / tiles_n;
+    S = S < 1 ? 1 : (S > GEMM_MAX_PROBLEMS ? GEMM_MAX_PROBLEMS : S);
+    S = S > ktiles ? ktiles : S;
+    const int chunk = ((ktiles + S - 1) / S) * 64;
+    GemmProblem p[GEMM_MAX_PROBLEMS];
+    float *part = (float *)(ws + L.splitk);
+    const size_t E = 2;
+    int used = 0;
+    for (int k0 = 0; k0 < f; k0 += chunk, used++) {
+      p[used] = problem(T, d, part + (size_t)used * T * d, d, 1);
+      const int klen = f - k0 < chunk ? f - k0 : chunk;
+      add_seg(p[used], ws + L.a_comb + (size_t)k0 * E, f, (const char *)w->W_down + (size_t)k0 * E, f, klen);
+      if (used == 0) add_seg(p[0], ws + L.Qw, R, ws + L.Bd_cat, R, R);
+    }
+    HIP_TRY(launch_gemm(dt, p, used, st));
+    HIP_TRY(launch_splitk_reduce(dt, part, used, (int64_t)T * d, y, st));
+  } else {
     GemmProblem p = problem(T, d, y, d, 0);
     add_seg(p, ws + L.a_comb, f, w->W_down, f, f);
     add_seg(p, ws + L.Qw, R, ws + L.Bd_cat, R, R);

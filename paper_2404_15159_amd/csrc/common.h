@@ -67,7 +67,7 @@ struct GemmProblem {
 };
 // Enqueue up to GEMM_MAX_PROBLEMS independent problems of identical M in one launch (N and the
 // output type may differ per problem).
-constexpr int GEMM_MAX_PROBLEMS = 5;
+constexpr int GEMM_MAX_PROBLEMS = 8;
 hipError_t launch_gemm(int dtype, const GemmProblem *probs, int nprob, hipStream_t st);
 
 // Measurement hook: HIP-event timing of every launch of the large-tile bf16 kernel between
@@ -151,6 +151,10 @@ hipError_t launch_scatter_blocks(int dtype, const PairCtx &pc, const float *src,
 // small_grp[row, q] = scale * src[(by_token ? t(row) : row), e(row)*r + q]   (float32)
 hipError_t launch_gather_small(const PairCtx &pc, const float *src, int by_token, int weighted,
                                float *small_grp, hipStream_t st);
+
+// out[i] = sum_{s<S} part[s][i], i < n, fixed order (closing step of a split-K GEMM)
+hipError_t launch_splitk_reduce(int dtype, const float *part, int S, int64_t n, void *out,
+                                hipStream_t st);
 
 // Weight re-layouts (tiny index permutations), batched into one launch:
 //   dst[dst0 + i0*d0 + i1*d1 + i2*d2] = scale * src[i0*s0 + i1*s1 + i2*s2]   (0 where i2 >= valid2)

@@ -347,6 +347,28 @@ hipError_t launch_gather_small(const PairCtx &pc, const float *src, int by_token
   return hipGetLastError();
 }
 
+// out[i] = sum over s < S of part[s][i]  (fixed order): closes a GEMM whose K range was split
+// over several workgroups because its output alone has too few tiles to cover the chip
+template <typename E>
+__global__ void splitk_reduce_kernel(const float *__restrict__ part, int S, int64_t n,
+                                     E *__restrict__ out) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float acc = 0.f;
+  for (int sp = 0; sp < S; sp++) acc += part[(int64_t)sp * n + i];
+  out[i] = from_f32<E>(acc);
+}
+
+hipError_t launch_splitk_reduce(int dtype, const float *part, int S, int64_t n, void *out,
+                                hipStream_t st) {
+  const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+  if (dtype == MIXLORA_BF16)
+    hipLaunchKernelGGL(splitk_reduce_kernel<bf16_t>, grid, block, 0, st, part, S, n, (bf16_t *)out);
+  else
+    hipLaunchKernelGGL(splitk_reduce_kernel<float>, grid, block, 0, st, part, S, n, (float *)out);
+  return hipGetLastError();
+}
+
 // ---- weight re-layouts (all tiny next to the frozen matrices) -------------------------------
 // Every re-layout is an index permutation of at most three loop dimensions (i2 fastest over the
 // threads):  dst[dst0 + i0*d0 + i1*d1 + i2*d2] = scale * src[i0*s0 + i1*s1 + i2*s2], with zeros

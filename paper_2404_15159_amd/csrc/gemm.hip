@@ -566,7 +566,9 @@ static hipError_t launch_bf16(const GemmBatch &b, int nprob, hipStream_t st) {
     attr_set = true;
   }
   const int tiles = ((b.p[0].M + BM - 1) / BM) * ((b.p[0].N + BN - 1) / BN);
-  const bool timed = BM == 256 && g_timer.on && g_timer.used < g_timer.cap;
+  // every launch of this kernel family is a frozen-projection launch (large tiles at training
+  // shapes, the narrow weight-streaming tiles at decode shapes): all are timed
+  const bool timed = g_timer.on && g_timer.used < g_timer.cap;
   if (timed) (void)hipEventRecord(g_timer.beg[g_timer.used], st);
   hipLaunchKernelGGL(kern, dim3(tiles, 1, nprob), dim3(WGM * WGN * 64), smem, st, b);
   if (timed) {
@@ -594,7 +596,9 @@ static hipError_t launch_bf16_dl(const GemmBatch &b, int nprob, hipStream_t st) 
     const int t = ((b.p[i].M + BM - 1) / BM) * ((b.p[i].N + BN - 1) / BN);
     tiles = t > tiles ? t : tiles;
   }
-  const bool timed = BM == 256 && g_timer.on && g_timer.used < g_timer.cap;
+  // every launch of this kernel family is a frozen-projection launch (large tiles at training
+  // shapes, the narrow weight-streaming tiles at decode shapes): all are timed
+  const bool timed = g_timer.on && g_timer.used < g_timer.cap;
   if (timed) (void)hipEventRecord(g_timer.beg[g_timer.used], st);
   hipLaunchKernelGGL(kern, dim3(tiles, 1, nprob), dim3(WGM * WGN * 64), smem, st, b);
   if (timed) {
@@ -639,6 +643,13 @@ hipError_t launch_gemm(int dtype, const GemmProblem *probs, int nprob, hipStream
     // of the last, partially filled round of workgroups).
     if (dl_eligible(b, nprob, 64)) return launch_bf16_dl<256, 256, 64, 2, 2, 4, true>(b, nprob, st);
     if (dl_eligible(b, nprob, 32)) return launch_bf16_dl<256, 256, 32, 4, 2, 4, false>(b, nprob, st);
+  }
+  if (dtype == MIXLORA_BF16 && M <= 128 && any_big && dl_eligible(b, nprob, 64)) {
+    // few rows (decode-shaped calls): the launch is bound by streaming the weights once, so the
+    // tiles are narrow (64 output columns: enough workgroups to cover the chip) and the ring is
+    // deep (4 K tiles in flight per workgroup, 2 workgroups per CU)
+    if (M <= 64) return launch_bf16_dl<64, 64, 64, 4, 1, 2, false>(b, nprob, st);
+    return launch_bf16_dl<128, 64, 64, 4, 2, 2, false>(b, nprob, st);
   }
   if (!uniform || nprob > 2) {   // the generic kernels take uniform batches of at most two
     for (int i = 0; i < nprob; i++) {

@@ -127,6 +127,9 @@ CONFIGS = {
     "llama3_8b_clusters": Config("llama3_8b_clusters", 5, T=16384, d=4096, d_ff=14336, N=16, k=2,
                                  r=8, alpha=16.0, dtype="bf16", b_std=0.01,
                                  structure="clusters4"),
+    # decode-shaped forward: 64 sequences, one new token each (weight-read-bound regime)
+    "llama2_7b_decode": Config("llama2_7b_decode", 7, T=64, d=4096, d_ff=11008, N=8, k=2, r=16,
+                               alpha=32.0, dtype="bf16", b_std=0.01, backward=False, seq_len=1),
     # two adapters trained together on one frozen base (the multi-adapter setting of the
     # paper's efficiency table): 4 sequences of 1024 tokens, alternating between the adapters
     "llama2_7b_multi2": Config("llama2_7b_multi2", 6, T=4096, d=4096, d_ff=11008, N=8, k=2, r=16,

@@ -65,6 +65,11 @@ SMALL_CASES = [
     ("bf16_top1", BASE_BF16, dict(T=200, d=128, d_ff=384, N=8, k=1, r=16)),
     ("bf16_one_expert", BASE_BF16, dict(T=70, d=64, d_ff=136, N=1, k=1, r=8, alpha=16.0)),
     ("bf16_one_token", BASE_BF16, dict(T=1, d=64, d_ff=128, N=8, k=2, r=16)),
+    # few tokens: narrow weight-streaming GEMM tiles and the K-split down projection
+    ("bf16_decode_64", BASE_BF16, dict(T=64, d=256, d_ff=1024, N=8, k=2, r=16)),
+    ("bf16_decode_17", BASE_BF16, dict(T=17, d=512, d_ff=704, N=8, k=2, r=16)),
+    ("bf16_decode_100", BASE_BF16, dict(T=100, d=256, d_ff=520, N=4, k=2, r=32, alpha=64.0)),
+    ("bf16_decode_128", BASE_BF16, dict(T=128, d=192, d_ff=576, N=8, k=2, r=8, alpha=16.0)),
     ("bf16_skew", synth.CONFIGS["llama2_13b_skew"], dict(T=600, d=256, d_ff=768)),
     ("bf16_clusters", synth.CONFIGS["llama3_8b_clusters"], dict(T=1024, d=256, d_ff=512, seq_len=64)),
     ("f32_ragged", BASE_F32, dict(T=333, d=72, d_ff=200, N=6, k=2, r=8)),
