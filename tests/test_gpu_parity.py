@@ -65,6 +65,7 @@ SMALL_CASES = [
     ("bf16_top1", BASE_BF16, dict(T=200, d=128, d_ff=384, N=8, k=1, r=16)),
     ("bf16_one_expert", BASE_BF16, dict(T=70, d=64, d_ff=136, N=1, k=1, r=8, alpha=16.0)),
     ("bf16_one_token", BASE_BF16, dict(T=1, d=64, d_ff=128, N=8, k=2, r=16)),
+    ("bf16_wide_d", BASE_BF16, dict(T=300, d=1024, d_ff=520, N=8, k=2, r=16)),
     # few tokens: narrow weight-streaming GEMM tiles and the K-split down projection
     ("bf16_decode_64", BASE_BF16, dict(T=64, d=256, d_ff=1024, N=8, k=2, r=16)),
     ("bf16_decode_17", BASE_BF16, dict(T=17, d=512, d_ff=704, N=8, k=2, r=16)),
@@ -111,6 +112,35 @@ def test_deterministic_reruns():
     b = m.results()
     for n in a:
         assert np.array_equal(np.asarray(a[n]), np.asarray(b[n])), n
+
+
+def test_caller_stream_and_forward_only_workspace():
+    """Everything is enqueued on the stream the caller passes (here a non-default one, with the
+    host not synchronising between the two calls), and a forward-only call needs only the
+    forward workspace; results equal those of the default-stream run bit for bit."""
+    cfg = synth.scaled(BASE_BF16, name="bf16_stream", T=520, d=256, d_ff=776, N=8, k=2, r=16)
+    host = synth.make_inputs(cfg)
+    m = MixLoraFFN(cfg, host)
+    m.forward(); m.backward()
+    a = m.results()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    for t in (m.y, m.dx, m.topk_w, *m.g.values()):
+        t.zero_()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        m.forward(stream=side)
+        m.backward(stream=side)
+    side.synchronize()
+    b = m.results()
+    for n in a:
+        assert np.array_equal(np.asarray(a[n]), np.asarray(b[n])), n
+    f = MixLoraFFN(cfg, host, with_backward=False)
+    assert f.ws_bytes < m.ws_bytes
+    f.forward()
+    c = f.results()
+    for n in c:
+        assert np.array_equal(np.asarray(a[n]), np.asarray(c[n])), n
 
 
 @pytest.mark.parametrize("mode", ["top1", "topk"])
