@@ -143,6 +143,40 @@ def test_caller_stream_and_forward_only_workspace():
         assert np.array_equal(np.asarray(a[n]), np.asarray(c[n])), n
 
 
+def test_graph_capture_and_replay():
+    """The call sequences allocate nothing and never synchronise, so forward + backward can be
+    captured into a HIP graph.  Every replay (with eager work and synchronisations between the
+    replays) must reproduce the eager result bit for bit."""
+    cfg = synth.scaled(BASE_BF16, name="bf16_graph", T=384, d=256, d_ff=648, N=8, k=2, r=16)
+    host = synth.make_inputs(cfg)
+    m = MixLoraFFN(cfg, host)
+    m.forward(); m.backward()          # eager: also sets the kernels' one-time attributes
+    ref = m.results()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        m.forward(stream=side)
+        m.backward(stream=side)
+        graph.capture_end()
+    torch.cuda.synchronize()
+    x0 = m.t["x"].clone()
+    for rep in range(3):
+        for t in (m.y, m.dx, m.topk_w, *m.g.values()):
+            t.zero_()
+        # eager work of the program's own between the replays: another input through the same
+        # workspace, then the original input restored
+        m.t["x"].copy_(torch.roll(x0, 1, dims=0))
+        m.forward()
+        torch.cuda.synchronize()
+        m.t["x"].copy_(x0)
+        graph.replay()
+        got = m.results()
+        for n in ref:
+            assert np.array_equal(np.asarray(ref[n]), np.asarray(got[n])), (rep, n)
+
+
 @pytest.mark.parametrize("mode", ["top1", "topk"])
 def test_aux_loss_entry(mode):
     T, N, k = 5000, 16, 2
