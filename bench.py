@@ -143,6 +143,22 @@ def main():
     torch.cuda.synchronize()
     k_ms, k_launches, k_flops_exec = B.mixlora_profile_end()
 
+    # context for the rooflines, measured live: what the matrix pipe alone sustains on
+    # pseudo-random bf16 operands (register-only MFMA loop) and what a plain device copy moves
+    sink = torch.empty(1 << 20, dtype=torch.float32, device="cuda:0")
+    mfma_ctx = max(B.mixlora_mfma_probe(sink, sink.numel() * 4, 2, 20000) for _ in range(2))
+    src = torch.empty(1 << 27, dtype=torch.int32, device="cuda:0")   # 512 MiB
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(4):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_tb_s = 4 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    del src, dst, sink
+
     if args.copy_calibration:
         src = torch.zeros(1 << 28, dtype=torch.int32, device="cuda:0")
         dst = torch.empty_like(src)
@@ -197,6 +213,9 @@ def main():
                    "algorithmic_tflop_per_step": step_flops / 1e12,
                    "paper_schedule_tflop_per_step": (fwd_paper + (bwd_paper if do_bwd else 0)) / 1e12,
                    "mfma_frac_whole_step": step_flops / (ms_per_step / 1e3) / MFMA_BF16_PEAK,
+                   "measured_context": {
+                       "mfma_register_only_random_operands_tflops": round(mfma_ctx, 1),
+                       "device_copy_read_plus_write_tb_s": round(copy_tb_s, 2)},
                    "input_generation_s": round(t_inputs, 1)},
         "roofline": roofline,
     }

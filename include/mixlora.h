@@ -181,6 +181,16 @@ MIXLORA_API int mixlora_transpose(const void *in, void *out, int32_t rows, int32
 MIXLORA_API int mixlora_profile_begin(int32_t max_launches);
 MIXLORA_API int mixlora_profile_end(double *ms_total, int32_t *launches, double *flops_total);
 
+/* Measurement aid: TFLOP/s that a register-only loop of bf16 MFMA 32x32x16 on pseudo-random
+ * operands sustains on the current device at waves_per_simd (1 or 2) wavefronts per SIMD - the
+ * practical ceiling of the matrix pipe on a power-limited part, beside the published peak.
+ * sink: device scratch of at least 2 * (number of CUs) * 1024 bytes (overwritten).
+ * Creates two HIP events and WAITS for the kernel (unlike every other call here).
+ * Errors: E_NULL, E_SHAPE (waves_per_simd, iters out of range), E_WORKSPACE (sink too small),
+ * E_HIP. */
+MIXLORA_API int mixlora_mfma_probe(void *sink, size_t sink_bytes, int32_t waves_per_simd,
+                                   int32_t iters, double *tflops, void *stream);
+
 /* Library version as major*10000 + minor*100 + patch.  Host-only. */
 MIXLORA_API int mixlora_version(void);
 

@@ -22,7 +22,8 @@ STATUS = {0: "OK", -1: "E_NULL", -2: "E_SHAPE", -3: "E_DTYPE", -4: "E_ALIGN", -5
 EXPORTS = ("mixlora_workspace_bytes", "mixlora_ffn_forward", "mixlora_ffn_backward",
            "mixlora_aux_loss", "mixlora_transpose", "mixlora_version",
            "mixlora_profile_begin", "mixlora_profile_end",
-           "mixlora_multi_workspace_bytes", "mixlora_multi_forward", "mixlora_multi_backward")
+           "mixlora_multi_workspace_bytes", "mixlora_multi_forward", "mixlora_multi_backward",
+           "mixlora_mfma_probe")
 
 
 class Dims(C.Structure):
@@ -93,6 +94,8 @@ def load():
     lib.mixlora_multi_backward.restype = C.c_int
     lib.mixlora_multi_backward.argtypes = [C.POINTER(Dims), C.POINTER(Multi), C.POINTER(Weights),
                                            vp, vp, vp, sz, vp, C.POINTER(Grads), vp]
+    lib.mixlora_mfma_probe.restype = C.c_int
+    lib.mixlora_mfma_probe.argtypes = [vp, sz, i32, i32, C.POINTER(C.c_double), vp]
     _lib = lib
     return lib
 
@@ -208,6 +211,16 @@ def mixlora_transpose(src, dst, rows: int, cols: int, dtype: int, stream=None) -
 
 def mixlora_version() -> int:
     return int(load().mixlora_version())
+
+
+def mixlora_mfma_probe(sink, sink_bytes: int, waves_per_simd: int, iters: int, stream=None) -> float:
+    """TFLOP/s of a register-only bf16 MFMA loop on pseudo-random operands (waits for the GPU)."""
+    v = C.c_double()
+    rc = load().mixlora_mfma_probe(_ptr(sink), sink_bytes, waves_per_simd, iters, C.byref(v),
+                                   _stream(stream))
+    if rc != 0:
+        raise MixLoraError("mixlora_mfma_probe", rc)
+    return v.value
 
 
 def mixlora_profile_begin(max_launches: int) -> None:

@@ -16,7 +16,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libmixlora.so")
-SOURCES = ("gemm.hip", "router.hip", "elementwise.hip", "grads.hip", "fused.hip", "api.hip")
+SOURCES = ("gemm.hip", "router.hip", "elementwise.hip", "grads.hip", "fused.hip", "probe.hip",
+           "api.hip")
 
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",

@@ -148,6 +148,16 @@ def test_multi_adapter_argument_errors(lib):
     assert ei.value.code == -5
 
 
+def test_mfma_probe_argument_errors(lib):
+    for kw, code in ((dict(sink=None), -1), (dict(waves_per_simd=0), -2), (dict(waves_per_simd=3), -2),
+                     (dict(iters=0), -2)):
+        a = dict(sink=FAKE, sink_bytes=1 << 30, waves_per_simd=1, iters=10)
+        a.update(kw)
+        with pytest.raises(B.MixLoraError) as ei:
+            B.mixlora_mfma_probe(stream=0, **a)
+        assert ei.value.code == code, kw
+
+
 def test_binding_refuses_missing_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))

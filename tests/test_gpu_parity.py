@@ -177,6 +177,17 @@ def test_graph_capture_and_replay():
             assert np.array_equal(np.asarray(ref[n]), np.asarray(got[n])), (rep, n)
 
 
+def test_mfma_probe_is_plausible():
+    sink = torch.empty(1 << 20, dtype=torch.float32, device="cuda:0")
+    one = B.mixlora_mfma_probe(sink, sink.numel() * 4, 1, 4000)
+    two = B.mixlora_mfma_probe(sink, sink.numel() * 4, 2, 4000)
+    print(f"register-only bf16 MFMA: {one:.0f} TFLOP/s at 1 wave/SIMD, {two:.0f} at 2", flush=True)
+    assert 300.0 < one < 2600.0 and 300.0 < two < 2600.0     # below the 2.5 PFLOP/s published peak
+    with pytest.raises(B.MixLoraError) as ei:
+        B.mixlora_mfma_probe(sink, 1024, 2, 100)
+    assert ei.value.code == -5
+
+
 @pytest.mark.parametrize("mode", ["top1", "topk"])
 def test_aux_loss_entry(mode):
     T, N, k = 5000, 16, 2
