@@ -138,10 +138,6 @@ int check_weights(const mixlora_weights *w) {
   return MIXLORA_OK;
 }
 
-__global__ void set_pair_kernel(int32_t *p, int a, int b) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) { p[0] = a; p[1] = b; }
-}
-
 #define HIP_TRY(expr)                                   \
   do {                                                  \
     hipError_t e_ = (expr);                             \
@@ -221,14 +217,12 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
   else
     HIP_TRY(launch_router(dt, x, w->W_router, T, d, N, k, probs, topk_idx, topk_w, idx, wts, Nl,
                           token_model, st));
-  HIP_TRY(launch_group_pairs(idx, T, N, k, (int32_t *)(ws + L.counts), expert_counts,
-                             (int32_t *)(ws + L.first_counts), offs, row_of_pair, pair_of_row, st));
-  // Eq. 8-9
-  HIP_TRY(launch_aux_loss(probs, idx, T, N, k, D.aux_coeff, D.aux_mode, aux_loss,
-                          (float *)(ws + L.F), (float *)(ws + L.P), nullptr, Nl, token_model,
-                          (int32_t *)(ws + L.model_tokens), st));
-  hipLaunchKernelGGL(set_pair_kernel, dim3(1), dim3(64), 0, st, (int32_t *)(ws + L.tok_offs), 0, T);
-  HIP_TRY(hipGetLastError());
+  // grouping of the pairs by expert and Eq. 8-9, one launch
+  HIP_TRY(launch_group_pairs_aux(idx, T, N, k, (int32_t *)(ws + L.counts), expert_counts,
+                                 (int32_t *)(ws + L.first_counts), offs, row_of_pair, pair_of_row,
+                                 (int32_t *)(ws + L.tok_offs), probs, D.aux_coeff, D.aux_mode,
+                                 aux_loss, (float *)(ws + L.F), (float *)(ws + L.P), Nl, token_model,
+                                 (int32_t *)(ws + L.model_tokens), st));
   PairCtx pc{offs, pair_of_row, row_of_pair, wts, idx, T, N, k, r};
   // Algorithm 1 lines 11-13 on the routed pairs, expert-grouped rows
   if (dt == MIXLORA_BF16) {

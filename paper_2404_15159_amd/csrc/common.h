@@ -91,6 +91,13 @@ hipError_t launch_route_logits(const float *Z, int ldz, int T, int N, int k, flo
 hipError_t launch_group_pairs(const int32_t *idx, int T, int N, int k, int32_t *counts,
                               int32_t *counts_out, int32_t *first_counts, int32_t *offs,
                               int32_t *row_of_pair, int32_t *pair_of_row, hipStream_t st);
+// launch_group_pairs and launch_aux_loss (without dprobs) in one launch; tok_offs gets {0, T}
+hipError_t launch_group_pairs_aux(const int32_t *idx, int T, int N, int k, int32_t *counts,
+                                  int32_t *counts_out, int32_t *first_counts, int32_t *offs,
+                                  int32_t *row_of_pair, int32_t *pair_of_row, int32_t *tok_offs,
+                                  const float *probs, float coeff, int mode, float *loss, float *F,
+                                  float *P, int Nl, const int32_t *token_model,
+                                  int32_t *model_tokens, hipStream_t st);
 // loss[N / Nl], one per adapter (statistics over the adapter's own tokens); model_tokens (may be
 // NULL) receives the token count of every adapter.
 hipError_t launch_aux_loss(const float *probs, const int32_t *idx, int T, int N, int k,

@@ -161,7 +161,7 @@ hipError_t launch_route_logits(const float *Z, int ldz, int T, int N, int k, flo
 // i.e. a stable counting sort: rows of one expert are in ascending pair order.
 constexpr int GP_WAVES = 16;
 
-__global__ __launch_bounds__(GP_WAVES * 64) void group_pairs_kernel(
+__device__ __forceinline__ void group_pairs_block(
     const int32_t *__restrict__ idx, int nP, int N, int k, int32_t *__restrict__ counts,
     int32_t *__restrict__ counts_out, int32_t *__restrict__ first_counts,
     int32_t *__restrict__ offs, int32_t *__restrict__ row_of_pair,
@@ -232,6 +232,14 @@ __global__ __launch_bounds__(GP_WAVES * 64) void group_pairs_kernel(
   }
 }
 
+__global__ __launch_bounds__(GP_WAVES * 64) void group_pairs_kernel(
+    const int32_t *__restrict__ idx, int nP, int N, int k, int32_t *__restrict__ counts,
+    int32_t *__restrict__ counts_out, int32_t *__restrict__ first_counts,
+    int32_t *__restrict__ offs, int32_t *__restrict__ row_of_pair,
+    int32_t *__restrict__ pair_of_row) {
+  group_pairs_block(idx, nP, N, k, counts, counts_out, first_counts, offs, row_of_pair, pair_of_row);
+}
+
 hipError_t launch_group_pairs(const int32_t *idx, int T, int N, int k, int32_t *counts,
                               int32_t *counts_out, int32_t *first_counts, int32_t *offs,
                               int32_t *row_of_pair, int32_t *pair_of_row, hipStream_t st) {
@@ -247,14 +255,14 @@ hipError_t launch_group_pairs(const int32_t *idx, int T, int N, int k, int32_t *
 // bit-reproducible.  With several adapters (N = M * Nl experts, expert e belongs to adapter
 // e / Nl, probs is zero outside a token's adapter) every adapter's F, P and loss are taken over
 // its own T_m tokens; an adapter without tokens has loss 0.
-__global__ __launch_bounds__(1024) void aux_loss_kernel(const float *__restrict__ probs,
-                                                        const int32_t *__restrict__ idx, int T,
-                                                        int N, int k, float coeff, int mode,
-                                                        float *__restrict__ loss,
-                                                        float *__restrict__ F_out,
-                                                        float *__restrict__ P_out, int Nl,
-                                                        const int32_t *__restrict__ token_model,
-                                                        int32_t *__restrict__ model_tokens) {
+__device__ __forceinline__ void aux_loss_block(const float *__restrict__ probs,
+                                               const int32_t *__restrict__ idx, int T, int N,
+                                               int k, float coeff, int mode,
+                                               float *__restrict__ loss,
+                                               float *__restrict__ F_out,
+                                               float *__restrict__ P_out, int Nl,
+                                               const int32_t *__restrict__ token_model,
+                                               int32_t *__restrict__ model_tokens) {
   __shared__ int hist[64];
   __shared__ int tm[64];
   __shared__ float part[1024];
@@ -298,6 +306,47 @@ __global__ __launch_bounds__(1024) void aux_loss_kernel(const float *__restrict_
     loss[tid] = coeff * (float)Nl * acc;
     if (model_tokens) model_tokens[tid] = tm[tid];
   }
+}
+
+__global__ __launch_bounds__(1024) void aux_loss_kernel(const float *__restrict__ probs,
+                                                        const int32_t *__restrict__ idx, int T,
+                                                        int N, int k, float coeff, int mode,
+                                                        float *__restrict__ loss,
+                                                        float *__restrict__ F_out,
+                                                        float *__restrict__ P_out, int Nl,
+                                                        const int32_t *__restrict__ token_model,
+                                                        int32_t *__restrict__ model_tokens) {
+  aux_loss_block(probs, idx, T, N, k, coeff, mode, loss, F_out, P_out, Nl, token_model, model_tokens);
+}
+
+// Grouping and auxiliary loss of one forward pass in one single-workgroup launch (both are bound
+// by their own latency); also writes the two-entry offsets {0, T} that let the grouped
+// outer-product kernel treat all tokens as one group.
+__global__ __launch_bounds__(GP_WAVES * 64) void group_pairs_aux_kernel(
+    const int32_t *__restrict__ idx, int T, int N, int k, int32_t *__restrict__ counts,
+    int32_t *__restrict__ counts_out, int32_t *__restrict__ first_counts,
+    int32_t *__restrict__ offs, int32_t *__restrict__ row_of_pair,
+    int32_t *__restrict__ pair_of_row, int32_t *__restrict__ tok_offs,
+    const float *__restrict__ probs, float coeff, int mode, float *__restrict__ loss,
+    float *__restrict__ F_out, float *__restrict__ P_out, int Nl,
+    const int32_t *__restrict__ token_model, int32_t *__restrict__ model_tokens) {
+  static_assert(GP_WAVES * 64 == 1024, "the auxiliary-loss block code assumes 1024 threads");
+  group_pairs_block(idx, T * k, N, k, counts, counts_out, first_counts, offs, row_of_pair, pair_of_row);
+  if (threadIdx.x == 0) { tok_offs[0] = 0; tok_offs[1] = T; }
+  __syncthreads();
+  aux_loss_block(probs, idx, T, N, k, coeff, mode, loss, F_out, P_out, Nl, token_model, model_tokens);
+}
+
+hipError_t launch_group_pairs_aux(const int32_t *idx, int T, int N, int k, int32_t *counts,
+                                  int32_t *counts_out, int32_t *first_counts, int32_t *offs,
+                                  int32_t *row_of_pair, int32_t *pair_of_row, int32_t *tok_offs,
+                                  const float *probs, float coeff, int mode, float *loss, float *F,
+                                  float *P, int Nl, const int32_t *token_model,
+                                  int32_t *model_tokens, hipStream_t st) {
+  hipLaunchKernelGGL(group_pairs_aux_kernel, dim3(1), dim3(GP_WAVES * 64), 0, st, idx, T, N, k,
+                     counts, counts_out, first_counts, offs, row_of_pair, pair_of_row, tok_offs,
+                     probs, coeff, mode, loss, F, P, Nl, token_model, model_tokens);
+  return hipGetLastError();
 }
 
 // d loss / d probs[t, e] = coeff * N * F_e / T   (F is piecewise constant)
