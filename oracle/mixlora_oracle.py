@@ -35,6 +35,10 @@ first-choice expert ("top1", as printed) or all k choices divided by k
   experts only; multi_forward / multi_backward are that definition, adapter by
   adapter, on top of the single-adapter functions.
 
+* Plain LoRA linear (Eq. 1 with the scale of the hyper-parameter table), which the method puts
+  on the attention projections (Section 3.2): y = x W^T + s (x A^T) B^T, W frozen;
+  lora_linear_forward / lora_linear_backward, pinned in tests/test_oracle_linear_pins.py.
+
 Pinned by tests/test_oracle_pins.py (dense-FFN special case, k = N mixture,
 merged-weight identity, brute-force loops, closed-form auxiliary losses,
 finite differences, autograd of an independent formulation) and, for the
@@ -257,3 +261,21 @@ def multi_backward(x, token_model, Ws, k, lora_scale, dy, d_aux=None, aux_coeff=
         dz[tok] = bw["dz"]
         grads.append({"d" + n: bw["d" + n] for n in names})
     return dict(dx=dx, dz=dz, grads=grads)
+
+
+def lora_linear_forward(x, W, A, B, lora_scale):
+    """Eq. 1 with scale: y = x W^T + s (x A^T) B^T.  x [T,d_in], W [d_out,d_in] (frozen),
+    A [r,d_in], B [d_out,r].  Returns y [T,d_out]."""
+    x, W, A, B = _f64(x), _f64(W), _f64(A), _f64(B)
+    return x @ W.T + lora_scale * ((x @ A.T) @ B.T)
+
+
+def lora_linear_backward(x, W, A, B, lora_scale, dy):
+    """Gradients of <y, dy> with W frozen: dx [T,d_in], dA [r,d_in], dB [d_out,r]."""
+    x, W, A, B, dy = _f64(x), _f64(W), _f64(A), _f64(B), _f64(dy)
+    p = x @ A.T                      # [T,r]
+    v = dy @ B                       # [T,r]
+    dx = dy @ W + lora_scale * (v @ A)
+    dA = lora_scale * (v.T @ x)
+    dB = lora_scale * (dy.T @ p)
+    return dict(dx=dx, dA=dA, dB=dB)
