@@ -83,6 +83,76 @@ def cpu_baseline(cfg, host, n_tokens):
                       f"{reps} runs in {dt:.1f} s"}
 
 
+LINEAR_WORKLOADS = {
+    # a q/k/v/o projection of the LLaMA-2-7B shape with its rank-16 adapter (alpha 32)
+    "llama2_7b_attn_proj": dict(T=4096, d_in=4096, d_out=4096, r=16, lora_scale=2.0, seed_index=8),
+}
+
+
+def bench_linear(args):
+    """Plain LoRA linear (the attention-projection form): forward + backward per step."""
+    import numpy as np
+    import torch
+    from paper_2404_15159_amd import binding as B
+    from paper_2404_15159_amd import synth
+    from paper_2404_15159_amd.runner import LoraLinear
+
+    w = LINEAR_WORKLOADS[args.workload]
+    T, di, dn, r, s = w["T"], w["d_in"], w["d_out"], w["r"], w["lora_scale"]
+    host = synth.make_linear_inputs(T, di, dn, r, "bf16", seed=synth.SEED_BASE + w["seed_index"])
+    m = LoraLinear(T, di, dn, r, s, "bf16", host)
+
+    def step():
+        m.forward()
+        m.backward()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) / args.steps * 1e3
+    B.mixlora_profile_begin(args.steps * 4)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    k_ms, k_launches, k_flops_exec = B.mixlora_profile_end()
+    unit = 2.0 * T * di * dn
+    step_flops = 2 * unit + T * 6.0 * r * (di + dn) * 1.5   # two frozen products + rank-r work
+    avg_launch_s = k_ms / 1e3 / max(k_launches, 1)
+    achieved = (2 * unit / max(k_launches / args.steps, 1e-9)) / avg_launch_s if k_launches else 0.0
+    out = {
+        "metric": "LoRA linear fwd+bwd tokens/sec on 1 MI355X + % bf16 MFMA peak",
+        "value": T / (ms_per_step / 1e3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: T={T} d_in={di} d_out={dn} r={r} bf16 forward+backward",
+                   "algorithmic_tflop_per_step": step_flops / 1e12,
+                   "mfma_frac_whole_step": step_flops / (ms_per_step / 1e3) / MFMA_BF16_PEAK},
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_dl_kernel<256,256,64,2 stages,8 waves>",
+                     "achieved": achieved / 1e12, "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_BF16_PEAK, "launches_per_step": k_launches / args.steps,
+                     "avg_launch_ms": avg_launch_s * 1e3, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import mixlora_oracle as orc
+        h64 = {n: np.asarray(v, dtype=np.float64) for n, v in host.items()}
+        reps, t0 = 0, time.perf_counter()
+        while True:
+            orc.lora_linear_forward(h64["x"], h64["W"], h64["A"], h64["B"], s)
+            orc.lora_linear_backward(h64["x"], h64["W"], h64["A"], h64["B"], s, h64["dy"])
+            reps += 1
+            dt = time.perf_counter() - t0
+            if dt >= 10.0 or reps >= 50:
+                break
+        out["cpu_baseline"] = {"value": reps * T / dt, "unit": "tokens/s", "cores": os.cpu_count() or 1,
+                               "kind": "oracle",
+                               "sample": f"all {T} tokens, forward+backward, float64 NumPy, {reps} runs in {dt:.1f} s"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -110,6 +180,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     B.load()   # raises if the HIP library is missing: there is no fallback path
+    if args.workload in LINEAR_WORKLOADS:
+        bench_linear(args)
+        return
     cfg = synth.CONFIGS[args.workload]
     if cfg.dtype != "bf16":
         print("bench.py: the timed workloads are the bf16 ones", file=sys.stderr)

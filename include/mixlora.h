@@ -181,6 +181,37 @@ MIXLORA_API int mixlora_transpose(const void *in, void *out, int32_t rows, int32
 MIXLORA_API int mixlora_profile_begin(int32_t max_launches);
 MIXLORA_API int mixlora_profile_end(double *ms_total, int32_t *launches, double *flops_total);
 
+/* ---- Plain LoRA linear (Eq. 1 with the scale alpha / r; the form the method puts on the
+ * attention projections, Section 3.2):  y = x W^T + s (x A^T) B^T,  W frozen ----------------
+ * Shapes (row-major, dtype = dims.dtype, device pointers, 16-byte aligned):
+ *   x [T, d_in], W [d_out, d_in], A [r, d_in], B [d_out, r], y / dy [T, d_out], dx [T, d_in];
+ *   dA [r, d_in], dB [d_out, r] float32, overwritten.
+ * Limits: r % 8 == 0, 8 <= r <= 64, d_in % 8 == 0, d_out % 8 == 0, T < 2^24.
+ * The workspace is the caller's; forward saves x A^T in it for the backward. */
+typedef struct {
+  int32_t T, d_in, d_out, r;
+  float lora_scale;
+  int32_t dtype;
+} mixlora_linear_dims;
+
+/* Bytes of workspace (0 for invalid dims). */
+MIXLORA_API size_t mixlora_lora_linear_workspace_bytes(const mixlora_linear_dims *dims,
+                                                       int for_backward);
+
+/* y = x W^T + s (x A^T) B^T.  Errors: E_NULL, E_SHAPE, E_DTYPE, E_ALIGN, E_WORKSPACE, E_HIP. */
+MIXLORA_API int mixlora_lora_linear_forward(const mixlora_linear_dims *dims, const void *W,
+                                            const void *A, const void *B, const void *x, void *y,
+                                            void *workspace, size_t workspace_bytes, void *stream);
+
+/* Gradients of <y, dy> on the workspace the forward filled: dx = dy W + s (dy B) A,
+ * dA = s (dy B)^T x, dB = s dy^T (x A^T).  W_T [d_in, d_out] is an optional pre-transposed copy
+ * of W (mixlora_transpose); when NULL the transpose is made per call inside the workspace. */
+MIXLORA_API int mixlora_lora_linear_backward(const mixlora_linear_dims *dims, const void *W,
+                                             const void *W_T, const void *A, const void *B,
+                                             const void *x, const void *dy, void *workspace,
+                                             size_t workspace_bytes, void *dx, float *dA,
+                                             float *dB, void *stream);
+
 /* Measurement aid: TFLOP/s that a register-only loop of bf16 MFMA 32x32x16 on pseudo-random
  * operands sustains on the current device at waves_per_simd (1 or 2) wavefronts per SIMD - the
  * practical ceiling of the matrix pipe on a power-limited part, beside the published peak.

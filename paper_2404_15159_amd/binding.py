@@ -23,7 +23,8 @@ EXPORTS = ("mixlora_workspace_bytes", "mixlora_ffn_forward", "mixlora_ffn_backwa
            "mixlora_aux_loss", "mixlora_transpose", "mixlora_version",
            "mixlora_profile_begin", "mixlora_profile_end",
            "mixlora_multi_workspace_bytes", "mixlora_multi_forward", "mixlora_multi_backward",
-           "mixlora_mfma_probe")
+           "mixlora_mfma_probe", "mixlora_lora_linear_workspace_bytes",
+           "mixlora_lora_linear_forward", "mixlora_lora_linear_backward")
 
 
 class Dims(C.Structure):
@@ -43,6 +44,11 @@ class Weights(C.Structure):
 
 class Grads(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in GRAD_FIELDS]
+
+
+class LinearDims(C.Structure):
+    _fields_ = [("T", C.c_int32), ("d_in", C.c_int32), ("d_out", C.c_int32), ("r", C.c_int32),
+                ("lora_scale", C.c_float), ("dtype", C.c_int32)]
 
 
 class Multi(C.Structure):
@@ -94,6 +100,13 @@ def load():
     lib.mixlora_multi_backward.restype = C.c_int
     lib.mixlora_multi_backward.argtypes = [C.POINTER(Dims), C.POINTER(Multi), C.POINTER(Weights),
                                            vp, vp, vp, sz, vp, C.POINTER(Grads), vp]
+    lib.mixlora_lora_linear_workspace_bytes.restype = sz
+    lib.mixlora_lora_linear_workspace_bytes.argtypes = [C.POINTER(LinearDims), C.c_int]
+    lib.mixlora_lora_linear_forward.restype = C.c_int
+    lib.mixlora_lora_linear_forward.argtypes = [C.POINTER(LinearDims), vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.mixlora_lora_linear_backward.restype = C.c_int
+    lib.mixlora_lora_linear_backward.argtypes = [C.POINTER(LinearDims), vp, vp, vp, vp, vp, vp, vp,
+                                                 sz, vp, vp, vp, vp]
     lib.mixlora_mfma_probe.restype = C.c_int
     lib.mixlora_mfma_probe.argtypes = [vp, sz, i32, i32, C.POINTER(C.c_double), vp]
     _lib = lib
@@ -211,6 +224,28 @@ def mixlora_transpose(src, dst, rows: int, cols: int, dtype: int, stream=None) -
 
 def mixlora_version() -> int:
     return int(load().mixlora_version())
+
+
+def mixlora_lora_linear_workspace_bytes(dims: LinearDims, for_backward: bool) -> int:
+    return int(load().mixlora_lora_linear_workspace_bytes(C.byref(dims), int(bool(for_backward))))
+
+
+def mixlora_lora_linear_forward(dims: LinearDims, W, A, B_, x, y, workspace, workspace_bytes: int,
+                                stream=None) -> None:
+    rc = load().mixlora_lora_linear_forward(C.byref(dims), _ptr(W), _ptr(A), _ptr(B_), _ptr(x),
+                                            _ptr(y), _ptr(workspace), workspace_bytes,
+                                            _stream(stream))
+    if rc != 0:
+        raise MixLoraError("mixlora_lora_linear_forward", rc)
+
+
+def mixlora_lora_linear_backward(dims: LinearDims, W, W_T, A, B_, x, dy, workspace,
+                                 workspace_bytes: int, dx, dA, dB, stream=None) -> None:
+    rc = load().mixlora_lora_linear_backward(C.byref(dims), _ptr(W), _ptr(W_T), _ptr(A), _ptr(B_),
+                                             _ptr(x), _ptr(dy), _ptr(workspace), workspace_bytes,
+                                             _ptr(dx), _ptr(dA), _ptr(dB), _stream(stream))
+    if rc != 0:
+        raise MixLoraError("mixlora_lora_linear_backward", rc)
 
 
 def mixlora_mfma_probe(sink, sink_bytes: int, waves_per_simd: int, iters: int, stream=None) -> float:

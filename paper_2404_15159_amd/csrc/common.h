@@ -159,6 +159,10 @@ hipError_t launch_scatter_blocks(int dtype, const PairCtx &pc, const float *src,
 hipError_t launch_gather_small(const PairCtx &pc, const float *src, int by_token, int weighted,
                                float *small_grp, hipStream_t st);
 
+// io[t, c] += s * sum_q P[t, q] * Wt[c, q]   (io [T,C] storage dtype, P [T,r] f32, Wt [C,r])
+hipError_t launch_lowrank_add(int dtype, void *io, const float *P, const void *Wt, int T, int C,
+                              int r, float s, hipStream_t st);
+
 // out[i] = sum_{s<S} part[s][i], i < n, fixed order (closing step of a split-K GEMM)
 hipError_t launch_splitk_reduce(int dtype, const float *part, int S, int64_t n, void *out,
                                 hipStream_t st);

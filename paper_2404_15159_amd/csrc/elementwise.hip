@@ -347,6 +347,79 @@ hipError_t launch_gather_small(const PairCtx &pc, const float *src, int by_token
   return hipGetLastError();
 }
 
+// Rank-r update of a GEMM result (Eq. 1):  io[t, c] += s * sum_q P[t, q] * Wt[c, q]
+// io [T, C] storage dtype (in place), P [T, r] float32, Wt [C, r] storage dtype.  A thread owns 8
+// columns of LRA_ROWS consecutive rows; its 8 rows of Wt stay in registers 16 rank entries at a time.
+constexpr int LRA_ROWS = 4;
+
+template <typename E>
+__global__ __launch_bounds__(256) void lowrank_add_kernel(E *__restrict__ io,
+                                                          const float *__restrict__ P,
+                                                          const E *__restrict__ Wt, int T, int C,
+                                                          int r, float s) {
+  const int cv = C / 8;                                    // 8-column chunks per row
+  const int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int chunk = (int)(id % cv);
+  const int t0 = (int)(id / cv) * LRA_ROWS;
+  if (t0 >= T) return;
+  const int c0 = chunk * 8;
+  // the rows to update are requested first, so their latency overlaps the rank-r arithmetic
+  Vec8<E> cur[LRA_ROWS];
+#pragma unroll
+  for (int i = 0; i < LRA_ROWS; i++) {
+    const int t = t0 + i < T ? t0 + i : T - 1;
+    cur[i].load(io + (int64_t)t * C + c0);
+  }
+  float acc[LRA_ROWS][8];
+#pragma unroll
+  for (int i = 0; i < LRA_ROWS; i++)
+#pragma unroll
+    for (int j = 0; j < 8; j++) acc[i][j] = 0.f;
+  for (int q0 = 0; q0 < r; q0 += 8) {
+    float wv[8][8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+      Vec8<E> v;
+      v.load(Wt + (int64_t)(c0 + j) * r + q0);
+#pragma unroll
+      for (int q = 0; q < 8; q++) wv[j][q] = v.get(q);
+    }
+#pragma unroll
+    for (int i = 0; i < LRA_ROWS; i++) {
+      const int t = t0 + i < T ? t0 + i : T - 1;
+      Vec8<float> pv;
+      pv.load(P + (int64_t)t * r + q0);
+#pragma unroll
+      for (int q = 0; q < 8; q++)
+#pragma unroll
+        for (int j = 0; j < 8; j++) acc[i][j] = fmaf(pv.get(q), wv[j][q], acc[i][j]);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < LRA_ROWS; i++) {
+    if (t0 + i < T) {
+      Vec8<E> v = cur[i];
+#pragma unroll
+      for (int j = 0; j < 8; j++) v.set(j, v.get(j) + s * acc[i][j]);
+      v.store(io + (int64_t)(t0 + i) * C + c0);
+    }
+  }
+}
+
+hipError_t launch_lowrank_add(int dtype, void *io, const float *P, const void *Wt, int T, int C,
+                              int r, float s, hipStream_t st) {
+  if (C % 8 || r % 8) return hipErrorInvalidValue;
+  const int64_t n = (int64_t)((T + LRA_ROWS - 1) / LRA_ROWS) * (C / 8);
+  const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+  if (dtype == MIXLORA_BF16)
+    hipLaunchKernelGGL(lowrank_add_kernel<bf16_t>, grid, block, 0, st, (bf16_t *)io, P,
+                       (const bf16_t *)Wt, T, C, r, s);
+  else
+    hipLaunchKernelGGL(lowrank_add_kernel<float>, grid, block, 0, st, (float *)io, P,
+                       (const float *)Wt, T, C, r, s);
+  return hipGetLastError();
+}
+
 // out[i] = sum over s < S of part[s][i]  (fixed order): closes a GEMM whose K range was split
 // over several workgroups because its output alone has too few tiles to cover the chip
 template <typename E>

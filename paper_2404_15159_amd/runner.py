@@ -100,3 +100,43 @@ class MixLoraFFN:
             for n, v in self.g.items():
                 out[n] = v.cpu().numpy()
         return out
+
+
+class LoraLinear:
+    """One plain LoRA linear problem (the attention-projection form) on cuda:0."""
+
+    def __init__(self, T: int, d_in: int, d_out: int, r: int, lora_scale: float, dtype: str,
+                 host: Dict[str, np.ndarray], pretransposed: bool = True, device: str = "cuda:0"):
+        B.load()
+        self.dev = torch.device(device)
+        td = _tdtype(dtype)
+        code = B.BF16 if dtype == "bf16" else B.F32
+        self.dims = B.LinearDims(T, d_in, d_out, r, lora_scale, code)
+        self.t = {n: torch.from_numpy(np.ascontiguousarray(host[n])).to(self.dev).to(td).contiguous()
+                  for n in ("x", "W", "A", "B", "dy")}
+        self.W_T = None
+        if pretransposed:
+            self.W_T = torch.empty((d_in, d_out), dtype=td, device=self.dev)
+            B.mixlora_transpose(self.t["W"], self.W_T, d_out, d_in, code)
+        self.ws_bytes = B.mixlora_lora_linear_workspace_bytes(self.dims, True)
+        if self.ws_bytes == 0:
+            raise ValueError("dims rejected by mixlora_lora_linear_workspace_bytes")
+        self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.dev)
+        self.y = torch.empty((T, d_out), dtype=td, device=self.dev)
+        self.dx = torch.empty((T, d_in), dtype=td, device=self.dev)
+        self.dA = torch.empty((r, d_in), dtype=torch.float32, device=self.dev)
+        self.dB = torch.empty((d_out, r), dtype=torch.float32, device=self.dev)
+
+    def forward(self, stream=None) -> None:
+        B.mixlora_lora_linear_forward(self.dims, self.t["W"], self.t["A"], self.t["B"], self.t["x"],
+                                      self.y, self.workspace, self.ws_bytes, stream)
+
+    def backward(self, stream=None) -> None:
+        B.mixlora_lora_linear_backward(self.dims, self.t["W"], self.W_T, self.t["A"], self.t["B"],
+                                       self.t["x"], self.t["dy"], self.workspace, self.ws_bytes,
+                                       self.dx, self.dA, self.dB, stream)
+
+    def results(self) -> Dict[str, np.ndarray]:
+        torch.cuda.synchronize()
+        return dict(y=self.y.float().cpu().numpy(), dx=self.dx.float().cpu().numpy(),
+                    dA=self.dA.cpu().numpy(), dB=self.dB.cpu().numpy())

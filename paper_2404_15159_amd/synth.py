@@ -240,3 +240,17 @@ def split_adapters(cfg: Config, host: Dict[str, np.ndarray]):
             Wm[n] = host[n][m * N:(m + 1) * N]
         out.append(Wm)
     return out
+
+
+def make_linear_inputs(T: int, d_in: int, d_out: int, r: int, dtype: str, seed: int,
+                       b_std: float = 0.01) -> Dict[str, np.ndarray]:
+    """Tensors of one plain LoRA linear (an attention projection with its adapter): x [T,d_in],
+    W [d_out,d_in] ~ N(0,0.02^2), A [r,d_in] ~ U(+-1/sqrt(d_in)), B [d_out,r] ~ N(0,b_std^2),
+    dy [T,d_out]; same generator and rounding as make_inputs."""
+    out = {}
+    out["x"] = _store((normal(seed, 0, T * d_in)).reshape(T, d_in), dtype)
+    out["W"] = _store((normal(seed, 1, d_out * d_in) * 0.02).reshape(d_out, d_in), dtype)
+    out["A"] = _store(((uniform01(seed, 4, r * d_in) * 2.0 - 1.0) / math.sqrt(d_in)).reshape(r, d_in), dtype)
+    out["B"] = _store((normal(seed, 5, d_out * r) * b_std).reshape(d_out, r), dtype)
+    out["dy"] = _store((normal(seed, 11, T * d_out)).reshape(T, d_out), dtype)
+    return out
