@@ -148,6 +148,44 @@ def test_multi_adapter_argument_errors(lib):
     assert ei.value.code == -5
 
 
+def test_lora_linear_argument_errors(lib):
+    def ld(**kw):
+        a = dict(T=4096, d_in=4096, d_out=4096, r=16, lora_scale=2.0, dtype=B.BF16)
+        a.update(kw)
+        return B.LinearDims(a["T"], a["d_in"], a["d_out"], a["r"], a["lora_scale"], a["dtype"])
+
+    fwd, bwd = (B.mixlora_lora_linear_workspace_bytes(ld(), f) for f in (False, True))
+    assert 4096 * 16 * 4 <= fwd < bwd
+    for bad in (dict(T=0), dict(r=4), dict(r=72), dict(r=12), dict(d_in=4100), dict(d_out=4), dict(dtype=3)):
+        assert B.mixlora_lora_linear_workspace_bytes(ld(**bad), True) == 0, bad
+
+    def fcode(d_, **kw):
+        a = dict(W=FAKE, A=FAKE, B_=FAKE, x=FAKE, y=FAKE, workspace=FAKE, workspace_bytes=1 << 40)
+        a.update(kw)
+        with pytest.raises(B.MixLoraError) as ei:
+            B.mixlora_lora_linear_forward(d_, stream=0, **a)
+        return ei.value.code
+
+    assert fcode(ld(r=20)) == -2
+    assert fcode(ld(dtype=9)) == -3
+    assert fcode(ld(), A=None) == -1
+    assert fcode(ld(), x=FAKE + 4) == -4
+    assert fcode(ld(), workspace_bytes=16) == -5
+
+    def bcode(d_, **kw):
+        a = dict(W=FAKE, W_T=None, A=FAKE, B_=FAKE, x=FAKE, dy=FAKE, workspace=FAKE,
+                 workspace_bytes=1 << 40, dx=FAKE, dA=FAKE, dB=FAKE)
+        a.update(kw)
+        with pytest.raises(B.MixLoraError) as ei:
+            B.mixlora_lora_linear_backward(d_, stream=0, **a)
+        return ei.value.code
+
+    assert bcode(ld(d_in=12)) == -2
+    assert bcode(ld(), dB=None) == -1
+    assert bcode(ld(), W_T=FAKE + 2) == -4
+    assert bcode(ld(), workspace_bytes=fwd) == -5
+
+
 def test_mfma_probe_argument_errors(lib):
     for kw, code in ((dict(sink=None), -1), (dict(waves_per_simd=0), -2), (dict(waves_per_simd=3), -2),
                      (dict(iters=0), -2)):
