@@ -65,6 +65,10 @@ SMALL_CASES = [
     ("bf16_top1", BASE_BF16, dict(T=200, d=128, d_ff=384, N=8, k=1, r=16)),
     ("bf16_one_expert", BASE_BF16, dict(T=70, d=64, d_ff=136, N=1, k=1, r=8, alpha=16.0)),
     ("bf16_one_token", BASE_BF16, dict(T=1, d=64, d_ff=128, N=8, k=2, r=16)),
+    # the largest expert count and rank-column total the library accepts, and a wide top-k
+    ("bf16_64_experts", BASE_BF16, dict(T=640, d=128, d_ff=256, N=64, k=4, r=8, alpha=16.0)),
+    ("bf16_top8_of_16", BASE_BF16, dict(T=200, d=128, d_ff=384, N=16, k=8, r=16)),
+    ("f32_64_experts", BASE_F32, dict(T=320, d=64, d_ff=136, N=64, k=2, r=8)),
     ("bf16_wide_d", BASE_BF16, dict(T=300, d=1024, d_ff=520, N=8, k=2, r=16)),
     # few tokens: narrow weight-streaming GEMM tiles and the K-split down projection
     ("bf16_decode_64", BASE_BF16, dict(T=64, d=256, d_ff=1024, N=8, k=2, r=16)),
