@@ -160,6 +160,7 @@ hipError_t launch_route_logits(const float *Z, int ldz, int T, int N, int k, flo
 // again and gives each pair the row  base[expert] + (number of earlier pairs of that expert),
 // i.e. a stable counting sort: rows of one expert are in ascending pair order.
 constexpr int GP_WAVES = 16;
+constexpr int GP_CACHE = 16;   // 64-pair steps of a wave's range kept in registers
 
 __device__ __forceinline__ void group_pairs_block(
     const int32_t *__restrict__ idx, int nP, int N, int k, int32_t *__restrict__ counts,
@@ -173,16 +174,29 @@ __device__ __forceinline__ void group_pairs_block(
   const int per = (((nP + GP_WAVES - 1) / GP_WAVES) + 63) & ~63;
   const int lo = wave * per;
   const int hi = lo + per < nP ? lo + per : nP;
+  // the first GP_CACHE 64-pair steps of the range are loaded up front (all loads in flight at
+  // once) and kept in registers for both passes; longer ranges read the rest as they go
+  int ec[GP_CACHE];
+#pragma unroll
+  for (int c = 0; c < GP_CACHE; c++) {
+    const int p = lo + c * 64 + lane;
+    ec[c] = p < hi ? idx[p] : -1;
+  }
   int cnt = 0, fcnt = 0;
-  for (int p0 = lo; p0 < hi; p0 += 64) {
-    const int p = p0 + lane;
-    const int e = p < hi ? idx[p] : -1;
+  auto count_step = [&](int e, int p) {
     const bool is_first = (p % k) == 0;
     for (int n = 0; n < N; n++) {
       const unsigned long long b = __ballot(e == n);
       const unsigned long long bf = __ballot(e == n && is_first);
       if (lane == n) { cnt += __popcll(b); fcnt += __popcll(bf); }
     }
+  };
+#pragma unroll
+  for (int c = 0; c < GP_CACHE; c++)
+    if (lo + c * 64 < hi) count_step(ec[c], lo + c * 64 + lane);
+  for (int p0 = lo + GP_CACHE * 64; p0 < hi; p0 += 64) {
+    const int p = p0 + lane;
+    count_step(p < hi ? idx[p] : -1, p);
   }
   tot[wave][lane] = cnt;
   first[wave][lane] = fcnt;
@@ -212,9 +226,7 @@ __device__ __forceinline__ void group_pairs_block(
   __syncthreads();
   int running = base[wave][lane];   // lane n: next free row of expert n for this wave
   const unsigned long long lt = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-  for (int p0 = lo; p0 < hi; p0 += 64) {
-    const int p = p0 + lane;
-    const int e = p < hi ? idx[p] : -1;
+  auto place_step = [&](int e, int p) {
     unsigned long long mine = 0;
     int add = 0;
     for (int n = 0; n < N; n++) {
@@ -229,6 +241,13 @@ __device__ __forceinline__ void group_pairs_block(
       pair_of_row[row] = p;
     }
     running += add;
+  };
+#pragma unroll
+  for (int c = 0; c < GP_CACHE; c++)
+    if (lo + c * 64 < hi) place_step(ec[c], lo + c * 64 + lane);
+  for (int p0 = lo + GP_CACHE * 64; p0 < hi; p0 += 64) {
+    const int p = p0 + lane;
+    place_step(p < hi ? idx[p] : -1, p);
   }
 }
 
@@ -284,8 +303,10 @@ __device__ __forceinline__ void aux_loss_block(const float *__restrict__ probs,
   const int G = 1024 / N;
   const int e = tid % N, g = tid / N;
   float s = 0.f;
-  if (g < G)
+  if (g < G) {
+#pragma unroll 8
     for (int t = g; t < T; t += G) s += probs[(int64_t)t * N + e];
+  }
   part[tid] = s;
   __syncthreads();
   if (tid < N) {
