@@ -212,6 +212,22 @@ MIXLORA_API int mixlora_lora_linear_backward(const mixlora_linear_dims *dims, co
                                              size_t workspace_bytes, void *dx, float *dA,
                                              float *dB, void *stream);
 
+/* ---- AdamW step on adapter parameters (the optimiser named in the paper's hyper-parameter
+ * table; decoupled weight decay):
+ *   p <- p (1 - lr wd);  m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2;
+ *   p <- p - lr (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps)
+ * param, grad, m, v: device float32 [n] (param, m, v updated in place); lowp: optional device
+ * copy of the parameters in lowp_dtype (bf16 or f32), refreshed from the new values, or NULL.
+ * step t is 1-based.  Errors: E_NULL, E_DTYPE, E_SHAPE (n < 1, step < 1, betas outside [0,1),
+ * eps <= 0), E_HIP. */
+typedef struct {
+  float lr, beta1, beta2, eps, weight_decay;
+  int32_t step;
+} mixlora_adamw;
+MIXLORA_API int mixlora_adamw_step(const mixlora_adamw *h, int64_t n, float *param,
+                                   const float *grad, float *m, float *v, void *lowp,
+                                   int32_t lowp_dtype, void *stream);
+
 /* Measurement aid: TFLOP/s that a register-only loop of bf16 MFMA 32x32x16 on pseudo-random
  * operands sustains on the current device at waves_per_simd (1 or 2) wavefronts per SIMD - the
  * practical ceiling of the matrix pipe on a power-limited part, beside the published peak.

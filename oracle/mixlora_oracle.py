@@ -39,6 +39,9 @@ first-choice expert ("top1", as printed) or all k choices divided by k
   on the attention projections (Section 3.2): y = x W^T + s (x A^T) B^T, W frozen;
   lora_linear_forward / lora_linear_backward, pinned in tests/test_oracle_linear_pins.py.
 
+* AdamW (the optimiser of the appendix hyper-parameter table; decoupled weight decay):
+  adamw_step, pinned against torch.optim.AdamW in tests/test_oracle_linear_pins.py.
+
 Pinned by tests/test_oracle_pins.py (dense-FFN special case, k = N mixture,
 merged-weight identity, brute-force loops, closed-form auxiliary losses,
 finite differences, autograd of an independent formulation) and, for the
@@ -279,3 +282,15 @@ def lora_linear_backward(x, W, A, B, lora_scale, dy):
     dA = lora_scale * (v.T @ x)
     dB = lora_scale * (dy.T @ p)
     return dict(dx=dx, dA=dA, dB=dB)
+
+
+def adamw_step(p, g, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01):
+    """One AdamW update (decoupled weight decay); step is 1-based.  Returns (p, m, v)."""
+    p, g, m, v = _f64(p), _f64(g), _f64(m), _f64(v)
+    p = p * (1.0 - lr * weight_decay)
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    mhat = m / (1.0 - beta1 ** step)
+    vhat = v / (1.0 - beta2 ** step)
+    p = p - lr * mhat / (np.sqrt(vhat) + eps)
+    return p, m, v

@@ -24,7 +24,7 @@ EXPORTS = ("mixlora_workspace_bytes", "mixlora_ffn_forward", "mixlora_ffn_backwa
            "mixlora_profile_begin", "mixlora_profile_end",
            "mixlora_multi_workspace_bytes", "mixlora_multi_forward", "mixlora_multi_backward",
            "mixlora_mfma_probe", "mixlora_lora_linear_workspace_bytes",
-           "mixlora_lora_linear_forward", "mixlora_lora_linear_backward")
+           "mixlora_lora_linear_forward", "mixlora_lora_linear_backward", "mixlora_adamw_step")
 
 
 class Dims(C.Structure):
@@ -49,6 +49,11 @@ class Grads(C.Structure):
 class LinearDims(C.Structure):
     _fields_ = [("T", C.c_int32), ("d_in", C.c_int32), ("d_out", C.c_int32), ("r", C.c_int32),
                 ("lora_scale", C.c_float), ("dtype", C.c_int32)]
+
+
+class AdamW(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float), ("step", C.c_int32)]
 
 
 class Multi(C.Structure):
@@ -107,6 +112,8 @@ def load():
     lib.mixlora_lora_linear_backward.restype = C.c_int
     lib.mixlora_lora_linear_backward.argtypes = [C.POINTER(LinearDims), vp, vp, vp, vp, vp, vp, vp,
                                                  sz, vp, vp, vp, vp]
+    lib.mixlora_adamw_step.restype = C.c_int
+    lib.mixlora_adamw_step.argtypes = [C.POINTER(AdamW), C.c_int64, vp, vp, vp, vp, vp, i32, vp]
     lib.mixlora_mfma_probe.restype = C.c_int
     lib.mixlora_mfma_probe.argtypes = [vp, sz, i32, i32, C.POINTER(C.c_double), vp]
     _lib = lib
@@ -246,6 +253,14 @@ def mixlora_lora_linear_backward(dims: LinearDims, W, W_T, A, B_, x, dy, workspa
                                              _ptr(dx), _ptr(dA), _ptr(dB), _stream(stream))
     if rc != 0:
         raise MixLoraError("mixlora_lora_linear_backward", rc)
+
+
+def mixlora_adamw_step(h: AdamW, n: int, param, grad, m, v, lowp=None, lowp_dtype: int = BF16,
+                       stream=None) -> None:
+    rc = load().mixlora_adamw_step(C.byref(h), n, _ptr(param), _ptr(grad), _ptr(m), _ptr(v),
+                                   _ptr(lowp), lowp_dtype, _stream(stream))
+    if rc != 0:
+        raise MixLoraError("mixlora_adamw_step", rc)
 
 
 def mixlora_mfma_probe(sink, sink_bytes: int, waves_per_simd: int, iters: int, stream=None) -> float:

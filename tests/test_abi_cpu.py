@@ -186,6 +186,24 @@ def test_lora_linear_argument_errors(lib):
     assert bcode(ld(), workspace_bytes=fwd) == -5
 
 
+def test_adamw_argument_errors(lib):
+    ok = dict(lr=2e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, step=1)
+
+    def code(n=16, param=FAKE, lowp=None, lowp_dtype=B.BF16, **kw):
+        a = dict(ok); a.update(kw)
+        h = B.AdamW(a["lr"], a["beta1"], a["beta2"], a["eps"], a["weight_decay"], a["step"])
+        with pytest.raises(B.MixLoraError) as ei:
+            B.mixlora_adamw_step(h, n, param, FAKE, FAKE, FAKE, lowp, lowp_dtype, stream=0)
+        return ei.value.code
+
+    assert code(param=None) == -1
+    assert code(n=0) == -2
+    assert code(step=0) == -2
+    assert code(beta1=1.0) == -2
+    assert code(eps=0.0) == -2
+    assert code(lowp=FAKE, lowp_dtype=5) == -3
+
+
 def test_mfma_probe_argument_errors(lib):
     for kw, code in ((dict(sink=None), -1), (dict(waves_per_simd=0), -2), (dict(waves_per_simd=3), -2),
                      (dict(iters=0), -2)):

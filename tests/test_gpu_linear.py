@@ -60,3 +60,32 @@ def test_lora_linear_full_size_attention_projection():
     g = orc.lora_linear_backward(host["x"], host["W"], host["A"], host["B"], s, host["dy"])
     for n in ("dx", "dA", "dB"):
         pu.assert_close(n, res[n], g[n], pu.TOL["bf16"])
+
+
+def test_adamw_step_matches_oracle():
+    """Three AdamW steps on 100003 parameters: float32 master values and moments against the
+    float64 oracle, and the bf16 copy equal to the rounded master values."""
+    import torch
+    from paper_2404_15159_amd import binding as B
+    n = 100003
+    rng = np.random.default_rng(21)
+    p0 = rng.standard_normal(n).astype(np.float32)
+    p = torch.from_numpy(p0.copy()).cuda()
+    m = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    v = torch.zeros_like(m)
+    low = torch.empty(n, dtype=torch.bfloat16, device="cuda:0")
+    rp, rm, rv = p0.astype(np.float64), np.zeros(n), np.zeros(n)
+    # the C struct carries the hyper-parameters as float32: the oracle gets the same values
+    lr, b1, b2, eps, wd = (float(np.float32(h)) for h in (2e-4, 0.9, 0.999, 1e-8, 0.01))
+    for t in range(1, 4):
+        g = (rng.standard_normal(n) * 0.3).astype(np.float32)
+        gd = torch.from_numpy(g).cuda()
+        B.mixlora_adamw_step(B.AdamW(lr, b1, b2, eps, wd, t), n, p, gd, m, v, low, B.BF16)
+        rp, rm, rv = orc.adamw_step(rp, g, rm, rv, t, lr, b1, b2, eps, wd)
+    torch.cuda.synchronize()
+    pu.assert_close("param", p.cpu().numpy(), rp, 1e-6)
+    pu.assert_close("m", m.cpu().numpy(), rm, 1e-6)
+    pu.assert_close("v", v.cpu().numpy(), rv, 1e-6)
+    assert torch.equal(low, p.to(torch.bfloat16))
+    # the update really moved the parameters by about lr per step
+    assert 1e-4 < np.abs(p.cpu().numpy() - p0).mean() < 1e-3

@@ -59,3 +59,20 @@ def test_backward_matches_finite_differences():
             up[i] += h; dn[i] -= h
             fd = (loss(**{name: up}) - loss(**{name: dn})) / (2 * h)
             assert abs(fd - g[key][i]) <= 1e-6 * max(1.0, abs(fd)), (name, i)
+
+
+def test_adamw_matches_torch_optimizer():
+    """Five steps of the oracle's AdamW against torch.optim.AdamW (an independent implementation)
+    with the paper's learning rate and a non-default weight decay."""
+    rng = np.random.default_rng(9)
+    p0 = rng.standard_normal(257)
+    grads = [rng.standard_normal(257) * (0.1 + i) for i in range(5)]
+    lr, b1, b2, eps, wd = 2e-4, 0.9, 0.999, 1e-8, 0.05
+    tp = torch.tensor(p0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.AdamW([tp], lr=lr, betas=(b1, b2), eps=eps, weight_decay=wd)
+    p, m, v = p0.copy(), np.zeros_like(p0), np.zeros_like(p0)
+    for t, g in enumerate(grads, start=1):
+        tp.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        p, m, v = orc.adamw_step(p, g, m, v, t, lr, b1, b2, eps, wd)
+        np.testing.assert_allclose(p, tp.detach().numpy(), rtol=1e-12, atol=1e-15)
