@@ -143,3 +143,36 @@ def test_aux_loss_is_per_adapter_statistic():
         Wm["W_router"] = wr
     fw = orc.multi_forward(x, tm, Ws, cfg.k, cfg.lora_scale, aux_coeff=0.01)
     np.testing.assert_allclose(fw["aux_loss"], 0.01 * cfg.N, rtol=1e-9)
+
+
+def test_per_adapter_aux_upstream_gradient():
+    """With dy = 0 and d_aux = the m-th unit vector the backward must return the gradient of
+    adapter m's auxiliary loss alone: zero for the other adapters, and for adapter m the central
+    finite difference of multi_forward's aux_loss[m] with respect to its router weights."""
+    cfg, host, tm = _case(M=2, T=48, seq_len=4)
+    Ws = synth.split_adapters(cfg, host)
+    Ws = [dict(W) for W in Ws]
+    for W in Ws:
+        W["W_router"] = W["W_router"] * 0.2      # soft routing: the loss varies smoothly
+    dy0 = np.zeros_like(host["dy"])
+    coeff = 0.7
+    for m in range(cfg.M):
+        d_aux = np.zeros(cfg.M); d_aux[m] = 1.0
+        bw = orc.multi_backward(host["x"], tm, Ws, cfg.k, cfg.lora_scale, dy0, d_aux, coeff)
+        other = 1 - m
+        for n in NAMES:
+            assert not bw["grads"][other]["d" + n].any(), n
+        g = bw["grads"][m]["dW_router"]
+        assert np.abs(g).max() > 0
+        rng = np.random.default_rng(m)
+        h = 1e-6
+        for _ in range(6):
+            i = (int(rng.integers(0, cfg.N)), int(rng.integers(0, cfg.d)))
+            vals = []
+            for sgn in (+1, -1):
+                Wp = [dict(W) for W in Ws]
+                wr = Wp[m]["W_router"].copy(); wr[i] += sgn * h
+                Wp[m]["W_router"] = wr
+                vals.append(orc.multi_forward(host["x"], tm, Wp, cfg.k, cfg.lora_scale, coeff)["aux_loss"][m])
+            fd = (vals[0] - vals[1]) / (2 * h)
+            assert abs(fd - g[i]) <= 1e-6 * max(1.0, abs(fd)) + 1e-9, (m, i, fd, g[i])
