@@ -99,8 +99,8 @@ Layout make_layout(const mixlora_dims &D) {
   size_t pr = group_outer_partial_floats(1, (int)N, (int)d);
   L.partial_floats = pf > pd ? pf : pd;
   if (pr > L.partial_floats) L.partial_floats = pr;
-  for (size_t v : {group_outer_mfma_partial_floats((int)N, (int)r, (int)f),
-                   group_outer_mfma_partial_floats((int)N, (int)r, (int)d),
+  for (size_t v : {GOM_MAX_JOBS * group_outer_mfma_partial_floats((int)N, (int)r, (int)f),
+                   GOM_MAX_JOBS * group_outer_mfma_partial_floats((int)N, (int)r, (int)d),
                    group_outer_mfma_partial_floats(1, (int)N, (int)d)})
     if (v > L.partial_floats) L.partial_floats = v;
   L.partials = take(L.partial_floats * 4);
@@ -446,14 +446,21 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
     GatherJob gj[6];
     for (int i = 0; i < 6; i++) gj[i] = GatherJob{fsrc[i], ws + L.small[i], by_token[i], weighted[i]};
     HIP_TRY(launch_gather_small_T(pc, gj, 6, L.ldT, st));
-    for (int i = 0; i < 6; i++) {
-      HIP_TRY(launch_group_outer_mfma(offs, N, kT, gat[i], k, ws + L.small[i], L.ldT, r, wide[i],
-                                      width[i], s, layout_qc[i], gout[i], part, pfl, st));
+    // the three sums over d_ff-wide operands in one launch, the three over gathered d-wide
+    // operands in another (same groups, width and gather mode within a launch)
+    const int wide_f[3] = {0, 1, 4}, wide_d[3] = {2, 3, 5};
+    GomJob jf[3], jd[3];
+    for (int j = 0; j < 3; j++) {
+      jf[j] = GomJob{ws + L.small[wide_f[j]], wide[wide_f[j]], gout[wide_f[j]], layout_qc[wide_f[j]]};
+      jd[j] = GomJob{ws + L.small[wide_d[j]], wide[wide_d[j]], gout[wide_d[j]], layout_qc[wide_d[j]]};
     }
+    HIP_TRY(launch_group_outer_mfma(offs, N, kT, nullptr, k, jf, 3, L.ldT, r, f, s, part, pfl, st));
+    HIP_TRY(launch_group_outer_mfma(offs, N, kT, pair_of_row, k, jd, 3, L.ldT, r, d, s, part, pfl, st));
     // dW_router = dz^T x
     HIP_TRY(launch_f32_to_bf16T((float *)(ws + L.dz), T, N, ws + L.dzT, L.ldTz, st));
-    HIP_TRY(launch_group_outer_mfma((int32_t *)(ws + L.tok_offs), 1, T, nullptr, 1, ws + L.dzT,
-                                    L.ldTz, N, x, d, 1.f, 1, grads->dW_router, part, pfl, st));
+    const GomJob jr{ws + L.dzT, x, grads->dW_router, 1};
+    HIP_TRY(launch_group_outer_mfma((int32_t *)(ws + L.tok_offs), 1, T, nullptr, 1, &jr, 1, L.ldTz, N,
+                                    d, 1.f, part, pfl, st));
   } else {
     for (int i = 0; i < 6; i++) {
       HIP_TRY(launch_gather_small(pc, fsrc[i], by_token[i], weighted[i], (float *)(ws + L.small[i]), st));

@@ -205,12 +205,20 @@ hipError_t launch_group_outer(int dtype, const int32_t *offs, int G, int max_row
 size_t group_outer_partial_floats(int G, int r, int C);
 
 // bf16 MFMA version: smallT is the transposed bf16 factor [r][ldT] (ldT % 8 == 0, readable up to
-// the next multiple of 16 rows past the last group), wide is bf16 with C % 8 == 0.
+// the next multiple of 16 rows past the last group), wide is bf16 with C % 8 == 0.  Up to
+// GOM_MAX_JOBS sums of the same shape (groups, C, gather mode, scale) go into one launch and
+// one reduction launch; partials must hold njobs * group_outer_mfma_partial_floats(G, r, C).
+struct GomJob {
+  const void *smallT;
+  const void *wide;
+  float *out;
+  int layout_qc;
+};
+constexpr int GOM_MAX_JOBS = 3;
 hipError_t launch_group_outer_mfma(const int32_t *offs, int G, int nrows,
-                                   const int32_t *pair_of_row, int k, const void *smallT, int ldT,
-                                   int r, const void *wide, int C, float scale, int layout_qc,
-                                   float *out, float *partials, size_t partial_floats,
-                                   hipStream_t st);
+                                   const int32_t *pair_of_row, int k, const GomJob *jobs, int njobs,
+                                   int ldT, int r, int C, float scale, float *partials,
+                                   size_t partial_floats, hipStream_t st);
 size_t group_outer_mfma_partial_floats(int G, int r, int C);
 // outT[q, row] = (w_row or 1) * src[(by_token ? t(row) : row), e(row)*r + q] as bf16, pitch ldT;
 // up to GATHER_MAX_JOBS factors in one launch

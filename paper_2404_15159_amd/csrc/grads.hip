@@ -73,10 +73,19 @@ __global__ __launch_bounds__(256) void group_outer_kernel(
   }
 }
 
-// out = scale * sum_split partial, written as [g][q][c] (layout_qc) or [g][c][q].
-__global__ void group_outer_reduce_kernel(const float *__restrict__ partial, int G, int r, int C,
-                                          int nsplit, float scale, int layout_qc,
-                                          float *__restrict__ out) {
+// out = scale * sum_split partial, written as [g][q][c] (layout_qc) or [g][c][q]; blockIdx.y picks
+// one of up to GOM_MAX_JOBS reductions of the same shape.
+struct ReduceBatch {
+  const float *partial[GOM_MAX_JOBS];
+  float *out[GOM_MAX_JOBS];
+  int layout_qc[GOM_MAX_JOBS];
+};
+
+__global__ void group_outer_reduce_kernel(ReduceBatch batch, int G, int r, int C, int nsplit,
+                                          float scale) {
+  const float *__restrict__ partial = batch.partial[blockIdx.y];
+  float *__restrict__ out = batch.out[blockIdx.y];
+  const int layout_qc = batch.layout_qc[blockIdx.y];
   const int64_t n = (int64_t)G * r * C;
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
@@ -133,8 +142,12 @@ hipError_t launch_group_outer(int dtype, const int32_t *offs, int G, int max_row
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int64_t n = (int64_t)G * r * C;
+  ReduceBatch rb{};
+  rb.partial[0] = partials;
+  rb.out[0] = out;
+  rb.layout_qc[0] = layout_qc;
   hipLaunchKernelGGL(group_outer_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
-                     st, partials, G, r, C, nsplit, scale, layout_qc, out);
+                     st, rb, G, r, C, nsplit, scale);
   return hipGetLastError();
 }
 
@@ -151,12 +164,24 @@ constexpr int GOM_CB = 8;     // column blocks per wave: a lane reads 8 adjacent
 // therefore stands for column c0 + 8*i + b.  In the result, lane (q, hi) register 4*gg + m of
 // block b is column c0 + 8*(8*gg + 4*hi + m) + b: for fixed (gg, m) the 8 blocks give 8
 // consecutive columns, stored as two float4.
+// Several sums of the same shape (same groups, same C, same gather mode) share one launch:
+// blockIdx.y = job * G + group.
+struct GomBatch {
+  const bf16_t *smallT[GOM_MAX_JOBS];
+  const bf16_t *wide[GOM_MAX_JOBS];
+  float *partial[GOM_MAX_JOBS];
+  float *out[GOM_MAX_JOBS];      // used when the rows are not split: the result is final
+  int layout_qc[GOM_MAX_JOBS];
+};
+
 template <bool GATHER, int NQ>
-__global__ __launch_bounds__(256) void group_outer_mfma_kernel(
+__global__ __launch_bounds__(256, NQ == 1 ? 2 : 1) void group_outer_mfma_kernel(
     const int32_t *__restrict__ offs, const int32_t *__restrict__ pair_of_row, int k, int nrows,
-    const bf16_t *__restrict__ smallT, int ldT, int r, const bf16_t *__restrict__ wide, int C,
-    int nsplit, float *__restrict__ partial) {
-  const int g = blockIdx.y, sp = blockIdx.z, G = gridDim.y;
+    GomBatch batch, int G, int ldT, int r, int C, int nsplit, float scale) {
+  const int job = blockIdx.y / G, g = blockIdx.y % G, sp = blockIdx.z;
+  const bf16_t *__restrict__ smallT = batch.smallT[job];
+  const bf16_t *__restrict__ wide = batch.wide[job];
+  float *__restrict__ partial = batch.partial[job];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int l31 = lane & 31, hi = lane >> 5;
   const int lo = offs[g], hi_ = offs[g + 1];
@@ -214,6 +239,33 @@ __global__ __launch_bounds__(256) void group_outer_mfma_kernel(
   for (int j = 0; j < NQ; j++) {
     const int q = j * 32 + l31;
     if (q < r) {
+      if (nsplit == 1) {
+        // rows not split: scale and write the result itself, [g][q][c] or [g][c][q]
+        float *out = batch.out[job];
+        const bool qc = batch.layout_qc[job] != 0;
+#pragma unroll
+        for (int gg = 0; gg < 4; gg++)
+#pragma unroll
+          for (int m = 0; m < 4; m++) {
+            const int c = c0 + 8 * (8 * gg + 4 * hi + m);
+            if (c + 7 < C) {
+              if (qc) {
+                float *o = out + ((int64_t)g * r + q) * C + c;
+                *reinterpret_cast<float4 *>(o) =
+                    make_float4(scale * acc[0][j][gg * 4 + m], scale * acc[1][j][gg * 4 + m],
+                                scale * acc[2][j][gg * 4 + m], scale * acc[3][j][gg * 4 + m]);
+                *reinterpret_cast<float4 *>(o + 4) =
+                    make_float4(scale * acc[4][j][gg * 4 + m], scale * acc[5][j][gg * 4 + m],
+                                scale * acc[6][j][gg * 4 + m], scale * acc[7][j][gg * 4 + m]);
+              } else {
+                float *o = out + ((int64_t)g * C + c) * r + q;
+#pragma unroll
+                for (int b = 0; b < GOM_CB; b++) o[(int64_t)b * r] = scale * acc[b][j][gg * 4 + m];
+              }
+            }
+          }
+        continue;
+      }
       float *o = partial + (((int64_t)sp * G + g) * r + q) * C;
 #pragma unroll
       for (int gg = 0; gg < 4; gg++)
@@ -231,10 +283,10 @@ __global__ __launch_bounds__(256) void group_outer_mfma_kernel(
   }
 }
 
-static int gom_splits(int G, int C) {
+static int gom_splits(int G, int C, int njobs = 1) {
   // one resident round: 256 CUs x 2 workgroups of 4 waves (the kernel runs 2 waves per SIMD)
   const int col_groups = (C + 1023) / 1024;
-  int s = 512 / (col_groups * G);
+  int s = 512 / (col_groups * G * njobs);
   if (s < 1) s = 1;
   if (s > 8 && G > 1) s = 8;     // partial sums cost HBM traffic: nsplit * G * r * C floats
   if (s > 32) s = 32;
@@ -246,25 +298,37 @@ size_t group_outer_mfma_partial_floats(int G, int r, int C) {
 }
 
 hipError_t launch_group_outer_mfma(const int32_t *offs, int G, int nrows,
-                                   const int32_t *pair_of_row, int k, const void *smallT, int ldT,
-                                   int r, const void *wide, int C, float scale, int layout_qc,
-                                   float *out, float *partials, size_t partial_floats,
-                                   hipStream_t st) {
-  const int nsplit = gom_splits(G, C);
-  if ((size_t)nsplit * G * r * C > partial_floats) return hipErrorInvalidValue;
-  const dim3 grid((C + 1023) / 1024, G, nsplit), block(256);
+                                   const int32_t *pair_of_row, int k, const GomJob *jobs, int njobs,
+                                   int ldT, int r, int C, float scale, float *partials,
+                                   size_t partial_floats, hipStream_t st) {
+  if (njobs < 1 || njobs > GOM_MAX_JOBS) return hipErrorInvalidValue;
+  const int nsplit = gom_splits(G, C, njobs);
+  const size_t per_job = (size_t)nsplit * G * r * C;
+  if (per_job * njobs > partial_floats) return hipErrorInvalidValue;
+  GomBatch b{};
+  ReduceBatch rb{};
+  for (int i = 0; i < njobs; i++) {
+    b.smallT[i] = (const bf16_t *)jobs[i].smallT;
+    b.wide[i] = (const bf16_t *)jobs[i].wide;
+    b.partial[i] = partials + per_job * i;
+    b.out[i] = jobs[i].out;
+    b.layout_qc[i] = jobs[i].layout_qc;
+    rb.partial[i] = b.partial[i];
+    rb.out[i] = jobs[i].out;
+    rb.layout_qc[i] = jobs[i].layout_qc;
+  }
+  const dim3 grid((C + 1023) / 1024, G * njobs, nsplit), block(256);
 #define MIXLORA_GOM(GA_, NQ_)                                                                   \
   hipLaunchKernelGGL((group_outer_mfma_kernel<GA_, NQ_>), grid, block, 0, st, offs, pair_of_row, \
-                     k, nrows, (const bf16_t *)smallT, ldT, r, (const bf16_t *)wide, C, nsplit,   \
-                     partials)
+                     k, nrows, b, G, ldT, r, C, nsplit, scale)
   if (pair_of_row) { if (r <= 32) MIXLORA_GOM(true, 1); else MIXLORA_GOM(true, 2); }
   else { if (r <= 32) MIXLORA_GOM(false, 1); else MIXLORA_GOM(false, 2); }
 #undef MIXLORA_GOM
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || nsplit == 1) return e;   // unsplit rows: the kernel wrote the results
   const int64_t n = (int64_t)G * r * C;
-  hipLaunchKernelGGL(group_outer_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
-                     st, partials, G, r, C, nsplit, scale, layout_qc, out);
+  hipLaunchKernelGGL(group_outer_reduce_kernel, dim3((unsigned)((n + 255) / 256), njobs), dim3(256),
+                     0, st, rb, G, r, C, nsplit, scale);
   return hipGetLastError();
 }
 

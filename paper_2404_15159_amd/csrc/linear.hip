@@ -180,11 +180,13 @@ int mixlora_lora_linear_backward(const mixlora_linear_dims *dims, const void *W,
   float *part = (float *)(ws + L.partials);
   if (dt == MIXLORA_BF16) {
     HIP_TRY(launch_f32_to_bf16T((const float *)(ws + L.VB), T, r, ws + L.VB_T, L.ldT, st));
-    HIP_TRY(launch_group_outer_mfma(tok, 1, T, nullptr, 1, ws + L.VB_T, L.ldT, r, x, di, s, 1, dA,
-                                    part, L.partial_floats, st));
+    const GomJob ja{ws + L.VB_T, x, dA, 1};
+    HIP_TRY(launch_group_outer_mfma(tok, 1, T, nullptr, 1, &ja, 1, L.ldT, r, di, s, part,
+                                    L.partial_floats, st));
     HIP_TRY(launch_f32_to_bf16T((const float *)(ws + L.P), T, r, ws + L.P_T, L.ldT, st));
-    HIP_TRY(launch_group_outer_mfma(tok, 1, T, nullptr, 1, ws + L.P_T, L.ldT, r, dy, dn, s, 0, dB,
-                                    part, L.partial_floats, st));
+    const GomJob jb{ws + L.P_T, dy, dB, 0};
+    HIP_TRY(launch_group_outer_mfma(tok, 1, T, nullptr, 1, &jb, 1, L.ldT, r, dn, s, part,
+                                    L.partial_floats, st));
   } else {
     HIP_TRY(launch_group_outer(dt, tok, 1, T, nullptr, 1, (const float *)(ws + L.VB), r, x, di, s, 1,
                                dA, part, L.partial_floats, st));
