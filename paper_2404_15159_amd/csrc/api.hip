@@ -224,13 +224,20 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
                                  aux_loss, (float *)(ws + L.F), (float *)(ws + L.P), Nl, token_model,
                                  (int32_t *)(ws + L.model_tokens), st));
   PairCtx pc{offs, pair_of_row, row_of_pair, wts, idx, T, N, k, r};
+  {
+    // s * B_down packed for the K-extension of the down GEMM; in bf16 also zeros for the
+    // block-sparse operand Qw, whose non-zero blocks the fused stage fills in
+    const RelayoutJob jobs[2] = {job_bank_cat(w->B_down, N, d, r, D.lora_scale, ws + L.Bd_cat, R, 0),
+                                 job_zero_fill(ws + L.Qw, (size_t)T * R * 2)};
+    HIP_TRY(launch_relayout(dt, jobs, dt == MIXLORA_BF16 ? 2 : 1, st));
+  }
   // Algorithm 1 lines 11-13 on the routed pairs, expert-grouped rows
   if (dt == MIXLORA_BF16) {
     // fused: LoRA deltas + SiLU * up + A_down of the row's expert, all on MFMA
     HIP_TRY(launch_swiglu_fwd_mfma(pc, f, D.lora_scale, ws + L.G, ws + L.U,
                                    (float *)(ws + L.Pg_all), (float *)(ws + L.Pu_all), w->B_gate,
                                    w->B_up, w->A_down, ws + L.a_grp, (float *)(ws + L.rank_part),
-                                   (float *)(ws + L.Q_all), st));
+                                   (float *)(ws + L.Q_all), ws + L.Qw, R, st));
   } else {
     HIP_TRY(launch_swiglu_fwd(dt, pc, f, D.lora_scale, ws + L.G, ws + L.U,
                               (float *)(ws + L.Pg_all), (float *)(ws + L.Pu_all), w->B_gate,
@@ -239,15 +246,12 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
     GemmProblem p = problem(kT, R, ws + L.Q_all, R, 1);
     add_seg(p, ws + L.a_grp, f, w->A_down, f, f);
     HIP_TRY(launch_gemm(dt, &p, 1, st));
+    // the block-sparse low-rank operand
+    HIP_TRY(launch_scatter_blocks(dt, pc, (float *)(ws + L.Q_all), 0, 1, R, 1, 1, ws + L.Qw, R, 0, st));
   }
   // weighted combine of the pair activations (Algorithm 1 line 15, moved in front of the linear
-  // frozen down projection) and the block-sparse low-rank operand
+  // frozen down projection)
   HIP_TRY(launch_pair_combine(dt, pc, f, ws + L.a_grp, ws + L.a_comb, 1, st));
-  HIP_TRY(launch_scatter_blocks(dt, pc, (float *)(ws + L.Q_all), 0, 1, R, 1, 1, ws + L.Qw, R, 0, st));
-  {
-    const RelayoutJob j = job_bank_cat(w->B_down, N, d, r, D.lora_scale, ws + L.Bd_cat, R, 0);
-    HIP_TRY(launch_relayout(dt, &j, 1, st));
-  }
   // down projection (Algorithm 1 line 14): y = a_comb W_down^T + Qw (s B_down)^T
   if (dt == MIXLORA_BF16 && (size_t)T <= SPLITK_MAX_ROWS) {
     // Few rows: the d output columns alone give too few tiles to stream W_down at full rate, so
@@ -382,15 +386,17 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
 
   // every re-layout of the LoRA banks and the router that the pass needs, in one launch
   {
-    const RelayoutJob jobs[7] = {
+    const RelayoutJob jobs[8] = {
         job_bank_T(w->B_down, N, d, r, ws + L.Bd_T),
         job_bank_T(w->B_gate, N, f, r, ws + L.Bg_T),
         job_bank_T(w->B_up, N, f, r, ws + L.Bu_T),
         job_A_cat(w->A_gate, N, r, d, s, ws + L.Bx, Kx, 0),
         job_A_cat(w->A_up, N, r, d, s, ws + L.Bx, Kx, R),
         job_router_T(w->W_router, N, d, ws + L.Bx, Kx, 2 * R, Kx - 2 * R),
-        job_bank_T(w->A_down, N, r, f, ws + L.AdT)};   // [N,r,f] -> [N,f,r], bf16 path only
-    HIP_TRY(launch_relayout(dt, jobs, dt == MIXLORA_BF16 ? 7 : 6, st));
+        job_bank_T(w->A_down, N, r, f, ws + L.AdT),   // [N,r,f] -> [N,f,r], bf16 path only
+        // bf16 path only: zeros for the block-sparse operand S, filled in by the fused stage
+        job_zero_fill(ws + L.S, (size_t)T * Kx * 2)};
+    HIP_TRY(launch_relayout(dt, jobs, dt == MIXLORA_BF16 ? 8 : 6, st));
   }
   // H = dy W_down  (once per token: the frozen down projection is shared and linear) and, in
   // the same launch, VB[t, e, :] = B_down[e]^T dy[t]
@@ -409,7 +415,7 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
                                    w->B_up, ws + L.AdT, ws + L.Bg_T, ws + L.Bu_T, ws + L.dg_grp,
                                    ws + L.du_grp, (float *)(ws + L.dw_part),
                                    (float *)(ws + L.rank_part), (float *)(ws + L.TG_all),
-                                   (float *)(ws + L.TU_all), st));
+                                   (float *)(ws + L.TU_all), ws + L.S, Kx, st));
   } else {
     HIP_TRY(launch_swiglu_bwd(dt, pc, f, s, ws + L.G, ws + L.U, (float *)(ws + L.Pg_all),
                               (float *)(ws + L.Pu_all), w->B_gate, w->B_up, ws + L.H,
@@ -441,7 +447,8 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
                             (float *)(ws + L.VB_all), (float *)(ws + L.Q_all), (float *)(ws + L.F),
                             s, d_aux, D.aux_coeff, (float *)(ws + L.dw), (float *)(ws + L.dz),
                             ws + L.S, Kx, 2 * R, Kx - 2 * R, Nl, token_model,
-                            (const int32_t *)(ws + L.model_tokens), st));
+                            (const int32_t *)(ws + L.model_tokens),
+                            dt == MIXLORA_BF16 ? ws + L.dzT : nullptr, L.ldTz, st));
   if (dt == MIXLORA_BF16) {
     GatherJob gj[6];
     for (int i = 0; i < 6; i++) gj[i] = GatherJob{fsrc[i], ws + L.small[i], by_token[i], weighted[i]};
@@ -456,8 +463,7 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
     }
     HIP_TRY(launch_group_outer_mfma(offs, N, kT, nullptr, k, jf, 3, L.ldT, r, f, s, part, pfl, st));
     HIP_TRY(launch_group_outer_mfma(offs, N, kT, pair_of_row, k, jd, 3, L.ldT, r, d, s, part, pfl, st));
-    // dW_router = dz^T x
-    HIP_TRY(launch_f32_to_bf16T((float *)(ws + L.dz), T, N, ws + L.dzT, L.ldTz, st));
+    // dW_router = dz^T x  (the transposed bf16 dz comes from the router backward)
     const GomJob jr{ws + L.dzT, x, grads->dW_router, 1};
     HIP_TRY(launch_group_outer_mfma((int32_t *)(ws + L.tok_offs), 1, T, nullptr, 1, &jr, 1, L.ldTz, N,
                                     d, 1.f, part, pfl, st));
@@ -471,9 +477,10 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
                                (float *)(ws + L.dz), N, x, d, 1.f, 1, grads->dW_router, part, pfl, st));
   }
   // dx = dgsum W_gate + dusum W_up + [TG | TU | dz] [s A_gate ; s A_up ; W_router]
-  HIP_TRY(launch_scatter_blocks(dt, pc, (float *)(ws + L.TG_all),
-                                (int64_t)((float *)(ws + L.TU_all) - (float *)(ws + L.TG_all)), 2, R,
-                                1, 0, ws + L.S, Kx, 0, st));
+  if (dt != MIXLORA_BF16)   // in bf16 the fused stage has already written these blocks
+    HIP_TRY(launch_scatter_blocks(dt, pc, (float *)(ws + L.TG_all),
+                                  (int64_t)((float *)(ws + L.TU_all) - (float *)(ws + L.TG_all)), 2, R,
+                                  1, 0, ws + L.S, Kx, 0, st));
   {
     GemmProblem p = problem(T, d, dx, d, 0);
     add_seg(p, ws + L.dgsum, f, WgT, f, f);

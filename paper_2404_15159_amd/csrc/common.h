@@ -128,12 +128,14 @@ hipError_t launch_swiglu_bwd(int dtype, const PairCtx &pc, int f, float s, const
                              void *du_grp, float *dw_part, int n_col_tiles, hipStream_t st);
 int swiglu_col_tiles(int f);
 
-// bf16 MFMA fusion of the above with the A_down projection of the row's expert: writes a_grp and Q_all[row, e(row)*r + q]; Q_part is scratch of
-// 8 * kT * r floats.
+// bf16 MFMA fusion of the above with the A_down projection of the row's expert: writes a_grp,
+// Q_all[row, e(row)*r + q] and the non-zero blocks of Qw[t, e*r + q] = w * Q (bf16, pitch ldqw;
+// the caller zero-fills Qw first).  Q_part is scratch of 8 * kT * r floats.
 hipError_t launch_swiglu_fwd_mfma(const PairCtx &pc, int f, float s, const void *G, const void *U,
                                   const float *Pg_all, const float *Pu_all, const void *B_gate,
                                   const void *B_up, const void *A_down, void *a_grp,
-                                  float *Q_part, float *Q_all, hipStream_t st);
+                                  float *Q_part, float *Q_all, void *Qw, int ldqw,
+                                  hipStream_t st);
 
 // bf16 MFMA backward of the same stage: dg_grp, du_grp, dw_part[row][split]
 // (split count = fused_splits(f)), TG_all / TU_all at [row, e(row)*r + q].  AdT = A_down re-laid
@@ -143,7 +145,7 @@ hipError_t launch_swiglu_bwd_mfma(const PairCtx &pc, int f, float s, const void 
                                   const float *VB_all, const void *B_gate, const void *B_up,
                                   const void *AdT, const void *BgT, const void *BuT, void *dg_grp,
                                   void *du_grp, float *dw_part, float *rank_part, float *TG_all,
-                                  float *TU_all, hipStream_t st);
+                                  float *TU_all, void *S, int lds_, hipStream_t st);
 int fused_splits(int f);
 
 // out[t,:] = sum_j (weighted ? w[t,j] : 1) * in_grp[row_of_pair[t,j], :]
@@ -178,9 +180,12 @@ struct RelayoutJob {
   int n0, n1, n2, valid2;
   float scale;
   int batched_transpose;
+  size_t zero_bytes;   // non-zero: the job is a plain zero fill of that many bytes at dst
 };
 constexpr int RELAYOUT_MAX_JOBS = 8;
 hipError_t launch_relayout(int dtype, const RelayoutJob *jobs, int njobs, hipStream_t st);
+// bytes (rounded up to a multiple of 16) of zeros at dst
+RelayoutJob job_zero_fill(void *dst, size_t bytes);
 // bank [N, rows, r] -> out[i, col0 + e*r + q] = scale * bank[e, i, q]   (out pitch ldo)
 RelayoutJob job_bank_cat(const void *bank, int N, int rows, int r, float scale, void *out,
                          int ldo, int col0);
@@ -241,6 +246,6 @@ hipError_t launch_router_bwd(int dtype, const PairCtx &pc, const float *probs, c
                              const float *F, float s, const AuxUpstream &d_aux, float aux_coeff,
                              float *dw_ws, float *dz, void *S, int lds_, int col0, int ncols,
                              int Nl, const int32_t *token_model, const int32_t *model_tokens,
-                             hipStream_t st);
+                             void *dzT, int ldTz, hipStream_t st);   // dzT: bf16 [N][ldTz] copy or NULL
 
 }  // namespace mixlora

@@ -456,28 +456,39 @@ __global__ __launch_bounds__(256) void relayout_kernel(RelayoutBatch batch) {
   const RelayoutJob &J = batch.job[blockIdx.y];
   const E *__restrict__ src = reinterpret_cast<const E *>(J.src);
   E *__restrict__ dst = reinterpret_cast<E *>(J.dst);
+  if (J.zero_bytes) {   // plain zero fill, 16 bytes per store (dst is 16-byte aligned)
+    uint4 *z = reinterpret_cast<uint4 *>(J.dst);
+    const size_t nv = J.zero_bytes / 16;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nv;
+         i += (size_t)gridDim.x * blockDim.x)
+      z[i] = make_uint4(0u, 0u, 0u, 0u);
+    return;
+  }
   if (J.batched_transpose) {
     // dst[dst0 + b*d0 + q*d1 + p] = scale * src[b*s0 + p*n2 + q] for b < n0, p < n1, q < n2
     // (zeros where p >= valid2): 64x64 tiles through LDS so that both the reads and the writes
-    // run along a contiguous dimension
-    __shared__ float tile[64][64 + 1];
+    // run along a contiguous dimension (long thin tiles for the rank-wide banks were measured
+    // slower)
+    constexpr int TP = 64, TQ = 64, pitch = TQ + 1;
+    __shared__ float tile[TP * pitch];
     const int P = J.n1, Q = J.n2, PV = J.valid2;
-    const int tp = (P + 63) / 64, tq = (Q + 63) / 64;
+    const int tp = (P + TP - 1) / TP, tq = (Q + TQ - 1) / TQ;
     const int ntiles = J.n0 * tp * tq;
     for (int tid = blockIdx.x; tid < ntiles; tid += gridDim.x) {
       const int b = tid / (tp * tq), rem = tid % (tp * tq);
-      const int p0 = (rem / tq) * 64, q0 = (rem % tq) * 64;
-      const int hp = P - p0 < 64 ? P - p0 : 64, hq = Q - q0 < 64 ? Q - q0 : 64;
+      const int p0 = (rem / tq) * TP, q0 = (rem % tq) * TQ;
+      const int hp = P - p0 < TP ? P - p0 : TP, hq = Q - q0 < TQ ? Q - q0 : TQ;
       // reads walk the source rows (hq contiguous elements each; one contiguous block when the
       // whole row fits), writes walk the destination rows (hp contiguous elements each)
       for (int x = threadIdx.x; x < hp * hq; x += 256) {
         const int i = x / hq, j = x - i * hq;
-        tile[i][j] = p0 + i < PV ? J.scale * to_f32(src[b * J.s0 + (int64_t)(p0 + i) * Q + q0 + j]) : 0.f;
+        tile[i * pitch + j] =
+            p0 + i < PV ? J.scale * to_f32(src[b * J.s0 + (int64_t)(p0 + i) * Q + q0 + j]) : 0.f;
       }
       __syncthreads();
       for (int x = threadIdx.x; x < hp * hq; x += 256) {
         const int j = x / hp, i = x - j * hp;
-        dst[J.dst0 + b * J.d0 + (q0 + j) * J.d1 + p0 + i] = from_f32<E>(tile[i][j]);
+        dst[J.dst0 + b * J.d0 + (q0 + j) * J.d1 + p0 + i] = from_f32<E>(tile[i * pitch + j]);
       }
       __syncthreads();
     }
@@ -504,7 +515,8 @@ hipError_t launch_relayout(int dtype, const RelayoutJob *jobs, int njobs, hipStr
     // blocks wanted: one per 256 elements, or one per 64x64 tile
     const int64_t want = b.job[i].batched_transpose
                              ? (int64_t)b.job[i].n0 * ((b.job[i].n1 + 63) / 64) * ((b.job[i].n2 + 63) / 64)
-                             : (n + 255) / 256;
+                             : b.job[i].zero_bytes ? (int64_t)(b.job[i].zero_bytes / 16 + 255) / 256
+                                                   : (n + 255) / 256;
     most = want > most ? want : most;
   }
   int64_t blocks = most;
@@ -515,6 +527,14 @@ hipError_t launch_relayout(int dtype, const RelayoutJob *jobs, int njobs, hipStr
   return hipGetLastError();
 }
 
+// bytes (rounded up to a multiple of 16; the buffer must have that room) of zeros at dst
+RelayoutJob job_zero_fill(void *dst, size_t bytes) {
+  RelayoutJob j{};
+  j.dst = dst;
+  j.zero_bytes = (bytes + 15) / 16 * 16;
+  j.n0 = j.n1 = j.n2 = 1;
+  return j;
+}
 // bank [N, rows, r]  ->  out[i, col0 + e*r + q] = scale * bank[e, i, q]     (out pitch ldo)
 RelayoutJob job_bank_cat(const void *bank, int N, int rows, int r, float scale, void *out,
                          int ldo, int col0) {

@@ -482,10 +482,15 @@ __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 2 : 1) void swiglu_bwd_mf
 }
 
 // dense[row, e(row)*r + q] = sum over splits of part[split][row][q]   (fixed order); blockIdx.y
-// picks the bank (partials bank_stride floats apart, outputs dense0 / dense1)
+// picks the bank (partials bank_stride floats apart, outputs dense0 / dense1).  The same value
+// (times the routing weight if weighted) also goes, as bf16, into the block-sparse per-token
+// operand of a K-extension:  sparse[t(row), col0 + bank*N*r + e*r + q]; the rest of that
+// operand was zero-filled beforehand.
 __global__ void reduce_rank_parts_kernel(PairCtx pc, const float *__restrict__ part0,
                                          int64_t bank_stride, int nsplit,
-                                         float *__restrict__ dense0, float *__restrict__ dense1) {
+                                         float *__restrict__ dense0, float *__restrict__ dense1,
+                                         bf16_t *__restrict__ sparse, int ld_sparse, int col0,
+                                         int weighted) {
   const int nP = pc.T * pc.k, r = pc.r;
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (int64_t)nP * r) return;
@@ -500,8 +505,12 @@ __global__ void reduce_rank_parts_kernel(PairCtx pc, const float *__restrict__ p
     acc += a0; acc += a1; acc += a2; acc += a3;
   }
   for (; sp < nsplit; sp++) acc += part[(int64_t)sp * nP * r + i];
-  const int e = pc.idx[pc.pair_of_row[row]];
-  dense[(int64_t)row * (pc.N * r) + e * r + q] = acc;
+  const int pair = pc.pair_of_row[row];
+  const int e = pc.idx[pair];
+  const int R = pc.N * r;
+  dense[(int64_t)row * R + e * r + q] = acc;
+  const float wv = weighted ? pc.w[pair] : 1.f;
+  sparse[(int64_t)(pair / pc.k) * ld_sparse + col0 + blockIdx.y * R + e * r + q] = (bf16_t)(wv * acc);
 }
 
 int fused_splits(int f) {
@@ -514,7 +523,8 @@ int fused_splits(int f) {
 hipError_t launch_swiglu_fwd_mfma(const PairCtx &pc, int f, float s, const void *G, const void *U,
                                   const float *Pg_all, const float *Pu_all, const void *B_gate,
                                   const void *B_up, const void *A_down, void *a_grp,
-                                  float *Q_part, float *Q_all, hipStream_t st) {
+                                  float *Q_part, float *Q_all, void *Qw, int ldqw,
+                                  hipStream_t st) {
   const int nP = pc.T * pc.k, nsplit = fused_splits(f);
   const dim3 grid((nP + FT_ROWS - 1) / FT_ROWS + pc.N, nsplit), block(FT_WAVES * 64);
 #define MIXLORA_FWD(KSR_, NQ_)                                                                   \
@@ -529,7 +539,7 @@ hipError_t launch_swiglu_fwd_mfma(const PairCtx &pc, int f, float s, const void 
   if (e != hipSuccess) return e;
   const int64_t n = (int64_t)nP * pc.r;
   hipLaunchKernelGGL(reduce_rank_parts_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                     pc, Q_part, (int64_t)0, nsplit, Q_all, Q_all);
+                     pc, Q_part, (int64_t)0, nsplit, Q_all, Q_all, (bf16_t *)Qw, ldqw, 0, 1);
   return hipGetLastError();
 }
 
@@ -538,7 +548,7 @@ hipError_t launch_swiglu_bwd_mfma(const PairCtx &pc, int f, float s, const void 
                                   const float *VB_all, const void *B_gate, const void *B_up,
                                   const void *AdT, const void *BgT, const void *BuT, void *dg_grp,
                                   void *du_grp, float *dw_part, float *rank_part, float *TG_all,
-                                  float *TU_all, hipStream_t st) {
+                                  float *TU_all, void *S, int lds_, hipStream_t st) {
   const int nP = pc.T * pc.k, nsplit = fused_splits(f);
   float *TG_part = rank_part, *TU_part = rank_part + (size_t)8 * nP * pc.r;
   const dim3 grid((nP + FT_ROWS - 1) / FT_ROWS + pc.N, nsplit), block(FT_WAVES * 64);
@@ -557,7 +567,7 @@ hipError_t launch_swiglu_bwd_mfma(const PairCtx &pc, int f, float s, const void 
   const int64_t n = (int64_t)nP * pc.r;
   const dim3 rgrid((unsigned)((n + 255) / 256), 2);
   hipLaunchKernelGGL(reduce_rank_parts_kernel, rgrid, dim3(256), 0, st, pc, TG_part,
-                     (int64_t)(TU_part - TG_part), nsplit, TG_all, TU_all);
+                     (int64_t)(TU_part - TG_part), nsplit, TG_all, TU_all, (bf16_t *)S, lds_, 0, 0);
   return hipGetLastError();
 }
 
