@@ -162,6 +162,10 @@ def main():
     ap.add_argument("--cpu-tokens", type=int, default=4096)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--forward-only", action="store_true")
+    ap.add_argument("--schedule", default="linear_down", choices=["linear_down", "shared", "vanilla"],
+                    help="linear_down: the library's schedule (3 frozen units per direction); "
+                         "shared / vanilla: the paper's Figure 3(b) / 3(a) schedules (2+k / 3k "
+                         "units), for comparison")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known HBM traffic, used to "
                          "scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -191,8 +195,10 @@ def main():
     t0 = time.perf_counter()
     host = synth.make_inputs(cfg)
     t_inputs = time.perf_counter() - t0
+    schedule = {"linear_down": B.SCHEDULE_LINEAR_DOWN, "shared": B.SCHEDULE_SHARED,
+                "vanilla": B.SCHEDULE_VANILLA}[args.schedule]
     m = MixLoraFFN(cfg, host, with_backward=do_bwd,
-                   token_model=synth.token_model(cfg) if cfg.M > 1 else None)
+                   token_model=synth.token_model(cfg) if cfg.M > 1 else None, schedule=schedule)
 
     def step():
         m.forward()
@@ -240,13 +246,24 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    unit, fwd_fl, bwd_fl = flop_model(cfg, 3, 3)
+    # frozen units per direction of the executed schedule; FLOPs are counted as executed
+    U = {"linear_down": 3, "shared": 2 + cfg.k, "vanilla": 3 * cfg.k}[args.schedule]
+    unit, fwd_fl, bwd_fl = flop_model(cfg, U, U)
     _, fwd_paper, bwd_paper = flop_model(cfg, 2 + cfg.k, 2 + cfg.k)
-    step_flops = fwd_fl + (bwd_fl if do_bwd else 0.0)
-    units_per_step = 3 + (3 if do_bwd else 0)
+    exec_flops = fwd_fl + (bwd_fl if do_bwd else 0.0)
+    _, fwd_min, bwd_min = flop_model(cfg, 3, 3)       # what the block needs at least
+    step_flops = fwd_min + (bwd_min if do_bwd else 0.0)
+    units_per_step = U + (U if do_bwd else 0)
+    schedule_text = {
+        "linear_down": "shared gate/up (2 units) + linear frozen down (1 unit) per direction; "
+                       "LoRA as rank-r terms on routed pairs",
+        "shared": "paper Figure 3(b): shared gate/up (2 units) + down projection per routed pair "
+                  "(k units) per direction; LoRA as rank-r terms on routed pairs",
+        "vanilla": "paper Figure 3(a): gate, up and down per routed pair (3k units) per direction; "
+                   "LoRA as rank-r terms on routed pairs"}[args.schedule]
     launches_per_step = k_launches / args.steps
     avg_launch_s = k_ms / 1e3 / max(k_launches, 1)
-    traffic = read_traffic(args.workload)
+    traffic = read_traffic(args.workload) if args.schedule == "linear_down" else None
     if cfg.T <= 128:
         # decode-shaped call: the frozen-projection launches stream every weight once and do
         # little arithmetic per byte, so their roofline is HBM bandwidth.  Algorithmic bytes per
@@ -280,10 +297,11 @@ def main():
         "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} d_ff={cfg.d_ff} N={cfg.N} "
                                f"top-{cfg.k} r={cfg.r} {'adapters=%d ' % cfg.M if cfg.M > 1 else ''}bf16 "
                                f"{'forward+backward' if do_bwd else 'forward'}",
-                   "schedule": "shared gate/up (2 units) + linear frozen down (1 unit) per "
-                               "direction; LoRA as rank-r terms on routed pairs",
+                   "schedule": schedule_text,
                    "frozen_gemm_units_per_step": units_per_step,
+                   "workspace_gib": round(m.ws_bytes / 2**30, 3),
                    "algorithmic_tflop_per_step": step_flops / 1e12,
+                   "executed_schedule_tflop_per_step": exec_flops / 1e12,
                    "paper_schedule_tflop_per_step": (fwd_paper + (bwd_paper if do_bwd else 0)) / 1e12,
                    "mfma_frac_whole_step": step_flops / (ms_per_step / 1e3) / MFMA_BF16_PEAK,
                    "measured_context": {

@@ -120,6 +120,41 @@ MIXLORA_API int mixlora_ffn_backward(const mixlora_dims *dims, const mixlora_wei
                          size_t workspace_bytes, void *dx, const mixlora_grads *grads,
                          void *stream);
 
+/* ---- The paper's own execution schedules of the same block (Section 3.3, "Reducing the
+ * Computational Complexity (I)", Figure 3), for measured comparison -----------------------------
+ * All three compute the same function; they differ in how often the frozen matrices are applied.
+ * With "unit" = one frozen d x d_ff product over T rows:
+ *   MIXLORA_SCHEDULE_LINEAR_DOWN  what mixlora_ffn_forward/backward run: gate and up once per
+ *       token (2 units), the pairs' activations combined with the routing weights in front of ONE
+ *       frozen down product (1 unit; W_down acts linearly on the weighted sum), LoRA terms rank-r.
+ *   MIXLORA_SCHEDULE_SHARED       Figure 3(b): gate and up once per token (2 units), the down
+ *       projection on every routed (token, expert) pair row (k units), combined afterwards.
+ *   MIXLORA_SCHEDULE_VANILLA      Figure 3(a): every expert applies gate, up and down to its own
+ *       slice of token rows (3k units).
+ * The backward pass mirrors the forward count (per-pair rows wherever the forward used them).
+ * SHARED and VANILLA exist for bf16 only (MIXLORA_E_DTYPE otherwise), need the larger workspace
+ * reported below, and the backward call must use the schedule of the forward call that filled
+ * the workspace.  Other arguments, outputs and errors as in mixlora_ffn_forward / _backward;
+ * an unknown schedule gives MIXLORA_E_SHAPE.                                                   */
+typedef enum {
+  MIXLORA_SCHEDULE_LINEAR_DOWN = 0,
+  MIXLORA_SCHEDULE_SHARED = 1,
+  MIXLORA_SCHEDULE_VANILLA = 2
+} mixlora_schedule;
+
+/* Workspace bytes for the given schedule (0 for invalid dims / schedule / dtype). */
+MIXLORA_API size_t mixlora_schedule_workspace_bytes(const mixlora_dims *dims, int32_t schedule,
+                                                    int for_backward);
+MIXLORA_API int mixlora_ffn_forward_schedule(const mixlora_dims *dims, int32_t schedule,
+                                 const mixlora_weights *w, const void *x, void *y,
+                                 int32_t *topk_idx, float *topk_w, int32_t *expert_counts,
+                                 float *aux_loss, void *workspace, size_t workspace_bytes,
+                                 void *stream);
+MIXLORA_API int mixlora_ffn_backward_schedule(const mixlora_dims *dims, int32_t schedule,
+                                  const mixlora_weights *w, const void *x, const void *dy,
+                                  float d_aux, void *workspace, size_t workspace_bytes, void *dx,
+                                  const mixlora_grads *grads, void *stream);
+
 /* ---- Several adapters on one frozen base (Section 3.3, "Optimizing Multi-MixLoRA Training and
  * Inference (II)"; outer loop of Algorithm 1) -------------------------------------------------
  * M MixLoRA adapters, each with its own router and N LoRA experts, share W_gate / W_up / W_down.

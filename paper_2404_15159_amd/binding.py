@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(HERE, "libmixlora.so")
 
 F32, BF16 = 0, 1
 AUX_TOP1, AUX_TOPK = 0, 1
+SCHEDULE_LINEAR_DOWN, SCHEDULE_SHARED, SCHEDULE_VANILLA = 0, 1, 2
 STATUS = {0: "OK", -1: "E_NULL", -2: "E_SHAPE", -3: "E_DTYPE", -4: "E_ALIGN", -5: "E_WORKSPACE",
           -6: "E_HIP"}
 
@@ -24,7 +25,9 @@ EXPORTS = ("mixlora_workspace_bytes", "mixlora_ffn_forward", "mixlora_ffn_backwa
            "mixlora_profile_begin", "mixlora_profile_end",
            "mixlora_multi_workspace_bytes", "mixlora_multi_forward", "mixlora_multi_backward",
            "mixlora_mfma_probe", "mixlora_lora_linear_workspace_bytes",
-           "mixlora_lora_linear_forward", "mixlora_lora_linear_backward", "mixlora_adamw_step")
+           "mixlora_lora_linear_forward", "mixlora_lora_linear_backward", "mixlora_adamw_step",
+           "mixlora_schedule_workspace_bytes", "mixlora_ffn_forward_schedule",
+           "mixlora_ffn_backward_schedule")
 
 
 class Dims(C.Structure):
@@ -86,6 +89,14 @@ def load():
     lib.mixlora_ffn_backward.restype = C.c_int
     lib.mixlora_ffn_backward.argtypes = [C.POINTER(Dims), C.POINTER(Weights), vp, vp, f32, vp, sz,
                                          vp, C.POINTER(Grads), vp]
+    lib.mixlora_schedule_workspace_bytes.restype = sz
+    lib.mixlora_schedule_workspace_bytes.argtypes = [C.POINTER(Dims), i32, C.c_int]
+    lib.mixlora_ffn_forward_schedule.restype = C.c_int
+    lib.mixlora_ffn_forward_schedule.argtypes = [C.POINTER(Dims), i32, C.POINTER(Weights), vp, vp,
+                                                 vp, vp, vp, vp, vp, sz, vp]
+    lib.mixlora_ffn_backward_schedule.restype = C.c_int
+    lib.mixlora_ffn_backward_schedule.argtypes = [C.POINTER(Dims), i32, C.POINTER(Weights), vp, vp,
+                                                  f32, vp, sz, vp, C.POINTER(Grads), vp]
     lib.mixlora_aux_loss.restype = C.c_int
     lib.mixlora_aux_loss.argtypes = [vp, vp, i32, i32, i32, f32, i32, vp, vp, vp, vp, vp]
     lib.mixlora_transpose.restype = C.c_int
@@ -177,6 +188,33 @@ def mixlora_ffn_backward(dims: Dims, weights: Weights, x, dy, d_aux: float, work
                                      C.byref(grads), _stream(stream))
     if rc != 0:
         raise MixLoraError("mixlora_ffn_backward", rc)
+
+
+def mixlora_schedule_workspace_bytes(dims: Dims, schedule: int, for_backward: bool) -> int:
+    return int(load().mixlora_schedule_workspace_bytes(C.byref(dims), int(schedule),
+                                                       int(bool(for_backward))))
+
+
+def mixlora_ffn_forward_schedule(dims: Dims, schedule: int, weights: Weights, x, y, topk_idx,
+                                 topk_w, expert_counts, aux_loss, workspace,
+                                 workspace_bytes: int, stream=None) -> None:
+    rc = load().mixlora_ffn_forward_schedule(C.byref(dims), int(schedule), C.byref(weights),
+                                             _ptr(x), _ptr(y), _ptr(topk_idx), _ptr(topk_w),
+                                             _ptr(expert_counts), _ptr(aux_loss), _ptr(workspace),
+                                             workspace_bytes, _stream(stream))
+    if rc != 0:
+        raise MixLoraError("mixlora_ffn_forward_schedule", rc)
+
+
+def mixlora_ffn_backward_schedule(dims: Dims, schedule: int, weights: Weights, x, dy,
+                                  d_aux: float, workspace, workspace_bytes: int, dx,
+                                  grads: Grads, stream=None) -> None:
+    rc = load().mixlora_ffn_backward_schedule(C.byref(dims), int(schedule), C.byref(weights),
+                                              _ptr(x), _ptr(dy), float(d_aux), _ptr(workspace),
+                                              workspace_bytes, _ptr(dx), C.byref(grads),
+                                              _stream(stream))
+    if rc != 0:
+        raise MixLoraError("mixlora_ffn_backward_schedule", rc)
 
 
 def make_multi(M: int, token_model, d_aux=None) -> Multi:

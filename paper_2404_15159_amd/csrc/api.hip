@@ -33,10 +33,17 @@ struct Layout {
   size_t partial_floats;
   size_t bwd_end;
   int Kx, nct;
+  // per-pair-row buffers of the paper's own schedules (Section 3.3, Figure 3); size 0 otherwise
+  size_t Xp, Gp, Up, Qp, Op;     // forward (Gp, Up are kept for the backward pass)
+  size_t dYp, Hp, Sp, dXp;       // backward scratch
 };
 
-Layout make_layout(const mixlora_dims &D) {
+// Buffers a schedule does not use get size 0 (per-token G, U in the unshared schedule, the
+// combined activations where the down projection runs per pair, ...).
+Layout make_layout(const mixlora_dims &D, int schedule = MIXLORA_SCHEDULE_LINEAR_DOWN) {
   Layout L{};
+  const bool pair_down = schedule != MIXLORA_SCHEDULE_LINEAR_DOWN;
+  const bool vanilla = schedule == MIXLORA_SCHEDULE_VANILLA;
   const size_t T = D.T, d = D.d, f = D.d_ff, N = D.N, k = D.k, r = D.r;
   const size_t R = N * r, kT = k * T;
   const size_t E = D.dtype == MIXLORA_BF16 ? 2 : 4;
@@ -55,14 +62,19 @@ Layout make_layout(const mixlora_dims &D) {
   L.P = take(N * 4);
   L.tok_offs = take(2 * 4);
   L.model_tokens = take(64 * 4);
-  L.G = take(T * f * E);
-  L.U = take(T * f * E);
+  L.G = take(vanilla ? 0 : T * f * E);
+  L.U = take(vanilla ? 0 : T * f * E);
   L.Pg_all = take(T * R * 4);
   L.Pu_all = take(T * R * 4);
   L.a_grp = take(kT * f * E);
   L.Q_all = take(kT * R * 4);
-  L.a_comb = take(T * f * E);
-  L.Qw = take(T * R * E);
+  L.a_comb = take(pair_down ? 0 : T * f * E);
+  L.Qw = take(pair_down ? 0 : T * R * E);
+  L.Xp = take(vanilla ? kT * d * E : 0);
+  L.Gp = take(vanilla ? kT * f * E : 0);
+  L.Up = take(vanilla ? kT * f * E : 0);
+  L.Qp = take(pair_down ? kT * R * E : 0);
+  L.Op = take(pair_down ? kT * d * E : 0);
   L.Bd_cat = take(d * R * E);
   L.rank_part = take(2 * 8 * kT * r * 4);   // per-split rank-r partial sums (two banks)
   // few tokens (decode-shaped calls): partial outputs of the K-split down projection
@@ -73,13 +85,15 @@ Layout make_layout(const mixlora_dims &D) {
   L.WdT = take(f * d * E);
   L.WgT = take(f * d * E);
   L.WuT = take(f * d * E);
-  L.H = take(T * f * E);
+  L.H = take(pair_down ? 0 : T * f * E);
+  L.dYp = take(pair_down ? kT * d * E : 0);
+  L.Hp = take(pair_down ? kT * f * E : 0);
   L.Bd_T = take(R * d * E);
   L.VB_all = take(T * R * 4);
   L.dg_grp = take(kT * f * E);
   L.du_grp = take(kT * f * E);
-  L.dgsum = take(T * f * E);
-  L.dusum = take(T * f * E);
+  L.dgsum = take(vanilla ? 0 : T * f * E);
+  L.dusum = take(vanilla ? 0 : T * f * E);
   L.dw_part = take(kT * (size_t)(L.nct > 8 ? L.nct : 8) * 4);
   L.dw = take(kT * 4);
   L.Bg_T = take(R * f * E);
@@ -91,7 +105,9 @@ Layout make_layout(const mixlora_dims &D) {
   L.ldTz = (int)((T + 15) / 16 * 16 + 16);
   for (int i = 0; i < 6; i++) L.small[i] = take(kT * r * 4 > (size_t)L.ldT * r * 2 ? kT * r * 4 : (size_t)L.ldT * r * 2);
   L.dzT = take((size_t)L.ldTz * N * 2);
-  L.S = take(T * (size_t)L.Kx * E);
+  L.S = take(vanilla ? 0 : T * (size_t)L.Kx * E);
+  L.Sp = take(vanilla ? kT * (size_t)L.Kx * E : 0);
+  L.dXp = take(vanilla ? kT * d * E : 0);
   L.Bx = take(d * (size_t)L.Kx * E);
   L.dz = take(T * N * 4);
   size_t pf = group_outer_partial_floats((int)N, (int)r, (int)f);
@@ -180,8 +196,11 @@ size_t mixlora_workspace_bytes(const mixlora_dims *dims, int for_backward) {
 static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_model,
                         const mixlora_weights *w, const void *x, void *y, int32_t *topk_idx,
                         float *topk_w, int32_t *expert_counts, float *aux_loss, void *workspace,
-                        size_t workspace_bytes, void *stream) {
-  const Layout L = make_layout(D);
+                        size_t workspace_bytes, void *stream,
+                        int schedule = MIXLORA_SCHEDULE_LINEAR_DOWN) {
+  const Layout L = make_layout(D, schedule);
+  const bool pair_down = schedule != MIXLORA_SCHEDULE_LINEAR_DOWN;   // down projection per pair
+  const bool vanilla = schedule == MIXLORA_SCHEDULE_VANILLA;         // gate/up per pair as well
   if (workspace_bytes < L.fwd_end) return MIXLORA_E_WORKSPACE;
 
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -208,7 +227,10 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
     add_seg(p[2], x, d, w->A_gate, d, d);
     add_seg(p[3], x, d, w->A_up, d, d);
     add_seg(p[4], x, d, w->W_router, d, d);
-    HIP_TRY(launch_gemm(dt, p, dt == MIXLORA_BF16 ? 5 : 4, st));
+    if (vanilla)   // unshared schedule: the frozen gate/up products follow the routing, per pair
+      HIP_TRY(launch_gemm(dt, p + 2, 3, st));
+    else
+      HIP_TRY(launch_gemm(dt, p, dt == MIXLORA_BF16 ? 5 : 4, st));
   }
   // Eq. 7 + Norm (Algorithm 1 lines 4-5)
   if (dt == MIXLORA_BF16)
@@ -228,8 +250,37 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
     // s * B_down packed for the K-extension of the down GEMM; in bf16 also zeros for the
     // block-sparse operand Qw, whose non-zero blocks the fused stage fills in
     const RelayoutJob jobs[2] = {job_bank_cat(w->B_down, N, d, r, D.lora_scale, ws + L.Bd_cat, R, 0),
-                                 job_zero_fill(ws + L.Qw, (size_t)T * R * 2)};
+                                 pair_down ? job_zero_fill(ws + L.Qp, (size_t)kT * R * 2)
+                                           : job_zero_fill(ws + L.Qw, (size_t)T * R * 2)};
     HIP_TRY(launch_relayout(dt, jobs, dt == MIXLORA_BF16 ? 2 : 1, st));
+  }
+  if (pair_down) {
+    // The paper's schedules (Figure 3): every expert runs its own frozen products on its slice of
+    // tokens.  (a) unshared: gate and up on the gathered token rows, k rows per token;
+    // (b) shared: gate and up once per token (above).  Both: the down projection on every pair
+    // row, combined with the routing weights afterwards (Algorithm 1 lines 14-15).
+    const char *Gsrc = ws + L.G, *Usrc = ws + L.U;
+    int rows_mode = ROWS_SPARSE;
+    if (vanilla) {
+      HIP_TRY(launch_gather_rows(dt, pc, d, x, ws + L.Xp, st));
+      GemmProblem p[2] = {problem(kT, f, ws + L.Gp, f, 0), problem(kT, f, ws + L.Up, f, 0)};
+      add_seg(p[0], ws + L.Xp, d, w->W_gate, d, d);
+      add_seg(p[1], ws + L.Xp, d, w->W_up, d, d);
+      HIP_TRY(launch_gemm(dt, p, 2, st));
+      Gsrc = ws + L.Gp;
+      Usrc = ws + L.Up;
+      rows_mode |= ROWS_GU;
+    }
+    HIP_TRY(launch_swiglu_fwd_mfma(pc, f, D.lora_scale, Gsrc, Usrc, (float *)(ws + L.Pg_all),
+                                   (float *)(ws + L.Pu_all), w->B_gate, w->B_up, w->A_down,
+                                   ws + L.a_grp, (float *)(ws + L.rank_part),
+                                   (float *)(ws + L.Q_all), ws + L.Qp, R, st, rows_mode));
+    GemmProblem p = problem(kT, d, ws + L.Op, d, 0);
+    add_seg(p, ws + L.a_grp, f, w->W_down, f, f);
+    add_seg(p, ws + L.Qp, R, ws + L.Bd_cat, R, R);
+    HIP_TRY(launch_gemm(dt, &p, 1, st));
+    HIP_TRY(launch_pair_combine(dt, pc, d, ws + L.Op, y, 1, st));
+    return MIXLORA_OK;
   }
   // Algorithm 1 lines 11-13 on the routed pairs, expert-grouped rows
   if (dt == MIXLORA_BF16) {
@@ -362,8 +413,11 @@ static int check_backward_args(const mixlora_dims *dims, const mixlora_weights *
 static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_model,
                          const AuxUpstream &d_aux, const mixlora_weights *w, const void *x,
                          const void *dy, void *workspace, size_t workspace_bytes, void *dx,
-                         const mixlora_grads *grads, void *stream) {
-  const Layout L = make_layout(D);
+                         const mixlora_grads *grads, void *stream,
+                         int schedule = MIXLORA_SCHEDULE_LINEAR_DOWN) {
+  const Layout L = make_layout(D, schedule);
+  const bool pair_down = schedule != MIXLORA_SCHEDULE_LINEAR_DOWN;
+  const bool vanilla = schedule == MIXLORA_SCHEDULE_VANILLA;
   if (workspace_bytes < L.bwd_end) return MIXLORA_E_WORKSPACE;
 
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -395,27 +449,42 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
         job_router_T(w->W_router, N, d, ws + L.Bx, Kx, 2 * R, Kx - 2 * R),
         job_bank_T(w->A_down, N, r, f, ws + L.AdT),   // [N,r,f] -> [N,f,r], bf16 path only
         // bf16 path only: zeros for the block-sparse operand S, filled in by the fused stage
-        job_zero_fill(ws + L.S, (size_t)T * Kx * 2)};
+        vanilla ? job_zero_fill(ws + L.Sp, (size_t)kT * Kx * 2)
+                : job_zero_fill(ws + L.S, (size_t)T * Kx * 2)};
     HIP_TRY(launch_relayout(dt, jobs, dt == MIXLORA_BF16 ? 8 : 6, st));
   }
   // H = dy W_down  (once per token: the frozen down projection is shared and linear) and, in
   // the same launch, VB[t, e, :] = B_down[e]^T dy[t]
-  {
+  if (pair_down) {
+    // the paper's schedules: the frozen down projection is differentiated per pair row
+    // (k rows per token); the routing weight is applied inside the fused stage as before
+    HIP_TRY(launch_gather_rows(dt, pc, d, dy, ws + L.dYp, st));
+    GemmProblem ph = problem(kT, f, ws + L.Hp, f, 0);
+    add_seg(ph, ws + L.dYp, d, WdT, d, d);
+    HIP_TRY(launch_gemm(dt, &ph, 1, st));
+    GemmProblem pv = problem(T, R, ws + L.VB_all, R, 1);
+    add_seg(pv, dy, d, ws + L.Bd_T, d, d);
+    HIP_TRY(launch_gemm(dt, &pv, 1, st));
+  } else {
     GemmProblem p[2] = {problem(T, f, ws + L.H, f, 0), problem(T, R, ws + L.VB_all, R, 1)};
     add_seg(p[0], dy, d, WdT, d, d);
     add_seg(p[1], dy, d, ws + L.Bd_T, d, d);
     HIP_TRY(launch_gemm(dt, p, 2, st));
   }
+  const int rows_mode = (pair_down ? ROWS_H : 0) | (vanilla ? ROWS_GU | ROWS_SPARSE : 0);
+  char *Sop = vanilla ? ws + L.Sp : ws + L.S;      // K-extension operand of the dx GEMM
   // through SiLU * up and the LoRA deltas, per pair; TG[row, e, :] = B_gate[e]^T dg[row] (and up)
   int nct = L.nct;
   if (dt == MIXLORA_BF16) {
     nct = fused_splits(f);
-    HIP_TRY(launch_swiglu_bwd_mfma(pc, f, s, ws + L.G, ws + L.U, ws + L.H, (float *)(ws + L.Pg_all),
+    HIP_TRY(launch_swiglu_bwd_mfma(pc, f, s, vanilla ? ws + L.Gp : ws + L.G,
+                                   vanilla ? ws + L.Up : ws + L.U, pair_down ? ws + L.Hp : ws + L.H,
+                                   (float *)(ws + L.Pg_all),
                                    (float *)(ws + L.Pu_all), (float *)(ws + L.VB_all), w->B_gate,
                                    w->B_up, ws + L.AdT, ws + L.Bg_T, ws + L.Bu_T, ws + L.dg_grp,
                                    ws + L.du_grp, (float *)(ws + L.dw_part),
                                    (float *)(ws + L.rank_part), (float *)(ws + L.TG_all),
-                                   (float *)(ws + L.TU_all), ws + L.S, Kx, st));
+                                   (float *)(ws + L.TU_all), Sop, Kx, st, rows_mode));
   } else {
     HIP_TRY(launch_swiglu_bwd(dt, pc, f, s, ws + L.G, ws + L.U, (float *)(ws + L.Pg_all),
                               (float *)(ws + L.Pu_all), w->B_gate, w->B_up, ws + L.H,
@@ -426,8 +495,10 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
     add_seg(p[1], ws + L.du_grp, f, ws + L.Bu_T, f, f);
     HIP_TRY(launch_gemm(dt, p, 2, st));
   }
-  HIP_TRY(launch_pair_combine(dt, pc, f, ws + L.dg_grp, ws + L.dgsum, 0, st));
-  HIP_TRY(launch_pair_combine(dt, pc, f, ws + L.du_grp, ws + L.dusum, 0, st));
+  if (!vanilla) {   // shared gate/up: their input gradient needs the per-token sums only
+    HIP_TRY(launch_pair_combine(dt, pc, f, ws + L.dg_grp, ws + L.dgsum, 0, st));
+    HIP_TRY(launch_pair_combine(dt, pc, f, ws + L.du_grp, ws + L.dusum, 0, st));
+  }
   // per-row rank-r factors of the LoRA gradients, then the grouped outer-product sums:
   //   dB_gate[e] = s sum dg (x) Pg ; dA_gate[e] = s sum TG (x) x ; same for up ;
   //   dA_down[e] = s sum (w B_down^T dy) (x) a ; dB_down[e] = s sum dy (x) (w A_down a)
@@ -446,9 +517,9 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
   HIP_TRY(launch_router_bwd(dt, pc, probs, (float *)(ws + L.dw_part), nct,
                             (float *)(ws + L.VB_all), (float *)(ws + L.Q_all), (float *)(ws + L.F),
                             s, d_aux, D.aux_coeff, (float *)(ws + L.dw), (float *)(ws + L.dz),
-                            ws + L.S, Kx, 2 * R, Kx - 2 * R, Nl, token_model,
+                            Sop, Kx, 2 * R, Kx - 2 * R, Nl, token_model,
                             (const int32_t *)(ws + L.model_tokens),
-                            dt == MIXLORA_BF16 ? ws + L.dzT : nullptr, L.ldTz, st));
+                            dt == MIXLORA_BF16 ? ws + L.dzT : nullptr, L.ldTz, st, vanilla ? 1 : 0));
   if (dt == MIXLORA_BF16) {
     GatherJob gj[6];
     for (int i = 0; i < 6; i++) gj[i] = GatherJob{fsrc[i], ws + L.small[i], by_token[i], weighted[i]};
@@ -481,7 +552,16 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
     HIP_TRY(launch_scatter_blocks(dt, pc, (float *)(ws + L.TG_all),
                                   (int64_t)((float *)(ws + L.TU_all) - (float *)(ws + L.TG_all)), 2, R,
                                   1, 0, ws + L.S, Kx, 0, st));
-  {
+  if (vanilla) {
+    // unshared schedule: every pair row goes through W_gate^T / W_up^T on its own, the k rows of
+    // a token are added afterwards
+    GemmProblem p = problem(kT, d, ws + L.dXp, d, 0);
+    add_seg(p, ws + L.dg_grp, f, WgT, f, f);
+    add_seg(p, ws + L.du_grp, f, WuT, f, f);
+    add_seg(p, ws + L.Sp, Kx, ws + L.Bx, Kx, Kx);
+    HIP_TRY(launch_gemm(dt, &p, 1, st));
+    HIP_TRY(launch_pair_combine(dt, pc, d, ws + L.dXp, dx, 0, st));
+  } else {
     GemmProblem p = problem(T, d, dx, d, 0);
     add_seg(p, ws + L.dgsum, f, WgT, f, f);
     add_seg(p, ws + L.dusum, f, WuT, f, f);
@@ -516,6 +596,48 @@ int mixlora_multi_backward(const mixlora_dims *dims, const mixlora_multi *multi,
   for (int m = 0; m < multi->M; m++) up.v[m] = multi->d_aux ? multi->d_aux[m] : 1.f;
   return backward_impl(all, dims->N, multi->token_model, up, w, x, dy, workspace, workspace_bytes,
                        dx, grads, stream);
+}
+
+static int check_schedule(const mixlora_dims *dims, int32_t schedule) {
+  if (!dims) return MIXLORA_E_NULL;
+  if (schedule < MIXLORA_SCHEDULE_LINEAR_DOWN || schedule > MIXLORA_SCHEDULE_VANILLA)
+    return MIXLORA_E_SHAPE;
+  if (schedule != MIXLORA_SCHEDULE_LINEAR_DOWN && dims->dtype != MIXLORA_BF16) return MIXLORA_E_DTYPE;
+  return MIXLORA_OK;
+}
+
+size_t mixlora_schedule_workspace_bytes(const mixlora_dims *dims, int32_t schedule,
+                                        int for_backward) {
+  if (check_dims(dims) != MIXLORA_OK || check_schedule(dims, schedule) != MIXLORA_OK) return 0;
+  const Layout L = make_layout(*dims, schedule);
+  return for_backward ? L.bwd_end : L.fwd_end;
+}
+
+int mixlora_ffn_forward_schedule(const mixlora_dims *dims, int32_t schedule,
+                                 const mixlora_weights *w, const void *x, void *y,
+                                 int32_t *topk_idx, float *topk_w, int32_t *expert_counts,
+                                 float *aux_loss, void *workspace, size_t workspace_bytes,
+                                 void *stream) {
+  int rc = check_forward_args(dims, w, x, y, topk_idx, topk_w, expert_counts, aux_loss, workspace);
+  if (rc) return rc;
+  rc = check_schedule(dims, schedule);
+  if (rc) return rc;
+  return forward_impl(*dims, dims->N, nullptr, w, x, y, topk_idx, topk_w, expert_counts, aux_loss,
+                      workspace, workspace_bytes, stream, schedule);
+}
+
+int mixlora_ffn_backward_schedule(const mixlora_dims *dims, int32_t schedule,
+                                  const mixlora_weights *w, const void *x, const void *dy,
+                                  float d_aux, void *workspace, size_t workspace_bytes, void *dx,
+                                  const mixlora_grads *grads, void *stream) {
+  int rc = check_backward_args(dims, w, x, dy, workspace, dx, grads);
+  if (rc) return rc;
+  rc = check_schedule(dims, schedule);
+  if (rc) return rc;
+  AuxUpstream up{};
+  up.v[0] = d_aux;
+  return backward_impl(*dims, dims->N, nullptr, up, w, x, dy, workspace, workspace_bytes, dx, grads,
+                       stream, schedule);
 }
 
 int mixlora_aux_loss(const float *probs, const int32_t *topk_idx, int32_t T, int32_t N,

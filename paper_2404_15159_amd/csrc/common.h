@@ -135,7 +135,11 @@ hipError_t launch_swiglu_fwd_mfma(const PairCtx &pc, int f, float s, const void 
                                   const float *Pg_all, const float *Pu_all, const void *B_gate,
                                   const void *B_up, const void *A_down, void *a_grp,
                                   float *Q_part, float *Q_all, void *Qw, int ldqw,
-                                  hipStream_t st);
+                                  hipStream_t st, int rows_mode = 0);
+// rows_mode of the fused stages (for the paper's own schedules, Figure 3): bit 0 = G and U hold
+// one row per grouped pair row instead of one per token; bit 1 = H likewise; bit 2 = the
+// block-sparse operand has one row per grouped pair row (unweighted) instead of one per token.
+constexpr int ROWS_GU = 1, ROWS_H = 2, ROWS_SPARSE = 4;
 
 // bf16 MFMA backward of the same stage: dg_grp, du_grp, dw_part[row][split]
 // (split count = fused_splits(f)), TG_all / TU_all at [row, e(row)*r + q].  AdT = A_down re-laid
@@ -145,12 +149,16 @@ hipError_t launch_swiglu_bwd_mfma(const PairCtx &pc, int f, float s, const void 
                                   const float *VB_all, const void *B_gate, const void *B_up,
                                   const void *AdT, const void *BgT, const void *BuT, void *dg_grp,
                                   void *du_grp, float *dw_part, float *rank_part, float *TG_all,
-                                  float *TU_all, void *S, int lds_, hipStream_t st);
+                                  float *TU_all, void *S, int lds_, hipStream_t st,
+                                  int rows_mode = 0);
 int fused_splits(int f);
 
 // out[t,:] = sum_j (weighted ? w[t,j] : 1) * in_grp[row_of_pair[t,j], :]
 hipError_t launch_pair_combine(int dtype, const PairCtx &pc, int width, const void *in_grp,
                                void *out, int weighted, hipStream_t st);
+// dst[row, :] = src[token of grouped row, :]   (width a multiple of 8)
+hipError_t launch_gather_rows(int dtype, const PairCtx &pc, int width, const void *src, void *dst,
+                              hipStream_t st);
 // dst[t, col0 + e_j*r + q] = scale_j * src[row_j, (src_dense ? e_j*r : 0) + q] for the kept
 // experts, 0 elsewhere; dst is in the storage dtype with leading dimension ldd.  nsrc sources
 // (src + b*src_stride, b < nsrc) fill consecutive N*r-column blocks in one launch.
@@ -246,6 +254,7 @@ hipError_t launch_router_bwd(int dtype, const PairCtx &pc, const float *probs, c
                              const float *F, float s, const AuxUpstream &d_aux, float aux_coeff,
                              float *dw_ws, float *dz, void *S, int lds_, int col0, int ncols,
                              int Nl, const int32_t *token_model, const int32_t *model_tokens,
-                             void *dzT, int ldTz, hipStream_t st);   // dzT: bf16 [N][ldTz] copy or NULL
+                             void *dzT, int ldTz, hipStream_t st,    // dzT: bf16 [N][ldTz] copy or NULL
+                             int s_by_first_pair = 0);   // S has one row per grouped pair row
 
 }  // namespace mixlora

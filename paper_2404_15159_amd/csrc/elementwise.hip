@@ -286,6 +286,33 @@ hipError_t launch_pair_combine(int dtype, const PairCtx &pc, int width, const vo
   return hipGetLastError();
 }
 
+// ---- dst[row, :] = src[token of grouped row, :] : the routed tokens' rows in expert-grouped order
+// (the per-expert input slices of the unshared schedule, Section 3.3 / Figure 3a)
+template <typename E>
+__global__ __launch_bounds__(256) void gather_rows_kernel(PairCtx pc, int width,
+                                                          const E *__restrict__ src,
+                                                          E *__restrict__ dst) {
+  const int row = blockIdx.x;
+  const int c = (blockIdx.y * 256 + threadIdx.x) * 8;
+  if (c >= width) return;
+  const int t = pc.pair_of_row[row] / pc.k;
+  Vec8<E> v;
+  v.load(src + (int64_t)t * width + c);
+  v.store(dst + (int64_t)row * width + c);
+}
+
+hipError_t launch_gather_rows(int dtype, const PairCtx &pc, int width, const void *src, void *dst,
+                              hipStream_t st) {
+  const dim3 grid(pc.T * pc.k, (width / 8 + 255) / 256), block(256);
+  if (dtype == MIXLORA_BF16)
+    hipLaunchKernelGGL(gather_rows_kernel<bf16_t>, grid, block, 0, st, pc, width, (const bf16_t *)src,
+                       (bf16_t *)dst);
+  else
+    hipLaunchKernelGGL(gather_rows_kernel<float>, grid, block, 0, st, pc, width, (const float *)src,
+                       (float *)dst);
+  return hipGetLastError();
+}
+
 // dst[t, col0 + e*r + q] = (w[t,j] or 1) * src[row_j, (src_dense ? e*r : 0) + q] when expert e is
 // slot j of token t, else 0.  Builds the block-sparse low-rank operand of a K-extension.
 // blockIdx.y = b handles a further source src + b*src_stride into columns col0 + b*N*r.

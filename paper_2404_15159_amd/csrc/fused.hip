@@ -100,7 +100,7 @@ __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 3 : 1) void swiglu_fwd_mf
     const float *__restrict__ Pg_all, const float *__restrict__ Pu_all,
     const bf16_t *__restrict__ B_gate, const bf16_t *__restrict__ B_up,
     const bf16_t *__restrict__ A_down, bf16_t *__restrict__ a_grp, float *__restrict__ Q_part,
-    int nsplit) {
+    int nsplit, int rows_mode) {
   constexpr int TILES = 2;
   constexpr int LDS_BYTES = FT_WAVES * TILES * FT_TILE * 2 > FT_WAVES * NQ * 16 * 64 * 4
                                 ? FT_WAVES * TILES * FT_TILE * 2 : FT_WAVES * NQ * 16 * 64 * 4;
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 3 : 1) void swiglu_fwd_mf
     const int rl = 8 * p + rr;
     rvalid[p] = rl < rows;
     const int row = row0 + (rvalid[p] ? rl : 0);
-    gsrc[p] = (int64_t)(pc.pair_of_row[row] / pc.k) * f;
+    gsrc[p] = (int64_t)((rows_mode & ROWS_GU) ? row : pc.pair_of_row[row] / pc.k) * f;
     adst[p] = (int64_t)row * f;
   }
   f32x16_t accq[NQ];
@@ -277,7 +277,7 @@ __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 2 : 1) void swiglu_bwd_mf
     const bf16_t *__restrict__ B_gate, const bf16_t *__restrict__ B_up,
     const bf16_t *__restrict__ AdT, const bf16_t *__restrict__ BgT, const bf16_t *__restrict__ BuT,
     bf16_t *__restrict__ dg_grp, bf16_t *__restrict__ du_grp, float *__restrict__ dw_part,
-    float *__restrict__ TG_part, float *__restrict__ TU_part, int nsplit) {
+    float *__restrict__ TG_part, float *__restrict__ TU_part, int nsplit, int rows_mode) {
   constexpr int TILES = 3;
   constexpr int LDS_BYTES = FT_WAVES * TILES * FT_TILE * 2 > FT_WAVES * NQ * 16 * 64 * 4
                                 ? FT_WAVES * TILES * FT_TILE * 2 : FT_WAVES * NQ * 16 * 64 * 4;
@@ -315,11 +315,12 @@ __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 2 : 1) void swiglu_bwd_mf
     rvalid[p] = rl < rows;
     const int row = row0 + (rvalid[p] ? rl : 0);
     const int pair = pc.pair_of_row[row];
-    gsrc[p] = (int64_t)(pair / pc.k) * f;
+    gsrc[p] = (int64_t)((rows_mode & ROWS_GU) ? row : pair / pc.k) * f;
     odst[p] = (int64_t)row * f;
     wrow[p] = pc.w[pair];
     dwacc[p] = 0.f;
   }
+  const bool h_by_row = (rows_mode & ROWS_H) != 0;
   f32x16_t acctg[NQ], acctu[NQ];
 #pragma unroll
   for (int j = 0; j < NQ; j++)
@@ -373,7 +374,7 @@ __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 2 : 1) void swiglu_bwd_mf
     const int64_t o = gsrc[p] + col_of(sb_first * FT_SB);
     gnx[p] = ld8(G + o);
     unx[p] = ld8(U + o);
-    hnx[p] = ld8(H + o);
+    hnx[p] = ld8(H + (h_by_row ? odst[p] : gsrc[p]) + col_of(sb_first * FT_SB));
   }
   load_wt(sb_first * FT_SB);
 
@@ -423,7 +424,7 @@ __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 2 : 1) void swiglu_bwd_mf
         const int64_t o = gsrc[p] + col_of(cn);
         gnx[p] = ld8(G + o);
         unx[p] = ld8(U + o);
-        hnx[p] = ld8(H + o);
+        hnx[p] = ld8(H + (h_by_row ? odst[p] : gsrc[p]) + col_of(cn));
       }
       if (rvalid[p] && cvalid) {
         *reinterpret_cast<bf16x8_t *>(dg_grp + odst[p] + col) = dgv;
@@ -485,12 +486,13 @@ __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 2 : 1) void swiglu_bwd_mf
 // picks the bank (partials bank_stride floats apart, outputs dense0 / dense1).  The same value
 // (times the routing weight if weighted) also goes, as bf16, into the block-sparse per-token
 // operand of a K-extension:  sparse[t(row), col0 + bank*N*r + e*r + q]; the rest of that
-// operand was zero-filled beforehand.
+// operand was zero-filled beforehand.  With by_row the operand has one row per grouped pair row
+// (sparse[row, ...]) instead of one per token.
 __global__ void reduce_rank_parts_kernel(PairCtx pc, const float *__restrict__ part0,
                                          int64_t bank_stride, int nsplit,
                                          float *__restrict__ dense0, float *__restrict__ dense1,
                                          bf16_t *__restrict__ sparse, int ld_sparse, int col0,
-                                         int weighted) {
+                                         int weighted, int by_row) {
   const int nP = pc.T * pc.k, r = pc.r;
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= (int64_t)nP * r) return;
@@ -510,7 +512,8 @@ __global__ void reduce_rank_parts_kernel(PairCtx pc, const float *__restrict__ p
   const int R = pc.N * r;
   dense[(int64_t)row * R + e * r + q] = acc;
   const float wv = weighted ? pc.w[pair] : 1.f;
-  sparse[(int64_t)(pair / pc.k) * ld_sparse + col0 + blockIdx.y * R + e * r + q] = (bf16_t)(wv * acc);
+  sparse[(int64_t)(by_row ? row : pair / pc.k) * ld_sparse + col0 + blockIdx.y * R + e * r + q] =
+      (bf16_t)(wv * acc);
 }
 
 int fused_splits(int f) {
@@ -524,13 +527,14 @@ hipError_t launch_swiglu_fwd_mfma(const PairCtx &pc, int f, float s, const void 
                                   const float *Pg_all, const float *Pu_all, const void *B_gate,
                                   const void *B_up, const void *A_down, void *a_grp,
                                   float *Q_part, float *Q_all, void *Qw, int ldqw,
-                                  hipStream_t st) {
+                                  hipStream_t st, int rows_mode) {
   const int nP = pc.T * pc.k, nsplit = fused_splits(f);
   const dim3 grid((nP + FT_ROWS - 1) / FT_ROWS + pc.N, nsplit), block(FT_WAVES * 64);
 #define MIXLORA_FWD(KSR_, NQ_)                                                                   \
   hipLaunchKernelGGL((swiglu_fwd_mfma_kernel<KSR_, NQ_>), grid, block, 0, st, pc, f, s,           \
                      (const bf16_t *)G, (const bf16_t *)U, Pg_all, Pu_all, (const bf16_t *)B_gate, \
-                     (const bf16_t *)B_up, (const bf16_t *)A_down, (bf16_t *)a_grp, Q_part, nsplit)
+                     (const bf16_t *)B_up, (const bf16_t *)A_down, (bf16_t *)a_grp, Q_part, nsplit, \
+                     rows_mode)
   if (pc.r <= 16) MIXLORA_FWD(1, 1);
   else if (pc.r <= 32) MIXLORA_FWD(2, 1);
   else MIXLORA_FWD(4, 2);
@@ -539,7 +543,8 @@ hipError_t launch_swiglu_fwd_mfma(const PairCtx &pc, int f, float s, const void 
   if (e != hipSuccess) return e;
   const int64_t n = (int64_t)nP * pc.r;
   hipLaunchKernelGGL(reduce_rank_parts_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                     pc, Q_part, (int64_t)0, nsplit, Q_all, Q_all, (bf16_t *)Qw, ldqw, 0, 1);
+                     pc, Q_part, (int64_t)0, nsplit, Q_all, Q_all, (bf16_t *)Qw, ldqw, 0,
+                     (rows_mode & ROWS_SPARSE) ? 0 : 1, (rows_mode & ROWS_SPARSE) ? 1 : 0);
   return hipGetLastError();
 }
 
@@ -548,7 +553,7 @@ hipError_t launch_swiglu_bwd_mfma(const PairCtx &pc, int f, float s, const void 
                                   const float *VB_all, const void *B_gate, const void *B_up,
                                   const void *AdT, const void *BgT, const void *BuT, void *dg_grp,
                                   void *du_grp, float *dw_part, float *rank_part, float *TG_all,
-                                  float *TU_all, void *S, int lds_, hipStream_t st) {
+                                  float *TU_all, void *S, int lds_, hipStream_t st, int rows_mode) {
   const int nP = pc.T * pc.k, nsplit = fused_splits(f);
   float *TG_part = rank_part, *TU_part = rank_part + (size_t)8 * nP * pc.r;
   const dim3 grid((nP + FT_ROWS - 1) / FT_ROWS + pc.N, nsplit), block(FT_WAVES * 64);
@@ -557,7 +562,7 @@ hipError_t launch_swiglu_bwd_mfma(const PairCtx &pc, int f, float s, const void 
                      (const bf16_t *)G, (const bf16_t *)U, (const bf16_t *)H, Pg_all, Pu_all,      \
                      VB_all, (const bf16_t *)B_gate, (const bf16_t *)B_up, (const bf16_t *)AdT,    \
                      (const bf16_t *)BgT, (const bf16_t *)BuT, (bf16_t *)dg_grp, (bf16_t *)du_grp, \
-                     dw_part, TG_part, TU_part, nsplit)
+                     dw_part, TG_part, TU_part, nsplit, rows_mode)
   if (pc.r <= 16) MIXLORA_BWD(1, 1);
   else if (pc.r <= 32) MIXLORA_BWD(2, 1);
   else MIXLORA_BWD(4, 2);
@@ -567,7 +572,8 @@ hipError_t launch_swiglu_bwd_mfma(const PairCtx &pc, int f, float s, const void 
   const int64_t n = (int64_t)nP * pc.r;
   const dim3 rgrid((unsigned)((n + 255) / 256), 2);
   hipLaunchKernelGGL(reduce_rank_parts_kernel, rgrid, dim3(256), 0, st, pc, TG_part,
-                     (int64_t)(TU_part - TG_part), nsplit, TG_all, TU_all, (bf16_t *)S, lds_, 0, 0);
+                     (int64_t)(TU_part - TG_part), nsplit, TG_all, TU_all, (bf16_t *)S, lds_, 0, 0,
+                     (rows_mode & ROWS_SPARSE) ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -402,7 +402,8 @@ __global__ __launch_bounds__(256) void router_bwd_kernel(
     const float *__restrict__ F, float s, AuxUpstream d_aux, float aux_coeff,
     float *__restrict__ dw_ws, float *__restrict__ dz, E *__restrict__ S, int lds_, int col0,
     int ncols, int Nl, const int32_t *__restrict__ token_model,
-    const int32_t *__restrict__ model_tokens, bf16_t *__restrict__ dzT, int ldTz) {
+    const int32_t *__restrict__ model_tokens, bf16_t *__restrict__ dzT, int ldTz,
+    int s_by_first_pair) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= pc.T) return;   // whole wave leaves together
@@ -446,8 +447,11 @@ __global__ __launch_bounds__(256) void router_bwd_kernel(
     // transposed bf16 copy: the row factor of the dW_router outer-product sum
     if (dzT) dzT[(int64_t)lane * ldTz + t] = (bf16_t)v;
   }
+  // row of the K-extension operand: the token's, or (operand with one row per grouped pair row)
+  // the row of the token's first slot, whose other rows keep zeros in these columns
+  const int64_t srow = s_by_first_pair ? pc.row_of_pair[t * pc.k] : t;
   for (int e = lane; e < ncols; e += 64)
-    S[(int64_t)t * lds_ + col0 + e] = from_f32<E>(e < N ? v : 0.f);
+    S[srow * lds_ + col0 + e] = from_f32<E>(e < N ? v : 0.f);
 }
 
 hipError_t launch_router_bwd(int dtype, const PairCtx &pc, const float *probs, const float *dw_part,
@@ -455,16 +459,18 @@ hipError_t launch_router_bwd(int dtype, const PairCtx &pc, const float *probs, c
                              const float *F, float s, const AuxUpstream &d_aux, float aux_coeff,
                              float *dw_ws, float *dz, void *S, int lds_, int col0, int ncols,
                              int Nl, const int32_t *token_model, const int32_t *model_tokens,
-                             void *dzT, int ldTz, hipStream_t st) {
+                             void *dzT, int ldTz, hipStream_t st, int s_by_first_pair) {
   const dim3 grid((pc.T + 3) / 4), block(256);
   if (dtype == MIXLORA_BF16)
     hipLaunchKernelGGL(router_bwd_kernel<bf16_t>, grid, block, 0, st, pc, probs, dw_part,
                        n_col_tiles, VB_all, Q_all, F, s, d_aux, aux_coeff, dw_ws, dz, (bf16_t *)S,
-                       lds_, col0, ncols, Nl, token_model, model_tokens, (bf16_t *)dzT, ldTz);
+                       lds_, col0, ncols, Nl, token_model, model_tokens, (bf16_t *)dzT, ldTz,
+                       s_by_first_pair);
   else
     hipLaunchKernelGGL(router_bwd_kernel<float>, grid, block, 0, st, pc, probs, dw_part,
                        n_col_tiles, VB_all, Q_all, F, s, d_aux, aux_coeff, dw_ws, dz, (float *)S,
-                       lds_, col0, ncols, Nl, token_model, model_tokens, (bf16_t *)dzT, ldTz);
+                       lds_, col0, ncols, Nl, token_model, model_tokens, (bf16_t *)dzT, ldTz,
+                       s_by_first_pair);
   return hipGetLastError();
 }
 

@@ -24,11 +24,16 @@ class MixLoraFFN:
 
     def __init__(self, cfg: synth.Config, host: Dict[str, np.ndarray], aux_mode: int = B.AUX_TOP1,
                  pretransposed: bool = True, with_backward: bool = True, device: str = "cuda:0",
-                 token_model: Optional[np.ndarray] = None, d_aux=None):
+                 token_model: Optional[np.ndarray] = None, d_aux=None,
+                 schedule: int = B.SCHEDULE_LINEAR_DOWN):
         """With cfg.M > 1 (several adapters on one frozen base) token_model [T] is required and
-        the multi-adapter entry points are used; the banks then hold M*N experts."""
+        the multi-adapter entry points are used; the banks then hold M*N experts.  A schedule
+        other than SCHEDULE_LINEAR_DOWN goes through the *_schedule entry points (one adapter)."""
         B.load()
         self.cfg = cfg
+        self.schedule = int(schedule)
+        if self.schedule != B.SCHEDULE_LINEAR_DOWN and cfg.M > 1:
+            raise ValueError("the paper's schedules are built for one adapter")
         self.M = cfg.M
         if (cfg.M > 1) != (token_model is not None):
             raise ValueError("token_model goes with cfg.M > 1")
@@ -51,8 +56,11 @@ class MixLoraFFN:
                 B.mixlora_transpose(self.t[n], out, rows, cols, self.dims.dtype)
                 self.t[n + "_T"] = out
         self.weights = B.make_weights(self.t)
-        self.ws_bytes = (B.mixlora_multi_workspace_bytes(self.dims, cfg.M, with_backward)
-                         if self.multi else B.mixlora_workspace_bytes(self.dims, with_backward))
+        if self.schedule != B.SCHEDULE_LINEAR_DOWN:
+            self.ws_bytes = B.mixlora_schedule_workspace_bytes(self.dims, self.schedule, with_backward)
+        else:
+            self.ws_bytes = (B.mixlora_multi_workspace_bytes(self.dims, cfg.M, with_backward)
+                             if self.multi else B.mixlora_workspace_bytes(self.dims, with_backward))
         if self.ws_bytes == 0:
             raise ValueError("dims rejected by mixlora_workspace_bytes")
         self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.dev)
@@ -76,6 +84,12 @@ class MixLoraFFN:
                                     self.topk_w, self.counts, self.aux, self.workspace,
                                     self.ws_bytes, stream)
             return
+        if self.schedule != B.SCHEDULE_LINEAR_DOWN:
+            B.mixlora_ffn_forward_schedule(self.dims, self.schedule, self.weights,
+                                           self.t["x"] if x is None else x, self.y, self.topk_idx,
+                                           self.topk_w, self.counts, self.aux, self.workspace,
+                                           self.ws_bytes, stream)
+            return
         B.mixlora_ffn_forward(self.dims, self.weights, self.t["x"] if x is None else x, self.y,
                               self.topk_idx, self.topk_w, self.counts, self.aux, self.workspace,
                               self.ws_bytes, stream)
@@ -85,6 +99,11 @@ class MixLoraFFN:
             B.mixlora_multi_backward(self.dims, self.multi, self.weights, self.t["x"],
                                      self.t["dy"] if dy is None else dy, self.workspace,
                                      self.ws_bytes, self.dx, self.grads, stream)
+            return
+        if self.schedule != B.SCHEDULE_LINEAR_DOWN:
+            B.mixlora_ffn_backward_schedule(self.dims, self.schedule, self.weights, self.t["x"],
+                                            self.t["dy"] if dy is None else dy, d_aux,
+                                            self.workspace, self.ws_bytes, self.dx, self.grads, stream)
             return
         B.mixlora_ffn_backward(self.dims, self.weights, self.t["x"],
                                self.t["dy"] if dy is None else dy, d_aux, self.workspace,

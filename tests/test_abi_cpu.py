@@ -99,6 +99,43 @@ def test_backward_argument_errors(lib):
     assert code(workspace_bytes=fwd_only) == -5
 
 
+def test_schedule_entry_points(lib):
+    """The paper's own schedules: workspace grows with the per-pair rows, bad schedules / dtypes /
+    workspaces are rejected on the host."""
+    d = dims()
+    ws = [B.mixlora_schedule_workspace_bytes(d, sch, True)
+          for sch in (B.SCHEDULE_LINEAR_DOWN, B.SCHEDULE_SHARED, B.SCHEDULE_VANILLA)]
+    assert ws[0] == B.mixlora_workspace_bytes(d, True)
+    assert ws[0] < ws[1] < ws[2]
+    # shared: the down projection's output and its backward input exist per pair row [kT, d]
+    assert ws[1] - ws[0] >= 2 * (2 * 4096) * 4096 * 2
+    # unshared: also the gathered token rows [kT, d] and their gradient [kT, d]
+    assert ws[2] - ws[1] >= 2 * (2 * 4096) * 4096 * 2
+    assert B.mixlora_schedule_workspace_bytes(d, 3, True) == 0
+    assert B.mixlora_schedule_workspace_bytes(d, -1, True) == 0
+    assert B.mixlora_schedule_workspace_bytes(dims(dtype=B.F32), B.SCHEDULE_SHARED, True) == 0
+    assert B.mixlora_schedule_workspace_bytes(dims(dtype=B.F32), B.SCHEDULE_LINEAR_DOWN, True) > 0
+
+    def fcode(dd, sch, **kw):
+        with pytest.raises(B.MixLoraError) as ei:
+            B.mixlora_ffn_forward_schedule(dd, sch, fake_weights(), stream=0, **fwd_args(**kw))
+        return ei.value.code
+
+    assert fcode(d, 5) == -2
+    assert fcode(dims(dtype=B.F32), B.SCHEDULE_VANILLA) == -3
+    assert fcode(d, B.SCHEDULE_SHARED, y=None) == -1
+    assert fcode(d, B.SCHEDULE_VANILLA, workspace_bytes=B.mixlora_workspace_bytes(d, False)) == -5
+    g = B.make_grads({n: FAKE for n in B.GRAD_FIELDS})
+    with pytest.raises(B.MixLoraError) as ei:
+        B.mixlora_ffn_backward_schedule(d, B.SCHEDULE_VANILLA, fake_weights(), FAKE, FAKE, 1.0, FAKE,
+                                        ws[0], FAKE, g, stream=0)
+    assert ei.value.code == -5
+    with pytest.raises(B.MixLoraError) as ei:
+        B.mixlora_ffn_backward_schedule(d, 9, fake_weights(), FAKE, FAKE, 1.0, FAKE, 1 << 40, FAKE,
+                                        g, stream=0)
+    assert ei.value.code == -2
+
+
 def test_aux_and_transpose_argument_errors(lib):
     with pytest.raises(B.MixLoraError) as ei:
         B.mixlora_aux_loss(FAKE, FAKE, 16, 4, 5, 0.01, 0, FAKE, stream=0)
