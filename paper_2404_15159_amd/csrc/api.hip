@@ -227,8 +227,8 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
     add_seg(p[2], x, d, w->A_gate, d, d);
     add_seg(p[3], x, d, w->A_up, d, d);
     add_seg(p[4], x, d, w->W_router, d, d);
-    if (vanilla)   // unshared schedule: the frozen gate/up products follow the routing, per pair
-      HIP_TRY(launch_gemm(dt, p + 2, 3, st));
+    if (vanilla)   // unshared schedule: the frozen gate/up products follow the routing, per pair;
+      HIP_TRY(launch_gemm(dt, p + 4, 1, st));   // only the router logits are needed up front
     else
       HIP_TRY(launch_gemm(dt, p, dt == MIXLORA_BF16 ? 5 : 4, st));
   }
@@ -263,10 +263,19 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
     int rows_mode = ROWS_SPARSE;
     if (vanilla) {
       HIP_TRY(launch_gather_rows(dt, pc, d, x, ws + L.Xp, st));
-      GemmProblem p[2] = {problem(kT, f, ws + L.Gp, f, 0), problem(kT, f, ws + L.Up, f, 0)};
+      // the LoRA A projections of every expert (per token) ride in the same launch
+      GemmProblem p[4] = {problem(kT, f, ws + L.Gp, f, 0), problem(kT, f, ws + L.Up, f, 0),
+                          problem(T, R, ws + L.Pg_all, R, 1), problem(T, R, ws + L.Pu_all, R, 1)};
       add_seg(p[0], ws + L.Xp, d, w->W_gate, d, d);
       add_seg(p[1], ws + L.Xp, d, w->W_up, d, d);
-      HIP_TRY(launch_gemm(dt, p, 2, st));
+      add_seg(p[2], x, d, w->A_gate, d, d);
+      add_seg(p[3], x, d, w->A_up, d, d);
+      if (gemm_mixed_rows_ok(dt, p, 4)) {
+        HIP_TRY(launch_gemm(dt, p, 4, st));
+      } else {   // shapes outside the large-tile kernel: problems of different M go separately
+        HIP_TRY(launch_gemm(dt, p, 2, st));
+        HIP_TRY(launch_gemm(dt, p + 2, 2, st));
+      }
       Gsrc = ws + L.Gp;
       Usrc = ws + L.Up;
       rows_mode |= ROWS_GU;
@@ -459,12 +468,15 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
     // the paper's schedules: the frozen down projection is differentiated per pair row
     // (k rows per token); the routing weight is applied inside the fused stage as before
     HIP_TRY(launch_gather_rows(dt, pc, d, dy, ws + L.dYp, st));
-    GemmProblem ph = problem(kT, f, ws + L.Hp, f, 0);
-    add_seg(ph, ws + L.dYp, d, WdT, d, d);
-    HIP_TRY(launch_gemm(dt, &ph, 1, st));
-    GemmProblem pv = problem(T, R, ws + L.VB_all, R, 1);
-    add_seg(pv, dy, d, ws + L.Bd_T, d, d);
-    HIP_TRY(launch_gemm(dt, &pv, 1, st));
+    GemmProblem p[2] = {problem(kT, f, ws + L.Hp, f, 0), problem(T, R, ws + L.VB_all, R, 1)};
+    add_seg(p[0], ws + L.dYp, d, WdT, d, d);
+    add_seg(p[1], dy, d, ws + L.Bd_T, d, d);
+    if (gemm_mixed_rows_ok(dt, p, 2)) {
+      HIP_TRY(launch_gemm(dt, p, 2, st));
+    } else {   // shapes outside the large-tile kernel: problems of different M go separately
+      HIP_TRY(launch_gemm(dt, p, 1, st));
+      HIP_TRY(launch_gemm(dt, p + 1, 1, st));
+    }
   } else {
     GemmProblem p[2] = {problem(T, f, ws + L.H, f, 0), problem(T, R, ws + L.VB_all, R, 1)};
     add_seg(p[0], dy, d, WdT, d, d);

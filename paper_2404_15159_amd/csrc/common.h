@@ -65,10 +65,13 @@ struct GemmProblem {
   int64_t ldc;
   int c_f32;  // 1: C is float32 regardless of the storage dtype
 };
-// Enqueue up to GEMM_MAX_PROBLEMS independent problems of identical M in one launch (N and the
-// output type may differ per problem).
+// Enqueue up to GEMM_MAX_PROBLEMS independent problems in one launch (N and the output type may
+// differ per problem; M too when the launch qualifies for the large-tile bf16 kernel, i.e. every
+// M > 128, some N > 128 and every K a multiple of 64 - otherwise differing M is an error).
 constexpr int GEMM_MAX_PROBLEMS = 8;
 hipError_t launch_gemm(int dtype, const GemmProblem *probs, int nprob, hipStream_t st);
+// whether problems of different M may share one launch_gemm call
+bool gemm_mixed_rows_ok(int dtype, const GemmProblem *probs, int nprob);
 
 // Measurement hook: HIP-event timing of every launch of the large-tile bf16 kernel between
 // begin and end (events are recorded on the launch stream).  Not thread-safe; off by default.

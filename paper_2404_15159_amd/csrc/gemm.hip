@@ -566,9 +566,9 @@ static hipError_t launch_bf16(const GemmBatch &b, int nprob, hipStream_t st) {
     attr_set = true;
   }
   const int tiles = ((b.p[0].M + BM - 1) / BM) * ((b.p[0].N + BN - 1) / BN);
-  // every launch of this kernel family is a frozen-projection launch (large tiles at training
-  // shapes, the narrow weight-streaming tiles at decode shapes): all are timed
-  const bool timed = g_timer.on && g_timer.used < g_timer.cap;
+  // launches that carry a frozen projection (more than 128 output columns) are timed; a launch
+  // of narrow rank-r or router problems alone is not
+  const bool timed = g_timer.on && g_timer.used < g_timer.cap && b.p[0].N > 128;
   if (timed) (void)hipEventRecord(g_timer.beg[g_timer.used], st);
   hipLaunchKernelGGL(kern, dim3(tiles, 1, nprob), dim3(WGM * WGN * 64), smem, st, b);
   if (timed) {
@@ -624,17 +624,35 @@ static bool dl_eligible(const GemmBatch &b, int nprob, int BK) {
   return true;
 }
 
+bool gemm_mixed_rows_ok(int dtype, const GemmProblem *probs, int nprob) {
+  if (dtype != MIXLORA_BF16 || nprob < 1 || nprob > GEMM_MAX_PROBLEMS) return false;
+  GemmBatch b;
+  bool any_big = false;
+  for (int i = 0; i < GEMM_MAX_PROBLEMS; i++) b.p[i] = probs[i < nprob ? i : 0];
+  for (int i = 0; i < nprob; i++) {
+    if (probs[i].M <= 128 || probs[i].N <= 0) return false;
+    if (probs[i].N > 128) any_big = true;
+  }
+  return any_big && dl_eligible(b, nprob, 64);
+}
+
 hipError_t launch_gemm(int dtype, const GemmProblem *probs, int nprob, hipStream_t st) {
   if (nprob < 1 || nprob > GEMM_MAX_PROBLEMS) return hipErrorInvalidValue;
   GemmBatch b;
   for (int i = 0; i < GEMM_MAX_PROBLEMS; i++) b.p[i] = probs[i < nprob ? i : 0];
   const int M = probs[0].M, N = probs[0].N;
-  bool uniform = true, any_big = false;
+  bool uniform = true, any_big = false, same_m = true;
   for (int i = 0; i < nprob; i++) {
-    if (probs[i].M != M) return hipErrorInvalidValue;
+    if (probs[i].M != M) same_m = false;
     if (probs[i].N != N || probs[i].c_f32 != probs[0].c_f32) uniform = false;
     if (probs[i].N > 128) any_big = true;
     if (probs[i].N <= 0) return hipErrorInvalidValue;
+  }
+  if (!same_m) {
+    // problems of different row counts (per-token and per-pair operands) can share a launch of
+    // the large-tile kernel only: every tile takes M from its own problem
+    if (!gemm_mixed_rows_ok(dtype, probs, nprob)) return hipErrorInvalidValue;
+    return launch_bf16_dl<256, 256, 64, 2, 2, 4, true>(b, nprob, st);
   }
   if (M <= 0) return hipSuccess;
   if (dtype == MIXLORA_BF16 && M > 128 && any_big) {
