@@ -18,13 +18,17 @@ constexpr size_t SPLITK_MAX_ROWS = 128;   // at most this many tokens: the down 
 inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 inline int up64(int v) { return (v + 63) / 64 * 64; }
 
+// Up to this many (token, expert) pairs the grouping runs in one workgroup (bound by its own
+// latency); longer batches use the multi-workgroup passes.
+constexpr size_t GROUP_SINGLE_WG_PAIRS = 8192;
+
 struct Layout {
   // saved by forward
   size_t probs, Z, idx, w, counts, first_counts, offs, row_of_pair, pair_of_row, F, P, tok_offs,
       model_tokens;
   size_t G, U, Pg_all, Pu_all, a_grp, Q_all;
   // forward scratch
-  size_t a_comb, Qw, Bd_cat, rank_part, splitk;
+  size_t a_comb, Qw, Bd_cat, rank_part, splitk, gp_scratch;
   size_t fwd_end;
   // backward scratch
   size_t WdT, WgT, WuT, H, Bd_T, VB_all, dg_grp, du_grp, dgsum, dusum, dw_part, dw, Bg_T, Bu_T, AdT,
@@ -79,6 +83,7 @@ Layout make_layout(const mixlora_dims &D, int schedule = MIXLORA_SCHEDULE_LINEAR
   L.rank_part = take(2 * 8 * kT * r * 4);   // per-split rank-r partial sums (two banks)
   // few tokens (decode-shaped calls): partial outputs of the K-split down projection
   L.splitk = take(T <= SPLITK_MAX_ROWS ? (size_t)GEMM_MAX_PROBLEMS * T * d * 4 : 0);
+  L.gp_scratch = take(kT > GROUP_SINGLE_WG_PAIRS ? group_pairs_scratch_bytes((int)T, (int)k) : 0);
   L.fwd_end = o;
   L.Kx = up64((int)(2 * R) + (int)N);   // whole K tiles of the GEMM's DMA path
   L.nct = swiglu_col_tiles((int)f);
@@ -240,11 +245,19 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
     HIP_TRY(launch_router(dt, x, w->W_router, T, d, N, k, probs, topk_idx, topk_w, idx, wts, Nl,
                           token_model, st));
   // grouping of the pairs by expert and Eq. 8-9, one launch
-  HIP_TRY(launch_group_pairs_aux(idx, T, N, k, (int32_t *)(ws + L.counts), expert_counts,
-                                 (int32_t *)(ws + L.first_counts), offs, row_of_pair, pair_of_row,
-                                 (int32_t *)(ws + L.tok_offs), probs, D.aux_coeff, D.aux_mode,
-                                 aux_loss, (float *)(ws + L.F), (float *)(ws + L.P), Nl, token_model,
-                                 (int32_t *)(ws + L.model_tokens), st));
+  if ((size_t)kT > GROUP_SINGLE_WG_PAIRS)
+    HIP_TRY(launch_group_pairs_aux_multi(idx, T, N, k, (int32_t *)(ws + L.counts), expert_counts,
+                                         (int32_t *)(ws + L.first_counts), offs, row_of_pair,
+                                         pair_of_row, (int32_t *)(ws + L.tok_offs), probs,
+                                         D.aux_coeff, D.aux_mode, aux_loss, (float *)(ws + L.F),
+                                         (float *)(ws + L.P), Nl, token_model,
+                                         (int32_t *)(ws + L.model_tokens), ws + L.gp_scratch, st));
+  else
+    HIP_TRY(launch_group_pairs_aux(idx, T, N, k, (int32_t *)(ws + L.counts), expert_counts,
+                                   (int32_t *)(ws + L.first_counts), offs, row_of_pair, pair_of_row,
+                                   (int32_t *)(ws + L.tok_offs), probs, D.aux_coeff, D.aux_mode,
+                                   aux_loss, (float *)(ws + L.F), (float *)(ws + L.P), Nl, token_model,
+                                   (int32_t *)(ws + L.model_tokens), st));
   PairCtx pc{offs, pair_of_row, row_of_pair, wts, idx, T, N, k, r};
   {
     // s * B_down packed for the K-extension of the down GEMM; in bf16 also zeros for the

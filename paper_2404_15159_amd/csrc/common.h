@@ -101,6 +101,17 @@ hipError_t launch_group_pairs_aux(const int32_t *idx, int T, int N, int k, int32
                                   const float *probs, float coeff, int mode, float *loss, float *F,
                                   float *P, int Nl, const int32_t *token_model,
                                   int32_t *model_tokens, hipStream_t st);
+// The same over many workgroups, for long token batches (identical row maps; the probability
+// sums of Eq. 9 are added in a different, equally fixed order).  scratch:
+// group_pairs_scratch_bytes(T, k) bytes.
+size_t group_pairs_scratch_bytes(int T, int k);
+hipError_t launch_group_pairs_aux_multi(const int32_t *idx, int T, int N, int k, int32_t *counts,
+                                        int32_t *counts_out, int32_t *first_counts, int32_t *offs,
+                                        int32_t *row_of_pair, int32_t *pair_of_row,
+                                        int32_t *tok_offs, const float *probs, float coeff, int mode,
+                                        float *loss, float *F, float *P, int Nl,
+                                        const int32_t *token_model, int32_t *model_tokens,
+                                        void *scratch, hipStream_t st);
 // loss[N / Nl], one per adapter (statistics over the adapter's own tokens); model_tokens (may be
 // NULL) receives the token count of every adapter.
 hipError_t launch_aux_loss(const float *probs, const int32_t *idx, int T, int N, int k,

@@ -370,6 +370,206 @@ hipError_t launch_group_pairs_aux(const int32_t *idx, int T, int N, int k, int32
   return hipGetLastError();
 }
 
+// ---- grouping and auxiliary loss over many workgroups (long token batches) --------------------
+// The pairs are cut into chunks of GPM_CHUNK; one wavefront owns a chunk.  Pass 1 counts the
+// chunk's pairs per expert (all slots and first slots) and sums its share of the tokens' router
+// probabilities and adapter ids; pass 2 (one workgroup) turns the counts into every chunk's
+// first row per expert - chunks in ascending order inside an expert, so the row order is the
+// same stable order the single-workgroup kernel produces - and finishes Eq. 8-9; pass 3 places
+// the pairs.  All sums run in a fixed order.  scratch: 4 arrays of [chunks][64] 4-byte words.
+constexpr int GPM_CHUNK = 256;
+
+size_t group_pairs_scratch_bytes(int T, int k) {
+  const size_t chunks = ((size_t)T * k + GPM_CHUNK - 1) / GPM_CHUNK;
+  return chunks * 64 * 4 * 4;
+}
+
+__global__ __launch_bounds__(256) void gpm_count_kernel(
+    const int32_t *__restrict__ idx, int T, int N, int k, int chunks,
+    const float *__restrict__ probs, const int32_t *__restrict__ token_model, int M,
+    int32_t *__restrict__ tot, int32_t *__restrict__ first, float *__restrict__ psum,
+    int32_t *__restrict__ tmc) {
+  const int lane = threadIdx.x & 63;
+  const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (c >= chunks) return;
+  const int nP = T * k;
+  int cnt = 0, fcnt = 0;
+#pragma unroll
+  for (int st = 0; st < GPM_CHUNK / 64; st++) {
+    const int p = c * GPM_CHUNK + st * 64 + lane;
+    const int e = p < nP ? idx[p] : -1;
+    const bool is_first = (p % k) == 0;
+    for (int n = 0; n < N; n++) {
+      const unsigned long long b = __ballot(e == n);
+      const unsigned long long bf = __ballot(e == n && is_first);
+      if (lane == n) { cnt += __popcll(b); fcnt += __popcll(bf); }
+    }
+  }
+  tot[(int64_t)c * 64 + lane] = cnt;
+  first[(int64_t)c * 64 + lane] = fcnt;
+  // this chunk's share of the tokens
+  const int tw = (T + chunks - 1) / chunks;
+  const int t0 = c * tw, t1 = t0 + tw < T ? t0 + tw : T;
+  const int G = 64 / N, e = lane % N, g = lane / N;
+  float s = 0.f;
+  if (g < G)
+    for (int t = t0 + g; t < t1; t += G) s += probs[(int64_t)t * N + e];
+  float acc = 0.f;
+  for (int gg = 0; gg < G; gg++) acc += __shfl(s, (e + gg * N) & 63, 64);   // ascending gg
+  psum[(int64_t)c * 64 + lane] = lane < N ? acc : 0.f;
+  int tmcnt = 0;
+  if (token_model) {
+    for (int tb = t0; tb < t1; tb += 64) {
+      const int t = tb + lane;
+      const int m = t < t1 ? token_model[t] : -1;
+      for (int n = 0; n < M; n++) {
+        const unsigned long long b = __ballot(m == n);
+        if (lane == n) tmcnt += __popcll(b);
+      }
+    }
+  } else if (lane == 0) {
+    tmcnt = t1 > t0 ? t1 - t0 : 0;
+  }
+  tmc[(int64_t)c * 64 + lane] = tmcnt;
+}
+
+__global__ __launch_bounds__(1024) void gpm_scan_kernel(
+    int T, int N, int k, int chunks, int32_t *__restrict__ tot, const int32_t *__restrict__ first,
+    const float *__restrict__ psum, const int32_t *__restrict__ tmc, int32_t *__restrict__ counts,
+    int32_t *__restrict__ counts_out, int32_t *__restrict__ first_counts,
+    int32_t *__restrict__ offs, int32_t *__restrict__ tok_offs, float coeff, int mode,
+    float *__restrict__ loss, float *__restrict__ F_out, float *__restrict__ P_out, int Nl,
+    int32_t *__restrict__ model_tokens) {
+  __shared__ int seg_tot[16][64], seg_first[16][64], seg_tm[16][64];
+  __shared__ float seg_p[16][64];
+  __shared__ int eoffs[64], tmtot[64];
+  __shared__ float fp[64];
+  const int n = threadIdx.x & 63, seg = threadIdx.x >> 6;
+  const int cs = (chunks + 15) / 16;
+  const int c0 = seg * cs, c1 = c0 + cs < chunks ? c0 + cs : chunks;
+  int st = 0, sf = 0, sm = 0;
+  float sp = 0.f;
+  for (int c = c0; c < c1; c++) {
+    st += tot[(int64_t)c * 64 + n];
+    sf += first[(int64_t)c * 64 + n];
+    sm += tmc[(int64_t)c * 64 + n];
+    sp += psum[(int64_t)c * 64 + n];
+  }
+  seg_tot[seg][n] = st;
+  seg_first[seg][n] = sf;
+  seg_tm[seg][n] = sm;
+  seg_p[seg][n] = sp;
+  __syncthreads();
+  const int M = N / Nl;
+  int c = 0, fc = 0;
+  float ps = 0.f;
+  if (threadIdx.x < 64) {
+    int tmv = 0;
+    for (int s2 = 0; s2 < 16; s2++) {
+      c += seg_tot[s2][n];
+      fc += seg_first[s2][n];
+      tmv += seg_tm[s2][n];
+      ps += seg_p[s2][n];
+    }
+    if (n >= N) c = 0;
+    int incl = c;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int v = __shfl_up(incl, o, 64);
+      if (n >= o) incl += v;
+    }
+    eoffs[n] = incl - c;
+    tmtot[n] = tmv;
+    if (n < N) {
+      counts[n] = c;
+      if (counts_out) counts_out[n] = c;
+      first_counts[n] = fc;
+      offs[n] = incl - c;
+      if (n == N - 1) offs[N] = incl;
+    }
+    if (n == 0) { tok_offs[0] = 0; tok_offs[1] = T; }
+  }
+  __syncthreads();
+  if (threadIdx.x < N) {
+    const int Tm = tmtot[n / Nl];
+    const float denom = mode == MIXLORA_AUX_TOP1 ? (float)Tm : (float)Tm * (float)k;
+    const float P = Tm > 0 ? ps / (float)Tm : 0.f;
+    const float F = Tm > 0 ? (float)(mode == MIXLORA_AUX_TOP1 ? fc : c) / denom : 0.f;
+    if (P_out) P_out[n] = P;
+    if (F_out) F_out[n] = F;
+    fp[n] = F * P;
+  }
+  __syncthreads();
+  if (threadIdx.x < M) {
+    float acc = 0.f;
+    for (int q = 0; q < Nl; q++) acc += fp[n * Nl + q];
+    loss[n] = coeff * (float)Nl * acc;
+    if (model_tokens) model_tokens[n] = tmtot[n];
+  }
+  // first row of every chunk per expert, written over the chunk's count
+  int run = eoffs[n];
+  for (int s2 = 0; s2 < seg; s2++) run += seg_tot[s2][n];
+  for (int c = c0; c < c1; c++) {
+    const int v = tot[(int64_t)c * 64 + n];
+    tot[(int64_t)c * 64 + n] = run;
+    run += v;
+  }
+}
+
+__global__ __launch_bounds__(256) void gpm_place_kernel(const int32_t *__restrict__ idx, int nP,
+                                                        int N, int chunks,
+                                                        const int32_t *__restrict__ base,
+                                                        int32_t *__restrict__ row_of_pair,
+                                                        int32_t *__restrict__ pair_of_row) {
+  const int lane = threadIdx.x & 63;
+  const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (c >= chunks) return;
+  int running = base[(int64_t)c * 64 + lane];
+  const unsigned long long lt = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+#pragma unroll
+  for (int st = 0; st < GPM_CHUNK / 64; st++) {
+    const int p = c * GPM_CHUNK + st * 64 + lane;
+    const int e = p < nP ? idx[p] : -1;
+    unsigned long long mine = 0;
+    int add = 0;
+    for (int n = 0; n < N; n++) {
+      const unsigned long long b = __ballot(e == n);
+      if (e == n) mine = b;
+      if (lane == n) add = __popcll(b);
+    }
+    const int start = __shfl(running, e < 0 ? 0 : e, 64);
+    if (e >= 0) {
+      const int row = start + __popcll(mine & lt);
+      row_of_pair[p] = row;
+      pair_of_row[row] = p;
+    }
+    running += add;
+  }
+}
+
+hipError_t launch_group_pairs_aux_multi(const int32_t *idx, int T, int N, int k, int32_t *counts,
+                                        int32_t *counts_out, int32_t *first_counts, int32_t *offs,
+                                        int32_t *row_of_pair, int32_t *pair_of_row,
+                                        int32_t *tok_offs, const float *probs, float coeff, int mode,
+                                        float *loss, float *F, float *P, int Nl,
+                                        const int32_t *token_model, int32_t *model_tokens,
+                                        void *scratch, hipStream_t st) {
+  const int nP = T * k;
+  const int chunks = (nP + GPM_CHUNK - 1) / GPM_CHUNK;
+  int32_t *tot = (int32_t *)scratch, *first = tot + (size_t)chunks * 64;
+  float *psum = (float *)(first + (size_t)chunks * 64);
+  int32_t *tmc = (int32_t *)(psum + (size_t)chunks * 64);
+  const dim3 grid((chunks + 3) / 4), block(256);
+  hipLaunchKernelGGL(gpm_count_kernel, grid, block, 0, st, idx, T, N, k, chunks, probs, token_model,
+                     N / Nl, tot, first, psum, tmc);
+  hipLaunchKernelGGL(gpm_scan_kernel, dim3(1), dim3(1024), 0, st, T, N, k, chunks, tot, first, psum,
+                     tmc, counts, counts_out, first_counts, offs, tok_offs, coeff, mode, loss, F, P,
+                     Nl, model_tokens);
+  hipLaunchKernelGGL(gpm_place_kernel, grid, block, 0, st, idx, nP, N, chunks, tot, row_of_pair,
+                     pair_of_row);
+  return hipGetLastError();
+}
+
 // d loss / d probs[t, e] = coeff * N * F_e / T   (F is piecewise constant)
 __global__ void aux_dprobs_kernel(const int32_t *__restrict__ idx, int T, int N, int k,
                                   float coeff, int mode, float *__restrict__ dprobs) {

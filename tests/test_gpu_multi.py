@@ -73,6 +73,11 @@ MULTI_CASES = [
      "skip_last", None),
     ("bf16_m8_top1", BASE_BF16, dict(T=512, d=128, d_ff=256, N=8, k=1, r=8, alpha=16.0, M=8, seq_len=16),
      "round_robin", None),
+    # more than 8192 pairs: grouping and Eq. 8-9 run as multi-workgroup passes
+    ("bf16_m3_long_batch", BASE_BF16, dict(T=4700, d=64, d_ff=136, N=5, k=2, r=8, alpha=16.0, M=3, seq_len=97),
+     "uneven", (1.0, 0.5, 2.0)),
+    ("f32_m2_long_skip", BASE_F32, dict(T=4400, d=32, d_ff=72, N=4, k=2, r=8, M=2, seq_len=100),
+     "skip_last", None),
 ]
 
 

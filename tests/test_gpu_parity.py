@@ -77,6 +77,11 @@ SMALL_CASES = [
     ("bf16_decode_128", BASE_BF16, dict(T=128, d=192, d_ff=576, N=8, k=2, r=8, alpha=16.0)),
     ("bf16_skew", synth.CONFIGS["llama2_13b_skew"], dict(T=600, d=256, d_ff=768)),
     ("bf16_clusters", synth.CONFIGS["llama3_8b_clusters"], dict(T=1024, d=256, d_ff=512, seq_len=64)),
+    # more than 8192 pairs: grouping and Eq. 8-9 run as multi-workgroup passes (ragged last chunk)
+    ("bf16_long_batch", BASE_BF16, dict(T=5001, d=64, d_ff=128, N=8, k=2, r=8, alpha=16.0)),
+    ("bf16_long_top3", BASE_BF16, dict(T=3100, d=64, d_ff=136, N=5, k=3, r=8, alpha=16.0)),
+    ("bf16_long_64_experts", BASE_BF16, dict(T=2500, d=64, d_ff=128, N=64, k=4, r=8, alpha=16.0)),
+    ("f32_long_batch", BASE_F32, dict(T=4200, d=32, d_ff=72, N=16, k=2, r=8)),
     ("f32_ragged", BASE_F32, dict(T=333, d=72, d_ff=200, N=6, k=2, r=8)),
     ("f32_top3", BASE_F32, dict(T=129, d=64, d_ff=136, N=8, k=3, r=16, alpha=32.0)),
 ]
