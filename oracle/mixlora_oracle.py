@@ -42,6 +42,14 @@ first-choice expert ("top1", as printed) or all k choices divided by k
 * AdamW (the optimiser of the appendix hyper-parameter table; decoupled weight decay):
   adamw_step, pinned against torch.optim.AdamW in tests/test_oracle_linear_pins.py.
 
+* Weight-decomposed experts ("MixDoRA", named in the experiment setup; the paper prints no
+  formula for it, so this is a reading: every expert projection follows the cited
+  weight-decomposition method): W'_e = diag(m_e / n_e) (W + s B_e A_e) with a trainable
+  magnitude m_e per output feature and n_e the row norms of W + s B_e A_e, which that method
+  treats as a constant in the backward pass.  dora_forward / dora_backward, pinned in
+  tests/test_oracle_dora_pins.py (m = n reduces to the LoRA block, explicit merged weights,
+  homogeneity in m, autograd with the norm detached, finite differences for dm and dx).
+
 Pinned by tests/test_oracle_pins.py (dense-FFN special case, k = N mixture,
 merged-weight identity, brute-force loops, closed-form auxiliary losses,
 finite differences, autograd of an independent formulation) and, for the
@@ -294,3 +302,124 @@ def adamw_step(p, g, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_de
     vhat = v / (1.0 - beta2 ** step)
     p = p - lr * mhat / (np.sqrt(vhat) + eps)
     return p, m, v
+
+
+# ---- weight-decomposed experts (reading of "MixDoRA", see the header) ---------------------------
+DORA_PROJ = (("gate", "W_gate", "A_gate", "B_gate"), ("up", "W_up", "A_up", "B_up"),
+             ("down", "W_down", "A_down", "B_down"))
+
+
+def dora_row_norms(W, e, s):
+    """n_e per projection: L2 norm over the input dimension of every row of W + s B_e A_e."""
+    out = {}
+    for name, wn, an, bn in DORA_PROJ:
+        V = _f64(W[wn]) + s * (_f64(W[bn][e]) @ _f64(W[an][e]))
+        out[name] = np.sqrt((V * V).sum(axis=1))
+    return out
+
+
+def dora_expert_forward(xe, W, mag, e, s):
+    """One weight-decomposed expert on rows xe [n,d]: every projection's output feature j is
+    (m_e[j] / n_e[j]) * ((W + s B_e A_e) x)[j].  mag: dict m_gate/m_up [N,f], m_down [N,d]."""
+    n = dora_row_norms(W, e, s)
+    cg, cu, cd = (_f64(mag["m_" + nm][e]) / n[nm] for nm in ("gate", "up", "down"))
+    pg = xe @ W["A_gate"][e].T
+    pu = xe @ W["A_up"][e].T
+    vg = xe @ W["W_gate"].T + s * (pg @ W["B_gate"][e].T)
+    vu = xe @ W["W_up"].T + s * (pu @ W["B_up"][e].T)
+    g, u = cg * vg, cu * vu
+    a = g * sigmoid(g) * u
+    q = a @ W["A_down"][e].T
+    vd = a @ W["W_down"].T + s * (q @ W["B_down"][e].T)
+    o = cd * vd
+    return dict(pg=pg, pu=pu, vg=vg, vu=vu, g=g, u=u, a=a, q=q, vd=vd, o=o, cg=cg, cu=cu, cd=cd,
+                n=n)
+
+
+def dora_forward(x, W, mag, k, lora_scale, aux_coeff=0.01, aux_mode="top1", keep=False):
+    """The block with weight-decomposed experts; routing, combination and auxiliary loss as in
+    forward().  Returns the same dict."""
+    x = _f64(x)
+    W = {n: _f64(v) for n, v in W.items()}
+    T, d = x.shape
+    N = W["W_router"].shape[0]
+    z, p, idx, w = router(x, W["W_router"], k)
+    y = np.zeros((T, d), dtype=F64)
+    counts = np.zeros(N, dtype=np.int64)
+    saved = {}
+    for e in range(N):
+        tok, slot = np.nonzero(idx == e)
+        counts[e] = tok.size
+        if tok.size == 0:
+            continue
+        res = dora_expert_forward(x[tok], W, mag, e, lora_scale)
+        np.add.at(y, tok, w[tok, slot][:, None] * res["o"])
+        if keep:
+            res["tok"], res["slot"] = tok, slot
+            saved[e] = res
+    loss, F, P = aux_loss(p, idx, N, aux_coeff, aux_mode)
+    out = dict(y=y, logits=z, probs=p, topk_idx=idx, topk_w=w, counts=counts,
+               aux_loss=loss, F=F, P=P)
+    if keep:
+        out["saved"] = saved
+    return out
+
+
+def dora_backward(x, W, mag, k, lora_scale, dy, d_aux=1.0, aux_coeff=0.01, aux_mode="top1"):
+    """Gradients of <y, dy> + d_aux * L_aux for the weight-decomposed block: base matrices
+    frozen, the row norms n_e held constant (no gradient flows through them), gradients for
+    A, B, the magnitudes (dm_gate/dm_up [N,f], dm_down [N,d]), W_router and x."""
+    x = _f64(x)
+    dy = _f64(dy)
+    W = {n: _f64(v) for n, v in W.items()}
+    s = lora_scale
+    fw = dora_forward(x, W, mag, k, s, aux_coeff, aux_mode, keep=True)
+    T, d = x.shape
+    N = W["W_router"].shape[0]
+    p, idx, w = fw["probs"], fw["topk_idx"], fw["topk_w"]
+    G = {n: np.zeros_like(W[n]) for n in
+         ("A_gate", "B_gate", "A_up", "B_up", "A_down", "B_down", "W_router")}
+    dm = {"m_" + nm: np.zeros_like(_f64(mag["m_" + nm])) for nm in ("gate", "up", "down")}
+    dx = np.zeros_like(x)
+    dw = np.zeros((T, k), dtype=F64)
+    for e, sv in fw["saved"].items():
+        tok, slot = sv["tok"], sv["slot"]
+        xe, dye = x[tok], dy[tok]
+        dw[tok, slot] = (dye * sv["o"]).sum(axis=1)
+        do = w[tok, slot][:, None] * dye
+        # o = cd * vd,  cd = m_down / n_down
+        dm["m_down"][e] = (do * sv["vd"]).sum(axis=0) / sv["n"]["down"]
+        dvd = do * sv["cd"]
+        G["B_down"][e] = s * (dvd.T @ sv["q"])
+        v = dvd @ W["B_down"][e]
+        G["A_down"][e] = s * (v.T @ sv["a"])
+        da = dvd @ W["W_down"] + s * (v @ W["A_down"][e])
+        g, u = sv["g"], sv["u"]
+        sg = sigmoid(g)
+        dg = da * u * sg * (1.0 + g * (1.0 - sg))
+        du = da * g * sg
+        dm["m_gate"][e] = (dg * sv["vg"]).sum(axis=0) / sv["n"]["gate"]
+        dm["m_up"][e] = (du * sv["vu"]).sum(axis=0) / sv["n"]["up"]
+        dvg, dvu = dg * sv["cg"], du * sv["cu"]
+        G["B_gate"][e] = s * (dvg.T @ sv["pg"])
+        tg = dvg @ W["B_gate"][e]
+        G["A_gate"][e] = s * (tg.T @ xe)
+        G["B_up"][e] = s * (dvu.T @ sv["pu"])
+        tu = dvu @ W["B_up"][e]
+        G["A_up"][e] = s * (tu.T @ xe)
+        dxe = dvg @ W["W_gate"] + dvu @ W["W_up"] + s * (tg @ W["A_gate"][e]) \
+            + s * (tu @ W["A_up"][e])
+        np.add.at(dx, tok, dxe)
+    kept = np.take_along_axis(p, idx, axis=1)
+    ssum = kept.sum(axis=1, keepdims=True)
+    dkept = (dw - (w * dw).sum(axis=1, keepdims=True)) / ssum
+    dp = np.zeros((T, N), dtype=F64)
+    np.put_along_axis(dp, idx, dkept, axis=1)
+    dp += d_aux * aux_loss_dprobs(p, idx, N, aux_coeff, aux_mode)
+    dz = p * (dp - (p * dp).sum(axis=1, keepdims=True))
+    G["W_router"] = dz.T @ x
+    dx += dz @ W["W_router"]
+    out = {"d" + n: v for n, v in G.items()}
+    out.update({"d" + n: v for n, v in dm.items()})
+    out.update(dx=dx, dw=dw, dz=dz, forward=fw)
+    return out
