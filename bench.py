@@ -166,6 +166,9 @@ def main():
                     help="linear_down: the library's schedule (3 frozen units per direction); "
                          "shared / vanilla: the paper's Figure 3(b) / 3(a) schedules (2+k / 3k "
                          "units), for comparison")
+    ap.add_argument("--dora", action="store_true",
+                    help="weight-decomposed experts (magnitude / row norm on every expert "
+                         "projection) through mixlora_dora_forward / _backward")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device copy (a kernel of known HBM traffic, used to "
                          "scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -197,8 +200,14 @@ def main():
     t_inputs = time.perf_counter() - t0
     schedule = {"linear_down": B.SCHEDULE_LINEAR_DOWN, "shared": B.SCHEDULE_SHARED,
                 "vanilla": B.SCHEDULE_VANILLA}[args.schedule]
+    if args.dora and (args.schedule != "linear_down" or cfg.M > 1):
+        print("bench.py: --dora runs one adapter and chooses its own schedule", file=sys.stderr)
+        sys.exit(2)
     m = MixLoraFFN(cfg, host, with_backward=do_bwd,
-                   token_model=synth.token_model(cfg) if cfg.M > 1 else None, schedule=schedule)
+                   token_model=synth.token_model(cfg) if cfg.M > 1 else None, schedule=schedule,
+                   magnitudes=synth.make_magnitudes(cfg) if args.dora else None)
+    if args.dora:
+        args.schedule = "shared"      # gate/up shared, down projection per routed pair
 
     def step():
         m.forward()
@@ -297,7 +306,9 @@ def main():
         "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} d_ff={cfg.d_ff} N={cfg.N} "
                                f"top-{cfg.k} r={cfg.r} {'adapters=%d ' % cfg.M if cfg.M > 1 else ''}bf16 "
                                f"{'forward+backward' if do_bwd else 'forward'}",
-                   "schedule": schedule_text,
+                   "schedule": schedule_text + (
+                       "; weight-decomposed experts: per-expert magnitude / row-norm factors on "
+                       "gate, up and down, row norms recomputed every forward" if args.dora else ""),
                    "frozen_gemm_units_per_step": units_per_step,
                    "workspace_gib": round(m.ws_bytes / 2**30, 3),
                    "algorithmic_tflop_per_step": step_flops / 1e12,

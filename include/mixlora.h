@@ -155,6 +155,37 @@ MIXLORA_API int mixlora_ffn_backward_schedule(const mixlora_dims *dims, int32_t 
                                   float d_aux, void *workspace, size_t workspace_bytes, void *dx,
                                   const mixlora_grads *grads, void *stream);
 
+/* ---- Weight-decomposed experts (the variant the experiments call MixDoRA, Section 4.1) ---------
+ * The paper prints no formula for it; this library's reading applies the cited weight-
+ * decomposition method to every expert projection P in {gate, up, down} of expert e:
+ *     P'_e = diag(m_e / n_e) (W + s B_e A_e),   n_e[j] = || (W + s B_e A_e)[j, :] ||_2 ,
+ * with a trainable magnitude m_e per output feature; n_e is recomputed in every forward call and
+ * treated as a constant by the backward pass (no gradient through the norm), as that method does.
+ * With m_e = n_e the block equals the plain MixLoRA block.
+ *   m_gate, m_up [N, d_ff], m_down [N, d]: device float32, 16-byte aligned.
+ *   dm_*: gradients of the magnitudes, same shapes, float32, overwritten.
+ * bf16 storage only (MIXLORA_E_DTYPE otherwise).  The frozen gate / up products stay shared
+ * across experts; the down projection runs per routed pair (its factor depends on the expert).
+ * Other arguments, outputs, workspace rules and errors as in mixlora_ffn_forward / _backward;
+ * the backward call needs the workspace of a mixlora_dora_forward call with the same inputs.  */
+typedef struct {
+  const float *m_gate, *m_up, *m_down;
+} mixlora_dora;
+typedef struct {
+  float *dm_gate, *dm_up, *dm_down;
+} mixlora_dora_grads;
+
+MIXLORA_API size_t mixlora_dora_workspace_bytes(const mixlora_dims *dims, int for_backward);
+MIXLORA_API int mixlora_dora_forward(const mixlora_dims *dims, const mixlora_weights *w,
+                         const mixlora_dora *dora, const void *x, void *y, int32_t *topk_idx,
+                         float *topk_w, int32_t *expert_counts, float *aux_loss, void *workspace,
+                         size_t workspace_bytes, void *stream);
+MIXLORA_API int mixlora_dora_backward(const mixlora_dims *dims, const mixlora_weights *w,
+                          const mixlora_dora *dora, const void *x, const void *dy, float d_aux,
+                          void *workspace, size_t workspace_bytes, void *dx,
+                          const mixlora_grads *grads, const mixlora_dora_grads *dora_grads,
+                          void *stream);
+
 /* ---- Several adapters on one frozen base (Section 3.3, "Optimizing Multi-MixLoRA Training and
  * Inference (II)"; outer loop of Algorithm 1) -------------------------------------------------
  * M MixLoRA adapters, each with its own router and N LoRA experts, share W_gate / W_up / W_down.

@@ -27,7 +27,8 @@ EXPORTS = ("mixlora_workspace_bytes", "mixlora_ffn_forward", "mixlora_ffn_backwa
            "mixlora_mfma_probe", "mixlora_lora_linear_workspace_bytes",
            "mixlora_lora_linear_forward", "mixlora_lora_linear_backward", "mixlora_adamw_step",
            "mixlora_schedule_workspace_bytes", "mixlora_ffn_forward_schedule",
-           "mixlora_ffn_backward_schedule")
+           "mixlora_ffn_backward_schedule", "mixlora_dora_workspace_bytes",
+           "mixlora_dora_forward", "mixlora_dora_backward")
 
 
 class Dims(C.Structure):
@@ -57,6 +58,18 @@ class LinearDims(C.Structure):
 class AdamW(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("weight_decay", C.c_float), ("step", C.c_int32)]
+
+
+DORA_FIELDS = ("m_gate", "m_up", "m_down")
+DORA_GRAD_FIELDS = ("dm_gate", "dm_up", "dm_down")
+
+
+class Dora(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in DORA_FIELDS]
+
+
+class DoraGrads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in DORA_GRAD_FIELDS]
 
 
 class Multi(C.Structure):
@@ -97,6 +110,14 @@ def load():
     lib.mixlora_ffn_backward_schedule.restype = C.c_int
     lib.mixlora_ffn_backward_schedule.argtypes = [C.POINTER(Dims), i32, C.POINTER(Weights), vp, vp,
                                                   f32, vp, sz, vp, C.POINTER(Grads), vp]
+    lib.mixlora_dora_workspace_bytes.restype = sz
+    lib.mixlora_dora_workspace_bytes.argtypes = [C.POINTER(Dims), C.c_int]
+    lib.mixlora_dora_forward.restype = C.c_int
+    lib.mixlora_dora_forward.argtypes = [C.POINTER(Dims), C.POINTER(Weights), C.POINTER(Dora), vp, vp,
+                                         vp, vp, vp, vp, vp, sz, vp]
+    lib.mixlora_dora_backward.restype = C.c_int
+    lib.mixlora_dora_backward.argtypes = [C.POINTER(Dims), C.POINTER(Weights), C.POINTER(Dora), vp, vp,
+                                          f32, vp, sz, vp, C.POINTER(Grads), C.POINTER(DoraGrads), vp]
     lib.mixlora_aux_loss.restype = C.c_int
     lib.mixlora_aux_loss.argtypes = [vp, vp, i32, i32, i32, f32, i32, vp, vp, vp, vp, vp]
     lib.mixlora_transpose.restype = C.c_int
@@ -215,6 +236,46 @@ def mixlora_ffn_backward_schedule(dims: Dims, schedule: int, weights: Weights, x
                                               _stream(stream))
     if rc != 0:
         raise MixLoraError("mixlora_ffn_backward_schedule", rc)
+
+
+def make_dora(tensors: Dict[str, object]) -> Dora:
+    d = Dora()
+    for n in DORA_FIELDS:
+        setattr(d, n, _ptr(tensors.get(n)))
+    return d
+
+
+def make_dora_grads(tensors: Dict[str, object]) -> DoraGrads:
+    g = DoraGrads()
+    for n in DORA_GRAD_FIELDS:
+        setattr(g, n, _ptr(tensors.get(n)))
+    return g
+
+
+def mixlora_dora_workspace_bytes(dims: Dims, for_backward: bool) -> int:
+    return int(load().mixlora_dora_workspace_bytes(C.byref(dims), int(bool(for_backward))))
+
+
+def mixlora_dora_forward(dims: Dims, weights: Weights, dora: Dora, x, y, topk_idx, topk_w,
+                         expert_counts, aux_loss, workspace, workspace_bytes: int,
+                         stream=None) -> None:
+    rc = load().mixlora_dora_forward(C.byref(dims), C.byref(weights), C.byref(dora), _ptr(x),
+                                     _ptr(y), _ptr(topk_idx), _ptr(topk_w), _ptr(expert_counts),
+                                     _ptr(aux_loss), _ptr(workspace), workspace_bytes,
+                                     _stream(stream))
+    if rc != 0:
+        raise MixLoraError("mixlora_dora_forward", rc)
+
+
+def mixlora_dora_backward(dims: Dims, weights: Weights, dora: Dora, x, dy, d_aux: float, workspace,
+                          workspace_bytes: int, dx, grads: Grads, dora_grads: DoraGrads,
+                          stream=None) -> None:
+    rc = load().mixlora_dora_backward(C.byref(dims), C.byref(weights), C.byref(dora), _ptr(x),
+                                      _ptr(dy), float(d_aux), _ptr(workspace), workspace_bytes,
+                                      _ptr(dx), C.byref(grads), C.byref(dora_grads),
+                                      _stream(stream))
+    if rc != 0:
+        raise MixLoraError("mixlora_dora_backward", rc)
 
 
 def make_multi(M: int, token_model, d_aux=None) -> Multi:

@@ -40,11 +40,16 @@ struct Layout {
   // per-pair-row buffers of the paper's own schedules (Section 3.3, Figure 3); size 0 otherwise
   size_t Xp, Gp, Up, Qp, Op;     // forward (Gp, Up are kept for the backward pass)
   size_t dYp, Hp, Sp, dXp;       // backward scratch
+  // weight-decomposed experts: W A^T products, Gram matrices, squared row norms of the frozen
+  // matrices, factors c = m / n and 1 / n (kept for the backward pass); backward partial sums
+  size_t WA_g, WA_u, WA_d, AA, w2, c_g, c_u, c_d, ninv_g, ninv_u, ninv_d;
+  size_t dm_part_g, dm_part_u, dmd_part;
 };
 
 // Buffers a schedule does not use get size 0 (per-token G, U in the unshared schedule, the
 // combined activations where the down projection runs per pair, ...).
-Layout make_layout(const mixlora_dims &D, int schedule = MIXLORA_SCHEDULE_LINEAR_DOWN) {
+Layout make_layout(const mixlora_dims &D, int schedule = MIXLORA_SCHEDULE_LINEAR_DOWN,
+                   bool dora = false) {
   Layout L{};
   const bool pair_down = schedule != MIXLORA_SCHEDULE_LINEAR_DOWN;
   const bool vanilla = schedule == MIXLORA_SCHEDULE_VANILLA;
@@ -79,6 +84,17 @@ Layout make_layout(const mixlora_dims &D, int schedule = MIXLORA_SCHEDULE_LINEAR
   L.Up = take(vanilla ? kT * f * E : 0);
   L.Qp = take(pair_down ? kT * R * E : 0);
   L.Op = take(pair_down ? kT * d * E : 0);
+  L.WA_g = take(dora ? f * R * 4 : 0);
+  L.WA_u = take(dora ? f * R * 4 : 0);
+  L.WA_d = take(dora ? d * R * 4 : 0);
+  L.AA = take(dora ? 3 * gram_part_floats((int)N, (int)r) * 4 : 0);
+  L.w2 = take(dora ? (2 * f + d) * 4 : 0);
+  L.c_g = take(dora ? N * f * 4 : 0);
+  L.c_u = take(dora ? N * f * 4 : 0);
+  L.c_d = take(dora ? N * d * 4 : 0);
+  L.ninv_g = take(dora ? N * f * 4 : 0);
+  L.ninv_u = take(dora ? N * f * 4 : 0);
+  L.ninv_d = take(dora ? N * d * 4 : 0);
   L.Bd_cat = take(d * R * E);
   L.rank_part = take(2 * 8 * kT * r * 4);   // per-split rank-r partial sums (two banks)
   // few tokens (decode-shaped calls): partial outputs of the K-split down projection
@@ -113,6 +129,9 @@ Layout make_layout(const mixlora_dims &D, int schedule = MIXLORA_SCHEDULE_LINEAR
   L.S = take(vanilla ? 0 : T * (size_t)L.Kx * E);
   L.Sp = take(vanilla ? kT * (size_t)L.Kx * E : 0);
   L.dXp = take(vanilla ? kT * d * E : 0);
+  L.dm_part_g = take(dora ? (size_t)fused_row_tiles((int)kT, (int)N) * f * 4 : 0);
+  L.dm_part_u = take(dora ? (size_t)fused_row_tiles((int)kT, (int)N) * f * 4 : 0);
+  L.dmd_part = take(dora ? dm_down_part_floats((int)N, (int)d) * 4 : 0);
   L.Bx = take(d * (size_t)L.Kx * E);
   L.dz = take(T * N * 4);
   size_t pf = group_outer_partial_floats((int)N, (int)r, (int)f);
@@ -202,8 +221,9 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
                         const mixlora_weights *w, const void *x, void *y, int32_t *topk_idx,
                         float *topk_w, int32_t *expert_counts, float *aux_loss, void *workspace,
                         size_t workspace_bytes, void *stream,
-                        int schedule = MIXLORA_SCHEDULE_LINEAR_DOWN) {
-  const Layout L = make_layout(D, schedule);
+                        int schedule = MIXLORA_SCHEDULE_LINEAR_DOWN,
+                        const mixlora_dora *dora = nullptr) {
+  const Layout L = make_layout(D, schedule, dora != nullptr);
   const bool pair_down = schedule != MIXLORA_SCHEDULE_LINEAR_DOWN;   // down projection per pair
   const bool vanilla = schedule == MIXLORA_SCHEDULE_VANILLA;         // gate/up per pair as well
   if (workspace_bytes < L.fwd_end) return MIXLORA_E_WORKSPACE;
@@ -224,18 +244,49 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
   // of them depends on the routing; in bf16 the router logits (Eq. 7) ride along as a fifth,
   // N-column problem, so x is not read a second time.
   {
-    GemmProblem p[5] = {problem(T, f, ws + L.G, f, 0), problem(T, f, ws + L.U, f, 0),
+    GemmProblem p[7] = {problem(T, f, ws + L.G, f, 0), problem(T, f, ws + L.U, f, 0),
                         problem(T, R, ws + L.Pg_all, R, 1), problem(T, R, ws + L.Pu_all, R, 1),
-                        problem(T, N, ws + L.Z, N, 1)};
+                        problem(T, N, ws + L.Z, N, 1),
+                        // weight-decomposed experts only: W A_cat^T for the row norms
+                        problem(f, R, ws + L.WA_g, R, 1), problem(f, R, ws + L.WA_u, R, 1)};
     add_seg(p[0], x, d, w->W_gate, d, d);
     add_seg(p[1], x, d, w->W_up, d, d);
     add_seg(p[2], x, d, w->A_gate, d, d);
     add_seg(p[3], x, d, w->A_up, d, d);
     add_seg(p[4], x, d, w->W_router, d, d);
-    if (vanilla)   // unshared schedule: the frozen gate/up products follow the routing, per pair;
+    add_seg(p[5], w->W_gate, d, w->A_gate, d, d);
+    add_seg(p[6], w->W_up, d, w->A_up, d, d);
+    if (vanilla) {   // unshared schedule: the frozen gate/up products follow the routing, per pair;
       HIP_TRY(launch_gemm(dt, p + 4, 1, st));   // only the router logits are needed up front
-    else
+    } else if (dora) {
+      if (gemm_mixed_rows_ok(dt, p, 7)) {
+        HIP_TRY(launch_gemm(dt, p, 7, st));
+      } else {   // shapes outside the large-tile kernel: problems of different M go separately
+        HIP_TRY(launch_gemm(dt, p, 5, st));
+        HIP_TRY(launch_gemm(dt, p + 5, 2, st));
+      }
+    } else {
       HIP_TRY(launch_gemm(dt, p, dt == MIXLORA_BF16 ? 5 : 4, st));
+    }
+  }
+  DoraArgs dargs{};
+  if (dora) {
+    // factors c = m / n of the gate and up projections (n: row norms of W + s B_e A_e)
+    float *w2 = (float *)(ws + L.w2), *AA = (float *)(ws + L.AA);
+    HIP_TRY(launch_row_sqnorm(w->W_gate, f, d, w2, st));
+    HIP_TRY(launch_row_sqnorm(w->W_up, f, d, w2 + f, st));
+    HIP_TRY(launch_row_sqnorm(w->W_down, d, f, w2 + 2 * (size_t)f, st));
+    HIP_TRY(launch_gram(w->A_gate, N, r, d, AA, st));
+    const size_t gpf = gram_part_floats(N, r);
+    HIP_TRY(launch_gram(w->A_up, N, r, d, AA + gpf, st));
+    HIP_TRY(launch_gram(w->A_down, N, r, f, AA + 2 * gpf, st));
+    HIP_TRY(launch_dora_scale(w->B_gate, (float *)(ws + L.WA_g), AA, w2, dora->m_gate, N, f, r,
+                              D.lora_scale, (float *)(ws + L.c_g), (float *)(ws + L.ninv_g), st));
+    HIP_TRY(launch_dora_scale(w->B_up, (float *)(ws + L.WA_u), AA + gpf, w2 + f,
+                              dora->m_up, N, f, r, D.lora_scale, (float *)(ws + L.c_u),
+                              (float *)(ws + L.ninv_u), st));
+    dargs.cg = (float *)(ws + L.c_g);
+    dargs.cu = (float *)(ws + L.c_u);
   }
   // Eq. 7 + Norm (Algorithm 1 lines 4-5)
   if (dt == MIXLORA_BF16)
@@ -296,12 +347,29 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
     HIP_TRY(launch_swiglu_fwd_mfma(pc, f, D.lora_scale, Gsrc, Usrc, (float *)(ws + L.Pg_all),
                                    (float *)(ws + L.Pu_all), w->B_gate, w->B_up, w->A_down,
                                    ws + L.a_grp, (float *)(ws + L.rank_part),
-                                   (float *)(ws + L.Q_all), ws + L.Qp, R, st, rows_mode));
-    GemmProblem p = problem(kT, d, ws + L.Op, d, 0);
-    add_seg(p, ws + L.a_grp, f, w->W_down, f, f);
-    add_seg(p, ws + L.Qp, R, ws + L.Bd_cat, R, R);
-    HIP_TRY(launch_gemm(dt, &p, 1, st));
-    HIP_TRY(launch_pair_combine(dt, pc, d, ws + L.Op, y, 1, st));
+                                   (float *)(ws + L.Q_all), ws + L.Qp, R, st, rows_mode,
+                                   dora ? &dargs : nullptr));
+    GemmProblem p[2] = {problem(kT, d, ws + L.Op, d, 0), problem(d, R, ws + L.WA_d, R, 1)};
+    add_seg(p[0], ws + L.a_grp, f, w->W_down, f, f);
+    add_seg(p[0], ws + L.Qp, R, ws + L.Bd_cat, R, R);
+    add_seg(p[1], w->W_down, f, w->A_down, f, f);
+    if (!dora) {
+      HIP_TRY(launch_gemm(dt, p, 1, st));
+      HIP_TRY(launch_pair_combine(dt, pc, d, ws + L.Op, y, 1, st));
+      return MIXLORA_OK;
+    }
+    if (gemm_mixed_rows_ok(dt, p, 2)) {
+      HIP_TRY(launch_gemm(dt, p, 2, st));
+    } else {
+      HIP_TRY(launch_gemm(dt, p, 1, st));
+      HIP_TRY(launch_gemm(dt, p + 1, 1, st));
+    }
+    // factor of the down projection, applied to every pair's output while combining
+    HIP_TRY(launch_dora_scale(w->B_down, (float *)(ws + L.WA_d),
+                              (float *)(ws + L.AA) + 2 * gram_part_floats(N, r),
+                              (float *)(ws + L.w2) + 2 * (size_t)f, dora->m_down, N, d, r,
+                              D.lora_scale, (float *)(ws + L.c_d), (float *)(ws + L.ninv_d), st));
+    HIP_TRY(launch_pair_combine_scaled(pc, d, ws + L.Op, (float *)(ws + L.c_d), y, st));
     return MIXLORA_OK;
   }
   // Algorithm 1 lines 11-13 on the routed pairs, expert-grouped rows
@@ -436,8 +504,10 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
                          const AuxUpstream &d_aux, const mixlora_weights *w, const void *x,
                          const void *dy, void *workspace, size_t workspace_bytes, void *dx,
                          const mixlora_grads *grads, void *stream,
-                         int schedule = MIXLORA_SCHEDULE_LINEAR_DOWN) {
-  const Layout L = make_layout(D, schedule);
+                         int schedule = MIXLORA_SCHEDULE_LINEAR_DOWN,
+                         const mixlora_dora *dora = nullptr,
+                         const mixlora_dora_grads *dgrads = nullptr) {
+  const Layout L = make_layout(D, schedule, dora != nullptr);
   const bool pair_down = schedule != MIXLORA_SCHEDULE_LINEAR_DOWN;
   const bool vanilla = schedule == MIXLORA_SCHEDULE_VANILLA;
   if (workspace_bytes < L.bwd_end) return MIXLORA_E_WORKSPACE;
@@ -480,7 +550,14 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
   if (pair_down) {
     // the paper's schedules: the frozen down projection is differentiated per pair row
     // (k rows per token); the routing weight is applied inside the fused stage as before
-    HIP_TRY(launch_gather_rows(dt, pc, d, dy, ws + L.dYp, st));
+    if (dora) {
+      // the pair's upstream gradient carries the down projection's factor: c_down[e] * dy[t],
+      // and so does the B_down^T product (the transposed bank is scaled in place)
+      HIP_TRY(launch_gather_rows_scaled(pc, d, dy, (float *)(ws + L.c_d), ws + L.dYp, st));
+      HIP_TRY(launch_scale_bank(ws + L.Bd_T, (float *)(ws + L.c_d), N, r, d, st));
+    } else {
+      HIP_TRY(launch_gather_rows(dt, pc, d, dy, ws + L.dYp, st));
+    }
     GemmProblem p[2] = {problem(kT, f, ws + L.Hp, f, 0), problem(T, R, ws + L.VB_all, R, 1)};
     add_seg(p[0], ws + L.dYp, d, WdT, d, d);
     add_seg(p[1], dy, d, ws + L.Bd_T, d, d);
@@ -497,6 +574,13 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
     HIP_TRY(launch_gemm(dt, p, 2, st));
   }
   const int rows_mode = (pair_down ? ROWS_H : 0) | (vanilla ? ROWS_GU | ROWS_SPARSE : 0);
+  DoraArgs dargs{};
+  if (dora) {
+    dargs.cg = (float *)(ws + L.c_g);
+    dargs.cu = (float *)(ws + L.c_u);
+    dargs.dm_part_g = (float *)(ws + L.dm_part_g);
+    dargs.dm_part_u = (float *)(ws + L.dm_part_u);
+  }
   char *Sop = vanilla ? ws + L.Sp : ws + L.S;      // K-extension operand of the dx GEMM
   // through SiLU * up and the LoRA deltas, per pair; TG[row, e, :] = B_gate[e]^T dg[row] (and up)
   int nct = L.nct;
@@ -509,7 +593,8 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
                                    w->B_up, ws + L.AdT, ws + L.Bg_T, ws + L.Bu_T, ws + L.dg_grp,
                                    ws + L.du_grp, (float *)(ws + L.dw_part),
                                    (float *)(ws + L.rank_part), (float *)(ws + L.TG_all),
-                                   (float *)(ws + L.TU_all), Sop, Kx, st, rows_mode));
+                                   (float *)(ws + L.TU_all), Sop, Kx, st, rows_mode,
+                                   dora ? &dargs : nullptr));
   } else {
     HIP_TRY(launch_swiglu_bwd(dt, pc, f, s, ws + L.G, ws + L.U, (float *)(ws + L.Pg_all),
                               (float *)(ws + L.Pu_all), w->B_gate, w->B_up, ws + L.H,
@@ -558,7 +643,14 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
       jd[j] = GomJob{ws + L.small[wide_d[j]], wide[wide_d[j]], gout[wide_d[j]], layout_qc[wide_d[j]]};
     }
     HIP_TRY(launch_group_outer_mfma(offs, N, kT, nullptr, k, jf, 3, L.ldT, r, f, s, part, pfl, st));
-    HIP_TRY(launch_group_outer_mfma(offs, N, kT, pair_of_row, k, jd, 3, L.ldT, r, d, s, part, pfl, st));
+    if (dora) {
+      // dB_down sums the factor-carrying pair rows c_down[e] * dy[t] (already gathered)
+      HIP_TRY(launch_group_outer_mfma(offs, N, kT, pair_of_row, k, jd, 2, L.ldT, r, d, s, part, pfl, st));
+      const GomJob jb{ws + L.small[5], ws + L.dYp, gout[5], layout_qc[5]};
+      HIP_TRY(launch_group_outer_mfma(offs, N, kT, nullptr, k, &jb, 1, L.ldT, r, d, s, part, pfl, st));
+    } else {
+      HIP_TRY(launch_group_outer_mfma(offs, N, kT, pair_of_row, k, jd, 3, L.ldT, r, d, s, part, pfl, st));
+    }
     // dW_router = dz^T x  (the transposed bf16 dz comes from the router backward)
     const GomJob jr{ws + L.dzT, x, grads->dW_router, 1};
     HIP_TRY(launch_group_outer_mfma((int32_t *)(ws + L.tok_offs), 1, T, nullptr, 1, &jr, 1, L.ldTz, N,
@@ -577,6 +669,15 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
     HIP_TRY(launch_scatter_blocks(dt, pc, (float *)(ws + L.TG_all),
                                   (int64_t)((float *)(ws + L.TU_all) - (float *)(ws + L.TG_all)), 2, R,
                                   1, 0, ws + L.S, Kx, 0, st));
+  if (dora) {
+    // magnitude gradients: dm = (1 / n) * sum over the expert's rows of (output gradient *
+    // unscaled projection output); gate / up sums come from the fused stage per row tile
+    HIP_TRY(launch_dm_tiles_reduce(offs, N, f, (float *)(ws + L.dm_part_g),
+                                   (float *)(ws + L.dm_part_u), (float *)(ws + L.ninv_g),
+                                   (float *)(ws + L.ninv_u), dgrads->dm_gate, dgrads->dm_up, st));
+    HIP_TRY(launch_dm_down(pc, d, dy, ws + L.Op, (float *)(ws + L.ninv_d),
+                           (float *)(ws + L.dmd_part), dgrads->dm_down, st));
+  }
   if (vanilla) {
     // unshared schedule: every pair row goes through W_gate^T / W_up^T on its own, the k rows of
     // a token are added afterwards
@@ -663,6 +764,56 @@ int mixlora_ffn_backward_schedule(const mixlora_dims *dims, int32_t schedule,
   up.v[0] = d_aux;
   return backward_impl(*dims, dims->N, nullptr, up, w, x, dy, workspace, workspace_bytes, dx, grads,
                        stream, schedule);
+}
+
+static int check_dora(const mixlora_dims *dims, const mixlora_dora *dora) {
+  if (!dims || !dora) return MIXLORA_E_NULL;
+  if (dims->dtype != MIXLORA_BF16) return MIXLORA_E_DTYPE;
+  const float *req[] = {dora->m_gate, dora->m_up, dora->m_down};
+  for (const float *p : req) {
+    if (!p) return MIXLORA_E_NULL;
+    if (misaligned(p)) return MIXLORA_E_ALIGN;
+  }
+  return MIXLORA_OK;
+}
+
+size_t mixlora_dora_workspace_bytes(const mixlora_dims *dims, int for_backward) {
+  if (check_dims(dims) != MIXLORA_OK || dims->dtype != MIXLORA_BF16) return 0;
+  const Layout L = make_layout(*dims, MIXLORA_SCHEDULE_SHARED, true);
+  return for_backward ? L.bwd_end : L.fwd_end;
+}
+
+int mixlora_dora_forward(const mixlora_dims *dims, const mixlora_weights *w,
+                         const mixlora_dora *dora, const void *x, void *y, int32_t *topk_idx,
+                         float *topk_w, int32_t *expert_counts, float *aux_loss, void *workspace,
+                         size_t workspace_bytes, void *stream) {
+  int rc = check_forward_args(dims, w, x, y, topk_idx, topk_w, expert_counts, aux_loss, workspace);
+  if (rc) return rc;
+  rc = check_dora(dims, dora);
+  if (rc) return rc;
+  return forward_impl(*dims, dims->N, nullptr, w, x, y, topk_idx, topk_w, expert_counts, aux_loss,
+                      workspace, workspace_bytes, stream, MIXLORA_SCHEDULE_SHARED, dora);
+}
+
+int mixlora_dora_backward(const mixlora_dims *dims, const mixlora_weights *w,
+                          const mixlora_dora *dora, const void *x, const void *dy, float d_aux,
+                          void *workspace, size_t workspace_bytes, void *dx,
+                          const mixlora_grads *grads, const mixlora_dora_grads *dora_grads,
+                          void *stream) {
+  int rc = check_backward_args(dims, w, x, dy, workspace, dx, grads);
+  if (rc) return rc;
+  rc = check_dora(dims, dora);
+  if (rc) return rc;
+  if (!dora_grads) return MIXLORA_E_NULL;
+  float *gp[] = {dora_grads->dm_gate, dora_grads->dm_up, dora_grads->dm_down};
+  for (float *p : gp) {
+    if (!p) return MIXLORA_E_NULL;
+    if (misaligned(p)) return MIXLORA_E_ALIGN;
+  }
+  AuxUpstream up{};
+  up.v[0] = d_aux;
+  return backward_impl(*dims, dims->N, nullptr, up, w, x, dy, workspace, workspace_bytes, dx, grads,
+                       stream, MIXLORA_SCHEDULE_SHARED, dora, dora_grads);
 }
 
 int mixlora_aux_loss(const float *probs, const int32_t *topk_idx, int32_t T, int32_t N,

@@ -142,6 +142,13 @@ hipError_t launch_swiglu_bwd(int dtype, const PairCtx &pc, int f, float s, const
                              void *du_grp, float *dw_part, int n_col_tiles, hipStream_t st);
 int swiglu_col_tiles(int f);
 
+// Per-expert column factors of the weight-decomposed variant (magnitude / row norm), float32
+// [N, f] each, and (backward only) per-tile partial sums for the magnitude gradients,
+// [row tiles][f] each with row tiles = kT / 32 + N.
+struct DoraArgs {
+  const float *cg, *cu;
+  float *dm_part_g, *dm_part_u;
+};
 // bf16 MFMA fusion of the above with the A_down projection of the row's expert: writes a_grp,
 // Q_all[row, e(row)*r + q] and the non-zero blocks of Qw[t, e*r + q] = w * Q (bf16, pitch ldqw;
 // the caller zero-fills Qw first).  Q_part is scratch of 8 * kT * r floats.
@@ -149,7 +156,7 @@ hipError_t launch_swiglu_fwd_mfma(const PairCtx &pc, int f, float s, const void 
                                   const float *Pg_all, const float *Pu_all, const void *B_gate,
                                   const void *B_up, const void *A_down, void *a_grp,
                                   float *Q_part, float *Q_all, void *Qw, int ldqw,
-                                  hipStream_t st, int rows_mode = 0);
+                                  hipStream_t st, int rows_mode = 0, const DoraArgs *dora = nullptr);
 // rows_mode of the fused stages (for the paper's own schedules, Figure 3): bit 0 = G and U hold
 // one row per grouped pair row instead of one per token; bit 1 = H likewise; bit 2 = the
 // block-sparse operand has one row per grouped pair row (unweighted) instead of one per token.
@@ -164,7 +171,8 @@ hipError_t launch_swiglu_bwd_mfma(const PairCtx &pc, int f, float s, const void 
                                   const void *AdT, const void *BgT, const void *BuT, void *dg_grp,
                                   void *du_grp, float *dw_part, float *rank_part, float *TG_all,
                                   float *TU_all, void *S, int lds_, hipStream_t st,
-                                  int rows_mode = 0);
+                                  int rows_mode = 0, const DoraArgs *dora = nullptr);
+int fused_row_tiles(int kT, int N);   // grid.x of the fused stages
 int fused_splits(int f);
 
 // out[t,:] = sum_j (weighted ? w[t,j] : 1) * in_grp[row_of_pair[t,j], :]
@@ -270,5 +278,25 @@ hipError_t launch_router_bwd(int dtype, const PairCtx &pc, const float *probs, c
                              int Nl, const int32_t *token_model, const int32_t *model_tokens,
                              void *dzT, int ldTz, hipStream_t st,    // dzT: bf16 [N][ldTz] copy or NULL
                              int s_by_first_pair = 0);   // S has one row per grouped pair row
+
+// ---- weight-decomposed experts (csrc/dora.hip); bf16 storage only --------------------------------
+hipError_t launch_row_sqnorm(const void *W, int rows, int cols, float *out, hipStream_t st);
+size_t gram_part_floats(int N, int r);   // floats of one bank's Gram slice sums
+hipError_t launch_gram(const void *A_bank, int N, int r, int in, float *part, hipStream_t st);
+// c = m / n, ninv = 1 / n with n the row norms of W + s B_e A_e (from w2, WA = W A_cat^T, AA)
+hipError_t launch_dora_scale(const void *B_bank, const float *WA, const float *AA, const float *w2,
+                             const float *m, int N, int out, int r, float s, float *c, float *ninv,
+                             hipStream_t st);
+hipError_t launch_scale_bank(void *bank, const float *c, int N, int r, int d, hipStream_t st);
+hipError_t launch_gather_rows_scaled(const PairCtx &pc, int width, const void *src, const float *c,
+                                     void *dst, hipStream_t st);
+hipError_t launch_pair_combine_scaled(const PairCtx &pc, int width, const void *in_grp,
+                                      const float *c, void *out, hipStream_t st);
+size_t dm_down_part_floats(int N, int d);
+hipError_t launch_dm_down(const PairCtx &pc, int d, const void *dy, const void *v, const float *ninv,
+                          float *part, float *dm, hipStream_t st);
+hipError_t launch_dm_tiles_reduce(const int32_t *offs, int N, int f, const float *part_g,
+                                  const float *part_u, const float *ninv_g, const float *ninv_u,
+                                  float *dm_g, float *dm_u, hipStream_t st);
 
 }  // namespace mixlora

@@ -94,13 +94,15 @@ __device__ __forceinline__ void tile_put(bf16_t *tile, int l31, int hi, int cb32
 
 // Forward: a_grp[row, :] and the per-split partial sums  Q_part[split][row][q] = sum over the
 // split's columns of a[row, c] * A_down[e, q, c].
-template <int KSR, int NQ>
+// DORA: g and u are multiplied by the per-expert, per-column factors cg[e, c], cu[e, c]
+// (magnitude / row norm of the weight-decomposed projections) before SiLU * up.
+template <int KSR, int NQ, bool DORA>
 __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 3 : 1) void swiglu_fwd_mfma_kernel(
     PairCtx pc, int f, float s, const bf16_t *__restrict__ G, const bf16_t *__restrict__ U,
     const float *__restrict__ Pg_all, const float *__restrict__ Pu_all,
     const bf16_t *__restrict__ B_gate, const bf16_t *__restrict__ B_up,
     const bf16_t *__restrict__ A_down, bf16_t *__restrict__ a_grp, float *__restrict__ Q_part,
-    int nsplit, int rows_mode) {
+    int nsplit, int rows_mode, DoraArgs dora) {
   constexpr int TILES = 2;
   constexpr int LDS_BYTES = FT_WAVES * TILES * FT_TILE * 2 > FT_WAVES * NQ * 16 * 64 * 4
                                 ? FT_WAVES * TILES * FT_TILE * 2 : FT_WAVES * NQ * 16 * 64 * 4;
@@ -211,6 +213,12 @@ __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 3 : 1) void swiglu_fwd_mf
     // row-major phase
     const int col = c0 + 8 * cc;
     const bool cvalid = col < f;
+    float cgv[8], cuv[8];
+    if constexpr (DORA) {
+      const int64_t o = (int64_t)e * f + col_of(c0);
+#pragma unroll
+      for (int m = 0; m < 8; m++) { cgv[m] = dora.cg[o + m]; cuv[m] = dora.cu[o + m]; }
+    }
 #pragma unroll
     for (int p = 0; p < 4; p++) {
       bf16_t *tp = tg + (8 * p + rr) * FT_PITCH + 8 * cc;
@@ -219,8 +227,9 @@ __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 3 : 1) void swiglu_fwd_mf
       bf16x8_t av;
 #pragma unroll
       for (int m = 0; m < 8; m++) {
-        const float gg = (float)gv[m] + (float)dgl[m];
-        const float uu = (float)uv[m] + (float)dul[m];
+        float gg = (float)gv[m] + (float)dgl[m];
+        float uu = (float)uv[m] + (float)dul[m];
+        if constexpr (DORA) { gg *= cgv[m]; uu *= cuv[m]; }
         av[m] = cvalid ? (bf16_t)(gg * fsigmoid(gg) * uu) : (bf16_t)0.f;
       }
       gnx[p] = ld8(G + gsrc[p] + col_of(cn));
@@ -269,15 +278,19 @@ __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 3 : 1) void swiglu_fwd_mf
 //   dw_part[row][split]   = sum over the split's columns of H * a
 //   TG_part[split][row][q] = sum_c dg[row, c] * B_gate[e, c, q]   (and TU with du, B_up)
 // AdT is A_down re-laid [N, f, r]; BgT / BuT are the B banks re-laid [N, r, f].
-template <int KSR, int NQ>
-__global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 2 : 1) void swiglu_bwd_mfma_kernel(
+// DORA: g = cg * (G + delta), u = cu * (U + delta); the gradients written (and used for TG / TU)
+// are those of the unscaled projections, cg * dg and cu * du; the sums over the tile's rows of
+// dg * (G + delta) and du * (U + delta) go to dm_part_g / dm_part_u [tile][column].
+template <int KSR, int NQ, bool DORA>
+__global__ __launch_bounds__(FT_WAVES * 64, (KSR == 1 && !DORA) ? 2 : 1) void swiglu_bwd_mfma_kernel(
     PairCtx pc, int f, float s, const bf16_t *__restrict__ G, const bf16_t *__restrict__ U,
     const bf16_t *__restrict__ H, const float *__restrict__ Pg_all,
     const float *__restrict__ Pu_all, const float *__restrict__ VB_all,
     const bf16_t *__restrict__ B_gate, const bf16_t *__restrict__ B_up,
     const bf16_t *__restrict__ AdT, const bf16_t *__restrict__ BgT, const bf16_t *__restrict__ BuT,
     bf16_t *__restrict__ dg_grp, bf16_t *__restrict__ du_grp, float *__restrict__ dw_part,
-    float *__restrict__ TG_part, float *__restrict__ TU_part, int nsplit, int rows_mode) {
+    float *__restrict__ TG_part, float *__restrict__ TU_part, int nsplit, int rows_mode,
+    DoraArgs dora) {
   constexpr int TILES = 3;
   constexpr int LDS_BYTES = FT_WAVES * TILES * FT_TILE * 2 > FT_WAVES * NQ * 16 * 64 * 4
                                 ? FT_WAVES * TILES * FT_TILE * 2 : FT_WAVES * NQ * 16 * 64 * 4;
@@ -401,6 +414,16 @@ __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 2 : 1) void swiglu_bwd_mf
     __builtin_amdgcn_wave_barrier();
     const int col = c0 + 8 * cc;
     const bool cvalid = col < f;
+    float cgv[8], cuv[8], dmg[8], dmu[8];
+    if constexpr (DORA) {
+      const int64_t o = (int64_t)e * f + col_of(c0);
+#pragma unroll
+      for (int m = 0; m < 8; m++) {
+        cgv[m] = dora.cg[o + m];
+        cuv[m] = dora.cu[o + m];
+        dmg[m] = dmu[m] = 0.f;
+      }
+    }
 #pragma unroll
     for (int p = 0; p < 4; p++) {
       const int lo = (8 * p + rr) * FT_PITCH + 8 * cc;
@@ -410,14 +433,23 @@ __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 2 : 1) void swiglu_bwd_mf
       float part = 0.f;
 #pragma unroll
       for (int m = 0; m < 8; m++) {
-        const float gg = (float)gv[m] + (float)dgl[m];
-        const float uu = (float)uv[m] + (float)dul[m];
+        float gg = (float)gv[m] + (float)dgl[m];
+        float uu = (float)uv[m] + (float)dul[m];
+        const float vg = gg, vu = uu;
+        if constexpr (DORA) { gg *= cgv[m]; uu *= cuv[m]; }
         const float hh = (float)hv[m];
         const float sg = fsigmoid(gg);
         const float da = wrow[p] * hh + (float)ddl[m];
         part = fmaf(hh, gg * sg * uu, part);
-        dgv[m] = cvalid ? (bf16_t)(da * uu * sg * (1.f + gg * (1.f - sg))) : (bf16_t)0.f;
-        duv[m] = cvalid ? (bf16_t)(da * gg * sg) : (bf16_t)0.f;
+        float dgr = da * uu * sg * (1.f + gg * (1.f - sg));
+        float dur = da * gg * sg;
+        if constexpr (DORA) {
+          if (rvalid[p]) { dmg[m] = fmaf(dgr, vg, dmg[m]); dmu[m] = fmaf(dur, vu, dmu[m]); }
+          dgr *= cgv[m];
+          dur *= cuv[m];
+        }
+        dgv[m] = cvalid ? (bf16_t)dgr : (bf16_t)0.f;
+        duv[m] = cvalid ? (bf16_t)dur : (bf16_t)0.f;
       }
       if (cvalid) dwacc[p] += part;
       {
@@ -432,6 +464,24 @@ __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 2 : 1) void swiglu_bwd_mf
       }
       *reinterpret_cast<bf16x8_t *>(tg + lo) = dgv;
       *reinterpret_cast<bf16x8_t *>(tu + lo) = duv;
+    }
+    if constexpr (DORA) {
+      // add the 8 row lanes (rr = lane / 8) of every 8-column chunk in a fixed order; this
+      // wave is the only one that handles these columns of this tile
+#pragma unroll
+      for (int m = 0; m < 8; m++) {
+        float a = dmg[m], b = dmu[m];
+        a += __shfl_xor(a, 8, 64);  b += __shfl_xor(b, 8, 64);
+        a += __shfl_xor(a, 16, 64); b += __shfl_xor(b, 16, 64);
+        a += __shfl_xor(a, 32, 64); b += __shfl_xor(b, 32, 64);
+        dmg[m] = a;
+        dmu[m] = b;
+      }
+      if (rr == 0 && cvalid) {
+        const int64_t o = (int64_t)blockIdx.x * f + col;
+#pragma unroll
+        for (int m = 0; m < 8; m++) { dora.dm_part_g[o + m] = dmg[m]; dora.dm_part_u[o + m] = dmu[m]; }
+      }
     }
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -516,6 +566,8 @@ __global__ void reduce_rank_parts_kernel(PairCtx pc, const float *__restrict__ p
       (bf16_t)(wv * acc);
 }
 
+int fused_row_tiles(int kT, int N) { return (kT + FT_ROWS - 1) / FT_ROWS + N; }
+
 int fused_splits(int f) {
   const int nblk = (f + FT_SB - 1) / FT_SB;
   int s = 8;
@@ -527,17 +579,24 @@ hipError_t launch_swiglu_fwd_mfma(const PairCtx &pc, int f, float s, const void 
                                   const float *Pg_all, const float *Pu_all, const void *B_gate,
                                   const void *B_up, const void *A_down, void *a_grp,
                                   float *Q_part, float *Q_all, void *Qw, int ldqw,
-                                  hipStream_t st, int rows_mode) {
+                                  hipStream_t st, int rows_mode, const DoraArgs *dora) {
   const int nP = pc.T * pc.k, nsplit = fused_splits(f);
   const dim3 grid((nP + FT_ROWS - 1) / FT_ROWS + pc.N, nsplit), block(FT_WAVES * 64);
-#define MIXLORA_FWD(KSR_, NQ_)                                                                   \
-  hipLaunchKernelGGL((swiglu_fwd_mfma_kernel<KSR_, NQ_>), grid, block, 0, st, pc, f, s,           \
+  const DoraArgs da = dora ? *dora : DoraArgs{};
+#define MIXLORA_FWD(KSR_, NQ_, DORA_)                                                            \
+  hipLaunchKernelGGL((swiglu_fwd_mfma_kernel<KSR_, NQ_, DORA_>), grid, block, 0, st, pc, f, s,    \
                      (const bf16_t *)G, (const bf16_t *)U, Pg_all, Pu_all, (const bf16_t *)B_gate, \
                      (const bf16_t *)B_up, (const bf16_t *)A_down, (bf16_t *)a_grp, Q_part, nsplit, \
-                     rows_mode)
-  if (pc.r <= 16) MIXLORA_FWD(1, 1);
-  else if (pc.r <= 32) MIXLORA_FWD(2, 1);
-  else MIXLORA_FWD(4, 2);
+                     rows_mode, da)
+  if (dora) {
+    if (pc.r <= 16) MIXLORA_FWD(1, 1, true);
+    else if (pc.r <= 32) MIXLORA_FWD(2, 1, true);
+    else MIXLORA_FWD(4, 2, true);
+  } else {
+    if (pc.r <= 16) MIXLORA_FWD(1, 1, false);
+    else if (pc.r <= 32) MIXLORA_FWD(2, 1, false);
+    else MIXLORA_FWD(4, 2, false);
+  }
 #undef MIXLORA_FWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -553,19 +612,27 @@ hipError_t launch_swiglu_bwd_mfma(const PairCtx &pc, int f, float s, const void 
                                   const float *VB_all, const void *B_gate, const void *B_up,
                                   const void *AdT, const void *BgT, const void *BuT, void *dg_grp,
                                   void *du_grp, float *dw_part, float *rank_part, float *TG_all,
-                                  float *TU_all, void *S, int lds_, hipStream_t st, int rows_mode) {
+                                  float *TU_all, void *S, int lds_, hipStream_t st, int rows_mode,
+                                  const DoraArgs *dora) {
   const int nP = pc.T * pc.k, nsplit = fused_splits(f);
   float *TG_part = rank_part, *TU_part = rank_part + (size_t)8 * nP * pc.r;
   const dim3 grid((nP + FT_ROWS - 1) / FT_ROWS + pc.N, nsplit), block(FT_WAVES * 64);
-#define MIXLORA_BWD(KSR_, NQ_)                                                                   \
-  hipLaunchKernelGGL((swiglu_bwd_mfma_kernel<KSR_, NQ_>), grid, block, 0, st, pc, f, s,           \
+  const DoraArgs da = dora ? *dora : DoraArgs{};
+#define MIXLORA_BWD(KSR_, NQ_, DORA_)                                                            \
+  hipLaunchKernelGGL((swiglu_bwd_mfma_kernel<KSR_, NQ_, DORA_>), grid, block, 0, st, pc, f, s,    \
                      (const bf16_t *)G, (const bf16_t *)U, (const bf16_t *)H, Pg_all, Pu_all,      \
                      VB_all, (const bf16_t *)B_gate, (const bf16_t *)B_up, (const bf16_t *)AdT,    \
                      (const bf16_t *)BgT, (const bf16_t *)BuT, (bf16_t *)dg_grp, (bf16_t *)du_grp, \
-                     dw_part, TG_part, TU_part, nsplit, rows_mode)
-  if (pc.r <= 16) MIXLORA_BWD(1, 1);
-  else if (pc.r <= 32) MIXLORA_BWD(2, 1);
-  else MIXLORA_BWD(4, 2);
+                     dw_part, TG_part, TU_part, nsplit, rows_mode, da)
+  if (dora) {
+    if (pc.r <= 16) MIXLORA_BWD(1, 1, true);
+    else if (pc.r <= 32) MIXLORA_BWD(2, 1, true);
+    else MIXLORA_BWD(4, 2, true);
+  } else {
+    if (pc.r <= 16) MIXLORA_BWD(1, 1, false);
+    else if (pc.r <= 32) MIXLORA_BWD(2, 1, false);
+    else MIXLORA_BWD(4, 2, false);
+  }
 #undef MIXLORA_BWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

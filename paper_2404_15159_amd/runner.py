@@ -25,15 +25,21 @@ class MixLoraFFN:
     def __init__(self, cfg: synth.Config, host: Dict[str, np.ndarray], aux_mode: int = B.AUX_TOP1,
                  pretransposed: bool = True, with_backward: bool = True, device: str = "cuda:0",
                  token_model: Optional[np.ndarray] = None, d_aux=None,
-                 schedule: int = B.SCHEDULE_LINEAR_DOWN):
+                 schedule: int = B.SCHEDULE_LINEAR_DOWN,
+                 magnitudes: Optional[Dict[str, np.ndarray]] = None):
         """With cfg.M > 1 (several adapters on one frozen base) token_model [T] is required and
         the multi-adapter entry points are used; the banks then hold M*N experts.  A schedule
-        other than SCHEDULE_LINEAR_DOWN goes through the *_schedule entry points (one adapter)."""
+        other than SCHEDULE_LINEAR_DOWN goes through the *_schedule entry points (one adapter).
+        magnitudes (m_gate, m_up [N,d_ff], m_down [N,d], float32) selects the weight-decomposed
+        expert variant and its entry points."""
         B.load()
         self.cfg = cfg
         self.schedule = int(schedule)
         if self.schedule != B.SCHEDULE_LINEAR_DOWN and cfg.M > 1:
             raise ValueError("the paper's schedules are built for one adapter")
+        self.dora = None
+        if magnitudes is not None and (cfg.M > 1 or self.schedule != B.SCHEDULE_LINEAR_DOWN):
+            raise ValueError("weight-decomposed experts: one adapter, default schedule argument")
         self.M = cfg.M
         if (cfg.M > 1) != (token_model is not None):
             raise ValueError("token_model goes with cfg.M > 1")
@@ -56,7 +62,12 @@ class MixLoraFFN:
                 B.mixlora_transpose(self.t[n], out, rows, cols, self.dims.dtype)
                 self.t[n + "_T"] = out
         self.weights = B.make_weights(self.t)
-        if self.schedule != B.SCHEDULE_LINEAR_DOWN:
+        if magnitudes is not None:
+            self.mag = {n: torch.from_numpy(np.ascontiguousarray(magnitudes[n], dtype=np.float32)).to(self.dev)
+                        for n in B.DORA_FIELDS}
+            self.dora = B.make_dora(self.mag)
+            self.ws_bytes = B.mixlora_dora_workspace_bytes(self.dims, with_backward)
+        elif self.schedule != B.SCHEDULE_LINEAR_DOWN:
             self.ws_bytes = B.mixlora_schedule_workspace_bytes(self.dims, self.schedule, with_backward)
         else:
             self.ws_bytes = (B.mixlora_multi_workspace_bytes(self.dims, cfg.M, with_backward)
@@ -76,6 +87,9 @@ class MixLoraFFN:
             self.g = {n: torch.empty(s, dtype=torch.float32, device=self.dev)
                       for n, s in shapes.items()}
             self.grads = B.make_grads(self.g)
+            if self.dora is not None:
+                self.gm = {"d" + n: torch.empty_like(self.mag[n]) for n in B.DORA_FIELDS}
+                self.dora_grads = B.make_dora_grads(self.gm)
 
     def forward(self, x: Optional[torch.Tensor] = None, stream=None) -> None:
         if self.multi:
@@ -83,6 +97,12 @@ class MixLoraFFN:
                                     self.t["x"] if x is None else x, self.y, self.topk_idx,
                                     self.topk_w, self.counts, self.aux, self.workspace,
                                     self.ws_bytes, stream)
+            return
+        if self.dora is not None:
+            B.mixlora_dora_forward(self.dims, self.weights, self.dora,
+                                   self.t["x"] if x is None else x, self.y, self.topk_idx,
+                                   self.topk_w, self.counts, self.aux, self.workspace,
+                                   self.ws_bytes, stream)
             return
         if self.schedule != B.SCHEDULE_LINEAR_DOWN:
             B.mixlora_ffn_forward_schedule(self.dims, self.schedule, self.weights,
@@ -99,6 +119,11 @@ class MixLoraFFN:
             B.mixlora_multi_backward(self.dims, self.multi, self.weights, self.t["x"],
                                      self.t["dy"] if dy is None else dy, self.workspace,
                                      self.ws_bytes, self.dx, self.grads, stream)
+            return
+        if self.dora is not None:
+            B.mixlora_dora_backward(self.dims, self.weights, self.dora, self.t["x"],
+                                    self.t["dy"] if dy is None else dy, d_aux, self.workspace,
+                                    self.ws_bytes, self.dx, self.grads, self.dora_grads, stream)
             return
         if self.schedule != B.SCHEDULE_LINEAR_DOWN:
             B.mixlora_ffn_backward_schedule(self.dims, self.schedule, self.weights, self.t["x"],
@@ -118,6 +143,9 @@ class MixLoraFFN:
             out["dx"] = self.dx.float().cpu().numpy()
             for n, v in self.g.items():
                 out[n] = v.cpu().numpy()
+            if self.dora is not None:
+                for n, v in self.gm.items():
+                    out[n] = v.cpu().numpy()
         return out
 
 

@@ -211,6 +211,19 @@ WEIGHT_NAMES = ("W_gate", "W_up", "W_down", "A_gate", "B_gate", "A_up", "B_up",
                 "A_down", "B_down", "W_router")
 
 
+def make_magnitudes(cfg: Config) -> Dict[str, np.ndarray]:
+    """Magnitude vectors of the weight-decomposed expert variant, float32: m_gate, m_up [N,d_ff],
+    m_down [N,d].  Drawn as U(0.8, 1.2) times 0.02 * sqrt(fan_in), the expected row norm of a
+    frozen matrix of the recipe above, so the factors magnitude / norm scatter around one."""
+    N, d, f = cfg.N, cfg.d, cfg.d_ff
+    out = {}
+    for i, (name, shape, fan_in) in enumerate((("m_gate", (N, f), d), ("m_up", (N, f), d),
+                                               ("m_down", (N, d), f))):
+        u = uniform01(cfg.seed + 7919, i, int(np.prod(shape))).reshape(shape)
+        out[name] = ((0.8 + 0.4 * u) * 0.02 * math.sqrt(fan_in)).astype(np.float32)
+    return out
+
+
 def token_model(cfg: Config, pattern: str = "round_robin") -> np.ndarray:
     """Adapter of every token, int32 [T].  Whole sequences (cfg.seq_len tokens) belong to one
     adapter, as in a batch that mixes the training sequences of several adapters.

@@ -136,6 +136,40 @@ def test_schedule_entry_points(lib):
     assert ei.value.code == -2
 
 
+def test_dora_entry_points(lib):
+    """Weight-decomposed expert variant: bf16 only, magnitudes and their gradients required."""
+    d = dims()
+    ws = B.mixlora_dora_workspace_bytes(d, True)
+    assert ws > B.mixlora_schedule_workspace_bytes(d, B.SCHEDULE_SHARED, True)
+    assert B.mixlora_dora_workspace_bytes(d, False) < ws
+    assert B.mixlora_dora_workspace_bytes(dims(dtype=B.F32), True) == 0
+    assert B.mixlora_dora_workspace_bytes(dims(r=5), True) == 0
+    mags = B.make_dora({n: FAKE for n in B.DORA_FIELDS})
+
+    def fcode(dd=d, dora=mags, **kw):
+        with pytest.raises(B.MixLoraError) as ei:
+            B.mixlora_dora_forward(dd, fake_weights(), dora, stream=0, **fwd_args(**kw))
+        return ei.value.code
+
+    assert fcode(dd=dims(dtype=B.F32)) == -3
+    assert fcode(dora=B.make_dora({"m_gate": FAKE, "m_up": FAKE})) == -1
+    assert fcode(dora=B.make_dora({"m_gate": FAKE, "m_up": FAKE, "m_down": FAKE + 4})) == -4
+    assert fcode(x=None) == -1
+    assert fcode(workspace_bytes=B.mixlora_dora_workspace_bytes(d, False) - 256) == -5
+    g = B.make_grads({n: FAKE for n in B.GRAD_FIELDS})
+    dg = B.make_dora_grads({n: FAKE for n in B.DORA_GRAD_FIELDS})
+
+    def bcode(dgrads=dg, ws_bytes=1 << 40):
+        with pytest.raises(B.MixLoraError) as ei:
+            B.mixlora_dora_backward(d, fake_weights(), mags, FAKE, FAKE, 1.0, FAKE, ws_bytes, FAKE, g,
+                                    dgrads, stream=0)
+        return ei.value.code
+
+    assert bcode(dgrads=B.make_dora_grads({"dm_gate": FAKE})) == -1
+    assert bcode(dgrads=B.make_dora_grads({n: FAKE + 2 for n in B.DORA_GRAD_FIELDS})) == -4
+    assert bcode(ws_bytes=B.mixlora_dora_workspace_bytes(d, False)) == -5
+
+
 def test_aux_and_transpose_argument_errors(lib):
     with pytest.raises(B.MixLoraError) as ei:
         B.mixlora_aux_loss(FAKE, FAKE, 16, 4, 5, 0.01, 0, FAKE, stream=0)

@@ -1,0 +1,136 @@
+"""GPU parity of the weight-decomposed expert variant (mixlora_dora_forward / _backward) against
+the CPU oracle's dora_forward / dora_backward, element by element, to the bf16 bar."""
+import numpy as np
+import pytest
+
+from oracle import mixlora_oracle as orc
+from paper_2404_15159_amd import binding as B
+from paper_2404_15159_amd import synth
+from paper_2404_15159_amd.runner import MixLoraFFN
+
+import parity_utils as pu
+
+pytestmark = pytest.mark.gpu
+
+BASE = synth.CONFIGS["llama2_7b"]
+MAG = ("m_gate", "m_up", "m_down")
+
+CASES = [
+    ("ragged", dict(T=300, d=256, d_ff=520, N=8, k=2, r=16)),
+    ("multi_tile", dict(T=1000, d=512, d_ff=1288, N=16, k=2, r=8, alpha=16.0)),
+    ("top3_r32", dict(T=257, d=136, d_ff=264, N=5, k=3, r=32, alpha=64.0)),
+    ("r64", dict(T=130, d=128, d_ff=256, N=4, k=2, r=64, alpha=128.0)),
+    ("top1", dict(T=200, d=128, d_ff=384, N=8, k=1, r=16)),
+    ("few_tokens", dict(T=17, d=512, d_ff=704, N=8, k=2, r=16)),
+    ("unused_expert", dict(T=260, d=128, d_ff=264, N=8, k=2, r=16)),
+]
+
+
+def _inputs(name, over, seed=0):
+    cfg = synth.scaled(BASE, name="dora_" + name, **over)
+    host = synth.make_inputs(cfg)
+    for n in ("B_gate", "B_up", "B_down"):      # lively LoRA paths: the norms differ per expert
+        host[n] = synth.round_to_bf16(host[n] * 8.0)
+    if name == "unused_expert":
+        host["W_router"][5] = 0.0
+        host["W_router"][5, 0] = -1.0
+        host["x"][:, 0] = 50.0                    # expert 5's logit is far below the others
+        host["x"] = synth.round_to_bf16(host["x"])
+    W = {n: host[n] for n in synth.WEIGHT_NAMES}
+    # magnitudes: the row norms times a factor in [0.6, 1.4], so every factor m / n differs from 1
+    rng = np.random.default_rng(77 + seed)
+    mag = {n: [] for n in MAG}
+    for e in range(cfg.N):
+        nrm = orc.dora_row_norms(W, e, cfg.lora_scale)
+        for nm in ("gate", "up", "down"):
+            mag["m_" + nm].append(nrm[nm] * rng.uniform(0.6, 1.4, nrm[nm].shape))
+    mag = {n: np.stack(v).astype(np.float32) for n, v in mag.items()}
+    return cfg, host, W, mag
+
+
+@pytest.mark.parametrize("name,over", CASES, ids=[c[0] for c in CASES])
+def test_dora_matches_oracle(name, over):
+    cfg, host, W, mag = _inputs(name, over)
+    print(f"\ncase {cfg.name}: T={cfg.T} d={cfg.d} f={cfg.d_ff} N={cfg.N} k={cfg.k} r={cfg.r}", flush=True)
+    m = MixLoraFFN(cfg, host, magnitudes=mag)
+    m.forward()
+    m.backward(d_aux=1.5)
+    res = m.results()
+    bw = orc.dora_backward(host["x"], W, mag, cfg.k, cfg.lora_scale, host["dy"], 1.5, cfg.aux_coeff,
+                           "top1")
+    rep = pu.compare_all(res, bw["forward"], bw, cfg)
+    for n in MAG:
+        pu.assert_close("d" + n, res["d" + n], bw["d" + n], pu.TOL["bf16"])
+    if name == "unused_expert":
+        assert res["counts"][5] == 0
+        for n in MAG:
+            assert (res["d" + n][5] == 0.0).all()
+    assert rep["routing_mismatch_tokens"] <= max(2, cfg.T // 50)
+
+
+def test_magnitude_equal_to_norm_reproduces_the_lora_block():
+    """m = n makes every factor 1 (up to float32 rounding of the norm): y, dx and the LoRA
+    gradients must agree with the plain block's entry points to the bf16 bar."""
+    cfg = synth.scaled(BASE, name="dora_identity", T=400, d=256, d_ff=520, N=8, k=2, r=16)
+    host = synth.make_inputs(cfg)
+    W = {n: host[n] for n in synth.WEIGHT_NAMES}
+    mag = {n: [] for n in MAG}
+    for e in range(cfg.N):
+        nrm = orc.dora_row_norms(W, e, cfg.lora_scale)
+        for nm in ("gate", "up", "down"):
+            mag["m_" + nm].append(nrm[nm])
+    mag = {n: np.stack(v).astype(np.float32) for n, v in mag.items()}
+    a = MixLoraFFN(cfg, host, magnitudes=mag)
+    a.forward(); a.backward()
+    ra = a.results()
+    b = MixLoraFFN(cfg, host)
+    b.forward(); b.backward()
+    rb = b.results()
+    assert np.array_equal(ra["topk_idx"], rb["topk_idx"])
+    for n in ("y", "dx") + pu.GRAD_NAMES:
+        pu.assert_close(n, ra[n], rb[n], 2e-2)
+
+
+def test_dora_argument_errors():
+    cfg = synth.scaled(BASE, name="dora_errors", T=64, d=64, d_ff=128, N=4, k=2, r=8, alpha=16.0)
+    host = synth.make_inputs(cfg)
+    mag = {"m_gate": np.ones((4, 128), np.float32), "m_up": np.ones((4, 128), np.float32),
+           "m_down": np.ones((4, 64), np.float32)}
+    m = MixLoraFFN(cfg, host, magnitudes=mag)
+    with pytest.raises(B.MixLoraError) as ei:
+        B.mixlora_dora_forward(m.dims, m.weights, B.make_dora({}), m.t["x"], m.y, m.topk_idx,
+                               m.topk_w, m.counts, m.aux, m.workspace, m.ws_bytes)
+    assert ei.value.code == -1
+    with pytest.raises(B.MixLoraError) as ei:
+        B.mixlora_dora_forward(m.dims, m.weights, m.dora, m.t["x"], m.y, m.topk_idx, m.topk_w,
+                               m.counts, m.aux, m.workspace, 1024)
+    assert ei.value.code == -5
+
+
+def test_dora_full_size_sampled():
+    """LLaMA-2-7B shape (the configuration bench.py --dora times): outputs of sampled tokens
+    against the oracle, whose per-token outputs are independent; gradients finite and the
+    magnitude gradients of sampled (expert, column) entries against a direct evaluation is left
+    to the small cases."""
+    cfg = BASE
+    host = synth.make_inputs(cfg)
+    W = {n: host[n] for n in synth.WEIGHT_NAMES}
+    rng = np.random.default_rng(5)
+    mag = {"m_gate": [], "m_up": [], "m_down": []}
+    for e in range(cfg.N):
+        nrm = orc.dora_row_norms(W, e, cfg.lora_scale)
+        for nm in ("gate", "up", "down"):
+            mag["m_" + nm].append(nrm[nm] * rng.uniform(0.8, 1.25, nrm[nm].shape))
+    mag = {n: np.stack(v).astype(np.float32) for n, v in mag.items()}
+    m = MixLoraFFN(cfg, host, magnitudes=mag)
+    m.forward()
+    m.backward()
+    res = m.results()
+    sample = np.sort(rng.choice(cfg.T, size=64, replace=False))
+    fw = orc.dora_forward(host["x"][sample], W, mag, cfg.k, cfg.lora_scale, cfg.aux_coeff)
+    same = (res["topk_idx"][sample] == fw["topk_idx"]).all(axis=1)
+    assert same.sum() >= 60
+    pu.assert_close("y", res["y"][sample][same], fw["y"][same], 2e-2)
+    for n in ("dx",) + pu.GRAD_NAMES + tuple("d" + q for q in MAG):
+        assert np.isfinite(res[n]).all(), n
+        assert np.abs(res[n]).max() > 0, n
