@@ -46,7 +46,8 @@ first-choice expert ("top1", as printed) or all k choices divided by k
   formula for it, so this is a reading: every expert projection follows the cited
   weight-decomposition method): W'_e = diag(m_e / n_e) (W + s B_e A_e) with a trainable
   magnitude m_e per output feature and n_e the row norms of W + s B_e A_e, which that method
-  treats as a constant in the backward pass.  dora_forward / dora_backward, pinned in
+  treats as a constant in the backward pass.  Parity unpinned with respect to the paper (it
+  prints nothing to pin to); pinned to that definition: dora_forward / dora_backward, in
   tests/test_oracle_dora_pins.py (m = n reduces to the LoRA block, explicit merged weights,
   homogeneity in m, autograd with the norm detached, finite differences for dm and dx).
 
