@@ -256,27 +256,41 @@ template <typename E>
 __global__ __launch_bounds__(256) void pair_combine_kernel(PairCtx pc, int width,
                                                            const E *__restrict__ in_grp,
                                                            E *__restrict__ out, int weighted) {
+  // a thread owns two 8-column chunks, 2048 columns apart: 2k independent loads in flight
   const int t = blockIdx.x;
-  const int c = (blockIdx.y * 256 + threadIdx.x) * 8;
-  if (c >= width) return;
-  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  const int c0 = (blockIdx.y * 512 + threadIdx.x) * 8;
+  const int c1 = c0 + 2048;
+  if (c0 >= width) return;
+  const bool two = c1 < width;
+  float acc0[8] = {0, 0, 0, 0, 0, 0, 0, 0}, acc1[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   for (int j = 0; j < pc.k; j++) {
     const int p = t * pc.k + j;
     const float w = weighted ? pc.w[p] : 1.f;
-    Vec8<E> v;
-    v.load(in_grp + (int64_t)pc.row_of_pair[p] * width + c);
+    const E *src = in_grp + (int64_t)pc.row_of_pair[p] * width;
+    Vec8<E> v0, v1;
+    v0.load(src + c0);
+    if (two) v1.load(src + c1);
 #pragma unroll
-    for (int i = 0; i < 8; i++) acc[i] = fmaf(w, v.get(i), acc[i]);
+    for (int i = 0; i < 8; i++) acc0[i] = fmaf(w, v0.get(i), acc0[i]);
+    if (two) {
+#pragma unroll
+      for (int i = 0; i < 8; i++) acc1[i] = fmaf(w, v1.get(i), acc1[i]);
+    }
   }
   Vec8<E> o;
 #pragma unroll
-  for (int i = 0; i < 8; i++) o.set(i, acc[i]);
-  o.store(out + (int64_t)t * width + c);
+  for (int i = 0; i < 8; i++) o.set(i, acc0[i]);
+  o.store(out + (int64_t)t * width + c0);
+  if (two) {
+#pragma unroll
+    for (int i = 0; i < 8; i++) o.set(i, acc1[i]);
+    o.store(out + (int64_t)t * width + c1);
+  }
 }
 
 hipError_t launch_pair_combine(int dtype, const PairCtx &pc, int width, const void *in_grp,
                                void *out, int weighted, hipStream_t st) {
-  const dim3 grid(pc.T, (width / 8 + 255) / 256), block(256);
+  const dim3 grid(pc.T, (width / 8 + 511) / 512), block(256);
   if (dtype == MIXLORA_BF16)
     hipLaunchKernelGGL(pair_combine_kernel<bf16_t>, grid, block, 0, st, pc, width,
                        (const bf16_t *)in_grp, (bf16_t *)out, weighted);
