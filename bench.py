@@ -175,7 +175,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(the block shards by tokens; see DESIGN.md)", file=sys.stderr)
+              "(the block would shard by tokens, data parallel, with one all-reduce of the "
+              "adapter gradients per step)", file=sys.stderr)
         sys.exit(2)
 
     import torch
