@@ -244,11 +244,12 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
   // of them depends on the routing; in bf16 the router logits (Eq. 7) ride along as a fifth,
   // N-column problem, so x is not read a second time.
   {
-    GemmProblem p[7] = {problem(T, f, ws + L.G, f, 0), problem(T, f, ws + L.U, f, 0),
+    GemmProblem p[8] = {problem(T, f, ws + L.G, f, 0), problem(T, f, ws + L.U, f, 0),
                         problem(T, R, ws + L.Pg_all, R, 1), problem(T, R, ws + L.Pu_all, R, 1),
                         problem(T, N, ws + L.Z, N, 1),
                         // weight-decomposed experts only: W A_cat^T for the row norms
-                        problem(f, R, ws + L.WA_g, R, 1), problem(f, R, ws + L.WA_u, R, 1)};
+                        problem(f, R, ws + L.WA_g, R, 1), problem(f, R, ws + L.WA_u, R, 1),
+                        problem(d, R, ws + L.WA_d, R, 1)};
     add_seg(p[0], x, d, w->W_gate, d, d);
     add_seg(p[1], x, d, w->W_up, d, d);
     add_seg(p[2], x, d, w->A_gate, d, d);
@@ -256,14 +257,19 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
     add_seg(p[4], x, d, w->W_router, d, d);
     add_seg(p[5], w->W_gate, d, w->A_gate, d, d);
     add_seg(p[6], w->W_up, d, w->A_up, d, d);
+    add_seg(p[7], w->W_down, f, w->A_down, f, f);
     if (vanilla) {   // unshared schedule: the frozen gate/up products follow the routing, per pair;
       HIP_TRY(launch_gemm(dt, p + 4, 1, st));   // only the router logits are needed up front
     } else if (dora) {
-      if (gemm_mixed_rows_ok(dt, p, 7)) {
-        HIP_TRY(launch_gemm(dt, p, 7, st));
+      // the W_down product has the longest K range: its tiles go first so that they do not
+      // trail the launch
+      const GemmProblem q[8] = {p[7], p[0], p[1], p[2], p[3], p[4], p[5], p[6]};
+      if (gemm_mixed_rows_ok(dt, q, 8)) {
+        HIP_TRY(launch_gemm(dt, q, 8, st));
       } else {   // shapes outside the large-tile kernel: problems of different M go separately
         HIP_TRY(launch_gemm(dt, p, 5, st));
         HIP_TRY(launch_gemm(dt, p + 5, 2, st));
+        HIP_TRY(launch_gemm(dt, p + 7, 1, st));
       }
     } else {
       HIP_TRY(launch_gemm(dt, p, dt == MIXLORA_BF16 ? 5 : 4, st));
@@ -271,7 +277,7 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
   }
   DoraArgs dargs{};
   if (dora) {
-    // factors c = m / n of the gate and up projections (n: row norms of W + s B_e A_e)
+    // factors c = m / n of the three projections (n: row norms of W + s B_e A_e)
     float *w2 = (float *)(ws + L.w2), *AA = (float *)(ws + L.AA);
     HIP_TRY(launch_row_sqnorm(w->W_gate, f, d, w2, st));
     HIP_TRY(launch_row_sqnorm(w->W_up, f, d, w2 + f, st));
@@ -285,6 +291,9 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
     HIP_TRY(launch_dora_scale(w->B_up, (float *)(ws + L.WA_u), AA + gpf, w2 + f,
                               dora->m_up, N, f, r, D.lora_scale, (float *)(ws + L.c_u),
                               (float *)(ws + L.ninv_u), st));
+    HIP_TRY(launch_dora_scale(w->B_down, (float *)(ws + L.WA_d), AA + 2 * gpf, w2 + 2 * (size_t)f,
+                              dora->m_down, N, d, r, D.lora_scale, (float *)(ws + L.c_d),
+                              (float *)(ws + L.ninv_d), st));
     dargs.cg = (float *)(ws + L.c_g);
     dargs.cu = (float *)(ws + L.c_u);
   }
@@ -349,26 +358,15 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
                                    ws + L.a_grp, (float *)(ws + L.rank_part),
                                    (float *)(ws + L.Q_all), ws + L.Qp, R, st, rows_mode,
                                    dora ? &dargs : nullptr));
-    GemmProblem p[2] = {problem(kT, d, ws + L.Op, d, 0), problem(d, R, ws + L.WA_d, R, 1)};
-    add_seg(p[0], ws + L.a_grp, f, w->W_down, f, f);
-    add_seg(p[0], ws + L.Qp, R, ws + L.Bd_cat, R, R);
-    add_seg(p[1], w->W_down, f, w->A_down, f, f);
+    GemmProblem p = problem(kT, d, ws + L.Op, d, 0);
+    add_seg(p, ws + L.a_grp, f, w->W_down, f, f);
+    add_seg(p, ws + L.Qp, R, ws + L.Bd_cat, R, R);
+    HIP_TRY(launch_gemm(dt, &p, 1, st));
     if (!dora) {
-      HIP_TRY(launch_gemm(dt, p, 1, st));
       HIP_TRY(launch_pair_combine(dt, pc, d, ws + L.Op, y, 1, st));
       return MIXLORA_OK;
     }
-    if (gemm_mixed_rows_ok(dt, p, 2)) {
-      HIP_TRY(launch_gemm(dt, p, 2, st));
-    } else {
-      HIP_TRY(launch_gemm(dt, p, 1, st));
-      HIP_TRY(launch_gemm(dt, p + 1, 1, st));
-    }
-    // factor of the down projection, applied to every pair's output while combining
-    HIP_TRY(launch_dora_scale(w->B_down, (float *)(ws + L.WA_d),
-                              (float *)(ws + L.AA) + 2 * gram_part_floats(N, r),
-                              (float *)(ws + L.w2) + 2 * (size_t)f, dora->m_down, N, d, r,
-                              D.lora_scale, (float *)(ws + L.c_d), (float *)(ws + L.ninv_d), st));
+    // the down projection's factor is applied to every pair's output while combining
     HIP_TRY(launch_pair_combine_scaled(pc, d, ws + L.Op, (float *)(ws + L.c_d), y, st));
     return MIXLORA_OK;
   }
