@@ -452,44 +452,50 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_dl_kernel(GemmBatch a
       }
     }
   };
-  // bf16 output with 8-element granularity: the accumulators go through a per-wave LDS tile
+  // Outputs whose rows are whole 16-byte pieces: the accumulators go through a per-wave LDS tile
   // (32 rows x TN columns, padded pitch; the ring is free by now) so that every global store is
-  // 16 bytes per lane and a whole 2*TN-byte row segment per TN/8 lanes, instead of 8-byte
-  // pieces of 32 different rows.  LDS operations of one wave execute in order, so the tile
-  // needs no workgroup barrier after the first one.
-  const bool row_major_store = !P.c_f32 && (N & 7) == 0 && (P.ldc & 7) == 0 &&
-                               (reinterpret_cast<uintptr_t>(P.C) & 15) == 0;
-  if (row_major_store) {
-    typedef bf16_t bf16x4_t __attribute__((ext_vector_type(4)));
-    constexpr int EP = TN + 8;                      // tile pitch in elements
-    constexpr int CPW = TN / 8, RPW = 64 / CPW;     // 16-byte chunks per row, rows per instruction
-    static_assert(NW * 32 * EP * 2 <= STAGES * STAGE_BYTES, "epilogue tiles fit in the ring");
+  // 16 bytes per lane and a whole row segment of the wave tile per group of lanes, instead of
+  // short pieces of 32 different rows.  LDS operations of one wave execute in order, so the
+  // tile needs no workgroup barrier after the first one.
+  auto store_rows = [&](auto *C) {
+    typedef typename std::remove_pointer<decltype(C)>::type OutT;
+    constexpr int PER = 16 / (int)sizeof(OutT);     // elements per 16-byte piece
+    constexpr int EP = TN + PER;                    // tile pitch in elements
+    constexpr int CPW = TN / PER, RPW = 64 / CPW;   // pieces per row, rows per instruction
+    static_assert(NW * 32 * EP * (int)sizeof(OutT) <= STAGES * STAGE_BYTES, "epilogue tiles fit in the ring");
+    static_assert(CPW <= 64 && 32 % RPW == 0, "lane mapping of the row-major stores");
+    typedef OutT out4_t __attribute__((ext_vector_type(4)));
+    typedef OutT outp_t __attribute__((ext_vector_type(PER)));
     __syncthreads();   // every wave has finished reading the last ring slot
-    bf16_t *tile = reinterpret_cast<bf16_t *>(smem) + wave * 32 * EP;
-    bf16_t *C = reinterpret_cast<bf16_t *>(P.C);
+    OutT *tile = reinterpret_cast<OutT *>(smem) + wave * 32 * EP;
     const int rr = lane / CPW, cc = lane % CPW;
-    const int c = col0 + wn * TN + cc * 8;
+    const int c = col0 + wn * TN + cc * PER;
 #pragma unroll
     for (int i = 0; i < MI; i++) {
 #pragma unroll
       for (int j = 0; j < NI; j++)
 #pragma unroll
         for (int g = 0; g < 4; g++) {
-          bf16x4_t v;
+          out4_t v;
 #pragma unroll
-          for (int m = 0; m < 4; m++) v[m] = (bf16_t)acc[i][j][g * 4 + m];
-          *reinterpret_cast<bf16x4_t *>(tile + l31 * EP + j * 32 + g * 8 + hi * 4) = v;
+          for (int m = 0; m < 4; m++) v[m] = (OutT)acc[i][j][g * 4 + m];
+          *reinterpret_cast<out4_t *>(tile + l31 * EP + j * 32 + g * 8 + hi * 4) = v;
         }
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int p = 0; p < 32 / RPW; p++) {
         const int rl = p * RPW + rr;
         const int r = row0 + wm * TM + i * 32 + rl;
-        const bf16x8_t v = *reinterpret_cast<const bf16x8_t *>(tile + rl * EP + cc * 8);
-        if (r < M && c < N) *reinterpret_cast<bf16x8_t *>(C + (int64_t)r * P.ldc + c) = v;
+        const outp_t v = *reinterpret_cast<const outp_t *>(tile + rl * EP + cc * PER);
+        if (r < M && c < N) *reinterpret_cast<outp_t *>(C + (int64_t)r * P.ldc + c) = v;
       }
       __builtin_amdgcn_wave_barrier();
     }
+  };
+  const int per = P.c_f32 ? 4 : 8;
+  if ((N % per) == 0 && (P.ldc % per) == 0 && (reinterpret_cast<uintptr_t>(P.C) & 15) == 0) {
+    if (P.c_f32) store_rows(reinterpret_cast<float *>(P.C));
+    else store_rows(reinterpret_cast<bf16_t *>(P.C));
     return;
   }
   if (P.c_f32) store_all(reinterpret_cast<float *>(P.C));
