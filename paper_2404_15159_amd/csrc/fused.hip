@@ -230,7 +230,7 @@ __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 3 : 1) void swiglu_fwd_mf
         float gg = (float)gv[m] + (float)dgl[m];
         float uu = (float)uv[m] + (float)dul[m];
         if constexpr (DORA) { gg *= cgv[m]; uu *= cuv[m]; }
-        av[m] = cvalid ? (bf16_t)(gg * fsigmoid(gg) * uu) : (bf16_t)0.f;
+        av[m] = (bf16_t)(gg * fsigmoid(gg) * uu);   // columns past f: finite, meet zeroed weights
       }
       gnx[p] = ld8(G + gsrc[p] + col_of(cn));
       unx[p] = ld8(U + gsrc[p] + col_of(cn));
@@ -448,8 +448,10 @@ __global__ __launch_bounds__(FT_WAVES * 64, (KSR == 1 && !DORA) ? 2 : 1) void sw
           dgr *= cgv[m];
           dur *= cuv[m];
         }
-        dgv[m] = cvalid ? (bf16_t)dgr : (bf16_t)0.f;
-        duv[m] = cvalid ? (bf16_t)dur : (bf16_t)0.f;
+        // columns past f hold finite values of clamped loads; they meet zeroed weights in the
+        // rank-r products below and are never stored
+        dgv[m] = (bf16_t)dgr;
+        duv[m] = (bf16_t)dur;
       }
       if (cvalid) dwacc[p] += part;
       {
