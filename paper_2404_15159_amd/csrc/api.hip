@@ -604,8 +604,8 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
     HIP_TRY(launch_gemm(dt, p, 2, st));
   }
   if (!vanilla) {   // shared gate/up: their input gradient needs the per-token sums only
-    HIP_TRY(launch_pair_combine(dt, pc, f, ws + L.dg_grp, ws + L.dgsum, 0, st));
-    HIP_TRY(launch_pair_combine(dt, pc, f, ws + L.du_grp, ws + L.dusum, 0, st));
+    HIP_TRY(launch_pair_combine2(dt, pc, f, ws + L.dg_grp, ws + L.dgsum, ws + L.du_grp,
+                                 ws + L.dusum, 0, st));
   }
   // per-row rank-r factors of the LoRA gradients, then the grouped outer-product sums:
   //   dB_gate[e] = s sum dg (x) Pg ; dA_gate[e] = s sum TG (x) x ; same for up ;

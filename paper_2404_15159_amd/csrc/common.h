@@ -178,6 +178,10 @@ int fused_splits(int f);
 // out[t,:] = sum_j (weighted ? w[t,j] : 1) * in_grp[row_of_pair[t,j], :]
 hipError_t launch_pair_combine(int dtype, const PairCtx &pc, int width, const void *in_grp,
                                void *out, int weighted, hipStream_t st);
+// two combines of the same shape in one launch (in_grp1 == NULL: only the first)
+hipError_t launch_pair_combine2(int dtype, const PairCtx &pc, int width, const void *in_grp0,
+                                void *out0, const void *in_grp1, void *out1, int weighted,
+                                hipStream_t st);
 // dst[row, :] = src[token of grouped row, :]   (width a multiple of 8)
 hipError_t launch_gather_rows(int dtype, const PairCtx &pc, int width, const void *src, void *dst,
                               hipStream_t st);

@@ -254,9 +254,14 @@ hipError_t launch_swiglu_bwd(int dtype, const PairCtx &pc, int f, float s, const
 // once, by one thread per 8 columns, slots added in ascending order (deterministic).
 template <typename E>
 __global__ __launch_bounds__(256) void pair_combine_kernel(PairCtx pc, int width,
-                                                           const E *__restrict__ in_grp,
-                                                           E *__restrict__ out, int weighted) {
+                                                           const E *__restrict__ in_grp0,
+                                                           E *__restrict__ out0,
+                                                           const E *__restrict__ in_grp1,
+                                                           E *__restrict__ out1, int weighted) {
+  // blockIdx.z picks one of two combines of the same shape that share the launch;
   // a thread owns two 8-column chunks, 2048 columns apart: 2k independent loads in flight
+  const E *__restrict__ in_grp = blockIdx.z ? in_grp1 : in_grp0;
+  E *__restrict__ out = blockIdx.z ? out1 : out0;
   const int t = blockIdx.x;
   const int c0 = (blockIdx.y * 512 + threadIdx.x) * 8;
   const int c1 = c0 + 2048;
@@ -288,16 +293,24 @@ __global__ __launch_bounds__(256) void pair_combine_kernel(PairCtx pc, int width
   }
 }
 
-hipError_t launch_pair_combine(int dtype, const PairCtx &pc, int width, const void *in_grp,
-                               void *out, int weighted, hipStream_t st) {
-  const dim3 grid(pc.T, (width / 8 + 511) / 512), block(256);
+hipError_t launch_pair_combine2(int dtype, const PairCtx &pc, int width, const void *in_grp0,
+                                void *out0, const void *in_grp1, void *out1, int weighted,
+                                hipStream_t st) {
+  const dim3 grid(pc.T, (width / 8 + 511) / 512, in_grp1 ? 2 : 1), block(256);
   if (dtype == MIXLORA_BF16)
     hipLaunchKernelGGL(pair_combine_kernel<bf16_t>, grid, block, 0, st, pc, width,
-                       (const bf16_t *)in_grp, (bf16_t *)out, weighted);
+                       (const bf16_t *)in_grp0, (bf16_t *)out0, (const bf16_t *)in_grp1,
+                       (bf16_t *)out1, weighted);
   else
     hipLaunchKernelGGL(pair_combine_kernel<float>, grid, block, 0, st, pc, width,
-                       (const float *)in_grp, (float *)out, weighted);
+                       (const float *)in_grp0, (float *)out0, (const float *)in_grp1,
+                       (float *)out1, weighted);
   return hipGetLastError();
+}
+
+hipError_t launch_pair_combine(int dtype, const PairCtx &pc, int width, const void *in_grp,
+                               void *out, int weighted, hipStream_t st) {
+  return launch_pair_combine2(dtype, pc, width, in_grp, out, nullptr, nullptr, weighted, st);
 }
 
 // ---- dst[row, :] = src[token of grouped row, :] : the routed tokens' rows in expert-grouped order
