@@ -460,9 +460,82 @@ __global__ __launch_bounds__(256) void lowrank_add_kernel(E *__restrict__ io,
   }
 }
 
+// Same update for r <= 16: a thread keeps the 16 rank entries of its 8 columns in registers and
+// walks LRB_ROWS rows (P[t, :] is uniform over the workgroup: scalar loads), so the weight rows
+// are read once per workgroup instead of once per 4 rows.
+constexpr int LRB_ROWS = 8;
+
+template <typename E>
+__global__ __launch_bounds__(256) void lowrank_add_r16_kernel(E *__restrict__ io,
+                                                              const float *__restrict__ P,
+                                                              const E *__restrict__ Wt, int T, int C,
+                                                              int r, float s) {
+  const int c0 = (blockIdx.x * 256 + threadIdx.x) * 8;
+  if (c0 >= C) return;
+  const int t0 = blockIdx.y * LRB_ROWS;
+  const int t1 = t0 + LRB_ROWS < T ? t0 + LRB_ROWS : T;
+  float w[8][16];
+#pragma unroll
+  for (int j = 0; j < 8; j++) {
+    Vec8<E> a, b;
+    a.load(Wt + (int64_t)(c0 + j) * r);
+    if (r > 8) b.load(Wt + (int64_t)(c0 + j) * r + 8);
+#pragma unroll
+    for (int q = 0; q < 8; q++) {
+      w[j][q] = s * a.get(q);
+      w[j][8 + q] = r > 8 ? s * b.get(q) : 0.f;
+    }
+  }
+  // four rows per step, the next four requested before the arithmetic of the current ones
+  Vec8<E> cur[4], nxt[4];
+  auto load4 = [&](int t, Vec8<E> (&v)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int tt = t + i < T ? t + i : T - 1;
+      v[i].load(io + (int64_t)tt * C + c0);
+    }
+  };
+  load4(t0, cur);
+  for (int t = t0; t < t1; t += 4) {
+    if (t + 4 < t1) load4(t + 4, nxt);
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      const int tt = t + i < T ? t + i : T - 1;
+      const float *pt = P + (int64_t)tt * r;
+      float acc[8];
+#pragma unroll
+      for (int j = 0; j < 8; j++) acc[j] = cur[i].get(j);
+#pragma unroll
+      for (int q = 0; q < 16; q++) {
+        const float pq = q < r ? pt[q] : 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; j++) acc[j] = fmaf(pq, w[j][q], acc[j]);
+      }
+      if (t + i < t1) {
+        Vec8<E> o;
+#pragma unroll
+        for (int j = 0; j < 8; j++) o.set(j, acc[j]);
+        o.store(io + (int64_t)(t + i) * C + c0);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++) cur[i] = nxt[i];
+  }
+}
+
 hipError_t launch_lowrank_add(int dtype, void *io, const float *P, const void *Wt, int T, int C,
                               int r, float s, hipStream_t st) {
   if (C % 8 || r % 8) return hipErrorInvalidValue;
+  if (r <= 16) {
+    const dim3 grid((C / 8 + 255) / 256, (T + LRB_ROWS - 1) / LRB_ROWS), block(256);
+    if (dtype == MIXLORA_BF16)
+      hipLaunchKernelGGL(lowrank_add_r16_kernel<bf16_t>, grid, block, 0, st, (bf16_t *)io, P,
+                         (const bf16_t *)Wt, T, C, r, s);
+    else
+      hipLaunchKernelGGL(lowrank_add_r16_kernel<float>, grid, block, 0, st, (float *)io, P,
+                         (const float *)Wt, T, C, r, s);
+    return hipGetLastError();
+  }
   const int64_t n = (int64_t)((T + LRA_ROWS - 1) / LRA_ROWS) * (C / 8);
   const dim3 grid((unsigned)((n + 255) / 256)), block(256);
   if (dtype == MIXLORA_BF16)
