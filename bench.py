@@ -1,13 +1,17 @@
 """Benchmark of the MixLoRA FFN block (forward + backward) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--forward-only]
+                    [--schedule linear_down|shared|vanilla] [--dora] [--no-cpu-baseline]
 
 One step = one pass of the whole hot path: mixlora_ffn_forward followed by
 mixlora_ffn_backward on the LLaMA-2-7B-shaped workload (T=4096 tokens, d=4096, d_ff=11008,
 8 experts, top-2, rank 16, bf16), inputs resident in HBM before the timed region.
 Prints ONE JSON line: tokens/s, the roofline record of the dominant kernel (the large-tile
 bf16 MFMA GEMM, timed live with HIP events on its stream) and the CPU oracle's rate on a
-bounded token sample of the same workload.
+bounded token sample of the same workload.  --workload picks the other shapes (13B-skew,
+L3-8B-clusters, two adapters, decode, the attention-projection LoRA linear); --schedule runs the
+paper's own shared / unshared schedules and --dora the weight-decomposed expert variant, for
+comparison with the default.
 """
 from __future__ import annotations
 
