@@ -205,6 +205,9 @@ def main():
     t_inputs = time.perf_counter() - t0
     schedule = {"linear_down": B.SCHEDULE_LINEAR_DOWN, "shared": B.SCHEDULE_SHARED,
                 "vanilla": B.SCHEDULE_VANILLA}[args.schedule]
+    if args.schedule != "linear_down" and cfg.M > 1:
+        print("bench.py: --schedule shared/vanilla runs one adapter", file=sys.stderr)
+        sys.exit(2)
     if args.dora and (args.schedule != "linear_down" or cfg.M > 1):
         print("bench.py: --dora runs one adapter and chooses its own schedule", file=sys.stderr)
         sys.exit(2)
