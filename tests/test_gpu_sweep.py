@@ -1,0 +1,103 @@
+"""Seeded random-shape sweep of every entry-point family against the oracle (small shapes: odd
+token counts around the tile sizes, d and d_ff at every multiple-of-8 remainder class, ranks
+8..64, 1..32 experts).  With fewer than 16 tokens the router-weight gradient is a sum of a few
+terms dz_t x_t whose dz_t is a difference of nearly equal numbers (the k routing-weight
+gradients), so bf16 rounding shows in it without averaging: its tolerance is relaxed there
+(measured identical for all schedules; the other tensors keep the bar)."""
+import numpy as np
+import pytest
+
+from oracle import mixlora_oracle as orc
+from paper_2404_15159_amd import binding as B
+from paper_2404_15159_amd import synth
+from paper_2404_15159_amd.runner import MixLoraFFN
+
+import parity_utils as pu
+
+pytestmark = pytest.mark.gpu
+
+KINDS = ("default", "shared", "vanilla", "dora", "multi", "f32")
+MAG = ("m_gate", "m_up", "m_down")
+
+
+def _draw(rng, ci):
+    kind = KINDS[ci % len(KINDS)]
+    N = int(rng.choice([1, 2, 3, 4, 5, 6, 8, 12, 16, 24, 32]))
+    k = int(rng.integers(1, min(N, 4) + 1))
+    r = int(rng.choice([8, 16, 24, 32, 40, 64]))
+    if N * r > 512:
+        r = 8
+    T = int(rng.choice([1, 2, 7, 33, 64, 65, 127, 128, 129, 200, 255, 256, 257, 511, 700, 1025, 2049]))
+    d = int(rng.choice([8, 16, 24, 64, 72, 128, 136, 192, 256, 264, 320, 512]))
+    f = int(rng.choice([8, 16, 40, 64, 120, 128, 136, 256, 264, 504, 512, 520, 1032]))
+    M = 1
+    if kind == "multi":
+        M = int(rng.choice([2, 3]))
+        if M * N > 64 or M * N * r > 512:
+            N, r, k = 4, 8, min(k, 4)
+    return kind, dict(T=T, d=d, d_ff=f, N=N, k=k, r=r, alpha=2.0 * r, M=M, seq_len=max(1, T // 7))
+
+
+def _check_grads(res, ref, cfg, all_same):
+    tol = pu.TOL[cfg.dtype]
+    for n in pu.GRAD_NAMES:
+        if not (all_same or cfg.dtype == "bf16"):
+            continue
+        t = tol * (10.0 if (n == "dW_router" and cfg.T < 16) else 1.0)
+        pu.assert_close(n, res[n], ref[n], t)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_random_shapes(seed):
+    rng = np.random.default_rng(seed)
+    for ci in range(36):
+        kind, over = _draw(rng, ci)
+        base = synth.CONFIGS["tiny_f32"] if kind == "f32" else synth.CONFIGS["llama2_7b"]
+        cfg = synth.scaled(base, name=f"sweep{seed}_{ci}_{kind}", **over)
+        print(f"case {ci} {kind}: {over}", flush=True)
+        host = synth.make_inputs(cfg)
+        for n in ("B_gate", "B_up", "B_down"):
+            host[n] = synth.round_to_bf16(host[n] * 4.0) if cfg.dtype == "bf16" else host[n] * 4.0
+        W = {n: host[n] for n in synth.WEIGHT_NAMES}
+        tol = pu.TOL[cfg.dtype]
+        if kind == "multi":
+            tm = synth.token_model(cfg, "uneven")
+            m = MixLoraFFN(cfg, host, token_model=tm)
+            m.forward()
+            m.backward()
+            res = m.results()
+            Ws = synth.split_adapters(cfg, host)
+            fw = orc.multi_forward(host["x"], tm, Ws, cfg.k, cfg.lora_scale, cfg.aux_coeff)
+            bw = orc.multi_backward(host["x"], tm, Ws, cfg.k, cfg.lora_scale, host["dy"], None,
+                                    cfg.aux_coeff)
+            same = pu.check_routing(res, fw, cfg, 2e-5, token_model=tm)
+            pu.assert_close("y", res["y"][same], fw["y"][same], tol)
+            pu.assert_close("dx", res["dx"][same], bw["dx"][same], tol)
+            ref = {n: np.concatenate([g[n] for g in bw["grads"]], axis=0) for n in pu.GRAD_NAMES}
+            _check_grads(res, ref, cfg, bool(same.all()))
+            continue
+        if kind == "dora":
+            mag = {n: [] for n in MAG}
+            for e in range(cfg.N):
+                nrm = orc.dora_row_norms(W, e, cfg.lora_scale)
+                for nm in ("gate", "up", "down"):
+                    mag["m_" + nm].append(nrm[nm] * rng.uniform(0.6, 1.4, nrm[nm].shape))
+            mag = {n: np.stack(v).astype(np.float32) for n, v in mag.items()}
+            m = MixLoraFFN(cfg, host, magnitudes=mag)
+            bw = orc.dora_backward(host["x"], W, mag, cfg.k, cfg.lora_scale, host["dy"], 1.5,
+                                   cfg.aux_coeff)
+        else:
+            sched = {"shared": B.SCHEDULE_SHARED, "vanilla": B.SCHEDULE_VANILLA}.get(
+                kind, B.SCHEDULE_LINEAR_DOWN)
+            m = MixLoraFFN(cfg, host, schedule=sched)
+            bw = orc.backward(host["x"], W, cfg.k, cfg.lora_scale, host["dy"], 1.5, cfg.aux_coeff)
+        m.forward()
+        m.backward(d_aux=1.5)
+        res = m.results()
+        rep = pu.compare_all(res, bw["forward"], bw, cfg, check_grads=False, verbose=False)
+        same = (res["topk_idx"] == bw["forward"]["topk_idx"]).all(axis=1)
+        pu.assert_close("dx", res["dx"][same], bw["dx"][same], tol)
+        _check_grads(res, bw, cfg, rep["routing_mismatch_tokens"] == 0)
+        if kind == "dora":
+            for n in MAG:
+                pu.assert_close("d" + n, res["d" + n], bw["d" + n], tol)
