@@ -111,10 +111,21 @@ def test_unused_expert_and_untransposed_weights():
         assert (res[n][5] == 0.0).all(), n
 
 
-def test_deterministic_reruns():
-    cfg = synth.scaled(BASE_BF16, name="bf16_rerun", T=700, d=256, d_ff=1032, N=8, k=2, r=16)
+@pytest.mark.parametrize("variant", ["default", "long_batch", "shared", "vanilla", "dora"])
+def test_deterministic_reruns(variant):
+    """No atomics, fixed summation orders: a second run on the same buffers gives the same bits.
+    long_batch goes through the multi-workgroup grouping passes."""
+    over = dict(T=700, d=256, d_ff=1032, N=8, k=2, r=16)
+    if variant == "long_batch":
+        over = dict(T=4500, d=64, d_ff=136, N=8, k=2, r=8, alpha=16.0)
+    cfg = synth.scaled(BASE_BF16, name="bf16_rerun_" + variant, **over)
     host = synth.make_inputs(cfg)
-    m = MixLoraFFN(cfg, host)
+    kw = {}
+    if variant in ("shared", "vanilla"):
+        kw["schedule"] = B.SCHEDULE_SHARED if variant == "shared" else B.SCHEDULE_VANILLA
+    if variant == "dora":
+        kw["magnitudes"] = synth.make_magnitudes(cfg)
+    m = MixLoraFFN(cfg, host, **kw)
     m.forward(); m.backward()
     a = m.results()
     m.forward(); m.backward()
