@@ -329,3 +329,26 @@ def test_synth_is_deterministic_and_in_dtype():
     assert abs(a["x"].std() - 1.0) < 0.05
     assert abs(a["W_gate"].std() - 0.02) < 0.002
     assert np.abs(a["A_gate"]).max() <= 1 / math.sqrt(cfg.d) + 1e-3
+
+
+def test_synth_magnitudes_and_token_patterns():
+    """Input recipes that hold none of the method's arithmetic: magnitudes scatter around the
+    expected row norm of a frozen matrix of the recipe (0.02 * sqrt(fan_in)), so the factors
+    magnitude / norm of the weight-decomposed variant stay near one; token-to-adapter patterns
+    assign whole sequences."""
+    cfg = synth.scaled(synth.CONFIGS["llama2_7b"], T=64, d=256, d_ff=512, N=4, M=3, seq_len=8)
+    m1, m2 = synth.make_magnitudes(cfg), synth.make_magnitudes(cfg)
+    assert set(m1) == {"m_gate", "m_up", "m_down"}
+    for n in m1:
+        assert np.array_equal(m1[n], m2[n]) and m1[n].dtype == np.float32 and (m1[n] > 0).all()
+    assert m1["m_gate"].shape == (4, 512) and m1["m_down"].shape == (4, 256)
+    host = synth.make_inputs(cfg, only=("W_gate", "W_down"))
+    for name, w in (("m_gate", host["W_gate"]), ("m_down", host["W_down"])):
+        ratio = m1[name] / np.linalg.norm(w.astype(np.float64), axis=1)[None, :]
+        assert 0.6 < ratio.min() and ratio.max() < 1.5, name
+    for pattern in ("round_robin", "uneven", "skip_last"):
+        tm = synth.token_model(cfg, pattern)
+        assert tm.shape == (64,) and tm.min() >= 0 and tm.max() < 3
+        assert (tm.reshape(8, 8) == tm.reshape(8, 8)[:, :1]).all()      # whole sequences
+    assert not (synth.token_model(cfg, "skip_last") == 2).any()
+    assert (np.bincount(synth.token_model(cfg, "uneven"), minlength=3) == [32, 16, 16]).all()
