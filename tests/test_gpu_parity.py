@@ -163,15 +163,28 @@ def test_caller_stream_and_forward_only_workspace():
         assert np.array_equal(np.asarray(a[n]), np.asarray(c[n])), n
 
 
-def test_graph_capture_and_replay():
+@pytest.mark.parametrize("variant", ["default", "long_batch", "shared", "vanilla", "dora"])
+def test_graph_capture_and_replay(variant):
     """The call sequences allocate nothing and never synchronise, so forward + backward can be
     captured into a HIP graph.  Every replay (with eager work and synchronisations between the
-    replays) must reproduce the eager result bit for bit."""
-    cfg = synth.scaled(BASE_BF16, name="bf16_graph", T=384, d=256, d_ff=648, N=8, k=2, r=16)
+    replays) must reproduce the eager result bit for bit; the same holds for the paper's two
+    schedules, the weight-decomposed variant and the multi-workgroup grouping of long batches."""
+    over = dict(T=384, d=256, d_ff=648, N=8, k=2, r=16)
+    if variant == "long_batch":
+        over = dict(T=4500, d=64, d_ff=136, N=8, k=2, r=8, alpha=16.0)
+    cfg = synth.scaled(BASE_BF16, name="bf16_graph_" + variant, **over)
     host = synth.make_inputs(cfg)
-    m = MixLoraFFN(cfg, host)
+    kw = {}
+    if variant in ("shared", "vanilla"):
+        kw["schedule"] = B.SCHEDULE_SHARED if variant == "shared" else B.SCHEDULE_VANILLA
+    if variant == "dora":
+        kw["magnitudes"] = synth.make_magnitudes(cfg)
+    m = MixLoraFFN(cfg, host, **kw)
     m.forward(); m.backward()          # eager: also sets the kernels' one-time attributes
     ref = m.results()
+    outputs = [m.y, m.dx, m.topk_w, *m.g.values()]
+    if variant == "dora":
+        outputs += list(m.gm.values())
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     graph = torch.cuda.CUDAGraph()
@@ -183,7 +196,7 @@ def test_graph_capture_and_replay():
     torch.cuda.synchronize()
     x0 = m.t["x"].clone()
     for rep in range(3):
-        for t in (m.y, m.dx, m.topk_w, *m.g.values()):
+        for t in outputs:
             t.zero_()
         # eager work of the program's own between the replays: another input through the same
         # workspace, then the original input restored
