@@ -487,7 +487,9 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_dl_kernel(GemmBatch a
         const int rl = p * RPW + rr;
         const int r = row0 + wm * TM + i * 32 + rl;
         const outp_t v = *reinterpret_cast<const outp_t *>(tile + rl * EP + cc * PER);
-        if (r < M && c < N) *reinterpret_cast<outp_t *>(C + (int64_t)r * P.ldc + c) = v;
+        // streaming (non-temporal) stores: an output tile is never read again by this launch,
+        // so it should not displace the operand tiles that other workgroups re-read from L2
+        if (r < M && c < N) __builtin_nontemporal_store(v, reinterpret_cast<outp_t *>(C + (int64_t)r * P.ldc + c));
       }
       __builtin_amdgcn_wave_barrier();
     }
