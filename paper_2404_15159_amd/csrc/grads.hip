@@ -390,7 +390,8 @@ hipError_t launch_f32_to_bf16T(const float *src, int rows, int r, void *outT, in
 // <H[t], a_row> plus the low-rank part  s <B_down[e]^T dy_t, A_down[e] a_row>  (lanes split the
 // terms, a butterfly adds them).  Then, with w_j = p_j / sum_kept p (Norm of Algorithm 1):
 // dp_j = (dw_j - sum_i w_i dw_i) / sum_kept p on the kept experts, plus the auxiliary term
-// d_aux * a * N * F_e / T  on every expert (Eq. 8-9; F is piecewise constant), and
+// d_aux * a * N * F_e / T  on every expert (Eq. 8-9; F is piecewise constant; evaluated as its
+// deviation from 1/N, see below), and
 // dz = p * (dp - <p, dp>) through the softmax of Eq. 7 (lane e holds expert e).  With several
 // adapters p is zero outside the token's adapter, so dz is too; T and the upstream gradient of
 // the auxiliary loss are those of the token's adapter.
@@ -438,7 +439,18 @@ __global__ __launch_bounds__(256) void router_bwd_kernel(
   // auxiliary term of the token's adapter: statistics over that adapter's own tokens
   const int m = __builtin_amdgcn_readfirstlane(token_model ? token_model[t] : 0);   // wave-uniform
   const float auxg = d_aux.v[m] * aux_coeff * (float)Nl / (float)model_tokens[m];
-  float dp = lane < N ? auxg * F[lane] : 0.f;
+  // The softmax Jacobian ignores a constant added to dp, so F_e - 1/Nl stands in for F_e: with
+  // nearly balanced loads (what the loss drives towards) p * (F_e - <p, F>) would otherwise be a
+  // difference of nearly equal numbers.  F_e * (k * tokens) is an integer in both modes of Eq. 9
+  // (k times the first-slot count, or the kept count), recovered exactly by rounding, so the
+  // deviation (num_e * Nl - k * tokens) / (k * tokens * Nl) has an exact numerator.
+  float dp = 0.f;
+  if (lane < N) {
+    const float kt = (float)k * (float)model_tokens[m];
+    const int64_t num = (int64_t)rintf(F[lane] * kt);
+    const int64_t dev = num * Nl - (int64_t)k * model_tokens[m];
+    dp = auxg * ((float)dev / (kt * (float)Nl));
+  }
   for (int j = 0; j < k; j++) {
     const int ej = __shfl(my_e, j, 64);
     const float dwj = __shfl(my_dw, j, 64);

@@ -84,6 +84,10 @@ SMALL_CASES = [
     ("f32_long_batch", BASE_F32, dict(T=4200, d=32, d_ff=72, N=16, k=2, r=8)),
     ("f32_ragged", BASE_F32, dict(T=333, d=72, d_ff=200, N=6, k=2, r=8)),
     ("f32_top3", BASE_F32, dict(T=129, d=64, d_ff=136, N=8, k=3, r=16, alpha=32.0)),
+    # top-1 with nearly balanced first-slot counts: the router is trained by the auxiliary term
+    # alone, p * (F_e - <p, F>) with every F_e within a percent of 1/N
+    ("f32_top1_balanced_aux", BASE_F32, dict(T=2049, d=128, d_ff=1032, N=3, k=1, r=16, alpha=32.0)),
+    ("f32_top1_balanced_aux_topk", BASE_F32, dict(T=2049, d=128, d_ff=264, N=3, k=3, r=8)),
 ]
 
 

@@ -38,10 +38,17 @@ def _draw(rng, ci):
     return kind, dict(T=T, d=d, d_ff=f, N=N, k=k, r=r, alpha=2.0 * r, M=M, seq_len=max(1, T // 7))
 
 
-def _check_grads(res, ref, cfg, all_same):
+def _check_grads(res, ref, cfg, all_same, F=None, x_max=1.0):
     tol = pu.TOL[cfg.dtype]
     for n in pu.GRAD_NAMES:
         if not (all_same or cfg.dtype == "bf16"):
+            continue
+        if n == "dW_router" and cfg.k == 1 and F is not None and np.ptp(F) == 0.0:
+            # top-1 keeps weight 1, so only the auxiliary term reaches the router, and with
+            # exactly equal F_e it is p * (F_e - <p, F>) = 0: the oracle's value is its own
+            # float64 rounding noise, so the HIP result is held to an absolute bound instead
+            assert np.abs(ref[n]).max() <= 1e-12 * x_max
+            assert np.abs(res[n]).max() <= 1e-7 * cfg.aux_coeff * x_max, n
             continue
         t = tol * (10.0 if (n == "dW_router" and cfg.T < 16) else 1.0)
         pu.assert_close(n, res[n], ref[n], t)
@@ -97,7 +104,8 @@ def test_random_shapes(seed):
         rep = pu.compare_all(res, bw["forward"], bw, cfg, check_grads=False, verbose=False)
         same = (res["topk_idx"] == bw["forward"]["topk_idx"]).all(axis=1)
         pu.assert_close("dx", res["dx"][same], bw["dx"][same], tol)
-        _check_grads(res, bw, cfg, rep["routing_mismatch_tokens"] == 0)
+        _check_grads(res, bw, cfg, rep["routing_mismatch_tokens"] == 0, F=bw["forward"]["F"],
+                     x_max=float(np.abs(host["x"]).max()))
         if kind == "dora":
             for n in MAG:
                 pu.assert_close("d" + n, res["d" + n], bw["d" + n], tol)

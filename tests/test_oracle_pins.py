@@ -290,6 +290,29 @@ def test_identities():
     np.testing.assert_allclose(y2, fw["y"], rtol=1e-12, atol=1e-13)
 
 
+def test_top1_with_balanced_counts_gives_no_router_gradient():
+    """Closed form from Eq. 7-9: with k = 1 the kept weight is 1 whatever the logits, so only the
+    auxiliary term reaches the router, dz = p * (gamma - <p, gamma>) with gamma_e proportional to
+    F_e; when every expert is first choice equally often gamma is constant and, the probabilities
+    summing to one, dz vanishes.  With unequal counts it does not."""
+    cfg = small_cfg(T=30, N=3, k=1)
+    t = inputs(cfg)
+    W = weights(t)
+    # make token i prefer expert i mod 3 by a wide margin: counts are 10 / 10 / 10
+    t["x"][:, :3] = 0.0
+    t["x"][np.arange(cfg.T), np.arange(cfg.T) % 3] = 4.0
+    W["W_router"][:, :3] = 3.0 * np.eye(3)
+    g = orc.backward(t["x"], W, 1, cfg.lora_scale, t["dy"], 1.0, 0.01, "top1")
+    assert (g["forward"]["counts"] == 10).all()
+    scale = np.abs(t["x"]).max() * 0.01
+    assert np.abs(g["dW_router"]).max() <= 1e-13 * scale
+    assert np.abs(g["dz"]).max() <= 1e-15
+    t["x"][0, :3] = (0.0, 4.0, 0.0)        # token 0 moves from expert 0 to expert 1: 9 / 11 / 10
+    g = orc.backward(t["x"], W, 1, cfg.lora_scale, t["dy"], 1.0, 0.01, "top1")
+    assert tuple(g["forward"]["counts"]) == (9, 11, 10)
+    assert np.abs(g["dW_router"]).max() > 1e-8 * scale
+
+
 def test_unused_expert_gets_zero_grads():
     cfg = small_cfg(T=20, N=5, k=2)
     t = inputs(cfg)
