@@ -80,14 +80,14 @@ constexpr int FT_TILE = FT_ROWS * FT_PITCH;
 
 __device__ __forceinline__ bf16x8_t ld8(const bf16_t *p) { return *reinterpret_cast<const bf16x8_t *>(p); }
 
-// write one 32x32 MFMA result block (scaled) into an LDS tile at column offset cb32
-__device__ __forceinline__ void tile_put(bf16_t *tile, int l31, int hi, int cb32, const f32x16_t &d,
-                                         float scale) {
+// write one 32x32 MFMA result block into an LDS tile at column offset cb32 (the LoRA scale is
+// already in the per-row operand fragments)
+__device__ __forceinline__ void tile_put(bf16_t *tile, int l31, int hi, int cb32, const f32x16_t &d) {
 #pragma unroll
   for (int g = 0; g < 4; g++) {
     bf16x4_t v;
 #pragma unroll
-    for (int m = 0; m < 4; m++) v[m] = (bf16_t)(scale * d[g * 4 + m]);
+    for (int m = 0; m < 4; m++) v[m] = (bf16_t)d[g * 4 + m];
     *reinterpret_cast<bf16x4_t *>(tile + l31 * FT_PITCH + cb32 + 8 * g + 4 * hi) = v;
   }
 }
@@ -123,8 +123,8 @@ __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 3 : 1) void swiglu_fwd_mf
     for (int ks = 0; ks < KSR; ks++) {
       const int q0 = ks * 16 + hi * 8;
       const bool v = q0 < r;
-      pg[ks] = cvt8(Pg_all + tm * R + e * r + (v ? q0 : 0), v, 1.f);
-      pu[ks] = cvt8(Pu_all + tm * R + e * r + (v ? q0 : 0), v, 1.f);
+      pg[ks] = cvt8(Pg_all + tm * R + e * r + (v ? q0 : 0), v, s);
+      pu[ks] = cvt8(Pu_all + tm * R + e * r + (v ? q0 : 0), v, s);
     }
   }
   // row-major role: the four rows (8p + rr) this lane serves
@@ -193,6 +193,7 @@ __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 3 : 1) void swiglu_fwd_mf
   for (int sb = sb_lo + wave; sb < sb_hi; sb += FT_WAVES) {
     const int c0 = sb * FT_SB;
     const int cn = sb + FT_WAVES < sb_hi ? c0 + FT_WAVES * FT_SB : c0;   // next (or again this)
+    const bool tail = c0 + FT_SB > f;                                    // wave-uniform
     // rank-r deltas of both 32-column blocks -> LDS tiles
 #pragma unroll
     for (int b = 0; b < 2; b++) {
@@ -201,12 +202,13 @@ __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 3 : 1) void swiglu_fwd_mf
       for (int i = 0; i < 16; i++) dg[i] = du[i] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < KSR; ks++) {
-        const bool v = ks * 16 + hi * 8 < r;
-        dg = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v ? wg[b][ks] : zero8(), pg[ks], dg, 0, 0, 0);
-        du = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v ? wu[b][ks] : zero8(), pu[ks], du, 0, 0, 0);
+        // rank entries past r: the row fragments hold zeros there, the weight fragments finite
+        // values of clamped loads
+        dg = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wg[b][ks], pg[ks], dg, 0, 0, 0);
+        du = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wu[b][ks], pu[ks], du, 0, 0, 0);
       }
-      tile_put(tg, l31, hi, 32 * b, dg, s);
-      tile_put(tu, l31, hi, 32 * b, du, s);
+      tile_put(tg, l31, hi, 32 * b, dg);
+      tile_put(tu, l31, hi, 32 * b, du);
     }
     load_w(cn);   // next iteration's delta weights: oldest outstanding loads from here on
     __builtin_amdgcn_wave_barrier();
@@ -242,11 +244,13 @@ __global__ __launch_bounds__(FT_WAVES * 64, KSR == 1 ? 3 : 1) void swiglu_fwd_mf
 #pragma unroll
     for (int s4 = 0; s4 < 4; s4++) {
       const bf16x8_t af = ld8(tg + l31 * FT_PITCH + 16 * s4 + 8 * hi);
-      const bool kv = c0 + 16 * s4 + 8 * hi < f;
 #pragma unroll
       for (int j = 0; j < NQ; j++) {
-        const bool v = kv && j * 32 + l31 < r;
-        accq[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, v ? wf[s4][j] : zero8(), accq[j], 0, 0, 0);
+        // outputs with q >= r are never stored; columns past f (last super-block only) hold
+        // finite values in the tile and must meet zeros
+        bf16x8_t w = wf[s4][j];
+        if (tail && c0 + 16 * s4 + 8 * hi >= f) w = zero8();
+        accq[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, w, accq[j], 0, 0, 0);
       }
     }
     load_wf(cn);
@@ -314,9 +318,9 @@ __global__ __launch_bounds__(FT_WAVES * 64, (KSR == 1 && !DORA) ? 2 : 1) void sw
       const int q0 = ks * 16 + hi * 8;
       const bool v = q0 < r;
       const int64_t o = tm * R + e * r + (v ? q0 : 0);
-      pg[ks] = cvt8(Pg_all + o, v, 1.f);
-      pu[ks] = cvt8(Pu_all + o, v, 1.f);
-      vw[ks] = cvt8(VB_all + o, v, wm);
+      pg[ks] = cvt8(Pg_all + o, v, s);
+      pu[ks] = cvt8(Pu_all + o, v, s);
+      vw[ks] = cvt8(VB_all + o, v, wm * s);
     }
   }
   int64_t gsrc[4], odst[4];
@@ -394,6 +398,7 @@ __global__ __launch_bounds__(FT_WAVES * 64, (KSR == 1 && !DORA) ? 2 : 1) void sw
   for (int sb = sb_lo + wave; sb < sb_hi; sb += FT_WAVES) {
     const int c0 = sb * FT_SB;
     const int cn = sb + FT_WAVES < sb_hi ? c0 + FT_WAVES * FT_SB : c0;
+    const bool tail = c0 + FT_SB > f;   // wave-uniform
 #pragma unroll
     for (int b = 0; b < 2; b++) {
       f32x16_t dgm, dum, ddm;
@@ -401,14 +406,13 @@ __global__ __launch_bounds__(FT_WAVES * 64, (KSR == 1 && !DORA) ? 2 : 1) void sw
       for (int i = 0; i < 16; i++) dgm[i] = dum[i] = ddm[i] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < KSR; ks++) {
-        const bool v = ks * 16 + hi * 8 < r;
-        dgm = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v ? wg[b][ks] : zero8(), pg[ks], dgm, 0, 0, 0);
-        dum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v ? wu[b][ks] : zero8(), pu[ks], dum, 0, 0, 0);
-        ddm = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v ? wd[b][ks] : zero8(), vw[ks], ddm, 0, 0, 0);
+        dgm = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wg[b][ks], pg[ks], dgm, 0, 0, 0);
+        dum = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wu[b][ks], pu[ks], dum, 0, 0, 0);
+        ddm = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wd[b][ks], vw[ks], ddm, 0, 0, 0);
       }
-      tile_put(tg, l31, hi, 32 * b, dgm, s);
-      tile_put(tu, l31, hi, 32 * b, dum, s);
-      tile_put(td, l31, hi, 32 * b, ddm, s);
+      tile_put(tg, l31, hi, 32 * b, dgm);
+      tile_put(tu, l31, hi, 32 * b, dum);
+      tile_put(td, l31, hi, 32 * b, ddm);
     }
     load_w(cn);
     __builtin_amdgcn_wave_barrier();
@@ -440,9 +444,11 @@ __global__ __launch_bounds__(FT_WAVES * 64, (KSR == 1 && !DORA) ? 2 : 1) void sw
         const float hh = (float)hv[m];
         const float sg = fsigmoid(gg);
         const float da = wrow[p] * hh + (float)ddl[m];
-        part = fmaf(hh, gg * sg * uu, part);
-        float dgr = da * uu * sg * (1.f + gg * (1.f - sg));
-        float dur = da * gg * sg;
+        const float gs = gg * sg;                       // SiLU(g)
+        part = fmaf(hh, gs * uu, part);
+        // d SiLU / dg = sig (1 + g (1 - sig)) = sig + SiLU(g) (1 - sig)
+        float dgr = (da * uu) * fmaf(gs, 1.f - sg, sg);
+        float dur = da * gs;
         if constexpr (DORA) {
           if (rvalid[p]) { dmg[m] = fmaf(dgr, vg, dmg[m]); dmu[m] = fmaf(dur, vu, dmu[m]); }
           dgr *= cgv[m];
@@ -490,12 +496,12 @@ __global__ __launch_bounds__(FT_WAVES * 64, (KSR == 1 && !DORA) ? 2 : 1) void sw
     for (int s4 = 0; s4 < 4; s4++) {
       const bf16x8_t fg = ld8(tg + l31 * FT_PITCH + 16 * s4 + 8 * hi);
       const bf16x8_t fu = ld8(tu + l31 * FT_PITCH + 16 * s4 + 8 * hi);
-      const bool kv = c0 + 16 * s4 + 8 * hi < f;
 #pragma unroll
       for (int j = 0; j < NQ; j++) {
-        const bool v = kv && j * 32 + l31 < r;
-        acctg[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fg, v ? tgw[s4][j] : zero8(), acctg[j], 0, 0, 0);
-        acctu[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fu, v ? tuw[s4][j] : zero8(), acctu[j], 0, 0, 0);
+        bf16x8_t wgt = tgw[s4][j], wut = tuw[s4][j];
+        if (tail && c0 + 16 * s4 + 8 * hi >= f) wgt = wut = zero8();
+        acctg[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fg, wgt, acctg[j], 0, 0, 0);
+        acctu[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fu, wut, acctu[j], 0, 0, 0);
       }
     }
     load_wt(cn);

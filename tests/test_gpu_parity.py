@@ -84,6 +84,10 @@ SMALL_CASES = [
     ("f32_long_batch", BASE_F32, dict(T=4200, d=32, d_ff=72, N=16, k=2, r=8)),
     ("f32_ragged", BASE_F32, dict(T=333, d=72, d_ff=200, N=6, k=2, r=8)),
     ("f32_top3", BASE_F32, dict(T=129, d=64, d_ff=136, N=8, k=3, r=16, alpha=32.0)),
+    # LoRA scales alpha / r that are not powers of two
+    ("bf16_scale_1p5", BASE_BF16, dict(T=300, d=256, d_ff=520, N=8, k=2, r=16, alpha=24.0)),
+    ("bf16_scale_0p7", BASE_BF16, dict(T=257, d=136, d_ff=264, N=5, k=3, r=40, alpha=28.0)),
+    ("f32_scale_1p3", BASE_F32, dict(T=333, d=72, d_ff=200, N=6, k=2, r=8, alpha=10.4)),
     # top-1 with nearly balanced first-slot counts: the router is trained by the auxiliary term
     # alone, p * (F_e - <p, F>) with every F_e within a percent of 1/N
     ("f32_top1_balanced_aux", BASE_F32, dict(T=2049, d=128, d_ff=1032, N=3, k=1, r=16, alpha=32.0)),
