@@ -96,7 +96,7 @@ Layout make_layout(const mixlora_dims &D, int schedule = MIXLORA_SCHEDULE_LINEAR
   L.ninv_u = take(dora ? N * f * 4 : 0);
   L.ninv_d = take(dora ? N * d * 4 : 0);
   L.Bd_cat = take(d * R * E);
-  L.rank_part = take(2 * 8 * kT * r * 4);   // per-split rank-r partial sums (two banks)
+  L.rank_part = take(2 * (size_t)fused_splits((int)f, (int)kT) * kT * r * 4);   // per-split rank-r partial sums (two banks)
   // few tokens (decode-shaped calls): partial outputs of the K-split down projection
   L.splitk = take(T <= SPLITK_MAX_ROWS ? (size_t)GEMM_MAX_PROBLEMS * T * d * 4 : 0);
   L.gp_scratch = take(kT > GROUP_SINGLE_WG_PAIRS ? group_pairs_scratch_bytes((int)T, (int)k) : 0);
@@ -115,7 +115,7 @@ Layout make_layout(const mixlora_dims &D, int schedule = MIXLORA_SCHEDULE_LINEAR
   L.du_grp = take(kT * f * E);
   L.dgsum = take(vanilla ? 0 : T * f * E);
   L.dusum = take(vanilla ? 0 : T * f * E);
-  L.dw_part = take(kT * (size_t)(L.nct > 8 ? L.nct : 8) * 4);
+  L.dw_part = take(kT * (size_t)(L.nct > FUSED_MAX_SPLITS ? L.nct : FUSED_MAX_SPLITS) * 4);
   L.dw = take(kT * 4);
   L.Bg_T = take(R * f * E);
   L.Bu_T = take(R * f * E);
@@ -583,7 +583,7 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
   // through SiLU * up and the LoRA deltas, per pair; TG[row, e, :] = B_gate[e]^T dg[row] (and up)
   int nct = L.nct;
   if (dt == MIXLORA_BF16) {
-    nct = fused_splits(f);
+    nct = fused_splits(f, (int)kT);
     HIP_TRY(launch_swiglu_bwd_mfma(pc, f, s, vanilla ? ws + L.Gp : ws + L.G,
                                    vanilla ? ws + L.Up : ws + L.U, pair_down ? ws + L.Hp : ws + L.H,
                                    (float *)(ws + L.Pg_all),

@@ -151,7 +151,7 @@ struct DoraArgs {
 };
 // bf16 MFMA fusion of the above with the A_down projection of the row's expert: writes a_grp,
 // Q_all[row, e(row)*r + q] and the non-zero blocks of Qw[t, e*r + q] = w * Q (bf16, pitch ldqw;
-// the caller zero-fills Qw first).  Q_part is scratch of 8 * kT * r floats.
+// the caller zero-fills Qw first).  Q_part is scratch of fused_splits(f, kT) * kT * r floats.
 hipError_t launch_swiglu_fwd_mfma(const PairCtx &pc, int f, float s, const void *G, const void *U,
                                   const float *Pg_all, const float *Pu_all, const void *B_gate,
                                   const void *B_up, const void *A_down, void *a_grp,
@@ -163,8 +163,8 @@ hipError_t launch_swiglu_fwd_mfma(const PairCtx &pc, int f, float s, const void 
 constexpr int ROWS_GU = 1, ROWS_H = 2, ROWS_SPARSE = 4;
 
 // bf16 MFMA backward of the same stage: dg_grp, du_grp, dw_part[row][split]
-// (split count = fused_splits(f)), TG_all / TU_all at [row, e(row)*r + q].  AdT = A_down re-laid
-// [N, f, r]; BgT / BuT = B banks re-laid [N, r, f]; rank_part is scratch of 16 * kT * r floats.
+// (split count = fused_splits(f, kT)), TG_all / TU_all at [row, e(row)*r + q].  AdT = A_down re-laid
+// [N, f, r]; BgT / BuT = B banks re-laid [N, r, f]; rank_part is scratch of 2 * fused_splits(f, kT) * kT * r floats.
 hipError_t launch_swiglu_bwd_mfma(const PairCtx &pc, int f, float s, const void *G, const void *U,
                                   const void *H, const float *Pg_all, const float *Pu_all,
                                   const float *VB_all, const void *B_gate, const void *B_up,
@@ -173,7 +173,8 @@ hipError_t launch_swiglu_bwd_mfma(const PairCtx &pc, int f, float s, const void 
                                   float *TU_all, void *S, int lds_, hipStream_t st,
                                   int rows_mode = 0, const DoraArgs *dora = nullptr);
 int fused_row_tiles(int kT, int N);   // grid.x of the fused stages
-int fused_splits(int f);
+int fused_splits(int f, int kT);   // at most FUSED_MAX_SPLITS
+constexpr int FUSED_MAX_SPLITS = 32;
 
 // out[t,:] = sum_j (weighted ? w[t,j] : 1) * in_grp[row_of_pair[t,j], :]
 hipError_t launch_pair_combine(int dtype, const PairCtx &pc, int width, const void *in_grp,

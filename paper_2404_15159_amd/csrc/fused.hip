@@ -576,9 +576,10 @@ __global__ void reduce_rank_parts_kernel(PairCtx pc, const float *__restrict__ p
 
 int fused_row_tiles(int kT, int N) { return (kT + FT_ROWS - 1) / FT_ROWS + N; }
 
-int fused_splits(int f) {
+int fused_splits(int f, int kT) {
   const int nblk = (f + FT_SB - 1) / FT_SB;
-  int s = 8;
+  // with few pairs (decode-shaped calls) the row tiles alone cannot fill the chip: finer column cuts
+  int s = kT <= 1024 ? FUSED_MAX_SPLITS : kT <= 2048 ? 16 : 8;
   while (s > 1 && nblk / s < FT_WAVES) s >>= 1;
   return s;
 }
@@ -588,7 +589,7 @@ hipError_t launch_swiglu_fwd_mfma(const PairCtx &pc, int f, float s, const void 
                                   const void *B_up, const void *A_down, void *a_grp,
                                   float *Q_part, float *Q_all, void *Qw, int ldqw,
                                   hipStream_t st, int rows_mode, const DoraArgs *dora) {
-  const int nP = pc.T * pc.k, nsplit = fused_splits(f);
+  const int nP = pc.T * pc.k, nsplit = fused_splits(f, nP);
   const dim3 grid((nP + FT_ROWS - 1) / FT_ROWS + pc.N, nsplit), block(FT_WAVES * 64);
   const DoraArgs da = dora ? *dora : DoraArgs{};
 #define MIXLORA_FWD(KSR_, NQ_, DORA_)                                                            \
@@ -622,8 +623,8 @@ hipError_t launch_swiglu_bwd_mfma(const PairCtx &pc, int f, float s, const void 
                                   void *du_grp, float *dw_part, float *rank_part, float *TG_all,
                                   float *TU_all, void *S, int lds_, hipStream_t st, int rows_mode,
                                   const DoraArgs *dora) {
-  const int nP = pc.T * pc.k, nsplit = fused_splits(f);
-  float *TG_part = rank_part, *TU_part = rank_part + (size_t)8 * nP * pc.r;
+  const int nP = pc.T * pc.k, nsplit = fused_splits(f, nP);
+  float *TG_part = rank_part, *TU_part = rank_part + (size_t)nsplit * nP * pc.r;
   const dim3 grid((nP + FT_ROWS - 1) / FT_ROWS + pc.N, nsplit), block(FT_WAVES * 64);
   const DoraArgs da = dora ? *dora : DoraArgs{};
 #define MIXLORA_BWD(KSR_, NQ_, DORA_)                                                            \
