@@ -106,6 +106,17 @@ def test_small_cases(name, base, over):
     pu.compare_all(res, fw, bw, cfg)
 
 
+def test_million_tokens():
+    """A very long batch of narrow rows (two million pairs): row indices times row widths pass
+    2^31 elements only in 64-bit arithmetic, the grouping runs as thousands of chunks, and the
+    reductions over tokens are long.  Everything against the oracle, element by element."""
+    cfg = synth.scaled(BASE_BF16, name="bf16_million", T=1000003, d=64, d_ff=136, N=8, k=2, r=8,
+                       alpha=16.0)
+    host = synth.make_inputs(cfg)
+    res, fw, bw, _ = run_case(cfg, host, d_aux=1.5)
+    pu.compare_all(res, fw, bw, cfg)
+
+
 def test_unused_expert_and_untransposed_weights():
     cfg = synth.scaled(synth.CONFIGS["llama2_13b_skew"], name="bf16_unused", T=260, d=128,
                        d_ff=264, N=8, k=2, r=16)
