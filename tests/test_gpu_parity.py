@@ -84,6 +84,9 @@ SMALL_CASES = [
     ("f32_long_batch", BASE_F32, dict(T=4200, d=32, d_ff=72, N=16, k=2, r=8)),
     ("f32_ragged", BASE_F32, dict(T=333, d=72, d_ff=200, N=6, k=2, r=8)),
     ("f32_top3", BASE_F32, dict(T=129, d=64, d_ff=136, N=8, k=3, r=16, alpha=32.0)),
+    # very wide model or hidden dimension (long contractions, many column tiles)
+    ("bf16_d_16384", BASE_BF16, dict(T=520, d=16384, d_ff=1032, N=4, k=2, r=64, alpha=128.0)),
+    ("bf16_dff_53248", BASE_BF16, dict(T=200, d=264, d_ff=53248, N=8, k=2, r=16)),
     # LoRA scales alpha / r that are not powers of two
     ("bf16_scale_1p5", BASE_BF16, dict(T=300, d=256, d_ff=520, N=8, k=2, r=16, alpha=24.0)),
     ("bf16_scale_0p7", BASE_BF16, dict(T=257, d=136, d_ff=264, N=5, k=3, r=40, alpha=28.0)),
