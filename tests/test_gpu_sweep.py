@@ -1,9 +1,22 @@
 """Seeded random-shape sweep of every entry-point family against the oracle (small shapes: odd
 token counts around the tile sizes, d and d_ff at every multiple-of-8 remainder class, ranks
-8..64, 1..32 experts).  With fewer than 16 tokens the router-weight gradient is a sum of a few
-terms dz_t x_t whose dz_t is a difference of nearly equal numbers (the k routing-weight
-gradients), so bf16 rounding shows in it without averaging: its tolerance is relaxed there
-(measured identical for all schedules; the other tensors keep the bar)."""
+8..64, 1..32 experts).
+
+One tensor needs a scale of its own in bf16 when there are only a few tokens.  The router
+gradient of a token is  dz_e = p_e (dp_e - <p, dp>)  with  dp_j = (dw_j - sum_i w_i dw_i) / sum_kept p
+on the kept experts, where  dw_j = <dy_t, E_j(x_t)> = sum_c dy_tc o_jc  is the gradient of routing
+weight j: dz is driven by DIFFERENCES of the dw_j, which for experts that share the frozen FFN
+are nearly equal numbers.  bf16 storage of the shared projections and of the rank-r deltas
+perturbs every dw_j by a few 1e-3 of the size of its terms (far inside the 2e-2 bar), but that
+is 3 to 10 % of dw_0 - dw_1, and with fewer than 16 tokens nothing averages it out in
+dW_router = sum_t dz_t x_t^T  (re-evaluating the definition on the CPU with only those roundings
+applied gives the same 2.5e-2 and 1.0e-1 that the kernels show on the two single-token cases
+of this sweep).  There the tensor is therefore held to the error that a tol-accurate dw
+implies through the exact map dw -> dW_router:  with  |delta dw_tj| <= tol * rss_tj,
+rss_tj = sqrt(sum_c (dy_tc o_jc)^2)  the root-sum-square of the terms of dw_tj, one has
+|delta dz_te| <= 2 w_e max_j |delta dw_tj|, hence
+|delta dW_router[e, c]| <= 2 tol sum_t max_j rss_tj |x_tc|   (plus tol * max |ref|).
+fp32 storage keeps the flat 1e-5 bar at every token count."""
 import numpy as np
 import pytest
 
@@ -38,7 +51,23 @@ def _draw(rng, ci):
     return kind, dict(T=T, d=d, d_ff=f, N=N, k=k, r=r, alpha=2.0 * r, M=M, seq_len=max(1, T // 7))
 
 
-def _check_grads(res, ref, cfg, all_same, F=None, x_max=1.0):
+def _dw_term_rss(fw, dy, T, k):
+    """rss[t, j] = sqrt(sum_c (dy[t, c] * o[t, j, c])^2) from the oracle's kept expert outputs."""
+    rss = np.zeros((T, k))
+    dy = np.asarray(dy, dtype=np.float64)
+    for sv in fw["saved"].values():
+        tok, slot = sv["tok"], sv["slot"]
+        rss[tok, slot] = np.sqrt(((dy[tok] * sv["o"]) ** 2).sum(axis=1))
+    return rss
+
+
+def _router_grad_bound(rss, x, tol):
+    """[d] bound on |delta dW_router[e, :]| implied by a tol-accurate dw (module docstring)."""
+    m = np.asarray(rss, dtype=np.float64).max(axis=1)            # [T]
+    return 2.0 * tol * (m[:, None] * np.abs(np.asarray(x, dtype=np.float64))).sum(axis=0)
+
+
+def _check_grads(res, ref, cfg, all_same, F=None, x_max=1.0, rss=None, x=None):
     tol = pu.TOL[cfg.dtype]
     for n in pu.GRAD_NAMES:
         if not (all_same or cfg.dtype == "bf16"):
@@ -50,8 +79,12 @@ def _check_grads(res, ref, cfg, all_same, F=None, x_max=1.0):
             assert np.abs(ref[n]).max() <= 1e-12 * x_max
             assert np.abs(res[n]).max() <= 1e-7 * cfg.aux_coeff * x_max, n
             continue
-        t = tol * (10.0 if (n == "dW_router" and cfg.T < 16) else 1.0)
-        pu.assert_close(n, res[n], ref[n], t)
+        if n == "dW_router" and cfg.T < 16 and cfg.dtype == "bf16":
+            bound = _router_grad_bound(rss, x, tol)[None, :] + tol * np.abs(ref[n]).max()
+            excess = np.abs(np.asarray(res[n], dtype=np.float64) - ref[n]) - bound
+            assert (excess <= 0.0).all(), f"dW_router beyond the dw-implied bound by {excess.max():.3e}"
+            continue
+        pu.assert_close(n, res[n], ref[n], tol)
 
 
 @pytest.mark.parametrize("seed", [1, 2, 3])
@@ -81,7 +114,15 @@ def test_random_shapes(seed):
             pu.assert_close("y", res["y"][same], fw["y"][same], tol)
             pu.assert_close("dx", res["dx"][same], bw["dx"][same], tol)
             ref = {n: np.concatenate([g[n] for g in bw["grads"]], axis=0) for n in pu.GRAD_NAMES}
-            _check_grads(res, ref, cfg, bool(same.all()))
+            rss = np.zeros((cfg.T, cfg.k))
+            if cfg.T < 16:   # terms of the routing-weight gradients, adapter by adapter
+                for mi in range(cfg.M):
+                    tok = np.nonzero(tm == mi)[0]
+                    if tok.size:
+                        fm = orc.forward(host["x"][tok], Ws[mi], cfg.k, cfg.lora_scale,
+                                         cfg.aux_coeff, keep=True)
+                        rss[tok] = _dw_term_rss(fm, host["dy"][tok], tok.size, cfg.k)
+            _check_grads(res, ref, cfg, bool(same.all()), rss=rss, x=host["x"])
             continue
         if kind == "dora":
             mag = {n: [] for n in MAG}
@@ -105,7 +146,8 @@ def test_random_shapes(seed):
         same = (res["topk_idx"] == bw["forward"]["topk_idx"]).all(axis=1)
         pu.assert_close("dx", res["dx"][same], bw["dx"][same], tol)
         _check_grads(res, bw, cfg, rep["routing_mismatch_tokens"] == 0, F=bw["forward"]["F"],
-                     x_max=float(np.abs(host["x"]).max()))
+                     x_max=float(np.abs(host["x"]).max()),
+                     rss=_dw_term_rss(bw["forward"], host["dy"], cfg.T, cfg.k), x=host["x"])
         if kind == "dora":
             for n in MAG:
                 pu.assert_close("d" + n, res["d" + n], bw["d" + n], tol)
