@@ -46,7 +46,9 @@ typedef enum {
   MIXLORA_E_DTYPE = -3,     /* unknown dtype or aux_mode value                         */
   MIXLORA_E_ALIGN = -4,     /* a pointer is not 16-byte aligned                        */
   MIXLORA_E_WORKSPACE = -5, /* workspace_bytes < mixlora_workspace_bytes(...)          */
-  MIXLORA_E_HIP = -6        /* a kernel launch failed (hipGetLastError after enqueue)  */
+  MIXLORA_E_HIP = -6,       /* a kernel launch failed (hipGetLastError after enqueue)  */
+  MIXLORA_E_SCRATCH = -7    /* the problem needs more scratch than the library's static
+                               device buffer holds (mixlora_ffn_forward_static only)    */
 } mixlora_status;
 
 typedef enum { MIXLORA_F32 = 0, MIXLORA_BF16 = 1 } mixlora_dtype;
@@ -108,6 +110,28 @@ MIXLORA_API int mixlora_ffn_forward(const mixlora_dims *dims, const mixlora_weig
                         void *y, int32_t *topk_idx, float *topk_w, int32_t *expert_counts,
                         float *aux_loss, void *workspace, size_t workspace_bytes,
                         void *stream);
+
+/* The same forward for callers that cannot allocate or hand over device memory of their own:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Every
+ * buffer that mixlora_ffn_forward takes from the caller's workspace (routing tables, grouped
+ * activations, partial results of the split down projection, ...) lives instead in a device
+ * array inside the library, MIXLORA_STATIC_SCRATCH_BYTES large, one copy per GPU, held until the
+ * process ends.  The call allocates nothing and frees nothing; inputs and outputs are the
+ * caller's as before, results are bit-identical to mixlora_ffn_forward.  Forward only: the
+ * array is not a handle for mixlora_ffn_backward.
+ *   - dims whose mixlora_workspace_bytes(dims, 0) exceeds MIXLORA_STATIC_SCRATCH_BYTES return
+ *     MIXLORA_E_SCRATCH (checked on the host, nothing enqueued).  40 MiB covers the LLaMA-2 7B /
+ *     13B and LLaMA-3 8B shapes of this block up to 128 tokens per call (decode batches).
+ *   - All calls on one GPU share that GPU's array and it keeps the previous call's contents; the
+ *     call itself clears what has to start at zero.  Calls that overlap on one GPU (two streams,
+ *     two threads) race: serialise them.
+ *   - The first call on each device looks the array's device address up (hipGetSymbolAddress) and
+ *     must therefore be made outside stream capture; later calls may be captured.           */
+#define MIXLORA_STATIC_SCRATCH_BYTES (40 * 1024 * 1024)
+MIXLORA_API int mixlora_ffn_forward_static(const mixlora_dims *dims, const mixlora_weights *w,
+                                           const void *x, void *y, int32_t *topk_idx,
+                                           float *topk_w, int32_t *expert_counts, float *aux_loss,
+                                           void *stream);
 
 /* Backward of the same block for the loss  <y, dy> + d_aux * aux_loss, base matrices frozen
  * (derived from Algorithm 1 lines 4-15; the paper leaves it to autograd).

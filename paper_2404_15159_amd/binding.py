@@ -18,7 +18,8 @@ F32, BF16 = 0, 1
 AUX_TOP1, AUX_TOPK = 0, 1
 SCHEDULE_LINEAR_DOWN, SCHEDULE_SHARED, SCHEDULE_VANILLA = 0, 1, 2
 STATUS = {0: "OK", -1: "E_NULL", -2: "E_SHAPE", -3: "E_DTYPE", -4: "E_ALIGN", -5: "E_WORKSPACE",
-          -6: "E_HIP"}
+          -6: "E_HIP", -7: "E_SCRATCH"}
+STATIC_SCRATCH_BYTES = 40 * 1024 * 1024
 
 EXPORTS = ("mixlora_workspace_bytes", "mixlora_ffn_forward", "mixlora_ffn_backward",
            "mixlora_aux_loss", "mixlora_transpose", "mixlora_version",
@@ -28,7 +29,7 @@ EXPORTS = ("mixlora_workspace_bytes", "mixlora_ffn_forward", "mixlora_ffn_backwa
            "mixlora_lora_linear_forward", "mixlora_lora_linear_backward", "mixlora_adamw_step",
            "mixlora_schedule_workspace_bytes", "mixlora_ffn_forward_schedule",
            "mixlora_ffn_backward_schedule", "mixlora_dora_workspace_bytes",
-           "mixlora_dora_forward", "mixlora_dora_backward")
+           "mixlora_dora_forward", "mixlora_dora_backward", "mixlora_ffn_forward_static")
 
 
 class Dims(C.Structure):
@@ -99,6 +100,9 @@ def load():
     lib.mixlora_ffn_forward.restype = C.c_int
     lib.mixlora_ffn_forward.argtypes = [C.POINTER(Dims), C.POINTER(Weights), vp, vp, vp, vp, vp,
                                         vp, vp, sz, vp]
+    lib.mixlora_ffn_forward_static.restype = C.c_int
+    lib.mixlora_ffn_forward_static.argtypes = [C.POINTER(Dims), C.POINTER(Weights), vp, vp, vp, vp,
+                                               vp, vp, vp]
     lib.mixlora_ffn_backward.restype = C.c_int
     lib.mixlora_ffn_backward.argtypes = [C.POINTER(Dims), C.POINTER(Weights), vp, vp, f32, vp, sz,
                                          vp, C.POINTER(Grads), vp]
@@ -200,6 +204,15 @@ def mixlora_ffn_forward(dims: Dims, weights: Weights, x, y, topk_idx, topk_w, ex
                                     _stream(stream))
     if rc != 0:
         raise MixLoraError("mixlora_ffn_forward", rc)
+
+
+def mixlora_ffn_forward_static(dims: Dims, weights: Weights, x, y, topk_idx, topk_w,
+                               expert_counts, aux_loss, stream=None) -> None:
+    rc = load().mixlora_ffn_forward_static(C.byref(dims), C.byref(weights), _ptr(x), _ptr(y),
+                                           _ptr(topk_idx), _ptr(topk_w), _ptr(expert_counts),
+                                           _ptr(aux_loss), _stream(stream))
+    if rc != 0:
+        raise MixLoraError("mixlora_ffn_forward_static", rc)
 
 
 def mixlora_ffn_backward(dims: Dims, weights: Weights, x, dy, d_aux: float, workspace,

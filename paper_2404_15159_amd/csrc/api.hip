@@ -9,6 +9,8 @@
 // K-extension of the same GEMM; its transpose is used the same way in the backward.
 #include "common.h"
 
+#include <mutex>
+
 using namespace mixlora;
 
 namespace {
@@ -812,6 +814,49 @@ int mixlora_dora_backward(const mixlora_dims *dims, const mixlora_weights *w,
   up.v[0] = d_aux;
   return backward_impl(*dims, dims->N, nullptr, up, w, x, dy, workspace, workspace_bytes, dx, grads,
                        stream, MIXLORA_SCHEDULE_SHARED, dora, dora_grads);
+}
+
+// ---- forward without a caller workspace ---------------------------------------------------------
+// The workspace of this entry point is a file-scope device array: every GPU the library runs on
+// holds its own copy at its own address until the process ends.  The array's name is only a
+// host-side handle; the device address is looked up once per device and used from then on.
+}  // extern "C"
+
+namespace {
+static __device__ __align__(256) unsigned char scratch[MIXLORA_STATIC_SCRATCH_BYTES];
+constexpr int STATIC_MAX_DEVICES = 64;
+void *g_scratch_ptr[STATIC_MAX_DEVICES] = {};
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (NULL on failure).
+void *static_scratch_ptr() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_MAX_DEVICES) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" {
+
+int mixlora_ffn_forward_static(const mixlora_dims *dims, const mixlora_weights *w, const void *x,
+                               void *y, int32_t *topk_idx, float *topk_w, int32_t *expert_counts,
+                               float *aux_loss, void *stream) {
+  // host-only checks first: a non-NULL stand-in passes the workspace pointer test
+  const int rc = check_forward_args(dims, w, x, y, topk_idx, topk_w, expert_counts, aux_loss,
+                                    reinterpret_cast<const void *>(uintptr_t{256}));
+  if (rc) return rc;
+  const Layout L = make_layout(*dims);
+  if (L.fwd_end > (size_t)MIXLORA_STATIC_SCRATCH_BYTES) return MIXLORA_E_SCRATCH;
+  void *ws = static_scratch_ptr();
+  if (!ws) return MIXLORA_E_HIP;
+  return forward_impl(*dims, dims->N, nullptr, w, x, y, topk_idx, topk_w, expert_counts, aux_loss,
+                      ws, (size_t)MIXLORA_STATIC_SCRATCH_BYTES, stream);
 }
 
 int mixlora_aux_loss(const float *probs, const int32_t *topk_idx, int32_t T, int32_t N,

@@ -80,6 +80,27 @@ def test_forward_argument_errors(lib):
     assert fwd_code(dims(), fake_weights(), workspace_bytes=1024) == -5
 
 
+def test_forward_static_argument_errors(lib):
+    """The forward that keeps its workspace in the library's static device array: the size limit
+    and the argument checks are host-side, before any HIP call."""
+    def code(d, w, **kw):
+        a = fwd_args(**kw)
+        a.pop("workspace"), a.pop("workspace_bytes")
+        with pytest.raises(B.MixLoraError) as ei:
+            B.mixlora_ffn_forward_static(d, w, stream=0, **a)
+        return ei.value.code
+
+    assert B.mixlora_workspace_bytes(dims(), False) > B.STATIC_SCRATCH_BYTES
+    assert code(dims(), fake_weights()) == -7                     # 4096 tokens: beyond the array
+    assert B.mixlora_workspace_bytes(dims(T=128), False) <= B.STATIC_SCRATCH_BYTES
+    assert code(dims(T=128, k=9), fake_weights()) == -2
+    assert code(dims(T=128), fake_weights(A_up=None)) == -1
+    assert code(dims(T=128), fake_weights(), y=FAKE + 4) == -4
+    text = open(os.path.join(ROOT, "include", "mixlora.h")).read()
+    m = re.search(r"#define MIXLORA_STATIC_SCRATCH_BYTES \((\d+) \* 1024 \* 1024\)", text)
+    assert m and int(m.group(1)) * 1024 * 1024 == B.STATIC_SCRATCH_BYTES
+
+
 def test_backward_argument_errors(lib):
     g = B.make_grads({n: FAKE for n in B.GRAD_FIELDS})
 
