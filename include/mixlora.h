@@ -262,14 +262,22 @@ MIXLORA_API int mixlora_aux_loss(const float *probs, const int32_t *topk_idx, in
 MIXLORA_API int mixlora_transpose(const void *in, void *out, int32_t rows, int32_t cols, int32_t dtype,
                       void *stream);
 
-/* Measurement hook for benchmarks (the only entry points that synchronise or create HIP
- * objects): between begin and end, every launch of the library's large-tile bf16 MFMA GEMM
- * kernel - the kernel that carries the frozen projections - is bracketed by HIP events on
- * its stream.  end waits for those events and returns, in HOST memory, the summed kernel
- * time in milliseconds, the number of launches and the floating-point operations those
- * launches executed (2*M*N*K over their K segments).  Not thread-safe.                  */
+/* Measurement hook for benchmarks.  These three and mixlora_mfma_probe are measurement aids, not
+ * part of the block's contract: they are the only entry points that synchronise or create HIP
+ * objects.  Between begin and end, every launch of the library is bracketed by HIP events on its
+ * stream (at most max_launches of them; later launches go untimed).  end waits for those events
+ * and returns, in HOST memory, the summed time in milliseconds, the number of launches and the
+ * floating-point operations (2*M*N*K over their K segments) of the bf16 MFMA GEMM launches that
+ * carry the frozen projections.  After end, mixlora_profile_kind returns the same three figures
+ * for one kind of launch, with work in algorithmic bytes for the bandwidth-bound kinds:
+ *   0 frozen-projection GEMMs (work = FLOPs), 1 per-pair SwiGLU stage forward, 2 the same
+ *   backward, 3 sums over a token's pair rows, 4 grouped outer-product sums (LoRA / router
+ *   gradients), 5 routing (softmax, top-k, grouping, auxiliary loss, router backward),
+ *   6 re-layouts and other small launches.  Unknown kind: MIXLORA_E_SHAPE.  Not thread-safe. */
 MIXLORA_API int mixlora_profile_begin(int32_t max_launches);
 MIXLORA_API int mixlora_profile_end(double *ms_total, int32_t *launches, double *flops_total);
+MIXLORA_API int mixlora_profile_kind(int32_t kind, double *ms_total, int32_t *launches,
+                                     double *work_total);
 
 /* ---- Plain LoRA linear (Eq. 1 with the scale alpha / r; the form the method puts on the
  * attention projections, Section 3.2):  y = x W^T + s (x A^T) B^T,  W frozen ----------------

@@ -23,7 +23,7 @@ STATIC_SCRATCH_BYTES = 40 * 1024 * 1024
 
 EXPORTS = ("mixlora_workspace_bytes", "mixlora_ffn_forward", "mixlora_ffn_backward",
            "mixlora_aux_loss", "mixlora_transpose", "mixlora_version",
-           "mixlora_profile_begin", "mixlora_profile_end",
+           "mixlora_profile_begin", "mixlora_profile_end", "mixlora_profile_kind",
            "mixlora_multi_workspace_bytes", "mixlora_multi_forward", "mixlora_multi_backward",
            "mixlora_mfma_probe", "mixlora_lora_linear_workspace_bytes",
            "mixlora_lora_linear_forward", "mixlora_lora_linear_backward", "mixlora_adamw_step",
@@ -133,6 +133,9 @@ def load():
     lib.mixlora_profile_end.restype = C.c_int
     lib.mixlora_profile_end.argtypes = [C.POINTER(C.c_double), C.POINTER(i32),
                                         C.POINTER(C.c_double)]
+    lib.mixlora_profile_kind.restype = C.c_int
+    lib.mixlora_profile_kind.argtypes = [i32, C.POINTER(C.c_double), C.POINTER(i32),
+                                         C.POINTER(C.c_double)]
     lib.mixlora_multi_workspace_bytes.restype = sz
     lib.mixlora_multi_workspace_bytes.argtypes = [C.POINTER(Dims), i32, C.c_int]
     lib.mixlora_multi_forward.restype = C.c_int
@@ -398,3 +401,17 @@ def mixlora_profile_end():
     if rc != 0:
         raise MixLoraError("mixlora_profile_end", rc)
     return ms.value, n.value, fl.value
+
+
+PROFILE_KINDS = ("gemm", "fused_forward", "fused_backward", "combine", "gradient_sums", "routing",
+                 "other")
+
+
+def mixlora_profile_kind(kind: int):
+    """After mixlora_profile_end: (summed ms, launches, declared work) of one kind of launch
+    (index into PROFILE_KINDS; work is FLOPs for kind 0, algorithmic bytes otherwise)."""
+    ms, n, wk = C.c_double(), C.c_int32(), C.c_double()
+    rc = load().mixlora_profile_kind(int(kind), C.byref(ms), C.byref(n), C.byref(wk))
+    if rc != 0:
+        raise MixLoraError("mixlora_profile_kind", rc)
+    return ms.value, n.value, wk.value

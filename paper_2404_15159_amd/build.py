@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libmixlora.so")
 SOURCES = ("gemm.hip", "router.hip", "elementwise.hip", "grads.hip", "fused.hip", "probe.hip",
-           "linear.hip", "optim.hip", "dora.hip", "api.hip")
+           "linear.hip", "optim.hip", "dora.hip", "prof.hip", "api.hip")
 
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",

@@ -186,6 +186,16 @@ int check_weights(const mixlora_weights *w) {
     if (e_ != hipSuccess) return MIXLORA_E_HIP;         \
   } while (0)
 
+// A launch bracketed for the measurement hook (no cost when the hook is off): kind and the
+// algorithmic bytes the launch moves, as stated where each kernel is described.
+#define HIP_TRY_AS(kind, bytes, expr)                                     \
+  do {                                                                    \
+    const int slot_ = prof_on() ? prof_mark_begin((kind), st) : -1;       \
+    hipError_t e_ = (expr);                                               \
+    if (slot_ >= 0) prof_mark_end(slot_, st, (double)(bytes));            \
+    if (e_ != hipSuccess) return MIXLORA_E_HIP;                           \
+  } while (0)
+
 GemmProblem problem(int M, int N, void *C, int64_t ldc, int c_f32) {
   GemmProblem p{};
   p.M = M;
@@ -234,6 +244,7 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
   char *ws = reinterpret_cast<char *>(workspace);
   const int T = D.T, d = D.d, f = D.d_ff, N = D.N, k = D.k, r = D.r, R = N * r, kT = k * T;
   const int dt = D.dtype;
+  const double Eb = dt == MIXLORA_BF16 ? 2.0 : 4.0;   // bytes per stored element (measurement hook)
   float *probs = (float *)(ws + L.probs);
   int32_t *idx = (int32_t *)(ws + L.idx);
   float *wts = (float *)(ws + L.w);
@@ -281,19 +292,19 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
   if (dora) {
     // factors c = m / n of the three projections (n: row norms of W + s B_e A_e)
     float *w2 = (float *)(ws + L.w2), *AA = (float *)(ws + L.AA);
-    HIP_TRY(launch_row_sqnorm(w->W_gate, f, d, w2, st));
-    HIP_TRY(launch_row_sqnorm(w->W_up, f, d, w2 + f, st));
-    HIP_TRY(launch_row_sqnorm(w->W_down, d, f, w2 + 2 * (size_t)f, st));
-    HIP_TRY(launch_gram(w->A_gate, N, r, d, AA, st));
+    HIP_TRY_AS(PROF_OTHER, 0, launch_row_sqnorm(w->W_gate, f, d, w2, st));
+    HIP_TRY_AS(PROF_OTHER, 0, launch_row_sqnorm(w->W_up, f, d, w2 + f, st));
+    HIP_TRY_AS(PROF_OTHER, 0, launch_row_sqnorm(w->W_down, d, f, w2 + 2 * (size_t)f, st));
+    HIP_TRY_AS(PROF_OTHER, 0, launch_gram(w->A_gate, N, r, d, AA, st));
     const size_t gpf = gram_part_floats(N, r);
-    HIP_TRY(launch_gram(w->A_up, N, r, d, AA + gpf, st));
-    HIP_TRY(launch_gram(w->A_down, N, r, f, AA + 2 * gpf, st));
-    HIP_TRY(launch_dora_scale(w->B_gate, (float *)(ws + L.WA_g), AA, w2, dora->m_gate, N, f, r,
+    HIP_TRY_AS(PROF_OTHER, 0, launch_gram(w->A_up, N, r, d, AA + gpf, st));
+    HIP_TRY_AS(PROF_OTHER, 0, launch_gram(w->A_down, N, r, f, AA + 2 * gpf, st));
+    HIP_TRY_AS(PROF_OTHER, 0, launch_dora_scale(w->B_gate, (float *)(ws + L.WA_g), AA, w2, dora->m_gate, N, f, r,
                               D.lora_scale, (float *)(ws + L.c_g), (float *)(ws + L.ninv_g), st));
-    HIP_TRY(launch_dora_scale(w->B_up, (float *)(ws + L.WA_u), AA + gpf, w2 + f,
+    HIP_TRY_AS(PROF_OTHER, 0, launch_dora_scale(w->B_up, (float *)(ws + L.WA_u), AA + gpf, w2 + f,
                               dora->m_up, N, f, r, D.lora_scale, (float *)(ws + L.c_u),
                               (float *)(ws + L.ninv_u), st));
-    HIP_TRY(launch_dora_scale(w->B_down, (float *)(ws + L.WA_d), AA + 2 * gpf, w2 + 2 * (size_t)f,
+    HIP_TRY_AS(PROF_OTHER, 0, launch_dora_scale(w->B_down, (float *)(ws + L.WA_d), AA + 2 * gpf, w2 + 2 * (size_t)f,
                               dora->m_down, N, d, r, D.lora_scale, (float *)(ws + L.c_d),
                               (float *)(ws + L.ninv_d), st));
     dargs.cg = (float *)(ws + L.c_g);
@@ -301,21 +312,21 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
   }
   // Eq. 7 + Norm (Algorithm 1 lines 4-5)
   if (dt == MIXLORA_BF16)
-    HIP_TRY(launch_route_logits((const float *)(ws + L.Z), N, T, N, k, probs, topk_idx, topk_w, idx,
+    HIP_TRY_AS(PROF_ROUTING, (double)T * N * 8, launch_route_logits((const float *)(ws + L.Z), N, T, N, k, probs, topk_idx, topk_w, idx,
                                 wts, Nl, token_model, st));
   else
-    HIP_TRY(launch_router(dt, x, w->W_router, T, d, N, k, probs, topk_idx, topk_w, idx, wts, Nl,
+    HIP_TRY_AS(PROF_ROUTING, (double)T * d * Eb, launch_router(dt, x, w->W_router, T, d, N, k, probs, topk_idx, topk_w, idx, wts, Nl,
                           token_model, st));
   // grouping of the pairs by expert and Eq. 8-9, one launch
   if ((size_t)kT > GROUP_SINGLE_WG_PAIRS)
-    HIP_TRY(launch_group_pairs_aux_multi(idx, T, N, k, (int32_t *)(ws + L.counts), expert_counts,
+    HIP_TRY_AS(PROF_ROUTING, (double)kT * 16, launch_group_pairs_aux_multi(idx, T, N, k, (int32_t *)(ws + L.counts), expert_counts,
                                          (int32_t *)(ws + L.first_counts), offs, row_of_pair,
                                          pair_of_row, (int32_t *)(ws + L.tok_offs), probs,
                                          D.aux_coeff, D.aux_mode, aux_loss, (float *)(ws + L.F),
                                          (float *)(ws + L.P), Nl, token_model,
                                          (int32_t *)(ws + L.model_tokens), ws + L.gp_scratch, st));
   else
-    HIP_TRY(launch_group_pairs_aux(idx, T, N, k, (int32_t *)(ws + L.counts), expert_counts,
+    HIP_TRY_AS(PROF_ROUTING, (double)kT * 16, launch_group_pairs_aux(idx, T, N, k, (int32_t *)(ws + L.counts), expert_counts,
                                    (int32_t *)(ws + L.first_counts), offs, row_of_pair, pair_of_row,
                                    (int32_t *)(ws + L.tok_offs), probs, D.aux_coeff, D.aux_mode,
                                    aux_loss, (float *)(ws + L.F), (float *)(ws + L.P), Nl, token_model,
@@ -327,7 +338,7 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
     const RelayoutJob jobs[2] = {job_bank_cat(w->B_down, N, d, r, D.lora_scale, ws + L.Bd_cat, R, 0),
                                  pair_down ? job_zero_fill(ws + L.Qp, (size_t)kT * R * 2)
                                            : job_zero_fill(ws + L.Qw, (size_t)T * R * 2)};
-    HIP_TRY(launch_relayout(dt, jobs, dt == MIXLORA_BF16 ? 2 : 1, st));
+    HIP_TRY_AS(PROF_OTHER, 0, launch_relayout(dt, jobs, dt == MIXLORA_BF16 ? 2 : 1, st));
   }
   if (pair_down) {
     // The paper's schedules (Figure 3): every expert runs its own frozen products on its slice of
@@ -337,7 +348,7 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
     const char *Gsrc = ws + L.G, *Usrc = ws + L.U;
     int rows_mode = ROWS_SPARSE;
     if (vanilla) {
-      HIP_TRY(launch_gather_rows(dt, pc, d, x, ws + L.Xp, st));
+      HIP_TRY_AS(PROF_OTHER, 2.0 * kT * d * Eb, launch_gather_rows(dt, pc, d, x, ws + L.Xp, st));
       // the LoRA A projections of every expert (per token) ride in the same launch
       GemmProblem p[4] = {problem(kT, f, ws + L.Gp, f, 0), problem(kT, f, ws + L.Up, f, 0),
                           problem(T, R, ws + L.Pg_all, R, 1), problem(T, R, ws + L.Pu_all, R, 1)};
@@ -355,7 +366,7 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
       Usrc = ws + L.Up;
       rows_mode |= ROWS_GU;
     }
-    HIP_TRY(launch_swiglu_fwd_mfma(pc, f, D.lora_scale, Gsrc, Usrc, (float *)(ws + L.Pg_all),
+    HIP_TRY_AS(PROF_FUSED_FWD, 3.0 * kT * f * Eb, launch_swiglu_fwd_mfma(pc, f, D.lora_scale, Gsrc, Usrc, (float *)(ws + L.Pg_all),
                                    (float *)(ws + L.Pu_all), w->B_gate, w->B_up, w->A_down,
                                    ws + L.a_grp, (float *)(ws + L.rank_part),
                                    (float *)(ws + L.Q_all), ws + L.Qp, R, st, rows_mode,
@@ -365,22 +376,22 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
     add_seg(p, ws + L.Qp, R, ws + L.Bd_cat, R, R);
     HIP_TRY(launch_gemm(dt, &p, 1, st));
     if (!dora) {
-      HIP_TRY(launch_pair_combine(dt, pc, d, ws + L.Op, y, 1, st));
+      HIP_TRY_AS(PROF_COMBINE, (double)(k + 1) * T * d * Eb, launch_pair_combine(dt, pc, d, ws + L.Op, y, 1, st));
       return MIXLORA_OK;
     }
     // the down projection's factor is applied to every pair's output while combining
-    HIP_TRY(launch_pair_combine_scaled(pc, d, ws + L.Op, (float *)(ws + L.c_d), y, st));
+    HIP_TRY_AS(PROF_COMBINE, (double)(k + 1) * T * d * Eb, launch_pair_combine_scaled(pc, d, ws + L.Op, (float *)(ws + L.c_d), y, st));
     return MIXLORA_OK;
   }
   // Algorithm 1 lines 11-13 on the routed pairs, expert-grouped rows
   if (dt == MIXLORA_BF16) {
     // fused: LoRA deltas + SiLU * up + A_down of the row's expert, all on MFMA
-    HIP_TRY(launch_swiglu_fwd_mfma(pc, f, D.lora_scale, ws + L.G, ws + L.U,
+    HIP_TRY_AS(PROF_FUSED_FWD, 3.0 * kT * f * Eb, launch_swiglu_fwd_mfma(pc, f, D.lora_scale, ws + L.G, ws + L.U,
                                    (float *)(ws + L.Pg_all), (float *)(ws + L.Pu_all), w->B_gate,
                                    w->B_up, w->A_down, ws + L.a_grp, (float *)(ws + L.rank_part),
                                    (float *)(ws + L.Q_all), ws + L.Qw, R, st));
   } else {
-    HIP_TRY(launch_swiglu_fwd(dt, pc, f, D.lora_scale, ws + L.G, ws + L.U,
+    HIP_TRY_AS(PROF_FUSED_FWD, 3.0 * kT * f * Eb, launch_swiglu_fwd(dt, pc, f, D.lora_scale, ws + L.G, ws + L.U,
                               (float *)(ws + L.Pg_all), (float *)(ws + L.Pu_all), w->B_gate,
                               w->B_up, ws + L.a_grp, st));
     // A_down of every expert on the grouped activations
@@ -388,11 +399,12 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
     add_seg(p, ws + L.a_grp, f, w->A_down, f, f);
     HIP_TRY(launch_gemm(dt, &p, 1, st));
     // the block-sparse low-rank operand
-    HIP_TRY(launch_scatter_blocks(dt, pc, (float *)(ws + L.Q_all), 0, 1, R, 1, 1, ws + L.Qw, R, 0, st));
+    HIP_TRY_AS(PROF_OTHER, 0, launch_scatter_blocks(dt, pc, (float *)(ws + L.Q_all), 0, 1, R, 1, 1, ws + L.Qw, R, 0, st));
   }
   // weighted combine of the pair activations (Algorithm 1 line 15, moved in front of the linear
   // frozen down projection)
-  HIP_TRY(launch_pair_combine(dt, pc, f, ws + L.a_grp, ws + L.a_comb, 1, st));
+  HIP_TRY_AS(PROF_COMBINE, (double)(k + 1) * T * f * Eb,
+             launch_pair_combine(dt, pc, f, ws + L.a_grp, ws + L.a_comb, 1, st));
   // down projection (Algorithm 1 line 14): y = a_comb W_down^T + Qw (s B_down)^T
   if (dt == MIXLORA_BF16 && (size_t)T <= SPLITK_MAX_ROWS) {
     // Few rows: the d output columns alone give too few tiles to stream W_down at full rate, so
@@ -414,7 +426,7 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
       if (used == 0) add_seg(p[0], ws + L.Qw, R, ws + L.Bd_cat, R, R);
     }
     HIP_TRY(launch_gemm(dt, p, used, st));
-    HIP_TRY(launch_splitk_reduce(dt, part, used, (int64_t)T * d, y, st));
+    HIP_TRY_AS(PROF_OTHER, 0, launch_splitk_reduce(dt, part, used, (int64_t)T * d, y, st));
   } else {
     GemmProblem p = problem(T, d, y, d, 0);
     add_seg(p, ws + L.a_comb, f, w->W_down, f, f);
@@ -516,6 +528,7 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
   char *ws = reinterpret_cast<char *>(workspace);
   const int T = D.T, d = D.d, f = D.d_ff, N = D.N, k = D.k, r = D.r, R = N * r, kT = k * T;
   const int dt = D.dtype, Kx = L.Kx;
+  const double Eb = dt == MIXLORA_BF16 ? 2.0 : 4.0;   // bytes per stored element (measurement hook)
   const float s = D.lora_scale;
   float *probs = (float *)(ws + L.probs);
   int32_t *idx = (int32_t *)(ws + L.idx);
@@ -526,9 +539,9 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
   PairCtx pc{offs, pair_of_row, row_of_pair, wts, idx, T, N, k, r};
 
   const void *WdT = w->W_down_T, *WgT = w->W_gate_T, *WuT = w->W_up_T;
-  if (!WdT) { HIP_TRY(launch_transpose(dt, w->W_down, ws + L.WdT, d, f, st)); WdT = ws + L.WdT; }
-  if (!WgT) { HIP_TRY(launch_transpose(dt, w->W_gate, ws + L.WgT, f, d, st)); WgT = ws + L.WgT; }
-  if (!WuT) { HIP_TRY(launch_transpose(dt, w->W_up, ws + L.WuT, f, d, st)); WuT = ws + L.WuT; }
+  if (!WdT) { HIP_TRY_AS(PROF_OTHER, 2.0 * d * f * Eb, launch_transpose(dt, w->W_down, ws + L.WdT, d, f, st)); WdT = ws + L.WdT; }
+  if (!WgT) { HIP_TRY_AS(PROF_OTHER, 2.0 * d * f * Eb, launch_transpose(dt, w->W_gate, ws + L.WgT, f, d, st)); WgT = ws + L.WgT; }
+  if (!WuT) { HIP_TRY_AS(PROF_OTHER, 2.0 * d * f * Eb, launch_transpose(dt, w->W_up, ws + L.WuT, f, d, st)); WuT = ws + L.WuT; }
 
   // every re-layout of the LoRA banks and the router that the pass needs, in one launch
   {
@@ -543,7 +556,7 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
         // bf16 path only: zeros for the block-sparse operand S, filled in by the fused stage
         vanilla ? job_zero_fill(ws + L.Sp, (size_t)kT * Kx * 2)
                 : job_zero_fill(ws + L.S, (size_t)T * Kx * 2)};
-    HIP_TRY(launch_relayout(dt, jobs, dt == MIXLORA_BF16 ? 8 : 6, st));
+    HIP_TRY_AS(PROF_OTHER, 0, launch_relayout(dt, jobs, dt == MIXLORA_BF16 ? 8 : 6, st));
   }
   // H = dy W_down  (once per token: the frozen down projection is shared and linear) and, in
   // the same launch, VB[t, e, :] = B_down[e]^T dy[t]
@@ -553,10 +566,10 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
     if (dora) {
       // the pair's upstream gradient carries the down projection's factor: c_down[e] * dy[t],
       // and so does the B_down^T product (the transposed bank is scaled in place)
-      HIP_TRY(launch_gather_rows_scaled(pc, d, dy, (float *)(ws + L.c_d), ws + L.dYp, st));
-      HIP_TRY(launch_scale_bank(ws + L.Bd_T, (float *)(ws + L.c_d), N, r, d, st));
+      HIP_TRY_AS(PROF_OTHER, 2.0 * kT * d * Eb, launch_gather_rows_scaled(pc, d, dy, (float *)(ws + L.c_d), ws + L.dYp, st));
+      HIP_TRY_AS(PROF_OTHER, 0, launch_scale_bank(ws + L.Bd_T, (float *)(ws + L.c_d), N, r, d, st));
     } else {
-      HIP_TRY(launch_gather_rows(dt, pc, d, dy, ws + L.dYp, st));
+      HIP_TRY_AS(PROF_OTHER, 2.0 * kT * d * Eb, launch_gather_rows(dt, pc, d, dy, ws + L.dYp, st));
     }
     GemmProblem p[2] = {problem(kT, f, ws + L.Hp, f, 0), problem(T, R, ws + L.VB_all, R, 1)};
     add_seg(p[0], ws + L.dYp, d, WdT, d, d);
@@ -586,7 +599,7 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
   int nct = L.nct;
   if (dt == MIXLORA_BF16) {
     nct = fused_splits(f, (int)kT);
-    HIP_TRY(launch_swiglu_bwd_mfma(pc, f, s, vanilla ? ws + L.Gp : ws + L.G,
+    HIP_TRY_AS(PROF_FUSED_BWD, 5.0 * kT * f * Eb, launch_swiglu_bwd_mfma(pc, f, s, vanilla ? ws + L.Gp : ws + L.G,
                                    vanilla ? ws + L.Up : ws + L.U, pair_down ? ws + L.Hp : ws + L.H,
                                    (float *)(ws + L.Pg_all),
                                    (float *)(ws + L.Pu_all), (float *)(ws + L.VB_all), w->B_gate,
@@ -596,7 +609,7 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
                                    (float *)(ws + L.TU_all), Sop, Kx, st, rows_mode,
                                    dora ? &dargs : nullptr));
   } else {
-    HIP_TRY(launch_swiglu_bwd(dt, pc, f, s, ws + L.G, ws + L.U, (float *)(ws + L.Pg_all),
+    HIP_TRY_AS(PROF_FUSED_BWD, 5.0 * kT * f * Eb, launch_swiglu_bwd(dt, pc, f, s, ws + L.G, ws + L.U, (float *)(ws + L.Pg_all),
                               (float *)(ws + L.Pu_all), w->B_gate, w->B_up, ws + L.H,
                               (float *)(ws + L.VB_all), w->A_down, ws + L.dg_grp, ws + L.du_grp,
                               (float *)(ws + L.dw_part), L.nct, st));
@@ -606,7 +619,7 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
     HIP_TRY(launch_gemm(dt, p, 2, st));
   }
   if (!vanilla) {   // shared gate/up: their input gradient needs the per-token sums only
-    HIP_TRY(launch_pair_combine2(dt, pc, f, ws + L.dg_grp, ws + L.dgsum, ws + L.du_grp,
+    HIP_TRY_AS(PROF_COMBINE, 2.0 * (k + 1) * T * f * Eb, launch_pair_combine2(dt, pc, f, ws + L.dg_grp, ws + L.dgsum, ws + L.du_grp,
                                  ws + L.dusum, 0, st));
   }
   // per-row rank-r factors of the LoRA gradients, then the grouped outer-product sums:
@@ -624,7 +637,7 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
   float *gout[6] = {grads->dB_gate, grads->dB_up, grads->dA_gate, grads->dA_up,
                     grads->dA_down, grads->dB_down};
   // router: dw -> dz (also written into the K-extension operand S)
-  HIP_TRY(launch_router_bwd(dt, pc, probs, (float *)(ws + L.dw_part), nct,
+  HIP_TRY_AS(PROF_ROUTING, (double)T * N * 8, launch_router_bwd(dt, pc, probs, (float *)(ws + L.dw_part), nct,
                             (float *)(ws + L.VB_all), (float *)(ws + L.Q_all), (float *)(ws + L.F),
                             s, d_aux, D.aux_coeff, (float *)(ws + L.dw), (float *)(ws + L.dz),
                             Sop, Kx, 2 * R, Kx - 2 * R, Nl, token_model,
@@ -633,7 +646,7 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
   if (dt == MIXLORA_BF16) {
     GatherJob gj[6];
     for (int i = 0; i < 6; i++) gj[i] = GatherJob{fsrc[i], ws + L.small[i], by_token[i], weighted[i]};
-    HIP_TRY(launch_gather_small_T(pc, gj, 6, L.ldT, st));
+    HIP_TRY_AS(PROF_OTHER, 0, launch_gather_small_T(pc, gj, 6, L.ldT, st));
     // the three sums over d_ff-wide operands in one launch, the three over gathered d-wide
     // operands in another (same groups, width and gather mode within a launch)
     const int wide_f[3] = {0, 1, 4}, wide_d[3] = {2, 3, 5};
@@ -642,40 +655,47 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
       jf[j] = GomJob{ws + L.small[wide_f[j]], wide[wide_f[j]], gout[wide_f[j]], layout_qc[wide_f[j]]};
       jd[j] = GomJob{ws + L.small[wide_d[j]], wide[wide_d[j]], gout[wide_d[j]], layout_qc[wide_d[j]]};
     }
-    HIP_TRY(launch_group_outer_mfma(offs, N, kT, nullptr, k, jf, 3, L.ldT, r, f, s, part, pfl, st));
+    HIP_TRY_AS(PROF_GRAD_SUMS, 3.0 * kT * f * Eb,
+               launch_group_outer_mfma(offs, N, kT, nullptr, k, jf, 3, L.ldT, r, f, s, part, pfl, st));
     if (dora) {
       // dB_down sums the factor-carrying pair rows c_down[e] * dy[t] (already gathered)
-      HIP_TRY(launch_group_outer_mfma(offs, N, kT, pair_of_row, k, jd, 2, L.ldT, r, d, s, part, pfl, st));
+      HIP_TRY_AS(PROF_GRAD_SUMS, 2.0 * kT * d * Eb,
+                 launch_group_outer_mfma(offs, N, kT, pair_of_row, k, jd, 2, L.ldT, r, d, s, part, pfl, st));
       const GomJob jb{ws + L.small[5], ws + L.dYp, gout[5], layout_qc[5]};
-      HIP_TRY(launch_group_outer_mfma(offs, N, kT, nullptr, k, &jb, 1, L.ldT, r, d, s, part, pfl, st));
+      HIP_TRY_AS(PROF_GRAD_SUMS, 1.0 * kT * d * Eb,
+                 launch_group_outer_mfma(offs, N, kT, nullptr, k, &jb, 1, L.ldT, r, d, s, part, pfl, st));
     } else {
-      HIP_TRY(launch_group_outer_mfma(offs, N, kT, pair_of_row, k, jd, 3, L.ldT, r, d, s, part, pfl, st));
+      HIP_TRY_AS(PROF_GRAD_SUMS, 3.0 * kT * d * Eb,
+                 launch_group_outer_mfma(offs, N, kT, pair_of_row, k, jd, 3, L.ldT, r, d, s, part, pfl, st));
     }
     // dW_router = dz^T x  (the transposed bf16 dz comes from the router backward)
     const GomJob jr{ws + L.dzT, x, grads->dW_router, 1};
-    HIP_TRY(launch_group_outer_mfma((int32_t *)(ws + L.tok_offs), 1, T, nullptr, 1, &jr, 1, L.ldTz, N,
-                                    d, 1.f, part, pfl, st));
+    HIP_TRY_AS(PROF_GRAD_SUMS, (double)T * d * Eb,
+               launch_group_outer_mfma((int32_t *)(ws + L.tok_offs), 1, T, nullptr, 1, &jr, 1, L.ldTz,
+                                       N, d, 1.f, part, pfl, st));
   } else {
     for (int i = 0; i < 6; i++) {
-      HIP_TRY(launch_gather_small(pc, fsrc[i], by_token[i], weighted[i], (float *)(ws + L.small[i]), st));
-      HIP_TRY(launch_group_outer(dt, offs, N, kT, gat[i], k, (float *)(ws + L.small[i]), r, wide[i],
-                                 width[i], s, layout_qc[i], gout[i], part, pfl, st));
+      HIP_TRY_AS(PROF_OTHER, 0, launch_gather_small(pc, fsrc[i], by_token[i], weighted[i], (float *)(ws + L.small[i]), st));
+      HIP_TRY_AS(PROF_GRAD_SUMS, (double)kT * width[i] * Eb,
+                 launch_group_outer(dt, offs, N, kT, gat[i], k, (float *)(ws + L.small[i]), r, wide[i],
+                                    width[i], s, layout_qc[i], gout[i], part, pfl, st));
     }
-    HIP_TRY(launch_group_outer(dt, (int32_t *)(ws + L.tok_offs), 1, T, nullptr, 1,
-                               (float *)(ws + L.dz), N, x, d, 1.f, 1, grads->dW_router, part, pfl, st));
+    HIP_TRY_AS(PROF_GRAD_SUMS, (double)T * d * Eb,
+               launch_group_outer(dt, (int32_t *)(ws + L.tok_offs), 1, T, nullptr, 1,
+                                  (float *)(ws + L.dz), N, x, d, 1.f, 1, grads->dW_router, part, pfl, st));
   }
   // dx = dgsum W_gate + dusum W_up + [TG | TU | dz] [s A_gate ; s A_up ; W_router]
   if (dt != MIXLORA_BF16)   // in bf16 the fused stage has already written these blocks
-    HIP_TRY(launch_scatter_blocks(dt, pc, (float *)(ws + L.TG_all),
+    HIP_TRY_AS(PROF_OTHER, 0, launch_scatter_blocks(dt, pc, (float *)(ws + L.TG_all),
                                   (int64_t)((float *)(ws + L.TU_all) - (float *)(ws + L.TG_all)), 2, R,
                                   1, 0, ws + L.S, Kx, 0, st));
   if (dora) {
     // magnitude gradients: dm = (1 / n) * sum over the expert's rows of (output gradient *
     // unscaled projection output); gate / up sums come from the fused stage per row tile
-    HIP_TRY(launch_dm_tiles_reduce(offs, N, f, (float *)(ws + L.dm_part_g),
+    HIP_TRY_AS(PROF_OTHER, 0, launch_dm_tiles_reduce(offs, N, f, (float *)(ws + L.dm_part_g),
                                    (float *)(ws + L.dm_part_u), (float *)(ws + L.ninv_g),
                                    (float *)(ws + L.ninv_u), dgrads->dm_gate, dgrads->dm_up, st));
-    HIP_TRY(launch_dm_down(pc, d, dy, ws + L.Op, (float *)(ws + L.ninv_d),
+    HIP_TRY_AS(PROF_OTHER, 0, launch_dm_down(pc, d, dy, ws + L.Op, (float *)(ws + L.ninv_d),
                            (float *)(ws + L.dmd_part), dgrads->dm_down, st));
   }
   if (vanilla) {
@@ -686,7 +706,7 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
     add_seg(p, ws + L.du_grp, f, WuT, f, f);
     add_seg(p, ws + L.Sp, Kx, ws + L.Bx, Kx, Kx);
     HIP_TRY(launch_gemm(dt, &p, 1, st));
-    HIP_TRY(launch_pair_combine(dt, pc, d, ws + L.dXp, dx, 0, st));
+    HIP_TRY_AS(PROF_COMBINE, (double)(k + 1) * T * d * Eb, launch_pair_combine(dt, pc, d, ws + L.dXp, dx, 0, st));
   } else {
     GemmProblem p = problem(T, d, dx, d, 0);
     add_seg(p, ws + L.dgsum, f, WgT, f, f);
@@ -872,13 +892,22 @@ int mixlora_aux_loss(const float *probs, const int32_t *topk_idx, int32_t T, int
 }
 
 int mixlora_profile_begin(int32_t max_launches) {
-  return gemm_timer_begin(max_launches) == 0 ? MIXLORA_OK : MIXLORA_E_HIP;
+  return prof_begin(max_launches) == 0 ? MIXLORA_OK : MIXLORA_E_HIP;
 }
 
 int mixlora_profile_end(double *ms_total, int32_t *launches, double *flops_total) {
   if (!ms_total || !launches || !flops_total) return MIXLORA_E_NULL;
+  if (prof_end() != 0) return MIXLORA_E_HIP;
   int n = 0;
-  if (gemm_timer_end(ms_total, &n, flops_total) != 0) return MIXLORA_E_HIP;
+  (void)prof_kind(PROF_GEMM, ms_total, &n, flops_total);
+  *launches = n;
+  return MIXLORA_OK;
+}
+
+int mixlora_profile_kind(int32_t kind, double *ms_total, int32_t *launches, double *work_total) {
+  if (!ms_total || !launches || !work_total) return MIXLORA_E_NULL;
+  int n = 0;
+  if (prof_kind(kind, ms_total, &n, work_total) != 0) return MIXLORA_E_SHAPE;
   *launches = n;
   return MIXLORA_OK;
 }

@@ -73,10 +73,26 @@ hipError_t launch_gemm(int dtype, const GemmProblem *probs, int nprob, hipStream
 // whether problems of different M may share one launch_gemm call
 bool gemm_mixed_rows_ok(int dtype, const GemmProblem *probs, int nprob);
 
-// Measurement hook: HIP-event timing of every launch of the large-tile bf16 kernel between
-// begin and end (events are recorded on the launch stream).  Not thread-safe; off by default.
-int gemm_timer_begin(int max_launches);
-int gemm_timer_end(double *ms_total, int *launches, double *flops_total);
+// Measurement hook (csrc/prof.hip): HIP-event timing of launches by kind between prof_begin and
+// prof_end (events are recorded on the launch stream).  Not thread-safe; off by default.
+// Work is floating-point operations for PROF_GEMM (the DMA-ring bf16 MFMA kernels that carry the
+// frozen projections) and algorithmic bytes for the bandwidth-bound kinds.
+enum ProfKind {
+  PROF_GEMM = 0,      // frozen-projection GEMM launches
+  PROF_FUSED_FWD,     // per-pair SwiGLU stage, forward
+  PROF_FUSED_BWD,     // per-pair SwiGLU stage, backward
+  PROF_COMBINE,       // weighted / unweighted sums of a token's pair rows
+  PROF_GRAD_SUMS,     // grouped outer-product sums (LoRA and router gradients)
+  PROF_ROUTING,       // softmax / top-k, grouping, auxiliary loss, router backward
+  PROF_OTHER,         // re-layouts, gathers, small reductions
+  PROF_KINDS
+};
+bool prof_on();
+int prof_begin(int max_launches);
+int prof_mark_begin(int kind, hipStream_t st);            // returns a slot (or -1 when off / full)
+void prof_mark_end(int slot, hipStream_t st, double work);
+int prof_end();
+int prof_kind(int kind, double *ms_total, int *launches, double *work_total);
 
 // ---- routing -----------------------------------------------------------------------------
 // N experts in all; with several adapters (token_model != NULL) token t is routed among the Nl

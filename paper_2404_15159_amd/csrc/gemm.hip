@@ -559,47 +559,13 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmBatch args) {
   }
 }
 
-// ---- optional timing of the large-tile kernel (measurement hook, off by default) -----------
-namespace {
-struct GemmTimer {
-  bool on = false;
-  int cap = 0, used = 0;
-  hipEvent_t *beg = nullptr, *end = nullptr;
-  double flops = 0.0;
-} g_timer;
-}  // namespace
-
-int gemm_timer_begin(int max_launches) {
-  if (g_timer.on || max_launches < 1) return -1;
-  if (g_timer.cap < max_launches) {
-    hipEvent_t *b = new hipEvent_t[max_launches], *e = new hipEvent_t[max_launches];
-    for (int i = 0; i < max_launches; i++) {
-      if (hipEventCreate(&b[i]) != hipSuccess || hipEventCreate(&e[i]) != hipSuccess) return -1;
-    }
-    g_timer.beg = b;   // an earlier, smaller pool is kept alive until process exit
-    g_timer.end = e;
-    g_timer.cap = max_launches;
-  }
-  g_timer.used = 0;
-  g_timer.flops = 0.0;
-  g_timer.on = true;
-  return 0;
-}
-
-int gemm_timer_end(double *ms_total, int *launches, double *flops_total) {
-  if (!g_timer.on) return -1;
-  g_timer.on = false;
-  double ms = 0.0;
-  for (int i = 0; i < g_timer.used; i++) {
-    if (hipEventSynchronize(g_timer.end[i]) != hipSuccess) return -1;
-    float t = 0.f;
-    if (hipEventElapsedTime(&t, g_timer.beg[i], g_timer.end[i]) != hipSuccess) return -1;
-    ms += t;
-  }
-  *ms_total = ms;
-  *launches = g_timer.used;
-  *flops_total = g_timer.flops;
-  return 0;
+// floating-point operations a launch executes (2 M N K over its problems' K segments)
+static double batch_flops(const GemmBatch &b, int nprob) {
+  double fl = 0.0;
+  for (int i = 0; i < nprob; i++)
+    for (int sgi = 0; sgi < b.p[i].nseg; sgi++)
+      fl += 2.0 * b.p[i].M * (double)b.p[i].N * b.p[i].seg[sgi].K;
+  return fl;
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, typename OutT>
@@ -614,17 +580,11 @@ static hipError_t launch_bf16(const GemmBatch &b, int nprob, hipStream_t st) {
     attr_set = true;
   }
   const int tiles = ((b.p[0].M + BM - 1) / BM) * ((b.p[0].N + BN - 1) / BN);
-  // launches that carry a frozen projection (more than 128 output columns) are timed; a launch
-  // of narrow rank-r or router problems alone is not
-  const bool timed = g_timer.on && g_timer.used < g_timer.cap && b.p[0].N > 128;
-  if (timed) (void)hipEventRecord(g_timer.beg[g_timer.used], st);
+  // launches that carry a frozen projection (more than 128 output columns) count as GEMM
+  // launches for the measurement hook; a launch of narrow rank-r or router problems does not
+  const int slot = prof_on() ? prof_mark_begin(b.p[0].N > 128 ? PROF_GEMM : PROF_OTHER, st) : -1;
   hipLaunchKernelGGL(kern, dim3(tiles, 1, nprob), dim3(WGM * WGN * 64), smem, st, b);
-  if (timed) {
-    (void)hipEventRecord(g_timer.end[g_timer.used++], st);
-    for (int i = 0; i < nprob; i++)
-      for (int sgi = 0; sgi < b.p[i].nseg; sgi++)
-        g_timer.flops += 2.0 * b.p[i].M * (double)b.p[i].N * b.p[i].seg[sgi].K;
-  }
+  if (slot >= 0) prof_mark_end(slot, st, b.p[0].N > 128 ? batch_flops(b, nprob) : 0.0);
   return hipGetLastError();
 }
 
@@ -645,16 +605,10 @@ static hipError_t launch_bf16_dl(const GemmBatch &b, int nprob, hipStream_t st) 
     tiles = t > tiles ? t : tiles;
   }
   // every launch of this kernel family is a frozen-projection launch (large tiles at training
-  // shapes, the narrow weight-streaming tiles at decode shapes): all are timed
-  const bool timed = g_timer.on && g_timer.used < g_timer.cap;
-  if (timed) (void)hipEventRecord(g_timer.beg[g_timer.used], st);
+  // shapes, the narrow weight-streaming tiles at decode shapes): all count as GEMM launches
+  const int slot = prof_on() ? prof_mark_begin(PROF_GEMM, st) : -1;
   hipLaunchKernelGGL(kern, dim3(tiles, 1, nprob), dim3(WGM * WGN * 64), smem, st, b);
-  if (timed) {
-    (void)hipEventRecord(g_timer.end[g_timer.used++], st);
-    for (int i = 0; i < nprob; i++)
-      for (int sgi = 0; sgi < b.p[i].nseg; sgi++)
-        g_timer.flops += 2.0 * b.p[i].M * (double)b.p[i].N * b.p[i].seg[sgi].K;
-  }
+  if (slot >= 0) prof_mark_end(slot, st, batch_flops(b, nprob));
   return hipGetLastError();
 }
 
