@@ -16,7 +16,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libmixlora.so")
-SOURCES = ("gemm.hip", "router.hip", "elementwise.hip", "grads.hip", "fused.hip", "probe.hip",
+SOURCES = ("gemm.hip", "router.hip", "elementwise.hip", "grads.hip", "fused.hip", "fused_pg.hip", "probe.hip",
            "linear.hip", "optim.hip", "dora.hip", "prof.hip", "api.hip")
 
 FLAGS = [

@@ -28,6 +28,7 @@ struct Layout {
   // saved by forward
   size_t probs, Z, idx, w, counts, first_counts, offs, row_of_pair, pair_of_row, F, P, tok_offs,
       model_tokens;
+  size_t pg_tok, pg_tiles, pg_ntiles;   // tokens grouped by expert pair (csrc/fused_pg.hip)
   size_t G, U, Pg_all, Pu_all, a_grp, Q_all;
   // forward scratch
   size_t a_comb, Qw, Bd_cat, rank_part, splitk, gp_scratch;
@@ -73,6 +74,9 @@ Layout make_layout(const mixlora_dims &D, int schedule = MIXLORA_SCHEDULE_LINEAR
   L.P = take(N * 4);
   L.tok_offs = take(2 * 4);
   L.model_tokens = take(64 * 4);
+  L.pg_tok = take(T * 4);
+  L.pg_tiles = take((size_t)fused_pg_max_tiles((int)T, (int)(N <= PG_MAX_EXPERTS ? N : 1)) * 16);
+  L.pg_ntiles = take(4);
   L.G = take(vanilla ? 0 : T * f * E);
   L.U = take(vanilla ? 0 : T * f * E);
   L.Pg_all = take(T * R * 4);
@@ -98,7 +102,10 @@ Layout make_layout(const mixlora_dims &D, int schedule = MIXLORA_SCHEDULE_LINEAR
   L.ninv_u = take(dora ? N * f * 4 : 0);
   L.ninv_d = take(dora ? N * d * 4 : 0);
   L.Bd_cat = take(d * R * E);
-  L.rank_part = take(2 * (size_t)fused_splits((int)f, (int)kT) * kT * r * 4);   // per-split rank-r partial sums (two banks)
+  {   // per-split rank-r partial sums (two banks), for the grouped and the token-major stages
+    const size_t sp_g = (size_t)fused_splits((int)f, (int)kT), sp_t = (size_t)fused_pg_splits((int)f, (int)T);
+    L.rank_part = take(2 * (sp_g > sp_t ? sp_g : sp_t) * kT * r * 4);
+  }
   // few tokens (decode-shaped calls): partial outputs of the K-split down projection
   L.splitk = take(T <= SPLITK_MAX_ROWS ? (size_t)GEMM_MAX_PROBLEMS * T * d * 4 : 0);
   L.gp_scratch = take(kT > GROUP_SINGLE_WG_PAIRS ? group_pairs_scratch_bytes((int)T, (int)k) : 0);
@@ -317,21 +324,31 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
   else
     HIP_TRY_AS(PROF_ROUTING, (double)T * d * Eb, launch_router(dt, x, w->W_router, T, d, N, k, probs, topk_idx, topk_w, idx, wts, Nl,
                           token_model, st));
+  PairCtx pc{offs, pair_of_row, row_of_pair, wts, idx, T, N, k, r};
+  // the per-pair stages on tokens grouped by expert pair (csrc/fused_pg.hip), when they apply
+  const bool use_pg = dt == MIXLORA_BF16 && !pair_down && !dora && fused_pg_ok(pc, f);
+  int32_t *pg_tok = (int32_t *)(ws + L.pg_tok), *pg_tiles = (int32_t *)(ws + L.pg_tiles),
+          *pg_ntiles = (int32_t *)(ws + L.pg_ntiles);
   // grouping of the pairs by expert and Eq. 8-9, one launch
-  if ((size_t)kT > GROUP_SINGLE_WG_PAIRS)
+  if ((size_t)kT > GROUP_SINGLE_WG_PAIRS) {
     HIP_TRY_AS(PROF_ROUTING, (double)kT * 16, launch_group_pairs_aux_multi(idx, T, N, k, (int32_t *)(ws + L.counts), expert_counts,
                                          (int32_t *)(ws + L.first_counts), offs, row_of_pair,
                                          pair_of_row, (int32_t *)(ws + L.tok_offs), probs,
                                          D.aux_coeff, D.aux_mode, aux_loss, (float *)(ws + L.F),
                                          (float *)(ws + L.P), Nl, token_model,
                                          (int32_t *)(ws + L.model_tokens), ws + L.gp_scratch, st));
-  else
-    HIP_TRY_AS(PROF_ROUTING, (double)kT * 16, launch_group_pairs_aux(idx, T, N, k, (int32_t *)(ws + L.counts), expert_counts,
-                                   (int32_t *)(ws + L.first_counts), offs, row_of_pair, pair_of_row,
-                                   (int32_t *)(ws + L.tok_offs), probs, D.aux_coeff, D.aux_mode,
-                                   aux_loss, (float *)(ws + L.F), (float *)(ws + L.P), Nl, token_model,
-                                   (int32_t *)(ws + L.model_tokens), st));
-  PairCtx pc{offs, pair_of_row, row_of_pair, wts, idx, T, N, k, r};
+    if (use_pg)
+      HIP_TRY_AS(PROF_ROUTING, (double)T * 12, launch_group_token_pairs(pc, pg_tok, pg_tiles, pg_ntiles, st));
+  } else {
+    // (the tokens' grouping by expert pair rides in the same launch as a second workgroup)
+    HIP_TRY_AS(PROF_ROUTING, (double)kT * 16 + (use_pg ? (double)T * 12 : 0.0),
+               launch_group_pairs_aux(idx, T, N, k, (int32_t *)(ws + L.counts), expert_counts,
+                                      (int32_t *)(ws + L.first_counts), offs, row_of_pair, pair_of_row,
+                                      (int32_t *)(ws + L.tok_offs), probs, D.aux_coeff, D.aux_mode,
+                                      aux_loss, (float *)(ws + L.F), (float *)(ws + L.P), Nl,
+                                      token_model, (int32_t *)(ws + L.model_tokens),
+                                      use_pg ? pg_tok : nullptr, pg_tiles, pg_ntiles, st));
+  }
   {
     // s * B_down packed for the K-extension of the down GEMM; in bf16 also zeros for the
     // block-sparse operand Qw, whose non-zero blocks the fused stage fills in
@@ -381,6 +398,24 @@ static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mode
     }
     // the down projection's factor is applied to every pair's output while combining
     HIP_TRY_AS(PROF_COMBINE, (double)(k + 1) * T * d * Eb, launch_pair_combine_scaled(pc, d, ws + L.Op, (float *)(ws + L.c_d), y, st));
+    return MIXLORA_OK;
+  }
+  if (use_pg) {
+    // tokens grouped by expert pair: rank-r deltas, SiLU * up, the weighted combination of a
+    // token's two pairs (Algorithm 1 lines 11-13 and 15) and the A_down projections in one pass
+    // that fetches G and U once per token; the grouped activations are kept only when a backward
+    // pass can follow
+    const int write_a = workspace_bytes >= L.bwd_end ? 1 : 0;
+    HIP_TRY_AS(PROF_FUSED_FWD, (double)(3 + 2 * write_a) * T * f * Eb,
+               launch_swiglu_fwd_pg(pc, f, D.lora_scale, pg_tok, pg_tiles, pg_ntiles,
+                                    ws + L.G, ws + L.U, (float *)(ws + L.Pg_all),
+                                    (float *)(ws + L.Pu_all), w->B_gate, w->B_up, w->A_down,
+                                    ws + L.a_grp, ws + L.a_comb, (float *)(ws + L.rank_part),
+                                    (float *)(ws + L.Q_all), ws + L.Qw, R, write_a, st));
+    GemmProblem p = problem(T, d, y, d, 0);
+    add_seg(p, ws + L.a_comb, f, w->W_down, f, f);
+    add_seg(p, ws + L.Qw, R, ws + L.Bd_cat, R, R);
+    HIP_TRY(launch_gemm(dt, &p, 1, st));
     return MIXLORA_OK;
   }
   // Algorithm 1 lines 11-13 on the routed pairs, expert-grouped rows

@@ -116,7 +116,8 @@ hipError_t launch_group_pairs_aux(const int32_t *idx, int T, int N, int k, int32
                                   int32_t *row_of_pair, int32_t *pair_of_row, int32_t *tok_offs,
                                   const float *probs, float coeff, int mode, float *loss, float *F,
                                   float *P, int Nl, const int32_t *token_model,
-                                  int32_t *model_tokens, hipStream_t st);
+                                  int32_t *model_tokens, int32_t *pg_tok, int32_t *pg_tiles,
+                                  int32_t *pg_ntiles, hipStream_t st);
 // The same over many workgroups, for long token batches (identical row maps; the probability
 // sums of Eq. 9 are added in a different, equally fixed order).  scratch:
 // group_pairs_scratch_bytes(T, k) bytes.
@@ -188,6 +189,33 @@ hipError_t launch_swiglu_bwd_mfma(const PairCtx &pc, int f, float s, const void 
                                   void *du_grp, float *dw_part, float *rank_part, float *TG_all,
                                   float *TU_all, void *S, int lds_, hipStream_t st,
                                   int rows_mode = 0, const DoraArgs *dora = nullptr);
+// Pair-grouped token tiles (csrc/fused_pg.hip) for top-2 routing, N <= PG_MAX_EXPERTS, 128 < T <=
+// PG_MAX_TOKENS: tokens are grouped by their unordered expert pair, a workgroup handles 32 tokens
+// of one pair with one set of wavefronts per expert, G / U (/ H) are fetched from HBM once per
+// token and the sums over a token's two pairs are written per token (no combine pass).
+// Tables: tok_of_pos [T], tile_info [fused_pg_max_tiles(T, N)][4], ntiles [1] (device int32).
+// Forward: a_comb[t] = w_t0 a_t0 + w_t1 a_t1, a_grp only when write_a, Q_all / Qw as above;
+// Q_part: fused_pg_splits(f, T) * kT * r floats.
+constexpr int PG_MAX_EXPERTS = 16;
+constexpr int PG_TILE_ROWS = 32;
+constexpr int PG_MAX_TOKENS = 1 << 16;
+bool fused_pg_ok(const PairCtx &pc, int f);
+int fused_pg_max_tiles(int T, int N);
+int fused_pg_splits(int f, int T);
+hipError_t launch_group_token_pairs(const PairCtx &pc, int32_t *tok_of_pos, int32_t *tile_info,
+                                    int32_t *ntiles, hipStream_t st);
+hipError_t launch_swiglu_fwd_pg(const PairCtx &pc, int f, float s, const int32_t *tok_of_pos,
+                                const int32_t *tile_info, const int32_t *ntiles, const void *G,
+                                const void *U, const float *Pg_all, const float *Pu_all,
+                                const void *B_gate, const void *B_up, const void *A_down,
+                                void *a_grp, void *a_comb, float *Q_part, float *Q_all, void *Qw,
+                                int ldqw, int write_a, hipStream_t st);
+// dense[row, e(row)*r + q] = sum over splits of part[split][row][q] (fixed order) for one bank
+// (dense1 == NULL) or two banks bank_stride floats apart; the value (times the routing weight if
+// weighted) also goes as bf16 into the block-sparse operand sparse[t(row) or row, bank*N*r + e*r + q]
+hipError_t launch_reduce_rank_parts(const PairCtx &pc, const float *part0, int64_t bank_stride,
+                                    int nsplit, float *dense0, float *dense1, void *sparse,
+                                    int ld_sparse, int weighted, int by_row, hipStream_t st);
 int fused_row_tiles(int kT, int N);   // grid.x of the fused stages
 int fused_splits(int f, int kT);   // at most FUSED_MAX_SPLITS
 constexpr int FUSED_MAX_SPLITS = 32;

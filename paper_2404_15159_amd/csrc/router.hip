@@ -340,9 +340,100 @@ __global__ __launch_bounds__(1024) void aux_loss_kernel(const float *__restrict_
   aux_loss_block(probs, idx, T, N, k, coeff, mode, loss, F_out, P_out, Nl, token_model, model_tokens);
 }
 
+constexpr int PG_GROUPS = PG_MAX_EXPERTS * PG_MAX_EXPERTS;   // group id a * N + b, a < b
+constexpr int PG_GWAVES = 16;
+
+// ---- tokens grouped by unordered expert pair (stable counting sort, one workgroup) -------------
+// tok_of_pos[pos] = token at position pos of the grouped order; tile_info[tile] = {group id,
+// first position, rows (<= 32), 0}; ntiles[0] = number of tiles.
+__device__ __forceinline__ void group_token_pairs_block(
+    const int32_t *__restrict__ idx, int T, int N, int32_t *__restrict__ tok_of_pos,
+    int32_t *__restrict__ tile_info, int32_t *__restrict__ ntiles) {
+  __shared__ int cnt[PG_GWAVES][PG_GROUPS];   // per wavefront: count, then next free position
+  __shared__ int gtot[PG_GROUPS];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int G = N * N;
+  for (int i = tid; i < PG_GWAVES * PG_GROUPS; i += PG_GWAVES * 64) (&cnt[0][0])[i] = 0;
+  __syncthreads();
+  const int per = (((T + PG_GWAVES - 1) / PG_GWAVES) + 63) & ~63;
+  const int lo = wave * per;
+  const int hi = lo + per < T ? lo + per : T;
+  auto group_of = [&](int t) {
+    const int e0 = idx[(int64_t)t * 2], e1 = idx[(int64_t)t * 2 + 1];
+    return e0 < e1 ? e0 * N + e1 : e1 * N + e0;
+  };
+  for (int t0 = lo; t0 < hi; t0 += 64) {
+    const int t = t0 + lane;
+    if (t < hi) atomicAdd(&cnt[wave][group_of(t)], 1);   // integer counts: order does not matter
+  }
+  __syncthreads();
+  if (tid < PG_GROUPS) {
+    int tot = 0;
+    if (tid < G)
+      for (int w = 0; w < PG_GWAVES; w++) tot += cnt[w][tid];
+    gtot[tid] = tot;
+  }
+  __syncthreads();
+  if (tid < G) {
+    int off = 0, tb = 0;
+    for (int g = 0; g < tid; g++) {
+      off += gtot[g];
+      tb += (gtot[g] + PG_TILE_ROWS - 1) / PG_TILE_ROWS;
+    }
+    const int tot = gtot[tid], nt = (tot + PG_TILE_ROWS - 1) / PG_TILE_ROWS;
+    int run = off;
+    for (int w = 0; w < PG_GWAVES; w++) {
+      const int c = cnt[w][tid];
+      cnt[w][tid] = run;
+      run += c;
+    }
+    for (int i = 0; i < nt; i++) {
+      int32_t *ti = tile_info + (int64_t)(tb + i) * 4;
+      ti[0] = tid;
+      ti[1] = off + i * PG_TILE_ROWS;
+      ti[2] = tot - i * PG_TILE_ROWS < PG_TILE_ROWS ? tot - i * PG_TILE_ROWS : PG_TILE_ROWS;
+      ti[3] = 0;
+    }
+    if (tid == G - 1) ntiles[0] = tb + nt;
+  }
+  __syncthreads();
+  const unsigned long long lt = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+  for (int t0 = lo; t0 < hi; t0 += 64) {
+    const int t = t0 + lane;
+    const bool valid = t < hi;
+    const int gid = valid ? group_of(t) : -1;
+    int pos = 0;
+    unsigned long long rem = __ballot(valid);
+    while (rem) {   // one trip per distinct group among the 64 tokens, in lane order of its first token
+      const int leader = __ffsll((long long)rem) - 1;
+      const int kk = __shfl(gid, leader, 64);
+      const unsigned long long m = __ballot(valid && gid == kk);
+      const int start = cnt[wave][kk];
+      if (valid && gid == kk) pos = start + __popcll(m & lt);
+      if (lane == leader) cnt[wave][kk] = start + __popcll(m);
+      rem &= ~m;
+    }
+    if (valid) tok_of_pos[pos] = t;
+  }
+}
+
+__global__ __launch_bounds__(PG_GWAVES * 64) void group_token_pairs_kernel(
+    const int32_t *__restrict__ idx, int T, int N, int32_t *__restrict__ tok_of_pos,
+    int32_t *__restrict__ tile_info, int32_t *__restrict__ ntiles) {
+  group_token_pairs_block(idx, T, N, tok_of_pos, tile_info, ntiles);
+}
+
+hipError_t launch_group_token_pairs(const PairCtx &pc, int32_t *tok_of_pos, int32_t *tile_info,
+                                    int32_t *ntiles, hipStream_t st) {
+  hipLaunchKernelGGL(group_token_pairs_kernel, dim3(1), dim3(PG_GWAVES * 64), 0, st, pc.idx, pc.T,
+                     pc.N, tok_of_pos, tile_info, ntiles);
+  return hipGetLastError();
+}
+
 // Grouping and auxiliary loss of one forward pass in one single-workgroup launch (both are bound
 // by their own latency); also writes the two-entry offsets {0, T} that let the grouped
-// outer-product kernel treat all tokens as one group.
+// outer-product kernel treat all tokens as one group.  With pg_tok != NULL a second workgroup
+// groups the tokens by expert pair at the same time (it needs the kept experts only).
 __global__ __launch_bounds__(GP_WAVES * 64) void group_pairs_aux_kernel(
     const int32_t *__restrict__ idx, int T, int N, int k, int32_t *__restrict__ counts,
     int32_t *__restrict__ counts_out, int32_t *__restrict__ first_counts,
@@ -350,8 +441,14 @@ __global__ __launch_bounds__(GP_WAVES * 64) void group_pairs_aux_kernel(
     int32_t *__restrict__ pair_of_row, int32_t *__restrict__ tok_offs,
     const float *__restrict__ probs, float coeff, int mode, float *__restrict__ loss,
     float *__restrict__ F_out, float *__restrict__ P_out, int Nl,
-    const int32_t *__restrict__ token_model, int32_t *__restrict__ model_tokens) {
+    const int32_t *__restrict__ token_model, int32_t *__restrict__ model_tokens,
+    int32_t *__restrict__ pg_tok, int32_t *__restrict__ pg_tiles, int32_t *__restrict__ pg_ntiles) {
   static_assert(GP_WAVES * 64 == 1024, "the auxiliary-loss block code assumes 1024 threads");
+  static_assert(PG_GWAVES == GP_WAVES, "both block routines run with the same workgroup size");
+  if (blockIdx.x == 1) {   // workgroup-uniform
+    group_token_pairs_block(idx, T, N, pg_tok, pg_tiles, pg_ntiles);
+    return;
+  }
   group_pairs_block(idx, T * k, N, k, counts, counts_out, first_counts, offs, row_of_pair, pair_of_row);
   if (threadIdx.x == 0) { tok_offs[0] = 0; tok_offs[1] = T; }
   __syncthreads();
@@ -363,10 +460,12 @@ hipError_t launch_group_pairs_aux(const int32_t *idx, int T, int N, int k, int32
                                   int32_t *row_of_pair, int32_t *pair_of_row, int32_t *tok_offs,
                                   const float *probs, float coeff, int mode, float *loss, float *F,
                                   float *P, int Nl, const int32_t *token_model,
-                                  int32_t *model_tokens, hipStream_t st) {
-  hipLaunchKernelGGL(group_pairs_aux_kernel, dim3(1), dim3(GP_WAVES * 64), 0, st, idx, T, N, k,
-                     counts, counts_out, first_counts, offs, row_of_pair, pair_of_row, tok_offs,
-                     probs, coeff, mode, loss, F, P, Nl, token_model, model_tokens);
+                                  int32_t *model_tokens, int32_t *pg_tok, int32_t *pg_tiles,
+                                  int32_t *pg_ntiles, hipStream_t st) {
+  hipLaunchKernelGGL(group_pairs_aux_kernel, dim3(pg_tok ? 2 : 1), dim3(GP_WAVES * 64), 0, st, idx,
+                     T, N, k, counts, counts_out, first_counts, offs, row_of_pair, pair_of_row,
+                     tok_offs, probs, coeff, mode, loss, F, P, Nl, token_model, model_tokens,
+                     pg_tok, pg_tiles, pg_ntiles);
   return hipGetLastError();
 }
 
