@@ -20,8 +20,11 @@
  *   - Storage dtype (dims.dtype) applies to x, y, dy, dx and all weight matrices; routing
  *     weights, probabilities, losses and all returned LoRA/router gradients are float32.
  *     All accumulation is float32.
- *   - Limits: 1 <= k <= N <= 64; N*r <= 512; r % 8 == 0; d % 8 == 0; d_ff % 8 == 0; T >= 1;
- *     T*k < 2^24.  Anything else returns MIXLORA_E_SHAPE.
+ *   - Limits: 1 <= k <= N <= 64; 1 <= r <= 64; N * (r rounded up to a multiple of 8) <= 512;
+ *     d % 8 == 0; d_ff % 8 == 0; T >= 1; T*k < 2^24.  Anything else returns MIXLORA_E_SHAPE.
+ *     A rank that is not a multiple of 8 (the rank study of Section 4.3 goes down to r = 2) runs
+ *     on zero-padded copies of the six LoRA banks kept in the workspace; the bank and gradient
+ *     arrays the caller passes keep their [N, r, .] / [N, ., r] shapes.
  */
 #ifndef MIXLORA_H
 #define MIXLORA_H
@@ -284,7 +287,8 @@ MIXLORA_API int mixlora_profile_kind(int32_t kind, double *ms_total, int32_t *la
  * Shapes (row-major, dtype = dims.dtype, device pointers, 16-byte aligned):
  *   x [T, d_in], W [d_out, d_in], A [r, d_in], B [d_out, r], y / dy [T, d_out], dx [T, d_in];
  *   dA [r, d_in], dB [d_out, r] float32, overwritten.
- * Limits: r % 8 == 0, 8 <= r <= 64, d_in % 8 == 0, d_out % 8 == 0, T < 2^24.
+ * Limits: 1 <= r <= 64 (ranks off the multiples of 8 run on zero-padded copies of A and B kept
+ * in the workspace), d_in % 8 == 0, d_out % 8 == 0, T < 2^24.
  * The workspace is the caller's; forward saves x A^T in it for the backward. */
 typedef struct {
   int32_t T, d_in, d_out, r;

@@ -47,7 +47,19 @@ struct Layout {
   // matrices, factors c = m / n and 1 / n (kept for the backward pass); backward partial sums
   size_t WA_g, WA_u, WA_d, AA, w2, c_g, c_u, c_d, ninv_g, ninv_u, ninv_d;
   size_t dm_part_g, dm_part_u, dmd_part;
+  // ranks that are not a multiple of 8 (Section 4.3's rank study goes down to r = 2): the six LoRA
+  // banks zero-padded to rp = 8 * ceil(r / 8) rank entries, and their fp32 gradients in that form
+  int rp;
+  size_t pad_w[6], pad_g[6];
 };
+
+inline int pad_rank(int r) { return (r + 7) & ~7; }
+
+// banks in the order A_gate, B_gate, A_up, B_up, A_down, B_down: elements of the rank-padded bank
+inline size_t bank_elems(int i, size_t N, size_t rp, size_t d, size_t f) {
+  const size_t width[6] = {d, f, d, f, f, d};
+  return N * rp * width[i];
+}
 
 // Buffers a schedule does not use get size 0 (per-token G, U in the unshared schedule, the
 // combined activations where the down projection runs per pair, ...).
@@ -56,11 +68,13 @@ Layout make_layout(const mixlora_dims &D, int schedule = MIXLORA_SCHEDULE_LINEAR
   Layout L{};
   const bool pair_down = schedule != MIXLORA_SCHEDULE_LINEAR_DOWN;
   const bool vanilla = schedule == MIXLORA_SCHEDULE_VANILLA;
-  const size_t T = D.T, d = D.d, f = D.d_ff, N = D.N, k = D.k, r = D.r;
+  const size_t T = D.T, d = D.d, f = D.d_ff, N = D.N, k = D.k, r = pad_rank(D.r);
   const size_t R = N * r, kT = k * T;
   const size_t E = D.dtype == MIXLORA_BF16 ? 2 : 4;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o = up(o + bytes); return at; };
+  L.rp = (int)r;
+  for (int i = 0; i < 6; i++) L.pad_w[i] = take((int)r != D.r ? bank_elems(i, N, r, d, f) * E : 0);
   L.probs = take(T * N * 4);
   L.Z = take(T * N * 4);
   L.idx = take(kT * 4);
@@ -142,6 +156,7 @@ Layout make_layout(const mixlora_dims &D, int schedule = MIXLORA_SCHEDULE_LINEAR
   L.dm_part_u = take(dora ? (size_t)fused_row_tiles((int)kT, (int)N) * f * 4 : 0);
   L.dmd_part = take(dora ? dm_down_part_floats((int)N, (int)d) * 4 : 0);
   L.Bx = take(d * (size_t)L.Kx * E);
+  for (int i = 0; i < 6; i++) L.pad_g[i] = take((int)r != D.r ? bank_elems(i, N, r, d, f) * 4 : 0);
   L.dz = take(T * N * 4);
   size_t pf = group_outer_partial_floats((int)N, (int)r, (int)f);
   size_t pd = group_outer_partial_floats((int)N, (int)r, (int)d);
@@ -162,10 +177,10 @@ int check_dims(const mixlora_dims *D) {
   if (D->dtype != MIXLORA_F32 && D->dtype != MIXLORA_BF16) return MIXLORA_E_DTYPE;
   if (D->aux_mode != MIXLORA_AUX_TOP1 && D->aux_mode != MIXLORA_AUX_TOPK) return MIXLORA_E_DTYPE;
   if (D->T < 1 || D->d < 8 || D->d_ff < 8 || D->N < 1 || D->N > 64 || D->k < 1 || D->k > D->N ||
-      D->r < 8)
+      D->r < 1)
     return MIXLORA_E_SHAPE;
-  if (D->r % 8 || D->d % 8 || D->d_ff % 8 || D->r > 64) return MIXLORA_E_SHAPE;
-  if ((int64_t)D->N * D->r > 512) return MIXLORA_E_SHAPE;
+  if (D->d % 8 || D->d_ff % 8 || D->r > 64) return MIXLORA_E_SHAPE;
+  if ((int64_t)D->N * pad_rank(D->r) > 512) return MIXLORA_E_SHAPE;
   if ((int64_t)D->T * D->k >= (1 << 24)) return MIXLORA_E_SHAPE;
   if ((int64_t)D->T * D->k * D->d_ff >= ((int64_t)1 << 40)) return MIXLORA_E_SHAPE;
   return MIXLORA_OK;
@@ -236,19 +251,46 @@ size_t mixlora_workspace_bytes(const mixlora_dims *dims, int for_backward) {
 
 // Forward pass on D.N experts in all, of which every adapter owns Nl consecutive ones
 // (token_model == NULL: one adapter).  Arguments are already validated.
-static int forward_impl(const mixlora_dims &D, int Nl, const int32_t *token_model,
+// Rank padding: bank i of the user's weights ([N, r, width] for the A banks, [N, width, r] for
+// the B banks) -> the same bank with rp rank entries, zeros in the added ones.  Zero rank entries
+// contribute nothing to any product of the pass, and their gradients come out zero.
+static RelayoutJob job_pad_bank(int i, const void *src, void *dst, int N, int r_src, int r_dst, int d, int f) {
+  const int width[6] = {d, f, d, f, f, d};
+  return job_rank_resize(src, dst, N, r_src, r_dst, width[i], /*rank_major=*/i == 0 || i == 2 || i == 4);
+}
+static hipError_t pad_weights(const Layout &L, char *ws, const mixlora_dims &Du, const mixlora_weights *w,
+                              mixlora_weights *wp, hipStream_t st) {
+  *wp = *w;
+  const void *src[6] = {w->A_gate, w->B_gate, w->A_up, w->B_up, w->A_down, w->B_down};
+  const void **dstp[6] = {&wp->A_gate, &wp->B_gate, &wp->A_up, &wp->B_up, &wp->A_down, &wp->B_down};
+  RelayoutJob jobs[6];
+  for (int i = 0; i < 6; i++) {
+    jobs[i] = job_pad_bank(i, src[i], ws + L.pad_w[i], Du.N, Du.r, L.rp, Du.d, Du.d_ff);
+    *dstp[i] = ws + L.pad_w[i];
+  }
+  return launch_relayout(Du.dtype, jobs, 6, st);
+}
+
+static int forward_impl(const mixlora_dims &Du, int Nl, const int32_t *token_model,
                         const mixlora_weights *w, const void *x, void *y, int32_t *topk_idx,
                         float *topk_w, int32_t *expert_counts, float *aux_loss, void *workspace,
                         size_t workspace_bytes, void *stream,
                         int schedule = MIXLORA_SCHEDULE_LINEAR_DOWN,
                         const mixlora_dora *dora = nullptr) {
-  const Layout L = make_layout(D, schedule, dora != nullptr);
+  const Layout L = make_layout(Du, schedule, dora != nullptr);
   const bool pair_down = schedule != MIXLORA_SCHEDULE_LINEAR_DOWN;   // down projection per pair
   const bool vanilla = schedule == MIXLORA_SCHEDULE_VANILLA;         // gate/up per pair as well
   if (workspace_bytes < L.fwd_end) return MIXLORA_E_WORKSPACE;
 
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   char *ws = reinterpret_cast<char *>(workspace);
+  mixlora_dims D = Du;   // the pass runs on the rank-padded banks
+  D.r = L.rp;
+  mixlora_weights wpad;
+  if (L.rp != Du.r) {
+    if (pad_weights(L, ws, Du, w, &wpad, st) != hipSuccess) return MIXLORA_E_HIP;
+    w = &wpad;
+  }
   const int T = D.T, d = D.d, f = D.d_ff, N = D.N, k = D.k, r = D.r, R = N * r, kT = k * T;
   const int dt = D.dtype;
   const double Eb = dt == MIXLORA_BF16 ? 2.0 : 4.0;   // bytes per stored element (measurement hook)
@@ -547,20 +589,37 @@ static int check_backward_args(const mixlora_dims *dims, const mixlora_weights *
 }
 
 // Backward pass; same conventions as forward_impl.
-static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_model,
+static int backward_impl(const mixlora_dims &Du, int Nl, const int32_t *token_model,
                          const AuxUpstream &d_aux, const mixlora_weights *w, const void *x,
                          const void *dy, void *workspace, size_t workspace_bytes, void *dx,
                          const mixlora_grads *grads, void *stream,
                          int schedule = MIXLORA_SCHEDULE_LINEAR_DOWN,
                          const mixlora_dora *dora = nullptr,
                          const mixlora_dora_grads *dgrads = nullptr) {
-  const Layout L = make_layout(D, schedule, dora != nullptr);
+  const Layout L = make_layout(Du, schedule, dora != nullptr);
   const bool pair_down = schedule != MIXLORA_SCHEDULE_LINEAR_DOWN;
   const bool vanilla = schedule == MIXLORA_SCHEDULE_VANILLA;
   if (workspace_bytes < L.bwd_end) return MIXLORA_E_WORKSPACE;
 
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   char *ws = reinterpret_cast<char *>(workspace);
+  mixlora_dims D = Du;   // rank-padded banks (the forward pass left them in the workspace) and
+  D.r = L.rp;            // rank-padded gradients, cut back to r entries at the end
+  mixlora_weights wpad;
+  mixlora_grads gpad;
+  const mixlora_grads *grads_user = grads;
+  if (L.rp != Du.r) {
+    wpad = *w;
+    gpad = *grads;
+    const void **wp[6] = {&wpad.A_gate, &wpad.B_gate, &wpad.A_up, &wpad.B_up, &wpad.A_down, &wpad.B_down};
+    float **gp[6] = {&gpad.dA_gate, &gpad.dB_gate, &gpad.dA_up, &gpad.dB_up, &gpad.dA_down, &gpad.dB_down};
+    for (int i = 0; i < 6; i++) {
+      *wp[i] = ws + L.pad_w[i];
+      *gp[i] = (float *)(ws + L.pad_g[i]);
+    }
+    w = &wpad;
+    grads = &gpad;
+  }
   const int T = D.T, d = D.d, f = D.d_ff, N = D.N, k = D.k, r = D.r, R = N * r, kT = k * T;
   const int dt = D.dtype, Kx = L.Kx;
   const double Eb = dt == MIXLORA_BF16 ? 2.0 : 4.0;   // bytes per stored element (measurement hook)
@@ -748,6 +807,14 @@ static int backward_impl(const mixlora_dims &D, int Nl, const int32_t *token_mod
     add_seg(p, ws + L.dusum, f, WuT, f, f);
     add_seg(p, ws + L.S, Kx, ws + L.Bx, Kx, Kx);
     HIP_TRY(launch_gemm(dt, &p, 1, st));
+  }
+  if (L.rp != Du.r) {
+    float *dst[6] = {grads_user->dA_gate, grads_user->dB_gate, grads_user->dA_up,
+                     grads_user->dB_up, grads_user->dA_down, grads_user->dB_down};
+    RelayoutJob jobs[6];
+    for (int i = 0; i < 6; i++)
+      jobs[i] = job_pad_bank(i, ws + L.pad_g[i], dst[i], N, L.rp, Du.r, d, f);
+    HIP_TRY_AS(PROF_OTHER, 0, launch_relayout(MIXLORA_F32, jobs, 6, st));
   }
   return MIXLORA_OK;
 }

@@ -270,6 +270,12 @@ RelayoutJob job_bank_cat(const void *bank, int N, int rows, int r, float scale, 
                          int ldo, int col0);
 // bank [N, rows, r] -> out[e*r + q, i]                                   (out is [N*r, rows])
 RelayoutJob job_bank_T(const void *bank, int N, int rows, int r, void *out);
+// A bank with another number of rank entries: [N, r_src, width] -> [N, r_dst, width] when
+// rank_major, else [N, width, r_src] -> [N, width, r_dst]; the first min(r_src, r_dst) entries are
+// copied, the rest (if any) are zeros.  Pads a bank to a whole multiple of 8 rank entries, or cuts
+// a padded gradient back.
+RelayoutJob job_rank_resize(const void *src, void *dst, int N, int r_src, int r_dst, int width,
+                            bool rank_major);
 // A [N, r, cols] -> out[c, col0 + e*r + q] = scale * A[e, q, c]
 RelayoutJob job_A_cat(const void *A, int N, int r, int cols, float scale, void *out, int ldo,
                       int col0);

@@ -682,6 +682,19 @@ RelayoutJob job_bank_T(const void *bank, int N, int rows, int r, void *out) {
   j.dst0 = 0; j.d0 = (int64_t)r * rows; j.d1 = rows;
   return j;
 }
+// [N, r_src, width] -> [N, r_dst, width] (rank_major) or [N, width, r_src] -> [N, width, r_dst]
+RelayoutJob job_rank_resize(const void *src, void *dst, int N, int r_src, int r_dst, int width,
+                            bool rank_major) {
+  RelayoutJob j{};
+  j.src = src; j.dst = dst; j.scale = 1.f;
+  j.n0 = N; j.n1 = width; j.n2 = r_dst;          // i2 walks the rank entries
+  j.valid2 = r_src < r_dst ? r_src : r_dst;
+  j.s0 = (int64_t)r_src * width;
+  j.d0 = (int64_t)r_dst * width;
+  if (rank_major) { j.s1 = 1; j.s2 = width; j.d1 = 1; j.d2 = width; }
+  else            { j.s1 = r_src; j.s2 = 1; j.d1 = r_dst; j.d2 = 1; }
+  return j;
+}
 // A [N, r, cols]  ->  out[c, col0 + e*r + q] = scale * A[e, q, c]
 RelayoutJob job_A_cat(const void *A, int N, int r, int cols, float scale, void *out, int ldo,
                       int col0) {

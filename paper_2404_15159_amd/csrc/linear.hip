@@ -13,7 +13,11 @@ constexpr size_t ALIGN = 256;
 inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
 
+inline int pad_rank(int r) { return (r + 7) & ~7; }
+
 struct LinLayout {
+  int rp;                         // rank entries the pass runs on: r rounded up to a multiple of 8
+  size_t padA, padB, padgA, padgB;   // zero-padded copies of A, B (kept for the backward) and of dA, dB
   size_t P, tok_offs, slices, fwd_end;
   size_t W_T, Bt, At, VB, VB_T, P_T, partials, bwd_end;
   size_t partial_floats;
@@ -22,10 +26,14 @@ struct LinLayout {
 
 LinLayout make_layout(const mixlora_linear_dims &D) {
   LinLayout L{};
-  const size_t T = D.T, di = D.d_in, dn = D.d_out, r = D.r;
+  const size_t T = D.T, di = D.d_in, dn = D.d_out, r = pad_rank(D.r);
   const size_t E = D.dtype == MIXLORA_BF16 ? 2 : 4;
+  const bool padded = (int)r != D.r;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o = up(o + bytes); return at; };
+  L.rp = (int)r;
+  L.padA = take(padded ? r * di * E : 0);
+  L.padB = take(padded ? dn * r * E : 0);
   L.P = take(T * r * 4);
   L.tok_offs = take(2 * 4);
   L.slices = take((size_t)(GEMM_MAX_PROBLEMS - 1) * T * r * 4);   // K-slice partial sums of a rank-r projection
@@ -46,6 +54,8 @@ LinLayout make_layout(const mixlora_linear_dims &D) {
     pf = v > pf ? v : pf;
   L.partial_floats = pf;
   L.partials = take(pf * 4);
+  L.padgA = take(padded ? r * di * 4 : 0);
+  L.padgB = take(padded ? dn * r * 4 : 0);
   L.bwd_end = o;
   return L;
 }
@@ -53,8 +63,8 @@ LinLayout make_layout(const mixlora_linear_dims &D) {
 int check_dims(const mixlora_linear_dims *D) {
   if (!D) return MIXLORA_E_NULL;
   if (D->dtype != MIXLORA_F32 && D->dtype != MIXLORA_BF16) return MIXLORA_E_DTYPE;
-  if (D->T < 1 || D->d_in < 8 || D->d_out < 8 || D->r < 8 || D->r > 64) return MIXLORA_E_SHAPE;
-  if (D->r % 8 || D->d_in % 8 || D->d_out % 8) return MIXLORA_E_SHAPE;
+  if (D->T < 1 || D->d_in < 8 || D->d_out < 8 || D->r < 1 || D->r > 64) return MIXLORA_E_SHAPE;
+  if (D->d_in % 8 || D->d_out % 8) return MIXLORA_E_SHAPE;
   if ((int64_t)D->T >= (1 << 24)) return MIXLORA_E_SHAPE;
   return MIXLORA_OK;
 }
@@ -127,11 +137,19 @@ int mixlora_lora_linear_forward(const mixlora_linear_dims *dims, const void *W, 
   if (!W || !A || !B || !x || !y || !workspace) return MIXLORA_E_NULL;
   for (const void *p : {W, A, B, x, (const void *)y, (const void *)workspace})
     if (misaligned(p)) return MIXLORA_E_ALIGN;
-  const mixlora_linear_dims &D = *dims;
+  mixlora_linear_dims D = *dims;
   const LinLayout L = make_layout(D);
   if (workspace_bytes < L.fwd_end) return MIXLORA_E_WORKSPACE;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   char *ws = reinterpret_cast<char *>(workspace);
+  if (L.rp != D.r) {   // run on zero-padded banks (they stay in the workspace for the backward)
+    const RelayoutJob jobs[2] = {job_rank_resize(A, ws + L.padA, 1, D.r, L.rp, D.d_in, true),
+                                 job_rank_resize(B, ws + L.padB, 1, D.r, L.rp, D.d_out, false)};
+    HIP_TRY(launch_relayout(D.dtype, jobs, 2, st));
+    A = ws + L.padA;
+    B = ws + L.padB;
+    D.r = L.rp;
+  }
   // y0 = x W^T and P = x A^T in one launch (both read x), then y = y0 + s P B^T in place
   const int grc = gemm_with_sliced_projection(D.dtype, D.T, D.d_out, D.r, D.d_in, x, W, y, A,
                                               (float *)(ws + L.P), (float *)(ws + L.slices), st);
@@ -157,7 +175,14 @@ int mixlora_lora_linear_backward(const mixlora_linear_dims *dims, const void *W,
   if (workspace_bytes < L.bwd_end) return MIXLORA_E_WORKSPACE;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   char *ws = reinterpret_cast<char *>(workspace);
-  const int T = D.T, di = D.d_in, dn = D.d_out, r = D.r, dt = D.dtype;
+  const int T = D.T, di = D.d_in, dn = D.d_out, r = L.rp, dt = D.dtype;
+  float *dA_user = dA, *dB_user = dB;
+  if (L.rp != D.r) {   // padded banks from the forward pass; padded gradients, cut back at the end
+    A = ws + L.padA;
+    B = ws + L.padB;
+    dA = (float *)(ws + L.padgA);
+    dB = (float *)(ws + L.padgB);
+  }
   const float s = D.lora_scale;
   if (!W_T) {
     HIP_TRY(launch_transpose(dt, W, ws + L.W_T, dn, di, st));
@@ -192,6 +217,11 @@ int mixlora_lora_linear_backward(const mixlora_linear_dims *dims, const void *W,
                                dA, part, L.partial_floats, st));
     HIP_TRY(launch_group_outer(dt, tok, 1, T, nullptr, 1, (const float *)(ws + L.P), r, dy, dn, s, 0,
                                dB, part, L.partial_floats, st));
+  }
+  if (L.rp != D.r) {
+    const RelayoutJob jobs[2] = {job_rank_resize(dA, dA_user, 1, L.rp, D.r, di, true),
+                                 job_rank_resize(dB, dB_user, 1, L.rp, D.r, dn, false)};
+    HIP_TRY(launch_relayout(MIXLORA_F32, jobs, 2, st));
   }
   return MIXLORA_OK;
 }

@@ -42,7 +42,10 @@ def test_workspace_bytes(lib):
     assert bwd > fwd
     assert bwd < 8 << 30
     assert B.mixlora_workspace_bytes(dims(T=8192), True) > bwd
-    for bad in (dict(k=0), dict(k=9), dict(N=65), dict(r=4), dict(r=12), dict(d=4100),
+    # ranks off the multiples of 8 run on zero-padded banks held in the workspace
+    assert B.mixlora_workspace_bytes(dims(r=2), True) > B.mixlora_workspace_bytes(dims(r=8), True)
+    assert B.mixlora_workspace_bytes(dims(r=12), False) > B.mixlora_workspace_bytes(dims(r=16), False)
+    for bad in (dict(k=0), dict(k=9), dict(N=65), dict(r=0), dict(r=65), dict(N=64, r=12), dict(d=4100),
                 dict(d_ff=11004), dict(T=0), dict(dtype=7), dict(aux_mode=3), dict(N=64, r=16),
                 dict(T=1 << 23, k=2)):
         assert B.mixlora_workspace_bytes(dims(**bad), True) == 0, bad
@@ -111,7 +114,7 @@ def test_backward_argument_errors(lib):
             B.mixlora_ffn_backward(d or dims(), w or fake_weights(), grads=grads, stream=0, **a)
         return ei.value.code
 
-    assert code(d=dims(r=7)) == -2
+    assert code(d=dims(r=0)) == -2
     assert code(dy=None) == -1
     assert code(grads=B.make_grads({n: FAKE for n in B.GRAD_FIELDS[:-1]})) == -1
     assert code(dx=FAKE + 2) == -4
@@ -164,7 +167,7 @@ def test_dora_entry_points(lib):
     assert ws > B.mixlora_schedule_workspace_bytes(d, B.SCHEDULE_SHARED, True)
     assert B.mixlora_dora_workspace_bytes(d, False) < ws
     assert B.mixlora_dora_workspace_bytes(dims(dtype=B.F32), True) == 0
-    assert B.mixlora_dora_workspace_bytes(dims(r=5), True) == 0
+    assert B.mixlora_dora_workspace_bytes(dims(r=65), True) == 0
     mags = B.make_dora({n: FAKE for n in B.DORA_FIELDS})
 
     def fcode(dd=d, dora=mags, **kw):
@@ -248,7 +251,7 @@ def test_lora_linear_argument_errors(lib):
 
     fwd, bwd = (B.mixlora_lora_linear_workspace_bytes(ld(), f) for f in (False, True))
     assert 4096 * 16 * 4 <= fwd < bwd
-    for bad in (dict(T=0), dict(r=4), dict(r=72), dict(r=12), dict(d_in=4100), dict(d_out=4), dict(dtype=3)):
+    for bad in (dict(T=0), dict(r=0), dict(r=72), dict(d_in=4100), dict(d_out=4), dict(dtype=3)):
         assert B.mixlora_lora_linear_workspace_bytes(ld(**bad), True) == 0, bad
 
     def fcode(d_, **kw):
@@ -258,7 +261,7 @@ def test_lora_linear_argument_errors(lib):
             B.mixlora_lora_linear_forward(d_, stream=0, **a)
         return ei.value.code
 
-    assert fcode(ld(r=20)) == -2
+    assert fcode(ld(r=65)) == -2
     assert fcode(ld(dtype=9)) == -3
     assert fcode(ld(), A=None) == -1
     assert fcode(ld(), x=FAKE + 4) == -4

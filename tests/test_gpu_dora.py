@@ -23,6 +23,8 @@ CASES = [
     ("top1", dict(T=200, d=128, d_ff=384, N=8, k=1, r=16)),
     ("few_tokens", dict(T=17, d=512, d_ff=704, N=8, k=2, r=16)),
     ("unused_expert", dict(T=260, d=128, d_ff=264, N=8, k=2, r=16)),
+    # the smallest rank of the rank study (Section 4.3), run on zero-padded banks
+    ("r2", dict(T=300, d=256, d_ff=688, N=8, k=2, r=2, alpha=4.0)),
 ]
 
 

@@ -91,6 +91,14 @@ SMALL_CASES = [
     ("bf16_scale_1p5", BASE_BF16, dict(T=300, d=256, d_ff=520, N=8, k=2, r=16, alpha=24.0)),
     ("bf16_scale_0p7", BASE_BF16, dict(T=257, d=136, d_ff=264, N=5, k=3, r=40, alpha=28.0)),
     ("f32_scale_1p3", BASE_F32, dict(T=333, d=72, d_ff=200, N=6, k=2, r=8, alpha=10.4)),
+    # ranks off the multiples of 8 (the rank study of Section 4.3 starts at r = 2), at the 7B
+    # model's d : d_ff ratio: the library runs them on zero-padded banks and cuts the gradients back
+    ("bf16_r2_7b_ratio", BASE_BF16, dict(T=300, d=256, d_ff=688, N=8, k=2, r=2, alpha=4.0)),
+    ("bf16_r4_7b_ratio", BASE_BF16, dict(T=300, d=256, d_ff=688, N=8, k=2, r=4, alpha=8.0)),
+    ("bf16_r1_decode", BASE_BF16, dict(T=33, d=128, d_ff=344, N=8, k=2, r=1, alpha=2.0)),
+    ("bf16_r12_top3", BASE_BF16, dict(T=257, d=136, d_ff=264, N=5, k=3, r=12, alpha=24.0)),
+    ("bf16_r20_long", BASE_BF16, dict(T=4200, d=64, d_ff=136, N=8, k=2, r=20, alpha=40.0)),
+    ("f32_r7", BASE_F32, dict(T=129, d=64, d_ff=136, N=8, k=2, r=7, alpha=14.0)),
     # top-1 with nearly balanced first-slot counts: the router is trained by the auxiliary term
     # alone, p * (F_e - <p, F>) with every F_e within a percent of 1/N
     ("f32_top1_balanced_aux", BASE_F32, dict(T=2049, d=128, d_ff=1032, N=3, k=1, r=16, alpha=32.0)),

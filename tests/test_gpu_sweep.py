@@ -37,8 +37,9 @@ def _draw(rng, ci):
     kind = KINDS[ci % len(KINDS)]
     N = int(rng.choice([1, 2, 3, 4, 5, 6, 8, 12, 16, 24, 32]))
     k = int(rng.integers(1, min(N, 4) + 1))
-    r = int(rng.choice([8, 16, 24, 32, 40, 64]))
-    if N * r > 512:
+    r = int(rng.choice([1, 2, 4, 8, 12, 16, 24, 32, 40, 64]))
+    rp = (r + 7) // 8 * 8   # the library's limit counts rank entries after padding to 8
+    if N * rp > 512:
         r = 8
     T = int(rng.choice([1, 2, 7, 33, 64, 65, 127, 128, 129, 200, 255, 256, 257, 511, 700, 1025, 2049]))
     d = int(rng.choice([8, 16, 24, 64, 72, 128, 136, 192, 256, 264, 320, 512]))
@@ -46,7 +47,7 @@ def _draw(rng, ci):
     M = 1
     if kind == "multi":
         M = int(rng.choice([2, 3]))
-        if M * N > 64 or M * N * r > 512:
+        if M * N > 64 or M * N * ((r + 7) // 8 * 8) > 512:
             N, r, k = 4, 8, min(k, 4)
     return kind, dict(T=T, d=d, d_ff=f, N=N, k=k, r=r, alpha=2.0 * r, M=M, seq_len=max(1, T // 7))
 
