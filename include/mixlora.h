@@ -191,12 +191,19 @@ MIXLORA_API int mixlora_ffn_backward_schedule(const mixlora_dims *dims, int32_t 
  * With m_e = n_e the block equals the plain MixLoRA block.
  *   m_gate, m_up [N, d_ff], m_down [N, d]: device float32, 16-byte aligned.
  *   dm_*: gradients of the magnitudes, same shapes, float32, overwritten.
+ * shared != 0 selects the other reading the paper's tables allow (the "# Params" columns of
+ * the rank study, Section 4.3, and of the main results are the same for MixLoRA and MixDoRA,
+ * which a magnitude per expert would raise by 0.10 points on LLaMA-2 7B and one per projection
+ * by 0.02): ONE magnitude vector per projection used by every expert, m_e = m.  Then m_gate,
+ * m_up are [d_ff], m_down is [d], and dm_* have those shapes and hold the sum over the experts
+ * (added in ascending expert order).  shared must be 0 or 1 (MIXLORA_E_SHAPE otherwise).
  * bf16 storage only (MIXLORA_E_DTYPE otherwise).  The frozen gate / up products stay shared
  * across experts; the down projection runs per routed pair (its factor depends on the expert).
  * Other arguments, outputs, workspace rules and errors as in mixlora_ffn_forward / _backward;
  * the backward call needs the workspace of a mixlora_dora_forward call with the same inputs.  */
 typedef struct {
   const float *m_gate, *m_up, *m_down;
+  int32_t shared;
 } mixlora_dora;
 typedef struct {
   float *dm_gate, *dm_up, *dm_down;

@@ -319,11 +319,21 @@ def dora_row_norms(W, e, s):
     return out
 
 
+def dora_magnitude(mag, nm, e):
+    """Magnitude vector of projection nm for expert e.  Two readings of the variant (the paper
+    prints no formula): a magnitude per expert, arrays [N, out]; or ONE magnitude per projection
+    used by every expert, m_e = m, arrays [out] - the reading under which the "# Params" columns of
+    the rank study and of the main results stay the same for MixLoRA and MixDoRA."""
+    m = _f64(mag["m_" + nm])
+    return m[e] if m.ndim == 2 else m
+
+
 def dora_expert_forward(xe, W, mag, e, s):
     """One weight-decomposed expert on rows xe [n,d]: every projection's output feature j is
-    (m_e[j] / n_e[j]) * ((W + s B_e A_e) x)[j].  mag: dict m_gate/m_up [N,f], m_down [N,d]."""
+    (m_e[j] / n_e[j]) * ((W + s B_e A_e) x)[j].  mag: dict m_gate/m_up [N,f], m_down [N,d], or
+    [f], [f], [d] for magnitudes shared by the experts."""
     n = dora_row_norms(W, e, s)
-    cg, cu, cd = (_f64(mag["m_" + nm][e]) / n[nm] for nm in ("gate", "up", "down"))
+    cg, cu, cd = (dora_magnitude(mag, nm, e) / n[nm] for nm in ("gate", "up", "down"))
     pg = xe @ W["A_gate"][e].T
     pu = xe @ W["A_up"][e].T
     vg = xe @ W["W_gate"].T + s * (pg @ W["B_gate"][e].T)
@@ -369,7 +379,8 @@ def dora_forward(x, W, mag, k, lora_scale, aux_coeff=0.01, aux_mode="top1", keep
 def dora_backward(x, W, mag, k, lora_scale, dy, d_aux=1.0, aux_coeff=0.01, aux_mode="top1"):
     """Gradients of <y, dy> + d_aux * L_aux for the weight-decomposed block: base matrices
     frozen, the row norms n_e held constant (no gradient flows through them), gradients for
-    A, B, the magnitudes (dm_gate/dm_up [N,f], dm_down [N,d]), W_router and x."""
+    A, B, the magnitudes (dm_gate/dm_up [N,f], dm_down [N,d]; with shared magnitudes [f], [f],
+    [d]: every expert's term lands on the same vector, so the terms add up), W_router and x."""
     x = _f64(x)
     dy = _f64(dy)
     W = {n: _f64(v) for n, v in W.items()}
@@ -389,7 +400,12 @@ def dora_backward(x, W, mag, k, lora_scale, dy, d_aux=1.0, aux_coeff=0.01, aux_m
         dw[tok, slot] = (dye * sv["o"]).sum(axis=1)
         do = w[tok, slot][:, None] * dye
         # o = cd * vd,  cd = m_down / n_down
-        dm["m_down"][e] = (do * sv["vd"]).sum(axis=0) / sv["n"]["down"]
+        def add_dm(nm, term):   # per expert: row e; shared: the one vector
+            if dm["m_" + nm].ndim == 2:
+                dm["m_" + nm][e] = term
+            else:
+                dm["m_" + nm] += term
+        add_dm("down", (do * sv["vd"]).sum(axis=0) / sv["n"]["down"])
         dvd = do * sv["cd"]
         G["B_down"][e] = s * (dvd.T @ sv["q"])
         v = dvd @ W["B_down"][e]
@@ -399,8 +415,8 @@ def dora_backward(x, W, mag, k, lora_scale, dy, d_aux=1.0, aux_coeff=0.01, aux_m
         sg = sigmoid(g)
         dg = da * u * sg * (1.0 + g * (1.0 - sg))
         du = da * g * sg
-        dm["m_gate"][e] = (dg * sv["vg"]).sum(axis=0) / sv["n"]["gate"]
-        dm["m_up"][e] = (du * sv["vu"]).sum(axis=0) / sv["n"]["up"]
+        add_dm("gate", (dg * sv["vg"]).sum(axis=0) / sv["n"]["gate"])
+        add_dm("up", (du * sv["vu"]).sum(axis=0) / sv["n"]["up"])
         dvg, dvu = dg * sv["cg"], du * sv["cu"]
         G["B_gate"][e] = s * (dvg.T @ sv["pg"])
         tg = dvg @ W["B_gate"][e]

@@ -66,7 +66,7 @@ DORA_GRAD_FIELDS = ("dm_gate", "dm_up", "dm_down")
 
 
 class Dora(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in DORA_FIELDS]
+    _fields_ = [(n, C.c_void_p) for n in DORA_FIELDS] + [("shared", C.c_int32)]
 
 
 class DoraGrads(C.Structure):
@@ -254,10 +254,12 @@ def mixlora_ffn_backward_schedule(dims: Dims, schedule: int, weights: Weights, x
         raise MixLoraError("mixlora_ffn_backward_schedule", rc)
 
 
-def make_dora(tensors: Dict[str, object]) -> Dora:
+def make_dora(tensors: Dict[str, object], shared: bool = False) -> Dora:
+    """shared: one magnitude vector per projection ([d_ff], [d_ff], [d]) used by every expert."""
     d = Dora()
     for n in DORA_FIELDS:
         setattr(d, n, _ptr(tensors.get(n)))
+    d.shared = int(shared)
     return d
 
 

@@ -348,13 +348,13 @@ static int forward_impl(const mixlora_dims &Du, int Nl, const int32_t *token_mod
     const size_t gpf = gram_part_floats(N, r);
     HIP_TRY_AS(PROF_OTHER, 0, launch_gram(w->A_up, N, r, d, AA + gpf, st));
     HIP_TRY_AS(PROF_OTHER, 0, launch_gram(w->A_down, N, r, f, AA + 2 * gpf, st));
-    HIP_TRY_AS(PROF_OTHER, 0, launch_dora_scale(w->B_gate, (float *)(ws + L.WA_g), AA, w2, dora->m_gate, N, f, r,
+    HIP_TRY_AS(PROF_OTHER, 0, launch_dora_scale(w->B_gate, (float *)(ws + L.WA_g), AA, w2, dora->m_gate, dora->shared, N, f, r,
                               D.lora_scale, (float *)(ws + L.c_g), (float *)(ws + L.ninv_g), st));
     HIP_TRY_AS(PROF_OTHER, 0, launch_dora_scale(w->B_up, (float *)(ws + L.WA_u), AA + gpf, w2 + f,
-                              dora->m_up, N, f, r, D.lora_scale, (float *)(ws + L.c_u),
+                              dora->m_up, dora->shared, N, f, r, D.lora_scale, (float *)(ws + L.c_u),
                               (float *)(ws + L.ninv_u), st));
     HIP_TRY_AS(PROF_OTHER, 0, launch_dora_scale(w->B_down, (float *)(ws + L.WA_d), AA + 2 * gpf, w2 + 2 * (size_t)f,
-                              dora->m_down, N, d, r, D.lora_scale, (float *)(ws + L.c_d),
+                              dora->m_down, dora->shared, N, d, r, D.lora_scale, (float *)(ws + L.c_d),
                               (float *)(ws + L.ninv_d), st));
     dargs.cg = (float *)(ws + L.c_g);
     dargs.cu = (float *)(ws + L.c_u);
@@ -788,9 +788,9 @@ static int backward_impl(const mixlora_dims &Du, int Nl, const int32_t *token_mo
     // unscaled projection output); gate / up sums come from the fused stage per row tile
     HIP_TRY_AS(PROF_OTHER, 0, launch_dm_tiles_reduce(offs, N, f, (float *)(ws + L.dm_part_g),
                                    (float *)(ws + L.dm_part_u), (float *)(ws + L.ninv_g),
-                                   (float *)(ws + L.ninv_u), dgrads->dm_gate, dgrads->dm_up, st));
+                                   (float *)(ws + L.ninv_u), dgrads->dm_gate, dgrads->dm_up, dora->shared, st));
     HIP_TRY_AS(PROF_OTHER, 0, launch_dm_down(pc, d, dy, ws + L.Op, (float *)(ws + L.ninv_d),
-                           (float *)(ws + L.dmd_part), dgrads->dm_down, st));
+                           (float *)(ws + L.dmd_part), dgrads->dm_down, dora->shared, st));
   }
   if (vanilla) {
     // unshared schedule: every pair row goes through W_gate^T / W_up^T on its own, the k rows of
@@ -891,6 +891,7 @@ int mixlora_ffn_backward_schedule(const mixlora_dims *dims, int32_t schedule,
 static int check_dora(const mixlora_dims *dims, const mixlora_dora *dora) {
   if (!dims || !dora) return MIXLORA_E_NULL;
   if (dims->dtype != MIXLORA_BF16) return MIXLORA_E_DTYPE;
+  if (dora->shared != 0 && dora->shared != 1) return MIXLORA_E_SHAPE;
   const float *req[] = {dora->m_gate, dora->m_up, dora->m_down};
   for (const float *p : req) {
     if (!p) return MIXLORA_E_NULL;

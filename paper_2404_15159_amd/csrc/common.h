@@ -340,8 +340,8 @@ size_t gram_part_floats(int N, int r);   // floats of one bank's Gram slice sums
 hipError_t launch_gram(const void *A_bank, int N, int r, int in, float *part, hipStream_t st);
 // c = m / n, ninv = 1 / n with n the row norms of W + s B_e A_e (from w2, WA = W A_cat^T, AA)
 hipError_t launch_dora_scale(const void *B_bank, const float *WA, const float *AA, const float *w2,
-                             const float *m, int N, int out, int r, float s, float *c, float *ninv,
-                             hipStream_t st);
+                             const float *m, int shared, int N, int out, int r, float s, float *c,
+                             float *ninv, hipStream_t st);
 hipError_t launch_scale_bank(void *bank, const float *c, int N, int r, int d, hipStream_t st);
 hipError_t launch_gather_rows_scaled(const PairCtx &pc, int width, const void *src, const float *c,
                                      void *dst, hipStream_t st);
@@ -349,9 +349,9 @@ hipError_t launch_pair_combine_scaled(const PairCtx &pc, int width, const void *
                                       const float *c, void *out, hipStream_t st);
 size_t dm_down_part_floats(int N, int d);
 hipError_t launch_dm_down(const PairCtx &pc, int d, const void *dy, const void *v, const float *ninv,
-                          float *part, float *dm, hipStream_t st);
+                          float *part, float *dm, int shared, hipStream_t st);
 hipError_t launch_dm_tiles_reduce(const int32_t *offs, int N, int f, const float *part_g,
                                   const float *part_u, const float *ninv_g, const float *ninv_u,
-                                  float *dm_g, float *dm_u, hipStream_t st);
+                                  float *dm_g, float *dm_u, int shared, hipStream_t st);
 
 }  // namespace mixlora

@@ -86,12 +86,14 @@ hipError_t launch_gram(const void *A_bank, int N, int r, int in, float *part, hi
 
 // ---- c[e, j] = m[e, j] / n_e[j],  ninv[e, j] = 1 / n_e[j] ----------------------------------------
 // B bank [N, out, r] bf16; WA [out, N*r] float32; AA: the Gram kernel's slice sums
-// [GRAM_SLICES][N][r][r]; w2 [out]; m, c, ninv [N, out].
+// [GRAM_SLICES][N][r][r]; w2 [out]; c, ninv [N, out]; m [N, out] (m_stride = out) or one [out]
+// vector shared by the experts (m_stride = 0).
 __global__ __launch_bounds__(256) void dora_scale_kernel(const bf16_t *__restrict__ B,
                                                          const float *__restrict__ WA,
                                                          const float *__restrict__ AA,
                                                          const float *__restrict__ w2,
-                                                         const float *__restrict__ m, int N, int out,
+                                                         const float *__restrict__ m,
+                                                         int64_t m_stride, int N, int out,
                                                          int r, float s, float *__restrict__ c,
                                                          float *__restrict__ ninv) {
   __shared__ float aa[64 * 64];
@@ -117,14 +119,15 @@ __global__ __launch_bounds__(256) void dora_scale_kernel(const bf16_t *__restric
   const float n2 = w2[j] + 2.f * s * cross + s * s * quad;
   const float inv = n2 > 0.f ? 1.f / sqrtf(n2) : 0.f;
   ninv[(int64_t)e * out + j] = inv;
-  c[(int64_t)e * out + j] = m[(int64_t)e * out + j] * inv;
+  c[(int64_t)e * out + j] = m[e * m_stride + j] * inv;
 }
 
 hipError_t launch_dora_scale(const void *B_bank, const float *WA, const float *AA, const float *w2,
-                             const float *m, int N, int out, int r, float s, float *c, float *ninv,
-                             hipStream_t st) {
+                             const float *m, int shared, int N, int out, int r, float s, float *c,
+                             float *ninv, hipStream_t st) {
   hipLaunchKernelGGL(dora_scale_kernel, dim3((out + 255) / 256, N), dim3(256), 0, st,
-                     (const bf16_t *)B_bank, WA, AA, w2, m, N, out, r, s, c, ninv);
+                     (const bf16_t *)B_bank, WA, AA, w2, m, (int64_t)(shared ? 0 : out), N, out, r, s,
+                     c, ninv);
   return hipGetLastError();
 }
 
@@ -233,55 +236,69 @@ __global__ __launch_bounds__(256) void dm_down_part_kernel(PairCtx pc, int d,
   for (int i = 0; i < 8; i++) o[i] = acc[i];
 }
 
+// per expert: dm [N, d]; shared magnitude: dm [d] = sum over the experts in ascending order
 __global__ void dm_down_reduce_kernel(const float *__restrict__ part, const float *__restrict__ ninv,
-                                      int64_t n, float *__restrict__ dm) {
+                                      int N, int d, int shared, float *__restrict__ dm) {
+  const int64_t n = (int64_t)N * d;
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  float acc = 0.f;
-  for (int sl = 0; sl < DMD_SLICES; sl++) acc += part[(int64_t)sl * n + i];
-  dm[i] = acc * ninv[i];
+  if (i >= (shared ? d : n)) return;
+  float tot = 0.f;
+  for (int e = 0; e < (shared ? N : 1); e++) {
+    const int64_t o = i + (int64_t)e * d;
+    float acc = 0.f;
+    for (int sl = 0; sl < DMD_SLICES; sl++) acc += part[(int64_t)sl * n + o];
+    tot += acc * ninv[o];
+  }
+  dm[i] = tot;
 }
 
 size_t dm_down_part_floats(int N, int d) { return (size_t)DMD_SLICES * N * d; }
 
 hipError_t launch_dm_down(const PairCtx &pc, int d, const void *dy, const void *v, const float *ninv,
-                          float *part, float *dm, hipStream_t st) {
+                          float *part, float *dm, int shared, hipStream_t st) {
   hipLaunchKernelGGL(dm_down_part_kernel, dim3((d / 8 + 255) / 256, pc.N, DMD_SLICES), dim3(256), 0,
                      st, pc, d, (const bf16_t *)dy, (const bf16_t *)v, part);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const int64_t n = (int64_t)pc.N * d;
+  const int64_t n = shared ? (int64_t)d : (int64_t)pc.N * d;
   hipLaunchKernelGGL(dm_down_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, part,
-                     ninv, n, dm);
+                     ninv, pc.N, d, shared, dm);
   return hipGetLastError();
 }
 
 // ---- magnitude gradients of gate / up from the fused stage's per-tile sums -----------------------
 // dm[e, c] = ninv[e, c] * sum over the row tiles of expert e (ascending) of part[tile][c];
 // blockIdx.z picks gate (0) or up (1).  The tiles of an expert are consecutive, 32 rows each.
+// With a magnitude shared by the experts (grid y = 1, N experts walked here) dm[c] is the sum of
+// the experts' terms in ascending order.
 __global__ __launch_bounds__(256) void dm_tiles_reduce_kernel(
-    const int32_t *__restrict__ offs, int f, const float *__restrict__ part_g,
+    const int32_t *__restrict__ offs, int f, int N, int shared, const float *__restrict__ part_g,
     const float *__restrict__ part_u, const float *__restrict__ ninv_g,
     const float *__restrict__ ninv_u, float *__restrict__ dm_g, float *__restrict__ dm_u) {
-  const int e = blockIdx.y;
   const int c = blockIdx.x * 256 + threadIdx.x;
   if (c >= f) return;
-  int tile0 = 0;
-  for (int q = 0; q < e; q++) tile0 += (offs[q + 1] - offs[q] + 31) / 32;
-  const int nt = (offs[e + 1] - offs[e] + 31) / 32;
   const float *part = blockIdx.z ? part_u : part_g;
-  float acc = 0.f;
-  for (int t = 0; t < nt; t++) acc += part[(int64_t)(tile0 + t) * f + c];
   const float *ninv = blockIdx.z ? ninv_u : ninv_g;
   float *dm = blockIdx.z ? dm_u : dm_g;
-  dm[(int64_t)e * f + c] = acc * ninv[(int64_t)e * f + c];
+  const int e_lo = shared ? 0 : blockIdx.y, e_hi = shared ? N : blockIdx.y + 1;
+  int tile0 = 0;
+  for (int q = 0; q < e_lo; q++) tile0 += (offs[q + 1] - offs[q] + 31) / 32;
+  float tot = 0.f;
+  for (int e = e_lo; e < e_hi; e++) {
+    const int nt = (offs[e + 1] - offs[e] + 31) / 32;
+    float acc = 0.f;
+    for (int t = 0; t < nt; t++) acc += part[(int64_t)(tile0 + t) * f + c];
+    tile0 += nt;
+    tot += acc * ninv[(int64_t)e * f + c];
+  }
+  dm[shared ? c : (int64_t)e_lo * f + c] = tot;
 }
 
 hipError_t launch_dm_tiles_reduce(const int32_t *offs, int N, int f, const float *part_g,
                                   const float *part_u, const float *ninv_g, const float *ninv_u,
-                                  float *dm_g, float *dm_u, hipStream_t st) {
-  hipLaunchKernelGGL(dm_tiles_reduce_kernel, dim3((f + 255) / 256, N, 2), dim3(256), 0, st, offs, f,
-                     part_g, part_u, ninv_g, ninv_u, dm_g, dm_u);
+                                  float *dm_g, float *dm_u, int shared, hipStream_t st) {
+  hipLaunchKernelGGL(dm_tiles_reduce_kernel, dim3((f + 255) / 256, shared ? 1 : N, 2), dim3(256), 0,
+                     st, offs, f, N, shared, part_g, part_u, ninv_g, ninv_u, dm_g, dm_u);
   return hipGetLastError();
 }
 

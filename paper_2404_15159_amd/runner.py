@@ -65,7 +65,8 @@ class MixLoraFFN:
         if magnitudes is not None:
             self.mag = {n: torch.from_numpy(np.ascontiguousarray(magnitudes[n], dtype=np.float32)).to(self.dev)
                         for n in B.DORA_FIELDS}
-            self.dora = B.make_dora(self.mag)
+            # 1-D magnitude vectors: one per projection, shared by the experts
+            self.dora = B.make_dora(self.mag, shared=self.mag["m_gate"].dim() == 1)
             self.ws_bytes = B.mixlora_dora_workspace_bytes(self.dims, with_backward)
         elif self.schedule != B.SCHEDULE_LINEAR_DOWN:
             self.ws_bytes = B.mixlora_schedule_workspace_bytes(self.dims, self.schedule, with_backward)

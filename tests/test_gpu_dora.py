@@ -70,6 +70,34 @@ def test_dora_matches_oracle(name, over):
     assert rep["routing_mismatch_tokens"] <= max(2, cfg.T // 50)
 
 
+@pytest.mark.parametrize("name,over", [CASES[0], CASES[1], CASES[-1]], ids=["ragged", "multi_tile", "r2"])
+def test_shared_magnitudes_match_oracle(name, over):
+    """The other reading of the variant: one magnitude vector per projection used by every expert
+    (shared = 1; m_* and dm_* are [d_ff], [d_ff], [d], dm the sum over the experts)."""
+    cfg, host, W, mag_e = _inputs(name, over, seed=3)
+    mag = {n: np.ascontiguousarray(v.mean(axis=0)) for n, v in mag_e.items()}
+    print(f"\ncase shared {cfg.name}: T={cfg.T} d={cfg.d} f={cfg.d_ff} N={cfg.N} k={cfg.k} r={cfg.r}", flush=True)
+    m = MixLoraFFN(cfg, host, magnitudes=mag)
+    assert m.dora.shared == 1
+    m.forward()
+    m.backward(d_aux=0.5)
+    res = m.results()
+    bw = orc.dora_backward(host["x"], W, mag, cfg.k, cfg.lora_scale, host["dy"], 0.5, cfg.aux_coeff,
+                           "top1")
+    rep = pu.compare_all(res, bw["forward"], bw, cfg)
+    for n in MAG:
+        assert res["d" + n].shape == mag[n].shape
+        pu.assert_close("d" + n, res["d" + n], bw["d" + n], pu.TOL["bf16"])
+    assert rep["routing_mismatch_tokens"] <= max(2, cfg.T // 50)
+    # bad flag value: rejected on the host
+    bad = B.make_dora(m.mag)
+    bad.shared = 2
+    with pytest.raises(B.MixLoraError) as ei:
+        B.mixlora_dora_forward(m.dims, m.weights, bad, m.t["x"], m.y, m.topk_idx, m.topk_w,
+                               m.counts, m.aux, m.workspace, m.ws_bytes)
+    assert ei.value.code == -2
+
+
 def test_magnitude_equal_to_norm_reproduces_the_lora_block():
     """m = n makes every factor 1 (up to float32 rounding of the norm): y, dx and the LoRA
     gradients must agree with the plain block's entry points to the bf16 bar."""

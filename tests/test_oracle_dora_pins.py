@@ -10,7 +10,13 @@ constant in the backward pass.  Pinned against things other than itself:
   * torch autograd of an independent formulation with the norm detached (all gradients);
   * finite differences of the forward for the gradients that do not pass through the norm
     (magnitudes and x).
+The second reading (one magnitude per projection shared by the experts) is pinned by torch
+autograd with ONE magnitude tensor feeding every expert's merged weights, by finite differences on
+that vector, and by the paper's "# Params" columns, which it fits and a magnitude per expert
+does not.
 """
+import math
+import os
 import numpy as np
 import torch
 
@@ -88,7 +94,8 @@ def _torch_block(tt, mag_t, cfg, s, detach=True):
             n = torch.linalg.norm(V, dim=1)
             if detach:
                 n = n.detach()
-            merged.append((mag_t["m_" + nm][e] / n)[:, None] * V)
+            m = mag_t["m_" + nm]
+            merged.append(((m[e] if m.dim() == 2 else m) / n)[:, None] * V)
         oe = lin(torch.nn.functional.silu(lin(x, merged[0])) * lin(x, merged[1]), merged[2])
         for j in range(cfg.k):
             y = y + (idx[:, j] == e).to(x.dtype)[:, None] * w[:, j:j + 1] * oe
@@ -183,3 +190,104 @@ def test_finite_differences_for_magnitudes_and_x():
             vals.append(loss(x2, mag))
         fd = (vals[0] - vals[1]) / (2 * h)
         assert abs(fd - g["dx"][i]) <= 2e-6 * max(1.0, abs(fd)), (i, fd, g["dx"][i])
+
+
+# ---- the reading with one magnitude per projection, shared by the experts ------------------------
+def _shared_mag(cfg, seed=0):
+    rng = np.random.default_rng(300 + seed)
+    return {"m_gate": rng.uniform(0.5, 1.5, cfg.d_ff), "m_up": rng.uniform(0.5, 1.5, cfg.d_ff),
+            "m_down": rng.uniform(0.5, 1.5, cfg.d)}
+
+
+def test_shared_magnitudes_against_autograd_of_one_tensor():
+    """One magnitude tensor per projection enters every expert's merged weight in the torch
+    formulation; autograd adds up the experts' contributions by itself."""
+    cfg, t, W, _ = _case(seed=6, T=32, N=6)
+    mag = _shared_mag(cfg)
+    s, a, d_aux = cfg.lora_scale, 0.03, 0.9
+    frozen = ("W_gate", "W_up", "W_down", "dy")
+    tt = {n: torch.tensor(t[n], requires_grad=(n not in frozen)) for n in list(WNAMES) + ["x", "dy"]}
+    mt = {n: torch.tensor(v, requires_grad=True) for n, v in mag.items()}
+    y, p, idx = _torch_block(tt, mt, cfg, s, detach=True)
+    F = torch.bincount(idx[:, 0], minlength=cfg.N).to(torch.float64) / cfg.T
+    aux = a * cfg.N * (F * p.mean(dim=0)).sum()
+    ((y * tt["dy"]).sum() + d_aux * aux).backward()
+    fw = orc.dora_forward(t["x"], W, mag, cfg.k, s, a)
+    np.testing.assert_allclose(fw["y"], y.detach().numpy(), rtol=1e-11, atol=1e-13)
+    g = orc.dora_backward(t["x"], W, mag, cfg.k, s, t["dy"], d_aux, a, "top1")
+    for name in MNAMES:
+        ref = mt[name].grad.numpy()
+        assert g["d" + name].shape == ref.shape == mag[name].shape
+        np.testing.assert_allclose(g["d" + name], ref, rtol=1e-9,
+                                   atol=1e-12 * max(1.0, np.abs(ref).max()), err_msg=name)
+    for name in ("x", "A_gate", "B_gate", "A_up", "B_up", "A_down", "B_down", "W_router"):
+        ref = tt[name].grad.numpy()
+        np.testing.assert_allclose(g["d" + name], ref, rtol=1e-9,
+                                   atol=1e-12 * max(1.0, np.abs(ref).max()), err_msg=name)
+
+
+def test_shared_magnitudes_are_the_per_expert_block_with_equal_rows():
+    """m_e = m for every e: same outputs, and the shared gradient is the sum over the experts of
+    the per-expert reading's gradients (an expert no token keeps contributes zero)."""
+    cfg, t, W, _ = _case(seed=7)
+    mag = _shared_mag(cfg, 1)
+    tiled = {n: np.tile(v, (cfg.N, 1)) for n, v in mag.items()}
+    a = orc.dora_backward(t["x"], W, mag, cfg.k, cfg.lora_scale, t["dy"], 0.4, 0.02)
+    b = orc.dora_backward(t["x"], W, tiled, cfg.k, cfg.lora_scale, t["dy"], 0.4, 0.02)
+    np.testing.assert_allclose(a["forward"]["y"], b["forward"]["y"], rtol=1e-13, atol=1e-15)
+    for n in MNAMES:
+        np.testing.assert_allclose(a["d" + n], b["d" + n].sum(axis=0), rtol=1e-12, atol=1e-14)
+    for n in ("dx", "dA_gate", "dB_down", "dW_router"):
+        np.testing.assert_allclose(a[n], b[n], rtol=1e-12, atol=1e-14)
+
+
+def test_shared_magnitude_finite_differences():
+    cfg, t, W, _ = _case(seed=8)
+    mag = _shared_mag(cfg, 2)
+    s, coeff, d_aux = cfg.lora_scale, 0.02, 0.6
+
+    def loss(mg):
+        fw = orc.dora_forward(t["x"], W, mg, cfg.k, s, coeff)
+        return float((fw["y"] * t["dy"]).sum()) + d_aux * fw["aux_loss"]
+
+    g = orc.dora_backward(t["x"], W, mag, cfg.k, s, t["dy"], d_aux, coeff)
+    rng = np.random.default_rng(11)
+    h = 1e-6
+    for name in MNAMES:
+        for _ in range(6):
+            i = int(rng.integers(0, mag[name].shape[0]))
+            vals = []
+            for sgn in (1, -1):
+                m2 = {n: v.copy() for n, v in mag.items()}
+                m2[name][i] += sgn * h
+                vals.append(loss(m2))
+            fd = (vals[0] - vals[1]) / (2 * h)
+            assert abs(fd - g["d" + name][i]) <= 2e-6 * max(1.0, abs(fd)), (name, i, fd)
+
+
+def test_params_columns_fit_shared_magnitudes_only():
+    """The paper's tables print the same trainable share for MixLoRA and MixDoRA (rank study:
+    0.38 / 0.74 / 1.46 / 2.91 / 5.80 % for both; main results: 2.9 % for both on LLaMA-2 7B).
+    Magnitudes per expert would add 32 * 8 * (2 * 11008 + 4096) = 6.7 M parameters, +0.10 points at
+    every rank (3.0 % in the main table); one magnitude per projection adds 0.8 M, +0.01 points."""
+    here = os.path.dirname(os.path.abspath(__file__))
+    printed = {}
+    for line in open(os.path.join(here, "golden", "paper_structure.txt")):
+        f = line.split()
+        if f and f[0] in ("params_pct_rank", "params_pct_rank_mixdora"):
+            printed[(f[0], int(f[1]))] = float(f[2])
+    L, d, f, V, N = 32, 4096, 11008, 32000, 8
+    base = L * (4 * d * d + 3 * d * f + 2 * d) + 2 * V * d + d
+    attn_m = L * 4 * d                       # magnitudes of the q, k, v, o adapters (either reading)
+    for r in (2, 4, 8, 16, 32):
+        assert printed[("params_pct_rank_mixdora", r)] == printed[("params_pct_rank", r)]
+        lora = L * (N * 3 * r * (d + f) + N * d + 4 * r * 2 * d)
+        share = lambda extra: 100.0 * (lora + extra) / (base + lora + extra)
+        per_expert = share(attn_m + L * N * (2 * f + d)) - share(0)
+        shared = share(attn_m + L * (2 * f + d)) - share(0)
+        assert 0.09 < per_expert < 0.11 and shared < 0.025
+    # main results table, r = 16: both methods print 2.9 %
+    lora = L * (N * 3 * 16 * (d + f) + N * d + 4 * 16 * 2 * d)
+    share = lambda extra: 100.0 * (lora + extra) / (base + lora + extra)
+    assert round(share(0), 1) == round(share(attn_m + L * (2 * f + d)), 1) == 2.9
+    assert round(share(attn_m + L * N * (2 * f + d)), 1) == 3.0
