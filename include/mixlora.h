@@ -14,7 +14,12 @@
  *   - Every data pointer is a DEVICE pointer (HIP, one GPU), row-major, 16-byte aligned,
  *     owned by the caller and not retained after the call returns.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
- *     enqueued on it; no entry point allocates, frees or synchronises.
+ *     enqueued on it; no entry point allocates, frees or synchronises (the measurement aids at
+ *     the end of this file excepted: they are not part of the block's contract).
+ *   - Stream capture: the first launch of a kernel that needs more than 64 KiB of LDS sets a
+ *     function attribute (hipFuncSetAttribute), once per process and kernel instance, which is
+ *     not a stream operation.  Call every entry point once eagerly with the dims that will be
+ *     captured before capturing it into a HIP graph; from then on its calls enqueue kernels only.
  *   - The return value is a mixlora_status.  Argument errors are detected on the host before
  *     any HIP call is made and leave all buffers untouched.  No C++ exception crosses the ABI.
  *   - Storage dtype (dims.dtype) applies to x, y, dy, dx and all weight matrices; routing

@@ -12,7 +12,8 @@ import os
 from typing import Dict, Optional
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libmixlora.so")
+# MIXLORA_LIB: another build of the same library (e.g. the host-sanitizer build of build.py)
+LIB_PATH = os.environ.get("MIXLORA_LIB") or os.path.join(HERE, "libmixlora.so")
 
 F32, BF16 = 0, 1
 AUX_TOP1, AUX_TOPK = 0, 1

@@ -691,7 +691,21 @@ static int backward_impl(const mixlora_dims &Du, int Nl, const int32_t *token_mo
   char *Sop = vanilla ? ws + L.Sp : ws + L.S;      // K-extension operand of the dx GEMM
   // through SiLU * up and the LoRA deltas, per pair; TG[row, e, :] = B_gate[e]^T dg[row] (and up)
   int nct = L.nct;
-  if (dt == MIXLORA_BF16) {
+  // tokens grouped by expert pair (tables left by the forward pass): the per-token sums of dg and
+  // du come out of the same launch
+  const bool use_pg = dt == MIXLORA_BF16 && !pair_down && !dora && fused_pg_ok(pc, f);
+  if (use_pg) {
+    nct = fused_pg_splits(f, T);
+    HIP_TRY_AS(PROF_FUSED_BWD, 9.0 * T * f * Eb,
+               launch_swiglu_bwd_pg(pc, f, s, (int32_t *)(ws + L.pg_tok), (int32_t *)(ws + L.pg_tiles),
+                                    (int32_t *)(ws + L.pg_ntiles), ws + L.G, ws + L.U, ws + L.H,
+                                    (float *)(ws + L.Pg_all), (float *)(ws + L.Pu_all),
+                                    (float *)(ws + L.VB_all), w->B_gate, w->B_up, ws + L.AdT,
+                                    ws + L.Bg_T, ws + L.Bu_T, ws + L.dg_grp, ws + L.du_grp,
+                                    ws + L.dgsum, ws + L.dusum, (float *)(ws + L.dw_part),
+                                    (float *)(ws + L.rank_part), (float *)(ws + L.TG_all),
+                                    (float *)(ws + L.TU_all), Sop, Kx, st));
+  } else if (dt == MIXLORA_BF16) {
     nct = fused_splits(f, (int)kT);
     HIP_TRY_AS(PROF_FUSED_BWD, 5.0 * kT * f * Eb, launch_swiglu_bwd_mfma(pc, f, s, vanilla ? ws + L.Gp : ws + L.G,
                                    vanilla ? ws + L.Up : ws + L.U, pair_down ? ws + L.Hp : ws + L.H,
@@ -712,7 +726,7 @@ static int backward_impl(const mixlora_dims &Du, int Nl, const int32_t *token_mo
     add_seg(p[1], ws + L.du_grp, f, ws + L.Bu_T, f, f);
     HIP_TRY(launch_gemm(dt, p, 2, st));
   }
-  if (!vanilla) {   // shared gate/up: their input gradient needs the per-token sums only
+  if (!vanilla && !use_pg) {   // shared gate/up: their input gradient needs the per-token sums only
     HIP_TRY_AS(PROF_COMBINE, 2.0 * (k + 1) * T * f * Eb, launch_pair_combine2(dt, pc, f, ws + L.dg_grp, ws + L.dgsum, ws + L.du_grp,
                                  ws + L.dusum, 0, st));
   }

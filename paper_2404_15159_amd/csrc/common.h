@@ -210,6 +210,16 @@ hipError_t launch_swiglu_fwd_pg(const PairCtx &pc, int f, float s, const int32_t
                                 const void *B_gate, const void *B_up, const void *A_down,
                                 void *a_grp, void *a_comb, float *Q_part, float *Q_all, void *Qw,
                                 int ldqw, int write_a, hipStream_t st);
+// backward on the same tiles: per-pair dg_grp, du_grp, dw_part [pair row][fused_pg_splits], TG / TU
+// (reduced into TG_all, TU_all and the block-sparse operand S) and the per-token sums dgsum, dusum
+hipError_t launch_swiglu_bwd_pg(const PairCtx &pc, int f, float s, const int32_t *tok_of_pos,
+                                const int32_t *tile_info, const int32_t *ntiles, const void *G,
+                                const void *U, const void *H, const float *Pg_all,
+                                const float *Pu_all, const float *VB_all, const void *B_gate,
+                                const void *B_up, const void *AdT, const void *BgT, const void *BuT,
+                                void *dg_grp, void *du_grp, void *dgsum, void *dusum, float *dw_part,
+                                float *rank_part, float *TG_all, float *TU_all, void *S, int ld_s,
+                                hipStream_t st);
 // dense[row, e(row)*r + q] = sum over splits of part[split][row][q] (fixed order) for one bank
 // (dense1 == NULL) or two banks bank_stride floats apart; the value (times the routing weight if
 // weighted) also goes as bf16 into the block-sparse operand sparse[t(row) or row, bank*N*r + e*r + q]
