@@ -360,9 +360,16 @@ static int forward_impl(const mixlora_dims &Du, int Nl, const int32_t *token_mod
     dargs.cu = (float *)(ws + L.c_u);
   }
   // Eq. 7 + Norm (Algorithm 1 lines 4-5)
+  // s * B_down packed for the K-extension of the down GEMM; in bf16 also zeros for the
+  // block-sparse operand Qw, whose non-zero blocks the fused stage fills in.  In bf16 these
+  // re-layouts ride in the routing launch.
+  const RelayoutJob fwd_jobs[2] = {job_bank_cat(w->B_down, N, d, r, D.lora_scale, ws + L.Bd_cat, R, 0),
+                                   pair_down ? job_zero_fill(ws + L.Qp, (size_t)kT * R * 2)
+                                             : job_zero_fill(ws + L.Qw, (size_t)T * R * 2)};
   if (dt == MIXLORA_BF16)
-    HIP_TRY_AS(PROF_ROUTING, (double)T * N * 8, launch_route_logits((const float *)(ws + L.Z), N, T, N, k, probs, topk_idx, topk_w, idx,
-                                wts, Nl, token_model, st));
+    HIP_TRY_AS(PROF_ROUTING, (double)T * N * 8,
+               launch_route_logits_relayout((const float *)(ws + L.Z), N, T, N, k, probs, topk_idx,
+                                            topk_w, idx, wts, Nl, token_model, fwd_jobs, 2, st));
   else
     HIP_TRY_AS(PROF_ROUTING, (double)T * d * Eb, launch_router(dt, x, w->W_router, T, d, N, k, probs, topk_idx, topk_w, idx, wts, Nl,
                           token_model, st));
@@ -391,14 +398,7 @@ static int forward_impl(const mixlora_dims &Du, int Nl, const int32_t *token_mod
                                       token_model, (int32_t *)(ws + L.model_tokens),
                                       use_pg ? pg_tok : nullptr, pg_tiles, pg_ntiles, st));
   }
-  {
-    // s * B_down packed for the K-extension of the down GEMM; in bf16 also zeros for the
-    // block-sparse operand Qw, whose non-zero blocks the fused stage fills in
-    const RelayoutJob jobs[2] = {job_bank_cat(w->B_down, N, d, r, D.lora_scale, ws + L.Bd_cat, R, 0),
-                                 pair_down ? job_zero_fill(ws + L.Qp, (size_t)kT * R * 2)
-                                           : job_zero_fill(ws + L.Qw, (size_t)T * R * 2)};
-    HIP_TRY_AS(PROF_OTHER, 0, launch_relayout(dt, jobs, dt == MIXLORA_BF16 ? 2 : 1, st));
-  }
+  if (dt != MIXLORA_BF16) HIP_TRY_AS(PROF_OTHER, 0, launch_relayout(dt, fwd_jobs, 1, st));
   if (pair_down) {
     // The paper's schedules (Figure 3): every expert runs its own frozen products on its slice of
     // tokens.  (a) unshared: gate and up on the gathered token rows, k rows per token;

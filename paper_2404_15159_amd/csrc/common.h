@@ -102,6 +102,12 @@ hipError_t launch_router(int dtype, const void *x, const void *W_router, int T, 
                          int k, float *probs, int32_t *idx_out, float *w_out, int32_t *idx_ws,
                          float *w_ws, int Nl, const int32_t *token_model, hipStream_t st);
 // Same routing from logits Z[t, n] (row pitch ldz) that a GEMM launch produced.
+struct RelayoutJob;
+// routing from logits plus weight re-layout jobs (bf16 storage) in one launch
+hipError_t launch_route_logits_relayout(const float *Z, int ldz, int T, int N, int k, float *probs,
+                                        int32_t *idx_out, float *w_out, int32_t *idx_ws,
+                                        float *w_ws, int Nl, const int32_t *token_model,
+                                        const RelayoutJob *jobs, int njobs, hipStream_t st);
 hipError_t launch_route_logits(const float *Z, int ldz, int T, int N, int k, float *probs,
                                int32_t *idx_out, float *w_out, int32_t *idx_ws, float *w_ws,
                                int Nl, const int32_t *token_model, hipStream_t st);

@@ -5,6 +5,7 @@
 // the tile's rows (Algorithm 1 lines 11-13: add the LoRA deltas to the shared gate/up
 // projections, then SiLU * up).
 #include "common.h"
+#include "relayout_body.h"
 
 namespace mixlora {
 
@@ -574,80 +575,17 @@ hipError_t launch_splitk_reduce(int dtype, const float *part, int S, int64_t n, 
 // threads):  dst[dst0 + i0*d0 + i1*d1 + i2*d2] = scale * src[i0*s0 + i1*s1 + i2*s2], with zeros
 // written where i2 >= valid2.  Up to RELAYOUT_MAX_JOBS of them run in one launch (blockIdx.y
 // picks the job), since each alone is dominated by its launch.
-struct RelayoutBatch {
-  RelayoutJob job[RELAYOUT_MAX_JOBS];
-};
-
 template <typename E>
 __global__ __launch_bounds__(256) void relayout_kernel(RelayoutBatch batch) {
-  const RelayoutJob &J = batch.job[blockIdx.y];
-  const E *__restrict__ src = reinterpret_cast<const E *>(J.src);
-  E *__restrict__ dst = reinterpret_cast<E *>(J.dst);
-  if (J.zero_bytes) {   // plain zero fill, 16 bytes per store (dst is 16-byte aligned)
-    uint4 *z = reinterpret_cast<uint4 *>(J.dst);
-    const size_t nv = J.zero_bytes / 16;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nv;
-         i += (size_t)gridDim.x * blockDim.x)
-      z[i] = make_uint4(0u, 0u, 0u, 0u);
-    return;
-  }
-  if (J.batched_transpose) {
-    // dst[dst0 + b*d0 + q*d1 + p] = scale * src[b*s0 + p*n2 + q] for b < n0, p < n1, q < n2
-    // (zeros where p >= valid2): 64x64 tiles through LDS so that both the reads and the writes
-    // run along a contiguous dimension (long thin tiles for the rank-wide banks were measured
-    // slower)
-    constexpr int TP = 64, TQ = 64, pitch = TQ + 1;
-    __shared__ float tile[TP * pitch];
-    const int P = J.n1, Q = J.n2, PV = J.valid2;
-    const int tp = (P + TP - 1) / TP, tq = (Q + TQ - 1) / TQ;
-    const int ntiles = J.n0 * tp * tq;
-    for (int tid = blockIdx.x; tid < ntiles; tid += gridDim.x) {
-      const int b = tid / (tp * tq), rem = tid % (tp * tq);
-      const int p0 = (rem / tq) * TP, q0 = (rem % tq) * TQ;
-      const int hp = P - p0 < TP ? P - p0 : TP, hq = Q - q0 < TQ ? Q - q0 : TQ;
-      // reads walk the source rows (hq contiguous elements each; one contiguous block when the
-      // whole row fits), writes walk the destination rows (hp contiguous elements each)
-      for (int x = threadIdx.x; x < hp * hq; x += 256) {
-        const int i = x / hq, j = x - i * hq;
-        tile[i * pitch + j] =
-            p0 + i < PV ? J.scale * to_f32(src[b * J.s0 + (int64_t)(p0 + i) * Q + q0 + j]) : 0.f;
-      }
-      __syncthreads();
-      for (int x = threadIdx.x; x < hp * hq; x += 256) {
-        const int j = x / hp, i = x - j * hp;
-        dst[J.dst0 + b * J.d0 + (q0 + j) * J.d1 + p0 + i] = from_f32<E>(tile[i * pitch + j]);
-      }
-      __syncthreads();
-    }
-    return;
-  }
-  // element counts are below 2^31 (checked by the launcher): 32-bit index arithmetic
-  const unsigned n2 = J.n2, n1 = J.n1, total = (unsigned)J.n0 * n1 * n2;
-  for (unsigned o = blockIdx.x * blockDim.x + threadIdx.x; o < total; o += gridDim.x * blockDim.x) {
-    const unsigned i2 = o % n2, t = o / n2;
-    const unsigned i1 = t % n1, i0 = t / n1;
-    const float v = (int)i2 < J.valid2 ? J.scale * to_f32(src[i0 * J.s0 + i1 * J.s1 + i2 * J.s2]) : 0.f;
-    dst[J.dst0 + i0 * J.d0 + i1 * J.d1 + i2 * J.d2] = from_f32<E>(v);
-  }
+  relayout_body<E>(batch.job[blockIdx.y], blockIdx.x, gridDim.x);
 }
 
 hipError_t launch_relayout(int dtype, const RelayoutJob *jobs, int njobs, hipStream_t st) {
   if (njobs < 1 || njobs > RELAYOUT_MAX_JOBS) return hipErrorInvalidValue;
   RelayoutBatch b;
-  int64_t most = 1;
-  for (int i = 0; i < RELAYOUT_MAX_JOBS; i++) {
-    b.job[i] = jobs[i < njobs ? i : 0];
-    const int64_t n = (int64_t)b.job[i].n0 * b.job[i].n1 * b.job[i].n2;
-    if (n >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
-    // blocks wanted: one per 256 elements, or one per 64x64 tile
-    const int64_t want = b.job[i].batched_transpose
-                             ? (int64_t)b.job[i].n0 * ((b.job[i].n1 + 63) / 64) * ((b.job[i].n2 + 63) / 64)
-                             : b.job[i].zero_bytes ? (int64_t)(b.job[i].zero_bytes / 16 + 255) / 256
-                                                   : (n + 255) / 256;
-    most = want > most ? want : most;
-  }
-  int64_t blocks = most;
-  if (blocks > 8192) blocks = 8192;   // grid-stride beyond that
+  for (int i = 0; i < RELAYOUT_MAX_JOBS; i++) b.job[i] = jobs[i < njobs ? i : 0];
+  const int64_t blocks = relayout_blocks(jobs, njobs);
+  if (blocks == 0) return hipErrorInvalidValue;
   const dim3 grid((unsigned)blocks, njobs), block(256);
   if (dtype == MIXLORA_BF16) hipLaunchKernelGGL(relayout_kernel<bf16_t>, grid, block, 0, st, b);
   else hipLaunchKernelGGL(relayout_kernel<float>, grid, block, 0, st, b);

@@ -2,6 +2,7 @@
 // Algorithm 1), stable grouping of the (token, expert) pairs by expert with wavefront ballots
 // and prefix counts, and the auxiliary load-balance loss (Eq. 8-9).
 #include "common.h"
+#include "relayout_body.h"
 
 namespace mixlora {
 
@@ -143,6 +144,43 @@ hipError_t launch_router(int dtype, const void *x, const void *W_router, int T, 
                                        Nl, token_model, st)
              : launch_router_t<float>(x, W_router, T, d, N, k, probs, idx_out, w_out, idx_ws, w_ws,
                                       Nl, token_model, st);
+}
+
+// The same routing with up to RELAYOUT_MAX_JOBS weight re-layout jobs (bf16) in the trailing
+// workgroups of the launch: the re-layouts of a forward pass depend on the weights only, and each
+// of the two launches alone is dominated by its own latency.
+__global__ __launch_bounds__(256) void route_logits_relayout_kernel(
+    const float *__restrict__ Z, int ldz, int T, int N, int k, float *__restrict__ probs,
+    int32_t *__restrict__ idx_out, float *__restrict__ w_out, int32_t *__restrict__ idx_ws,
+    float *__restrict__ w_ws, int Nl, const int32_t *__restrict__ token_model, int route_blocks,
+    RelayoutBatch batch, int rblocks) {
+  if ((int)blockIdx.x >= route_blocks) {   // workgroup-uniform
+    const int b = blockIdx.x - route_blocks;
+    relayout_body<bf16_t>(batch.job[b / rblocks], b % rblocks, rblocks);
+    return;
+  }
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  const float z = lane < N ? Z[(int64_t)t * ldz + lane] : -INFINITY;
+  const int lo = token_model ? token_model[t] * Nl : 0;
+  route_token(z, lane, t, lo, Nl, N, k, probs, idx_out, w_out, idx_ws, w_ws);
+}
+
+hipError_t launch_route_logits_relayout(const float *Z, int ldz, int T, int N, int k, float *probs,
+                                        int32_t *idx_out, float *w_out, int32_t *idx_ws,
+                                        float *w_ws, int Nl, const int32_t *token_model,
+                                        const RelayoutJob *jobs, int njobs, hipStream_t st) {
+  if (njobs < 1 || njobs > RELAYOUT_MAX_JOBS) return hipErrorInvalidValue;
+  RelayoutBatch b;
+  for (int i = 0; i < RELAYOUT_MAX_JOBS; i++) b.job[i] = jobs[i < njobs ? i : 0];
+  const int64_t rblocks = relayout_blocks(jobs, njobs);
+  if (rblocks == 0) return hipErrorInvalidValue;
+  const int route_blocks = (T + 3) / 4;
+  hipLaunchKernelGGL(route_logits_relayout_kernel, dim3((unsigned)(route_blocks + njobs * rblocks)),
+                     dim3(256), 0, st, Z, ldz, T, N, k, probs, idx_out, w_out, idx_ws, w_ws, Nl,
+                     token_model, route_blocks, b, (int)rblocks);
+  return hipGetLastError();
 }
 
 hipError_t launch_route_logits(const float *Z, int ldz, int T, int N, int k, float *probs,
