@@ -91,6 +91,16 @@ SMALL_CASES = [
     ("bf16_scale_1p5", BASE_BF16, dict(T=300, d=256, d_ff=520, N=8, k=2, r=16, alpha=24.0)),
     ("bf16_scale_0p7", BASE_BF16, dict(T=257, d=136, d_ff=264, N=5, k=3, r=40, alpha=28.0)),
     ("f32_scale_1p3", BASE_F32, dict(T=333, d=72, d_ff=200, N=6, k=2, r=8, alpha=10.4)),
+    # edges of the stage that runs on token tiles of one expert pair (top-2, bf16, r <= 16,
+    # N <= 16, 128 < T <= 65536, d_ff >= 64): fewest tokens, a single pair group with many tiles,
+    # sixteen experts (120 groups, most tiles ragged) with a ragged last column block, the
+    # narrowest d_ff, the largest token count and the first one past it (expert-grouped path)
+    ("bf16_pg_129_tokens", BASE_BF16, dict(T=129, d=128, d_ff=264, N=8, k=2, r=16)),
+    ("bf16_pg_two_experts", BASE_BF16, dict(T=300, d=128, d_ff=328, N=2, k=2, r=16)),
+    ("bf16_pg_16_experts_r4", BASE_BF16, dict(T=1500, d=128, d_ff=392, N=16, k=2, r=4, alpha=8.0)),
+    ("bf16_pg_dff_64", BASE_BF16, dict(T=200, d=64, d_ff=64, N=4, k=2, r=8, alpha=16.0)),
+    ("bf16_pg_65536_tokens", BASE_BF16, dict(T=65536, d=64, d_ff=136, N=8, k=2, r=8, alpha=16.0)),
+    ("bf16_pg_65537_tokens", BASE_BF16, dict(T=65537, d=64, d_ff=72, N=8, k=2, r=8, alpha=16.0)),
     # ranks off the multiples of 8 (the rank study of Section 4.3 starts at r = 2), at the 7B
     # model's d : d_ff ratio: the library runs them on zero-padded banks and cuts the gradients back
     ("bf16_r2_7b_ratio", BASE_BF16, dict(T=300, d=256, d_ff=688, N=8, k=2, r=2, alpha=4.0)),
