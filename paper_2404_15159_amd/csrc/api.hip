@@ -271,6 +271,24 @@ static hipError_t pad_weights(const Layout &L, char *ws, const mixlora_dims &Du,
   return launch_relayout(Du.dtype, jobs, 6, st);
 }
 
+// Every re-layout of the LoRA banks and the router that the backward pass needs (eight jobs, the
+// last two for bf16 storage only).
+static void bwd_relayout_jobs(const Layout &L, char *ws, const mixlora_weights *w, int N, int d,
+                              int f, int r, int kT, int T, float s, bool vanilla,
+                              RelayoutJob jobs[8]) {
+  const int R = N * r, Kx = L.Kx;
+  jobs[0] = job_bank_T(w->B_down, N, d, r, ws + L.Bd_T);
+  jobs[1] = job_bank_T(w->B_gate, N, f, r, ws + L.Bg_T);
+  jobs[2] = job_bank_T(w->B_up, N, f, r, ws + L.Bu_T);
+  jobs[3] = job_A_cat(w->A_gate, N, r, d, s, ws + L.Bx, Kx, 0);
+  jobs[4] = job_A_cat(w->A_up, N, r, d, s, ws + L.Bx, Kx, R);
+  jobs[5] = job_router_T(w->W_router, N, d, ws + L.Bx, Kx, 2 * R, Kx - 2 * R);
+  jobs[6] = job_bank_T(w->A_down, N, r, f, ws + L.AdT);   // [N,r,f] -> [N,f,r], bf16 path only
+  // bf16 path only: zeros for the block-sparse operand S, filled in by the fused stage
+  jobs[7] = vanilla ? job_zero_fill(ws + L.Sp, (size_t)kT * Kx * 2)
+                    : job_zero_fill(ws + L.S, (size_t)T * Kx * 2);
+}
+
 static int forward_impl(const mixlora_dims &Du, int Nl, const int32_t *token_model,
                         const mixlora_weights *w, const void *x, void *y, int32_t *topk_idx,
                         float *topk_w, int32_t *expert_counts, float *aux_loss, void *workspace,
@@ -389,7 +407,7 @@ static int forward_impl(const mixlora_dims &Du, int Nl, const int32_t *token_mod
     if (use_pg)
       HIP_TRY_AS(PROF_ROUTING, (double)T * 12, launch_group_token_pairs(pc, pg_tok, pg_tiles, pg_ntiles, st));
   } else {
-    // (the tokens' grouping by expert pair rides in the same launch as a second workgroup)
+    // (Eq. 8-9 and the tokens' grouping by expert pair run as further workgroups of the launch)
     HIP_TRY_AS(PROF_ROUTING, (double)kT * 16 + (use_pg ? (double)T * 12 : 0.0),
                launch_group_pairs_aux(idx, T, N, k, (int32_t *)(ws + L.counts), expert_counts,
                                       (int32_t *)(ws + L.first_counts), offs, row_of_pair, pair_of_row,
@@ -639,17 +657,8 @@ static int backward_impl(const mixlora_dims &Du, int Nl, const int32_t *token_mo
 
   // every re-layout of the LoRA banks and the router that the pass needs, in one launch
   {
-    const RelayoutJob jobs[8] = {
-        job_bank_T(w->B_down, N, d, r, ws + L.Bd_T),
-        job_bank_T(w->B_gate, N, f, r, ws + L.Bg_T),
-        job_bank_T(w->B_up, N, f, r, ws + L.Bu_T),
-        job_A_cat(w->A_gate, N, r, d, s, ws + L.Bx, Kx, 0),
-        job_A_cat(w->A_up, N, r, d, s, ws + L.Bx, Kx, R),
-        job_router_T(w->W_router, N, d, ws + L.Bx, Kx, 2 * R, Kx - 2 * R),
-        job_bank_T(w->A_down, N, r, f, ws + L.AdT),   // [N,r,f] -> [N,f,r], bf16 path only
-        // bf16 path only: zeros for the block-sparse operand S, filled in by the fused stage
-        vanilla ? job_zero_fill(ws + L.Sp, (size_t)kT * Kx * 2)
-                : job_zero_fill(ws + L.S, (size_t)T * Kx * 2)};
+    RelayoutJob jobs[8];
+    bwd_relayout_jobs(L, ws, w, N, d, f, r, kT, T, s, vanilla, jobs);
     HIP_TRY_AS(PROF_OTHER, 0, launch_relayout(dt, jobs, dt == MIXLORA_BF16 ? 8 : 6, st));
   }
   // H = dy W_down  (once per token: the frozen down projection is shared and linear) and, in

@@ -9,7 +9,7 @@ struct RelayoutBatch {
   RelayoutJob job[RELAYOUT_MAX_JOBS];
 };
 
-// One job, as block bx of gx blocks of 256 threads.
+// One job, as block bx of gx blocks (any workgroup size; every thread of the workgroup calls it).
 template <typename E>
 __device__ __forceinline__ void relayout_body(const RelayoutJob &J, int bx, int gx) {
   const E *__restrict__ src = reinterpret_cast<const E *>(J.src);
@@ -17,7 +17,7 @@ __device__ __forceinline__ void relayout_body(const RelayoutJob &J, int bx, int 
   if (J.zero_bytes) {   // plain zero fill, 16 bytes per store (dst is 16-byte aligned)
     uint4 *z = reinterpret_cast<uint4 *>(J.dst);
     const size_t nv = J.zero_bytes / 16;
-    for (size_t i = (size_t)bx * 256 + threadIdx.x; i < nv; i += (size_t)gx * 256)
+    for (size_t i = (size_t)bx * blockDim.x + threadIdx.x; i < nv; i += (size_t)gx * blockDim.x)
       z[i] = make_uint4(0u, 0u, 0u, 0u);
     return;
   }
@@ -37,13 +37,13 @@ __device__ __forceinline__ void relayout_body(const RelayoutJob &J, int bx, int 
       const int hp = P - p0 < TP ? P - p0 : TP, hq = Q - q0 < TQ ? Q - q0 : TQ;
       // reads walk the source rows (hq contiguous elements each; one contiguous block when the
       // whole row fits), writes walk the destination rows (hp contiguous elements each)
-      for (int x = threadIdx.x; x < hp * hq; x += 256) {
+      for (int x = threadIdx.x; x < hp * hq; x += (int)blockDim.x) {
         const int i = x / hq, j = x - i * hq;
         tile[i * pitch + j] =
             p0 + i < PV ? J.scale * to_f32(src[b * J.s0 + (int64_t)(p0 + i) * Q + q0 + j]) : 0.f;
       }
       __syncthreads();
-      for (int x = threadIdx.x; x < hp * hq; x += 256) {
+      for (int x = threadIdx.x; x < hp * hq; x += (int)blockDim.x) {
         const int j = x / hp, i = x - j * hp;
         dst[J.dst0 + b * J.d0 + (q0 + j) * J.d1 + p0 + i] = from_f32<E>(tile[i * pitch + j]);
       }
@@ -53,7 +53,7 @@ __device__ __forceinline__ void relayout_body(const RelayoutJob &J, int bx, int 
   }
   // element counts are below 2^31 (checked by the launcher): 32-bit index arithmetic
   const unsigned n2 = J.n2, n1 = J.n1, total = (unsigned)J.n0 * n1 * n2;
-  for (unsigned o = (unsigned)bx * 256u + threadIdx.x; o < total; o += (unsigned)gx * 256u) {
+  for (unsigned o = (unsigned)bx * blockDim.x + threadIdx.x; o < total; o += (unsigned)gx * blockDim.x) {
     const unsigned i2 = o % n2, t = o / n2;
     const unsigned i1 = t % n1, i0 = t / n1;
     const float v = (int)i2 < J.valid2 ? J.scale * to_f32(src[i0 * J.s0 + i1 * J.s1 + i2 * J.s2]) : 0.f;

@@ -468,10 +468,10 @@ hipError_t launch_group_token_pairs(const PairCtx &pc, int32_t *tok_of_pos, int3
   return hipGetLastError();
 }
 
-// Grouping and auxiliary loss of one forward pass in one single-workgroup launch (both are bound
-// by their own latency); also writes the two-entry offsets {0, T} that let the grouped
-// outer-product kernel treat all tokens as one group.  With pg_tok != NULL a second workgroup
-// groups the tokens by expert pair at the same time (it needs the kept experts only).
+// Grouping and auxiliary loss of one forward pass in one launch of a few workgroups, each bound
+// by its own latency and independent of the others: the grouping of the pairs by expert (which
+// also writes the two-entry offsets {0, T} that let the grouped outer-product kernel treat all
+// tokens as one group), Eq. 8-9, and with pg_tok != NULL the grouping of the tokens by expert pair.
 __global__ __launch_bounds__(GP_WAVES * 64) void group_pairs_aux_kernel(
     const int32_t *__restrict__ idx, int T, int N, int k, int32_t *__restrict__ counts,
     int32_t *__restrict__ counts_out, int32_t *__restrict__ first_counts,
@@ -483,14 +483,15 @@ __global__ __launch_bounds__(GP_WAVES * 64) void group_pairs_aux_kernel(
     int32_t *__restrict__ pg_tok, int32_t *__restrict__ pg_tiles, int32_t *__restrict__ pg_ntiles) {
   static_assert(GP_WAVES * 64 == 1024, "the auxiliary-loss block code assumes 1024 threads");
   static_assert(PG_GWAVES == GP_WAVES, "both block routines run with the same workgroup size");
-  if (blockIdx.x == 1) {   // workgroup-uniform
+  // independent pieces of work, one workgroup each (all workgroup-uniform branches)
+  if (blockIdx.x == 0) {
+    group_pairs_block(idx, T * k, N, k, counts, counts_out, first_counts, offs, row_of_pair, pair_of_row);
+    if (threadIdx.x == 0) { tok_offs[0] = 0; tok_offs[1] = T; }
+  } else if (blockIdx.x == 1) {
+    aux_loss_block(probs, idx, T, N, k, coeff, mode, loss, F_out, P_out, Nl, token_model, model_tokens);
+  } else if (pg_tok) {
     group_token_pairs_block(idx, T, N, pg_tok, pg_tiles, pg_ntiles);
-    return;
   }
-  group_pairs_block(idx, T * k, N, k, counts, counts_out, first_counts, offs, row_of_pair, pair_of_row);
-  if (threadIdx.x == 0) { tok_offs[0] = 0; tok_offs[1] = T; }
-  __syncthreads();
-  aux_loss_block(probs, idx, T, N, k, coeff, mode, loss, F_out, P_out, Nl, token_model, model_tokens);
 }
 
 hipError_t launch_group_pairs_aux(const int32_t *idx, int T, int N, int k, int32_t *counts,
@@ -500,7 +501,7 @@ hipError_t launch_group_pairs_aux(const int32_t *idx, int T, int N, int k, int32
                                   float *P, int Nl, const int32_t *token_model,
                                   int32_t *model_tokens, int32_t *pg_tok, int32_t *pg_tiles,
                                   int32_t *pg_ntiles, hipStream_t st) {
-  hipLaunchKernelGGL(group_pairs_aux_kernel, dim3(pg_tok ? 2 : 1), dim3(GP_WAVES * 64), 0, st, idx,
+  hipLaunchKernelGGL(group_pairs_aux_kernel, dim3(pg_tok ? 3 : 2), dim3(GP_WAVES * 64), 0, st, idx,
                      T, N, k, counts, counts_out, first_counts, offs, row_of_pair, pair_of_row,
                      tok_offs, probs, coeff, mode, loss, F, P, Nl, token_model, model_tokens,
                      pg_tok, pg_tiles, pg_ntiles);
