@@ -117,7 +117,7 @@ Layout make_layout(const mixlora_dims &D, int schedule = MIXLORA_SCHEDULE_LINEAR
   L.ninv_d = take(dora ? N * d * 4 : 0);
   L.Bd_cat = take(d * R * E);
   {   // per-split rank-r partial sums (two banks), for the grouped and the token-major stages
-    const size_t sp_g = (size_t)fused_splits((int)f, (int)kT), sp_t = (size_t)fused_pg_splits((int)f, (int)T);
+    const size_t sp_g = (size_t)fused_splits((int)f, (int)kT), sp_t = (size_t)fused_pg_splits((int)f, (int)T, (int)(N <= PG_MAX_EXPERTS ? N : 1));
     L.rank_part = take(2 * (sp_g > sp_t ? sp_g : sp_t) * kT * r * 4);
   }
   // few tokens (decode-shaped calls): partial outputs of the K-split down projection
@@ -704,7 +704,7 @@ static int backward_impl(const mixlora_dims &Du, int Nl, const int32_t *token_mo
   // du come out of the same launch
   const bool use_pg = dt == MIXLORA_BF16 && !pair_down && !dora && fused_pg_ok(pc, f);
   if (use_pg) {
-    nct = fused_pg_splits(f, T);
+    nct = fused_pg_splits(f, T, N);
     HIP_TRY_AS(PROF_FUSED_BWD, 9.0 * T * f * Eb,
                launch_swiglu_bwd_pg(pc, f, s, (int32_t *)(ws + L.pg_tok), (int32_t *)(ws + L.pg_tiles),
                                     (int32_t *)(ws + L.pg_ntiles), ws + L.G, ws + L.U, ws + L.H,

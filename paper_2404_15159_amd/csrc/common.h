@@ -201,13 +201,13 @@ hipError_t launch_swiglu_bwd_mfma(const PairCtx &pc, int f, float s, const void 
 // token and the sums over a token's two pairs are written per token (no combine pass).
 // Tables: tok_of_pos [T], tile_info [fused_pg_max_tiles(T, N)][4], ntiles [1] (device int32).
 // Forward: a_comb[t] = w_t0 a_t0 + w_t1 a_t1, a_grp only when write_a, Q_all / Qw as above;
-// Q_part: fused_pg_splits(f, T) * kT * r floats.
+// Q_part: fused_pg_splits(f, T, N) * kT * r floats.
 constexpr int PG_MAX_EXPERTS = 16;
 constexpr int PG_TILE_ROWS = 32;
 constexpr int PG_MAX_TOKENS = 1 << 16;
 bool fused_pg_ok(const PairCtx &pc, int f);
 int fused_pg_max_tiles(int T, int N);
-int fused_pg_splits(int f, int T);
+int fused_pg_splits(int f, int T, int N);
 hipError_t launch_group_token_pairs(const PairCtx &pc, int32_t *tok_of_pos, int32_t *tile_info,
                                     int32_t *ntiles, hipStream_t st);
 hipError_t launch_swiglu_fwd_pg(const PairCtx &pc, int f, float s, const int32_t *tok_of_pos,

@@ -160,6 +160,17 @@ __global__ __launch_bounds__(FT_WAVES * 64, 2) void swiglu_fwd_pg_kernel(
     const bool tail = c0 + FT_SB > f;
     const uint32_t col = (c0 + 8 * cc) * 2u;   // bytes
     const bool cvalid = c0 + 8 * cc < f;
+    // The next piece's shared projections, requested a whole piece before they are needed and
+    // moved into (gnx, unx) at the end of this one.  Requested inside the row loop instead (into
+    // the registers each row frees) they are copied into place at the loop's back edge while
+    // still in flight, and the wavefront waits there: measured 156 against 148 us.
+    bf16x8_t gny[4], uny[4];
+#pragma unroll
+    for (int p = 0; p < 4; p++) {
+      gny[p] = ldg8(G, gsrc[p] + col_of(cn));
+      uny[p] = ldg8(U, gsrc[p] + col_of(cn));
+    }
+    __builtin_amdgcn_sched_barrier(0);
     // rank-r deltas of both experts and both 32-column blocks -> LDS tiles
 #pragma unroll
     for (int x = 0; x < 2; x++)
@@ -182,8 +193,6 @@ __global__ __launch_bounds__(FT_WAVES * 64, 2) void swiglu_fwd_pg_kernel(
     for (int p = 0; p < 4; p++) {
       const int toff = (8 * p + rr) * FT_PITCH + 8 * cc;
       const bf16x8_t gv = gnx[p], uv = unx[p];
-      gnx[p] = ldg8(G, gsrc[p] + col_of(cn));
-      unx[p] = ldg8(U, gsrc[p] + col_of(cn));
       float gf[8], uf[8], comb[8];
 #pragma unroll
       for (int m = 0; m < 8; m++) {
@@ -231,6 +240,12 @@ __global__ __launch_bounds__(FT_WAVES * 64, 2) void swiglu_fwd_pg_kernel(
     }
     load_wf(cn);
     __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int p = 0; p < 4; p++) {
+      gnx[p] = gny[p];
+      unx[p] = uny[p];
+    }
   }
   // accq[x][j][i]: row 8*(i/4) + 4*hi + i%4 of the tile, q = j*32 + l31.  Each wavefront parks its
   // sums in its own (now dead) tile space; then the four are added in a fixed order.
@@ -533,10 +548,16 @@ bool fused_pg_ok(const PairCtx &pc, int f) {
 
 int fused_pg_max_tiles(int T, int N) { return (T + FT_ROWS - 1) / FT_ROWS + N * N; }
 
-int fused_pg_splits(int f, int T) {
+// Column splits (grid.y).  Measured at the LLaMA shapes: a workgroup pays a few microseconds of
+// set-up (metadata chain, first fetches) and of final reduction, so few long workgroups beat many
+// short ones, and best of all is a grid that fits the chip in one round (two 4-wave workgroups
+// per compute unit: 512 slots).  tiles = T / 32 plus half a ragged tile per pair group.
+int fused_pg_splits(int f, int T, int N) {
   const int nblk = (f + FT_SB - 1) / FT_SB;
-  int s = T <= 1024 ? 16 : 8;
-  while (s > 1 && nblk / s < FT_WAVES) s >>= 1;
+  const int tiles = (T + FT_ROWS - 1) / FT_ROWS + N * (N - 1) / 4;
+  const int fit = 512 / (tiles > 0 ? tiles : 1);
+  int s = fit >= 3 ? (fit < 16 ? fit : 16) : 4;
+  while (s > 1 && nblk / s < FT_WAVES) s--;
   return s;
 }
 
@@ -547,7 +568,7 @@ hipError_t launch_swiglu_fwd_pg(const PairCtx &pc, int f, float s, const int32_t
                                 void *a_grp, void *a_comb, float *Q_part, float *Q_all, void *Qw,
                                 int ldqw, int write_a, hipStream_t st) {
   if (!fused_pg_ok(pc, f)) return hipErrorInvalidValue;
-  const int nsplit = fused_pg_splits(f, pc.T);
+  const int nsplit = fused_pg_splits(f, pc.T, pc.N);
   const dim3 grid(fused_pg_max_tiles(pc.T, pc.N), nsplit), block(FT_WAVES * 64);
 #define MIXLORA_PGF(KSR_, NQ_)                                                                    \
   do {                                                                                            \
@@ -581,7 +602,7 @@ hipError_t launch_swiglu_bwd_pg(const PairCtx &pc, int f, float s, const int32_t
                                 float *rank_part, float *TG_all, float *TU_all, void *S, int ld_s,
                                 hipStream_t st) {
   if (!fused_pg_ok(pc, f)) return hipErrorInvalidValue;
-  const int nP = pc.T * 2, nsplit = fused_pg_splits(f, pc.T);
+  const int nP = pc.T * 2, nsplit = fused_pg_splits(f, pc.T, pc.N);
   float *TG_part = rank_part, *TU_part = rank_part + (size_t)nsplit * nP * pc.r;
   const dim3 grid(fused_pg_max_tiles(pc.T, pc.N), nsplit), block(2 * FT_WAVES * 64);
   auto kern = swiglu_bwd_pg_kernel<1, 1>;   // fused_pg_ok: r <= 16
