@@ -196,9 +196,10 @@ hipError_t launch_swiglu_bwd_mfma(const PairCtx &pc, int f, float s, const void 
                                   float *TU_all, void *S, int lds_, hipStream_t st,
                                   int rows_mode = 0, const DoraArgs *dora = nullptr);
 // Pair-grouped token tiles (csrc/fused_pg.hip) for top-2 routing, N <= PG_MAX_EXPERTS, 128 < T <=
-// PG_MAX_TOKENS: tokens are grouped by their unordered expert pair, a workgroup handles 32 tokens
-// of one pair with one set of wavefronts per expert, G / U (/ H) are fetched from HBM once per
-// token and the sums over a token's two pairs are written per token (no combine pass).
+// PG_MAX_TOKENS, r <= 16: tokens are grouped by their unordered expert pair, a workgroup handles
+// 32 tokens of one pair (forward: one wavefront computes both experts of its columns; backward: one
+// set of wavefronts per expert), G / U (/ H) are fetched from HBM once per token and the sums over
+// a token's two pairs are written per token (no combine pass).
 // Tables: tok_of_pos [T], tile_info [fused_pg_max_tiles(T, N)][4], ntiles [1] (device int32).
 // Forward: a_comb[t] = w_t0 a_t0 + w_t1 a_t1, a_grp only when write_a, Q_all / Qw as above;
 // Q_part: fused_pg_splits(f, T, N) * kT * r floats.

@@ -11,9 +11,12 @@
 // their weighted sum is formed.  Per-pair outputs (a, rank-r partial sums) go to the
 // expert-grouped rows that the backward stages and gradient sums read.
 //
-// The stage is bound by vector-ALU issue (exp and rcp of the sigmoid run at quarter rate), not by
-// memory: per token and column it now spends about 31 vector instructions for both experts where
-// the expert-grouped kernel plus the combine pass spent about 56.
+// The forward kernel spends about 31 vector instructions per token and column for both experts
+// and the combination, where the expert-grouped kernel plus the combine pass spent about 56; what
+// it mostly does, though, is wait for memory (its time does not change with the shader clock), so
+// the next piece's operands are requested a whole piece ahead and the grid is cut into few, long
+// workgroups (fused_pg_splits).  The backward kernel keeps one wavefront per expert (two roles per
+// tile) and forms the per-token sums of dg and du from the two roles' LDS tiles.
 //
 // Lane roles, LDS tiles and MFMA fragment layout are those of csrc/fused.hip.
 #include "fused_common.h"
