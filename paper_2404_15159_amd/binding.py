@@ -94,6 +94,14 @@ def load():
         return _lib
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} not built; run `python -m paper_2404_15159_amd.build`")
+    # The device pointers callers pass come from PyTorch, which ships its own copy of the HIP
+    # runtime.  It has to be in the process before this library is, so that both use the same
+    # runtime: loaded the other way round the process ends up with two, and every launch on a
+    # torch tensor fails with MIXLORA_E_HIP.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(LIB_PATH)
     vp, i32, f32, sz = C.c_void_p, C.c_int32, C.c_float, C.c_size_t
     lib.mixlora_workspace_bytes.restype = sz
