@@ -210,6 +210,12 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_kernel(GemmBatch args
 // The loads and their s_waitcnt are inline asm: the compiler's own bookkeeping would wait for
 // all outstanding LDS DMA before every LDS read and collapse the ring to depth one.
 // Requires every K_s % BK == 0 and operands below 4 GiB (32-bit lane offsets).
+// PW > 0 makes only the first PW waves issue the copies (all of them, IA + IB instructions each).
+// A compute unit's vector-memory front end takes one 1 KiB copy instruction per ~16 cycles, so
+// the 64 instructions of a 256x256x64 tile keep their issuing waves stalled for ~1000 cycles
+// right after the barrier.  If every wave issues its share, both waves of each SIMD stall
+// together and the matrix pipe runs dry; with one issuing wave per SIMD (PW = 4 of 8 waves)
+// the other wave works through its MFMAs meanwhile, and the issuing wave follows with its own.
 __device__ __forceinline__ void dma16(uint32_t voff, const void *sbase, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
@@ -227,18 +233,19 @@ __device__ __forceinline__ const void *uniform_ptr(const void *p) {
   return reinterpret_cast<const void *>(((uint64_t)hi << 32) | lo);
 }
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool PIPE = false>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool PIPE = false, int PW = 0>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_dl_kernel(GemmBatch args) {
   constexpr int NW = WGM * WGN;
+  constexpr int NPW = PW > 0 ? PW : NW;   // waves that issue the copies
   constexpr int ROWB = BK * 2;            // bytes per tile row in LDS
   constexpr int CPR = BK / 8;             // 16-byte chunks per row
   constexpr int RPI = 64 / CPR;           // rows covered by one wave-wide DMA instruction
   constexpr int RPB = 256 / ROWB;         // rows per 256-byte bank row
-  constexpr int IA = BM / RPI / NW, IB = BN / RPI / NW;   // DMA instructions per wave per tile
+  constexpr int IA = BM / RPI / NPW, IB = BN / RPI / NPW;   // DMA instructions per issuing wave per tile
   constexpr int IPW = IA + IB;
   constexpr int STAGE_BYTES = (BM + BN) * ROWB;
   constexpr int TM = BM / WGM, TN = BN / WGN, MI = TM / 32, NI = TN / 32, KS = BK / 16;
-  static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tile/waves mismatch");
+  static_assert(NPW <= NW && BM % (RPI * NPW) == 0 && BN % (RPI * NPW) == 0, "tile/waves mismatch");
   static_assert((STAGES - 2) * IPW < 64 && STAGES >= 2, "ring depth");
 
   extern __shared__ __align__(16) unsigned char smem[];
@@ -295,10 +302,12 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_dl_kernel(GemmBatch a
     const void *gb = uniform_ptr(baseB + (size_t)k0 * 2);
     const uint32_t la = lds0 + stage * STAGE_BYTES + wave * IA * 1024;
     const uint32_t lb = lds0 + stage * STAGE_BYTES + BM * ROWB + wave * IB * 1024;
+    if (NPW == NW || wave < NPW) {   // the other waves' offsets point past the tile and are never used
 #pragma unroll
-    for (int j = 0; j < IA; j++) dma16(offA[j], ga, la + j * 1024);
+      for (int j = 0; j < IA; j++) dma16(offA[j], ga, la + j * 1024);
 #pragma unroll
-    for (int j = 0; j < IB; j++) dma16(offB[j], gb, lb + j * 1024);
+      for (int j = 0; j < IB; j++) dma16(offB[j], gb, lb + j * 1024);
+    }
   };
 
   int total_tiles = 0;
@@ -332,6 +341,7 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_dl_kernel(GemmBatch a
 
   auto wait_tile = [&](int it) {
     // tiles it+1 .. min(it+STAGES-2, last) may stay in flight; tile `it` must have landed
+    // (a wave that issues no copies has nothing outstanding: it learns of the tile at the barrier)
     const int newer = total_tiles - 1 - it;
     if (newer >= STAGES - 2) wait_vmcnt<(STAGES - 2) * IPW>();
     else if (STAGES > 3 && newer == 1) wait_vmcnt<IPW>();
@@ -588,10 +598,10 @@ static hipError_t launch_bf16(const GemmBatch &b, int nprob, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool PIPE = false>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool PIPE = false, int PW = 0>
 static hipError_t launch_bf16_dl(const GemmBatch &b, int nprob, hipStream_t st) {
   constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * sizeof(bf16_t);
-  auto kern = gemm_bf16_dl_kernel<BM, BN, BK, STAGES, WGM, WGN, PIPE>;
+  auto kern = gemm_bf16_dl_kernel<BM, BN, BK, STAGES, WGM, WGN, PIPE, PW>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -654,14 +664,14 @@ hipError_t launch_gemm(int dtype, const GemmProblem *probs, int nprob, hipStream
     // problems of different row counts (per-token and per-pair operands) can share a launch of
     // the large-tile kernel only: every tile takes M from its own problem
     if (!gemm_mixed_rows_ok(dtype, probs, nprob)) return hipErrorInvalidValue;
-    return launch_bf16_dl<256, 256, 64, 2, 2, 4, true>(b, nprob, st);
+    return launch_bf16_dl<256, 256, 64, 2, 2, 4, true, 4>(b, nprob, st);
   }
   if (M <= 0) return hipSuccess;
   if (dtype == MIXLORA_BF16 && M > 128 && any_big) {
     // large tiles: direct-to-LDS ring; BK = 64 needs whole 64-wide K tiles, else BK = 32.
     // Problems of one launch may differ in N and output type (narrow ones ride in the slack
     // of the last, partially filled round of workgroups).
-    if (dl_eligible(b, nprob, 64)) return launch_bf16_dl<256, 256, 64, 2, 2, 4, true>(b, nprob, st);
+    if (dl_eligible(b, nprob, 64)) return launch_bf16_dl<256, 256, 64, 2, 2, 4, true, 4>(b, nprob, st);
     if (dl_eligible(b, nprob, 32)) return launch_bf16_dl<256, 256, 32, 4, 2, 4, false>(b, nprob, st);
   }
   if (dtype == MIXLORA_BF16 && M <= 128 && any_big && dl_eligible(b, nprob, 64)) {
