@@ -479,12 +479,15 @@ static int forward_impl(const mixlora_dims &Du, int Nl, const int32_t *token_mod
     return MIXLORA_OK;
   }
   // Algorithm 1 lines 11-13 on the routed pairs, expert-grouped rows
+  // (few tokens: the sum of the stage's rank-r partial products rides in the combine's launch;
+  // each of the two launches alone is little more than its own latency)
+  const bool merge_tail = dt == MIXLORA_BF16 && (size_t)T <= SPLITK_MAX_ROWS && k * r <= 256;
   if (dt == MIXLORA_BF16) {
     // fused: LoRA deltas + SiLU * up + A_down of the row's expert, all on MFMA
     HIP_TRY_AS(PROF_FUSED_FWD, 3.0 * kT * f * Eb, launch_swiglu_fwd_mfma(pc, f, D.lora_scale, ws + L.G, ws + L.U,
                                    (float *)(ws + L.Pg_all), (float *)(ws + L.Pu_all), w->B_gate,
                                    w->B_up, w->A_down, ws + L.a_grp, (float *)(ws + L.rank_part),
-                                   (float *)(ws + L.Q_all), ws + L.Qw, R, st));
+                                   (float *)(ws + L.Q_all), ws + L.Qw, R, st, 0, nullptr, !merge_tail));
   } else {
     HIP_TRY_AS(PROF_FUSED_FWD, 3.0 * kT * f * Eb, launch_swiglu_fwd(dt, pc, f, D.lora_scale, ws + L.G, ws + L.U,
                               (float *)(ws + L.Pg_all), (float *)(ws + L.Pu_all), w->B_gate,
@@ -498,8 +501,13 @@ static int forward_impl(const mixlora_dims &Du, int Nl, const int32_t *token_mod
   }
   // weighted combine of the pair activations (Algorithm 1 line 15, moved in front of the linear
   // frozen down projection)
-  HIP_TRY_AS(PROF_COMBINE, (double)(k + 1) * T * f * Eb,
-             launch_pair_combine(dt, pc, f, ws + L.a_grp, ws + L.a_comb, 1, st));
+  if (merge_tail)
+    HIP_TRY_AS(PROF_COMBINE, (double)(k + 1) * T * f * Eb,
+               launch_pair_combine_reduce(pc, f, ws + L.a_grp, ws + L.a_comb, (float *)(ws + L.rank_part),
+                                          fused_splits(f, kT), (float *)(ws + L.Q_all), ws + L.Qw, R, st));
+  else
+    HIP_TRY_AS(PROF_COMBINE, (double)(k + 1) * T * f * Eb,
+               launch_pair_combine(dt, pc, f, ws + L.a_grp, ws + L.a_comb, 1, st));
   // down projection (Algorithm 1 line 14): y = a_comb W_down^T + Qw (s B_down)^T
   if (dt == MIXLORA_BF16 && (size_t)T <= SPLITK_MAX_ROWS) {
     // Few rows: the d output columns alone give too few tiles to stream W_down at full rate, so

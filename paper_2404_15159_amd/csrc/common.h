@@ -179,7 +179,8 @@ hipError_t launch_swiglu_fwd_mfma(const PairCtx &pc, int f, float s, const void 
                                   const float *Pg_all, const float *Pu_all, const void *B_gate,
                                   const void *B_up, const void *A_down, void *a_grp,
                                   float *Q_part, float *Q_all, void *Qw, int ldqw,
-                                  hipStream_t st, int rows_mode = 0, const DoraArgs *dora = nullptr);
+                                  hipStream_t st, int rows_mode = 0, const DoraArgs *dora = nullptr,
+                                  bool reduce_parts = true);   // false: the caller sums Q_part itself
 // rows_mode of the fused stages (for the paper's own schedules, Figure 3): bit 0 = G and U hold
 // one row per grouped pair row instead of one per token; bit 1 = H likewise; bit 2 = the
 // block-sparse operand has one row per grouped pair row (unweighted) instead of one per token.
@@ -238,6 +239,11 @@ int fused_splits(int f, int kT);   // at most FUSED_MAX_SPLITS
 constexpr int FUSED_MAX_SPLITS = 32;
 
 // out[t,:] = sum_j (weighted ? w[t,j] : 1) * in_grp[row_of_pair[t,j], :]
+// launch_pair_combine (bf16, weighted) and the one-bank weighted per-token launch_reduce_rank_parts
+// as one launch (few tokens; k * r <= 256)
+hipError_t launch_pair_combine_reduce(const PairCtx &pc, int width, const void *in_grp, void *out,
+                                      const float *part, int nsplit, float *dense, void *sparse,
+                                      int ld_sparse, hipStream_t st);
 hipError_t launch_pair_combine(int dtype, const PairCtx &pc, int width, const void *in_grp,
                                void *out, int weighted, hipStream_t st);
 // two combines of the same shape in one launch (in_grp1 == NULL: only the first)

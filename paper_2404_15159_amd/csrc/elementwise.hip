@@ -254,17 +254,11 @@ hipError_t launch_swiglu_bwd(int dtype, const PairCtx &pc, int f, float s, const
 // Gather form of the weighted combine (Eq. 6; Algorithm 1 line 15): each output row is written
 // once, by one thread per 8 columns, slots added in ascending order (deterministic).
 template <typename E>
-__global__ __launch_bounds__(256) void pair_combine_kernel(PairCtx pc, int width,
-                                                           const E *__restrict__ in_grp0,
-                                                           E *__restrict__ out0,
-                                                           const E *__restrict__ in_grp1,
-                                                           E *__restrict__ out1, int weighted) {
-  // blockIdx.z picks one of two combines of the same shape that share the launch;
+__device__ __forceinline__ void pair_combine_body(const PairCtx &pc, int width,
+                                                  const E *__restrict__ in_grp,
+                                                  E *__restrict__ out, int weighted, int t, int by) {
   // a thread owns two 8-column chunks, 2048 columns apart: 2k independent loads in flight
-  const E *__restrict__ in_grp = blockIdx.z ? in_grp1 : in_grp0;
-  E *__restrict__ out = blockIdx.z ? out1 : out0;
-  const int t = blockIdx.x;
-  const int c0 = (blockIdx.y * 512 + threadIdx.x) * 8;
+  const int c0 = (by * 512 + threadIdx.x) * 8;
   const int c1 = c0 + 2048;
   if (c0 >= width) return;
   const bool two = c1 < width;
@@ -292,6 +286,60 @@ __global__ __launch_bounds__(256) void pair_combine_kernel(PairCtx pc, int width
     for (int i = 0; i < 8; i++) o.set(i, acc1[i]);
     o.store(out + (int64_t)t * width + c1);
   }
+}
+
+template <typename E>
+__global__ __launch_bounds__(256) void pair_combine_kernel(PairCtx pc, int width,
+                                                           const E *__restrict__ in_grp0,
+                                                           E *__restrict__ out0,
+                                                           const E *__restrict__ in_grp1,
+                                                           E *__restrict__ out1, int weighted) {
+  // blockIdx.z picks one of two combines of the same shape that share the launch
+  pair_combine_body<E>(pc, width, blockIdx.z ? in_grp1 : in_grp0, blockIdx.z ? out1 : out0, weighted,
+                       blockIdx.x, blockIdx.y);
+}
+
+// Few tokens: the weighted combine and, as one more slice of workgroups (blockIdx.y == ny), the sum
+// over column splits of the per-pair rank-r partial products of a token's k pairs - what
+// reduce_rank_parts_kernel (csrc/fused.hip) does for one bank, weighted, per token, with the same
+// order of additions.  Needs k * r <= 256.
+__global__ __launch_bounds__(256) void pair_combine_reduce_kernel(
+    PairCtx pc, int width, const bf16_t *__restrict__ in_grp, bf16_t *__restrict__ out, int ny,
+    const float *__restrict__ part, int nsplit, float *__restrict__ dense,
+    bf16_t *__restrict__ sparse, int ld_sparse) {
+  const int t = blockIdx.x;
+  if ((int)blockIdx.y < ny) {
+    pair_combine_body<bf16_t>(pc, width, in_grp, out, 1, t, blockIdx.y);
+    return;
+  }
+  const int r = pc.r, i = threadIdx.x;
+  if (i >= pc.k * r) return;
+  const int pair = t * pc.k + i / r, q = i % r, row = pc.row_of_pair[pair];
+  const int64_t n = (int64_t)pc.T * pc.k * r, at = (int64_t)row * r + q;
+  float acc = 0.f;
+  int sp = 0;
+  for (; sp + 8 <= nsplit; sp += 8) {   // eight loads in flight; additions in split order
+    float a[8];
+#pragma unroll
+    for (int u = 0; u < 8; u++) a[u] = part[(sp + u) * n + at];
+#pragma unroll
+    for (int u = 0; u < 8; u++) acc += a[u];
+  }
+  for (; sp < nsplit; sp++) acc += part[sp * n + at];
+  const int e = pc.idx[pair], R = pc.N * r;
+  dense[(int64_t)row * R + e * r + q] = acc;
+  sparse[(int64_t)t * ld_sparse + e * r + q] = (bf16_t)(pc.w[pair] * acc);
+}
+
+hipError_t launch_pair_combine_reduce(const PairCtx &pc, int width, const void *in_grp, void *out,
+                                      const float *part, int nsplit, float *dense, void *sparse,
+                                      int ld_sparse, hipStream_t st) {
+  if (pc.k * pc.r > 256) return hipErrorInvalidValue;
+  const int ny = (width / 8 + 511) / 512;
+  hipLaunchKernelGGL(pair_combine_reduce_kernel, dim3(pc.T, ny + 1), dim3(256), 0, st, pc, width,
+                     (const bf16_t *)in_grp, (bf16_t *)out, ny, part, nsplit, dense,
+                     (bf16_t *)sparse, ld_sparse);
+  return hipGetLastError();
 }
 
 hipError_t launch_pair_combine2(int dtype, const PairCtx &pc, int width, const void *in_grp0,

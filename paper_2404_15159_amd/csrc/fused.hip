@@ -525,7 +525,8 @@ hipError_t launch_swiglu_fwd_mfma(const PairCtx &pc, int f, float s, const void 
                                   const float *Pg_all, const float *Pu_all, const void *B_gate,
                                   const void *B_up, const void *A_down, void *a_grp,
                                   float *Q_part, float *Q_all, void *Qw, int ldqw,
-                                  hipStream_t st, int rows_mode, const DoraArgs *dora) {
+                                  hipStream_t st, int rows_mode, const DoraArgs *dora,
+                                  bool reduce_parts) {
   const int nP = pc.T * pc.k, nsplit = fused_splits(f, nP);
   const dim3 grid((nP + FT_ROWS - 1) / FT_ROWS + pc.N, nsplit), block(FT_WAVES * 64);
   const DoraArgs da = dora ? *dora : DoraArgs{};
@@ -545,7 +546,7 @@ hipError_t launch_swiglu_fwd_mfma(const PairCtx &pc, int f, float s, const void 
   }
 #undef MIXLORA_FWD
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || !reduce_parts) return e;
   const int64_t n = (int64_t)nP * pc.r;
   hipLaunchKernelGGL(reduce_rank_parts_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
                      pc, Q_part, (int64_t)0, nsplit, Q_all, Q_all, (bf16_t *)Qw, ldqw, 0,
