@@ -75,6 +75,11 @@ SMALL_CASES = [
     ("bf16_decode_17", BASE_BF16, dict(T=17, d=512, d_ff=704, N=8, k=2, r=16)),
     ("bf16_decode_100", BASE_BF16, dict(T=100, d=256, d_ff=520, N=4, k=2, r=32, alpha=64.0)),
     ("bf16_decode_128", BASE_BF16, dict(T=128, d=192, d_ff=576, N=8, k=2, r=8, alpha=16.0)),
+    # few tokens: the rank-r partial sums ride in the combine's launch while k * r <= 256 ...
+    ("bf16_decode_top8_r32", BASE_BF16, dict(T=40, d=256, d_ff=640, N=8, k=8, r=32, alpha=64.0)),
+    ("bf16_decode_1_token", BASE_BF16, dict(T=1, d=256, d_ff=520, N=8, k=2, r=16)),
+    # ... and have a launch of their own beyond that
+    ("bf16_decode_top8_r64", BASE_BF16, dict(T=24, d=256, d_ff=576, N=8, k=8, r=64, alpha=128.0)),
     ("bf16_skew", synth.CONFIGS["llama2_13b_skew"], dict(T=600, d=256, d_ff=768)),
     ("bf16_clusters", synth.CONFIGS["llama3_8b_clusters"], dict(T=1024, d=256, d_ff=512, seq_len=64)),
     # more than 8192 pairs: grouping and Eq. 8-9 run as multi-workgroup passes (ragged last chunk)
