@@ -435,8 +435,8 @@ def main():
                     "executed_tflop_per_launch": k_flops_exec / max(launches_per_step, 1e-9) / 1e12,
                     "traffic": traffic, "traffic_source": traffic_note}
 
-    # bandwidth-bound kernel families: algorithmic bytes (as declared at each launch site and
-    # stated in the design doc) over the HIP-event time of their launches, against the HBM peak
+    # bandwidth-bound kernel families: algorithmic bytes (as declared at each launch site in
+    # csrc/api.hip) over the HIP-event time of their launches, against the HBM peak
     hbm_kernels = {}
     for name in ("fused_forward", "fused_backward", "combine", "gradient_sums"):
         ms, n, work = kinds[name]
