@@ -440,18 +440,22 @@ __device__ __forceinline__ void group_token_pairs_block(
     const int t = t0 + lane;
     const bool valid = t < hi;
     const int gid = valid ? group_of(t) : -1;
-    int pos = 0;
-    unsigned long long rem = __ballot(valid);
-    while (rem) {   // one trip per distinct group among the 64 tokens, in lane order of its first token
-      const int leader = __ffsll((long long)rem) - 1;
-      const int kk = __shfl(gid, leader, 64);
-      const unsigned long long m = __ballot(valid && gid == kk);
-      const int start = cnt[wave][kk];
-      if (valid && gid == kk) pos = start + __popcll(m & lt);
-      if (lane == leader) cnt[wave][kk] = start + __popcll(m);
-      rem &= ~m;
+    // m = the lanes whose token is in this lane's group: one ballot per bit of the group id
+    // (ids are below PG_GROUPS = 256), no loop over the groups present
+    unsigned long long m = __ballot(valid);
+#pragma unroll
+    for (int b = 0; b < 8; b++) {
+      const unsigned long long has = __ballot(valid && ((gid >> b) & 1));
+      m &= ((gid >> b) & 1) ? has : ~has;
     }
-    if (valid) tok_of_pos[pos] = t;
+    if (valid) {
+      // every lane of the group reads the group's next free position (one LDS instruction for
+      // the whole wavefront), then the group's first lane moves it on
+      const int start = cnt[wave][gid];
+      const int pos = start + __popcll(m & lt);
+      if ((m & lt) == 0) cnt[wave][gid] = start + __popcll(m);
+      tok_of_pos[pos] = t;
+    }
   }
 }
 
