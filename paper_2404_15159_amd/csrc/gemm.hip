@@ -19,6 +19,8 @@ struct GemmBatch {
   GemmProblem p[GEMM_MAX_PROBLEMS];
 };
 
+constexpr int GEMM_LONG_K = 8192;   // summed K of a problem from which the half-slot ring is used
+
 // Map the hardware block id to a tile so that (a) blocks that land on the same XCD (id % 8)
 // get consecutive logical ids and (b) consecutive logical ids walk GROUP tile-rows at a time.
 __device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int &tm, int &tn) {
@@ -216,6 +218,12 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_kernel(GemmBatch args
 // right after the barrier.  If every wave issues its share, both waves of each SIMD stall
 // together and the matrix pipe runs dry; with one issuing wave per SIMD (PW = 4 of 8 waves)
 // the other wave works through its MFMAs meanwhile, and the issuing wave follows with its own.
+// H5 replaces the two whole stages by five half-slots of one operand's K tile each (all 160 KB
+// of LDS).  A and B tiles rotate through them separately, so the A tile of step t+3 is requested
+// together with the B tile of step t+2: a barrier still frees and refills 64 KB, but the half
+// needed at the next barrier is first in the burst and the other half has one tile longer to
+// arrive.  That pays where the copies come from HBM rather than from L2 (one round of tiles over
+// a long K, operands last touched by other kernels); over short K it costs a few percent.
 __device__ __forceinline__ void dma16(uint32_t voff, const void *sbase, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
@@ -233,7 +241,7 @@ __device__ __forceinline__ const void *uniform_ptr(const void *p) {
   return reinterpret_cast<const void *>(((uint64_t)hi << 32) | lo);
 }
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool PIPE = false, int PW = 0>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool PIPE = false, int PW = 0, bool H5 = false>
 __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_dl_kernel(GemmBatch args) {
   constexpr int NW = WGM * WGN;
   constexpr int NPW = PW > 0 ? PW : NW;   // waves that issue the copies
@@ -327,8 +335,10 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_dl_kernel(GemmBatch a
     }
     issued++;
   };
+  if constexpr (!H5) {
 #pragma unroll
-  for (int s0 = 0; s0 < STAGES - 1; s0++) issue_next();
+    for (int s0 = 0; s0 < STAGES - 1; s0++) issue_next();
+  }
 
   // --- consumer side: swizzled fragment addresses -------------------------------------------
   const int l31 = lane & 31, hi = lane >> 5;
@@ -348,7 +358,134 @@ __global__ __launch_bounds__(WGM *WGN * 64) void gemm_bf16_dl_kernel(GemmBatch a
     else if (STAGES > 4 && newer == 2) wait_vmcnt<2 * IPW>();
     else wait_vmcnt<0>();
   };
-  if constexpr (!PIPE) {
+  if constexpr (H5) {
+    static_assert(BM == BN && IA == IB && KS == 4 && PIPE, "half-slot ring shape");
+    constexpr int HS = BM * ROWB, NSLOT = 5;
+    // the two operands advance through the K segments separately
+    int segA = 0, segB = 0, k0A = 0, k0B = 0, KA = Kcur, KB = Kcur, nA = 0, nB = 0;
+    const unsigned char *bA = baseA, *bB = baseB;
+    const void *gA = uniform_ptr(bA), *gB = uniform_ptr(bB);   // also the source of copies issued past the end
+    auto setupA = [&](int sgi) {
+      const GemmSeg &S = P.seg[sgi];
+#pragma unroll
+      for (int j = 0; j < IA; j++) {
+        const int rt = (wave * IA + j) * RPI + lrow;
+        const int kc = lpos ^ ((rt / RPB) % CPR);
+        int r = row0 + rt;
+        r = r < M ? r : M - 1;
+        offA[j] = (uint32_t)r * (uint32_t)S.lda * 2u + kc * 16;
+      }
+      bA = reinterpret_cast<const unsigned char *>(S.A);
+      KA = S.K;
+    };
+    auto setupB = [&](int sgi) {
+      const GemmSeg &S = P.seg[sgi];
+#pragma unroll
+      for (int j = 0; j < IB; j++) {
+        const int rt = (wave * IB + j) * RPI + lrow;
+        const int kc = lpos ^ ((rt / RPB) % CPR);
+        int c = col0 + rt;
+        c = c < N ? c : N - 1;
+        offB[j] = (uint32_t)c * (uint32_t)S.ldb * 2u + kc * 16;
+      }
+      bB = reinterpret_cast<const unsigned char *>(S.B);
+      KB = S.K;
+    };
+    // Past the last tile the previous address is copied again into the slot that is free anyway,
+    // so that the number of copies in flight at every wait is the same constant.
+    auto issueA = [&]() {
+      if (nA < total_tiles) {
+        if (k0A >= KA) {
+          segA++;
+          setupA(segA);
+          k0A = 0;
+        }
+        gA = uniform_ptr(bA + (size_t)k0A * 2);
+        k0A += BK;
+      }
+      const uint32_t l = lds0 + ((2 * nA) % NSLOT) * HS + wave * IA * 1024;
+      if (NPW == NW || wave < NPW) {
+#pragma unroll
+        for (int j = 0; j < IA; j++) dma16(offA[j], gA, l + j * 1024);
+      }
+      nA++;
+    };
+    auto issueB = [&]() {
+      if (nB < total_tiles) {
+        if (k0B >= KB) {
+          segB++;
+          setupB(segB);
+          k0B = 0;
+        }
+        gB = uniform_ptr(bB + (size_t)k0B * 2);
+        k0B += BK;
+      }
+      const uint32_t l = lds0 + ((2 * nB + 1) % NSLOT) * HS + wave * IB * 1024;
+      if (NPW == NW || wave < NPW) {
+#pragma unroll
+        for (int j = 0; j < IB; j++) dma16(offB[j], gB, l + j * 1024);
+      }
+      nB++;
+    };
+    bf16x8_t af[2][MI], bfr[2][NI];
+    const unsigned char *a5 = smem + (wm * TM + l31) * ROWB, *b5 = smem + (wn * TN + l31) * ROWB;
+    auto load_frags = [&](int buf, int sa, int sb, int ks) {
+      const unsigned char *a = a5 + sa * HS + koff[ks];
+      const unsigned char *b = b5 + sb * HS + koff[ks];
+#pragma unroll
+      for (int i = 0; i < MI; i++) af[buf][i] = *reinterpret_cast<const bf16x8_t *>(a + i * 32 * ROWB);
+#pragma unroll
+      for (int j = 0; j < NI; j++) bfr[buf][j] = *reinterpret_cast<const bf16x8_t *>(b + j * 32 * ROWB);
+    };
+    auto mfma_step = [&](int cur) {
+#pragma unroll
+      for (int i = 0; i < MI; i++)
+#pragma unroll
+        for (int j = 0; j < NI; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][j], af[cur][i], acc[i][j], 0, 0, 0);
+    };
+    issueA(); issueB(); issueA(); issueB(); issueA();    // A0 B0 A1 B1 A2
+    wait_vmcnt<3 * IA>();                                // A0 and B0 have landed
+    __syncthreads();
+    int sa = 0, sb = 1;                                  // half-slots of the tile being consumed
+    load_frags(0, sa, sb, 0);
+    for (int t = 0; t + 1 < total_tiles; t++) {
+      const int sa1 = sa + 2 >= NSLOT ? sa + 2 - NSLOT : sa + 2;
+      const int sb1 = sb + 2 >= NSLOT ? sb + 2 - NSLOT : sb + 2;
+#pragma unroll
+      for (int ks = 0; ks < KS; ks++) {
+        const int cur = ks & 1, nxt = cur ^ 1;
+        if (ks + 1 < KS) {
+          load_frags(nxt, sa, sb, ks + 1);
+        } else {
+          wait_vmcnt<IA>();     // A(t+2) may be in flight; A(t+1) and B(t+1) have landed
+          __syncthreads();      // ... for every wave, and the half-slots of A(t) and B(t) are free
+          issueB();             // B(t+2) into A(t)'s half-slot: needed at the next barrier
+          issueA();             // A(t+3) into B(t)'s: needed one barrier later
+          load_frags(nxt, sa1, sb1, 0);
+        }
+        mfma_step(cur);
+#pragma unroll
+        for (int q = 0; q < MI + NI; q++) {
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read ...
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // ... then one MFMA
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - MI - NI, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      sa = sa1;
+      sb = sb1;
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+      const int cur = ks & 1;
+      if (ks + 1 < KS) load_frags(cur ^ 1, sa, sb, ks + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfma_step(cur);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    wait_vmcnt<0>();            // the copies issued past the end have to be out of the ring
+  } else if constexpr (!PIPE) {
     for (int it = 0; it < total_tiles; it++) {
       wait_tile(it);
       __syncthreads();
@@ -598,10 +735,10 @@ static hipError_t launch_bf16(const GemmBatch &b, int nprob, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool PIPE = false, int PW = 0>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool PIPE = false, int PW = 0, bool H5 = false>
 static hipError_t launch_bf16_dl(const GemmBatch &b, int nprob, hipStream_t st) {
-  constexpr size_t smem = (size_t)STAGES * (BM + BN) * BK * sizeof(bf16_t);
-  auto kern = gemm_bf16_dl_kernel<BM, BN, BK, STAGES, WGM, WGN, PIPE, PW>;
+  constexpr size_t smem = H5 ? (size_t)5 * BM * BK * sizeof(bf16_t) : (size_t)STAGES * (BM + BN) * BK * sizeof(bf16_t);
+  auto kern = gemm_bf16_dl_kernel<BM, BN, BK, STAGES, WGM, WGN, PIPE, PW, H5>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -671,7 +808,17 @@ hipError_t launch_gemm(int dtype, const GemmProblem *probs, int nprob, hipStream
     // large tiles: direct-to-LDS ring; BK = 64 needs whole 64-wide K tiles, else BK = 32.
     // Problems of one launch may differ in N and output type (narrow ones ride in the slack
     // of the last, partially filled round of workgroups).
-    if (dl_eligible(b, nprob, 64)) return launch_bf16_dl<256, 256, 64, 2, 2, 4, true, 4>(b, nprob, st);
+    if (dl_eligible(b, nprob, 64)) {
+      // long K (the down projection and the input-gradient products): the half-slot ring
+      bool long_k = true;
+      for (int i = 0; i < nprob; i++) {
+        int64_t kt = 0;
+        for (int sgi = 0; sgi < probs[i].nseg; sgi++) kt += probs[i].seg[sgi].K;
+        if (kt < GEMM_LONG_K) long_k = false;
+      }
+      if (long_k) return launch_bf16_dl<256, 256, 64, 2, 2, 4, true, 4, true>(b, nprob, st);
+      return launch_bf16_dl<256, 256, 64, 2, 2, 4, true, 4>(b, nprob, st);
+    }
     if (dl_eligible(b, nprob, 32)) return launch_bf16_dl<256, 256, 32, 4, 2, 4, false>(b, nprob, st);
   }
   if (dtype == MIXLORA_BF16 && M <= 128 && any_big && dl_eligible(b, nprob, 64)) {
