@@ -768,6 +768,38 @@ static int backward_impl(const mixlora_dims &Du, int Nl, const int32_t *token_mo
                             Sop, Kx, 2 * R, Kx - 2 * R, Nl, token_model,
                             (const int32_t *)(ws + L.model_tokens),
                             dt == MIXLORA_BF16 ? ws + L.dzT : nullptr, L.ldTz, st, vanilla ? 1 : 0));
+  // The input gradient goes before the gradient sums: those stream what the fused stage wrote, and
+  // measured 15 us faster behind this long GEMM launch than right behind that stage.
+  // dx = dgsum W_gate + dusum W_up + [TG | TU | dz] [s A_gate ; s A_up ; W_router]
+  if (dt != MIXLORA_BF16)   // in bf16 the fused stage has already written these blocks
+    HIP_TRY_AS(PROF_OTHER, 0, launch_scatter_blocks(dt, pc, (float *)(ws + L.TG_all),
+                                  (int64_t)((float *)(ws + L.TU_all) - (float *)(ws + L.TG_all)), 2, R,
+                                  1, 0, ws + L.S, Kx, 0, st));
+  if (dora) {
+    // magnitude gradients: dm = (1 / n) * sum over the expert's rows of (output gradient *
+    // unscaled projection output); gate / up sums come from the fused stage per row tile
+    HIP_TRY_AS(PROF_OTHER, 0, launch_dm_tiles_reduce(offs, N, f, (float *)(ws + L.dm_part_g),
+                                   (float *)(ws + L.dm_part_u), (float *)(ws + L.ninv_g),
+                                   (float *)(ws + L.ninv_u), dgrads->dm_gate, dgrads->dm_up, dora->shared, st));
+    HIP_TRY_AS(PROF_OTHER, 0, launch_dm_down(pc, d, dy, ws + L.Op, (float *)(ws + L.ninv_d),
+                           (float *)(ws + L.dmd_part), dgrads->dm_down, dora->shared, st));
+  }
+  if (vanilla) {
+    // unshared schedule: every pair row goes through W_gate^T / W_up^T on its own, the k rows of
+    // a token are added afterwards
+    GemmProblem p = problem(kT, d, ws + L.dXp, d, 0);
+    add_seg(p, ws + L.dg_grp, f, WgT, f, f);
+    add_seg(p, ws + L.du_grp, f, WuT, f, f);
+    add_seg(p, ws + L.Sp, Kx, ws + L.Bx, Kx, Kx);
+    HIP_TRY(launch_gemm(dt, &p, 1, st));
+    HIP_TRY_AS(PROF_COMBINE, (double)(k + 1) * T * d * Eb, launch_pair_combine(dt, pc, d, ws + L.dXp, dx, 0, st));
+  } else {
+    GemmProblem p = problem(T, d, dx, d, 0);
+    add_seg(p, ws + L.dgsum, f, WgT, f, f);
+    add_seg(p, ws + L.dusum, f, WuT, f, f);
+    add_seg(p, ws + L.S, Kx, ws + L.Bx, Kx, Kx);
+    HIP_TRY(launch_gemm(dt, &p, 1, st));
+  }
   if (dt == MIXLORA_BF16) {
     GatherJob gj[6];
     for (int i = 0; i < 6; i++) gj[i] = GatherJob{fsrc[i], ws + L.small[i], by_token[i], weighted[i]};
@@ -808,36 +840,6 @@ static int backward_impl(const mixlora_dims &Du, int Nl, const int32_t *token_mo
     HIP_TRY_AS(PROF_GRAD_SUMS, (double)T * d * Eb,
                launch_group_outer(dt, (int32_t *)(ws + L.tok_offs), 1, T, nullptr, 1,
                                   (float *)(ws + L.dz), N, x, d, 1.f, 1, grads->dW_router, part, pfl, st));
-  }
-  // dx = dgsum W_gate + dusum W_up + [TG | TU | dz] [s A_gate ; s A_up ; W_router]
-  if (dt != MIXLORA_BF16)   // in bf16 the fused stage has already written these blocks
-    HIP_TRY_AS(PROF_OTHER, 0, launch_scatter_blocks(dt, pc, (float *)(ws + L.TG_all),
-                                  (int64_t)((float *)(ws + L.TU_all) - (float *)(ws + L.TG_all)), 2, R,
-                                  1, 0, ws + L.S, Kx, 0, st));
-  if (dora) {
-    // magnitude gradients: dm = (1 / n) * sum over the expert's rows of (output gradient *
-    // unscaled projection output); gate / up sums come from the fused stage per row tile
-    HIP_TRY_AS(PROF_OTHER, 0, launch_dm_tiles_reduce(offs, N, f, (float *)(ws + L.dm_part_g),
-                                   (float *)(ws + L.dm_part_u), (float *)(ws + L.ninv_g),
-                                   (float *)(ws + L.ninv_u), dgrads->dm_gate, dgrads->dm_up, dora->shared, st));
-    HIP_TRY_AS(PROF_OTHER, 0, launch_dm_down(pc, d, dy, ws + L.Op, (float *)(ws + L.ninv_d),
-                           (float *)(ws + L.dmd_part), dgrads->dm_down, dora->shared, st));
-  }
-  if (vanilla) {
-    // unshared schedule: every pair row goes through W_gate^T / W_up^T on its own, the k rows of
-    // a token are added afterwards
-    GemmProblem p = problem(kT, d, ws + L.dXp, d, 0);
-    add_seg(p, ws + L.dg_grp, f, WgT, f, f);
-    add_seg(p, ws + L.du_grp, f, WuT, f, f);
-    add_seg(p, ws + L.Sp, Kx, ws + L.Bx, Kx, Kx);
-    HIP_TRY(launch_gemm(dt, &p, 1, st));
-    HIP_TRY_AS(PROF_COMBINE, (double)(k + 1) * T * d * Eb, launch_pair_combine(dt, pc, d, ws + L.dXp, dx, 0, st));
-  } else {
-    GemmProblem p = problem(T, d, dx, d, 0);
-    add_seg(p, ws + L.dgsum, f, WgT, f, f);
-    add_seg(p, ws + L.dusum, f, WuT, f, f);
-    add_seg(p, ws + L.S, Kx, ws + L.Bx, Kx, Kx);
-    HIP_TRY(launch_gemm(dt, &p, 1, st));
   }
   if (L.rp != Du.r) {
     float *dst[6] = {grads_user->dA_gate, grads_user->dB_gate, grads_user->dA_up,
